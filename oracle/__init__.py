@@ -1,0 +1,144 @@
+"""CPU oracle for the speculative-decoding verify step -- TEST INFRASTRUCTURE ONLY.
+
+A thin ctypes loader around ``respec_oracle.c`` (plain C, fp64).  Only the tests,
+``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg may import this
+package; the product (``paper_2510_26475_amd``) never does and the two share no code.
+
+Arrays are numpy, host side.  bf16 data is passed as ``uint16`` bit patterns.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "respec_oracle.c")
+_LIB = os.path.join(_HERE, "librespec_oracle.so")
+
+F32 = 0
+BF16 = 1
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no HIP, no third-party code)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        c = ctypes
+        lib.respec_oracle_verify_attention.restype = c.c_int
+        lib.respec_oracle_verify_attention.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_double, c.c_int, c.c_int]
+        lib.respec_oracle_rejection_sample.restype = c.c_int
+        lib.respec_oracle_rejection_sample.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_double, c.c_int, c.c_int]
+        lib.respec_oracle_softmax_rows.restype = c.c_int
+        lib.respec_oracle_softmax_rows.argtypes = [
+            c.c_void_p, c.c_int32, c.c_int32, c.c_int64, c.c_double, c.c_int, c.c_void_p]
+        lib.respec_oracle_max_threads.restype = c.c_int
+        _lib = lib
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().respec_oracle_max_threads())
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check_elems(a: np.ndarray, dtype: int, name: str) -> np.ndarray:
+    want = np.float32 if dtype == F32 else np.uint16
+    if a.dtype != want:
+        raise TypeError(f"{name}: expected {want.__name__} for dtype code {dtype}, got {a.dtype}")
+    return np.ascontiguousarray(a)
+
+
+def verify_attention(q, k_cache, v_cache, q_indptr, kv_indptr, Hq, Hkv, D, sm_scale, dtype,
+                     want_lse=False, n_threads=1):
+    """q [total_q,Hq,D], k_cache/v_cache [total_kv,Hkv,D] (float32 or uint16 bf16 bits).
+
+    Returns out [total_q,Hq,D] float64 (and lse [total_q,Hq] float64 when asked).
+    """
+    q = _check_elems(q, dtype, "q")
+    k_cache = _check_elems(k_cache, dtype, "k_cache")
+    v_cache = _check_elems(v_cache, dtype, "v_cache")
+    q_indptr = np.ascontiguousarray(q_indptr, dtype=np.int32)
+    kv_indptr = np.ascontiguousarray(kv_indptr, dtype=np.int64)
+    B = q_indptr.shape[0] - 1
+    total_q = int(q_indptr[-1])
+    total_kv = int(kv_indptr[-1])
+    assert q.size == total_q * Hq * D, "q size does not match q_indptr"
+    assert k_cache.size == total_kv * Hkv * D and v_cache.size == total_kv * Hkv * D
+    out = np.zeros((total_q, Hq, D), dtype=np.float64)
+    lse = np.zeros((total_q, Hq), dtype=np.float64) if want_lse else None
+    rc = _load().respec_oracle_verify_attention(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(q_indptr), _ptr(kv_indptr), _ptr(out),
+        _ptr(lse), B, Hq, Hkv, D, float(sm_scale), dtype, n_threads)
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_verify_attention failed with code {rc}")
+    return (out, lse) if want_lse else out
+
+
+def rejection_sample(target_logits, draft_logits, draft_tokens, q_indptr, u_accept, u_final,
+                     max_k, temperature, dtype, n_threads=1):
+    """target_logits [total_q,V], draft_logits [total_q-B,V] (float32 or uint16 bf16 bits).
+
+    The temperature is rounded to binary32 first: the boundary passes it as a C float.
+    Returns (out_tokens [B,max_k+1] int32, num_accepted [B] int32, flags [B] int32).
+    """
+    target_logits = _check_elems(target_logits, dtype, "target_logits")
+    q_indptr = np.ascontiguousarray(q_indptr, dtype=np.int32)
+    B = q_indptr.shape[0] - 1
+    V = target_logits.shape[-1]
+    assert target_logits.ndim == 2 and target_logits.shape[0] == int(q_indptr[-1])
+    n_draft = int(q_indptr[-1]) - B
+    if n_draft > 0:
+        draft_logits = _check_elems(draft_logits, dtype, "draft_logits")
+        assert draft_logits.shape == (n_draft, V)
+        draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+        u_accept = np.ascontiguousarray(u_accept, dtype=np.float32)
+        assert draft_tokens.shape == (n_draft,) and u_accept.shape == (n_draft,)
+    else:
+        draft_logits = draft_tokens = u_accept = None
+    u_final = np.ascontiguousarray(u_final, dtype=np.float32)
+    assert u_final.shape == (B,)
+    out_tokens = np.empty((B, max_k + 1), dtype=np.int32)
+    num_accepted = np.empty((B,), dtype=np.int32)
+    flags = np.empty((B,), dtype=np.int32)
+    rc = _load().respec_oracle_rejection_sample(
+        _ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens), _ptr(q_indptr),
+        _ptr(u_accept), _ptr(u_final), _ptr(out_tokens), _ptr(num_accepted), _ptr(flags),
+        B, max_k, V, V, V, float(np.float32(temperature)), dtype, n_threads)
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_rejection_sample failed with code {rc}")
+    return out_tokens, num_accepted, flags
+
+
+def softmax_rows(logits, temperature, dtype):
+    """softmax(logits/T) row by row in fp64, as the sampler oracle computes it."""
+    logits = _check_elems(logits, dtype, "logits")
+    n, V = logits.shape
+    out = np.empty((n, V), dtype=np.float64)
+    rc = _load().respec_oracle_softmax_rows(_ptr(logits), n, V, V, float(np.float32(temperature)), dtype,
+                                            _ptr(out))
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_softmax_rows failed with code {rc}")
+    return out

@@ -1,0 +1,343 @@
+/*
+ * respec_oracle.c -- CPU oracle for the speculative-decoding verify step.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, obviously
+ * correct fp64 implementation of what the verify step computes, written from the
+ * paper's statement of speculative decoding (Section 2.2: the draft/validate
+ * procedure, the acceptance rule Eq. 1 and the residual distribution Eq. 2).
+ * Only tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ * It shares no code, header, table or helper with the HIP library.
+ *
+ * Parity pins (all functions here are pinned, none is "parity unpinned"):
+ *   attention  -- dense numpy brute force on tiny shapes, closed forms (identical
+ *                 keys => running mean of V, constant V, one visible key),
+ *                 causality and GQA-sharing invariants, split/merge identity,
+ *                 a library routine (scaled_dot_product_attention) for one query.
+ *   sampler    -- q == p accepts every draft, k = 0 equals numpy's
+ *                 cumsum/searchsorted sampler, chi-square of the emitted-token
+ *                 marginal against p over 10^6 draws, acceptance rate against
+ *                 1 - TV(p,q), disjoint supports, exact enumeration over a
+ *                 stratified uniform grid.
+ *
+ * Conventions (the paper fixes Eq. 1 and Eq. 2 only; the rest are this build's
+ * stated readings):
+ *   - Sequence b has R_b = q_indptr[b+1]-q_indptr[b] = k_b+1 query/target rows and
+ *     L_b = kv_indptr[b+1]-kv_indptr[b] cached tokens, the R_b new ones included.
+ *     Query row i sits at absolute position L_b-R_b+i and sees keys 0..L_b-R_b+i.
+ *   - Target row i is the distribution of the token that follows query row i, so
+ *     it verifies drafted token i (i < k_b); row k_b is the bonus row.
+ *   - Drafted tokens are tested in order; the first rejected one is replaced by
+ *     one sample from the residual distribution and validation stops (Section 2.2,
+ *     "Validation").  If none is rejected one bonus token is drawn from row k_b.
+ *   - Randomness is supplied: accept iff u < min(1, p/q) (strict), and the single
+ *     final draw per sequence is an inverse-CDF walk in ascending token id that
+ *     returns the first x whose running sum exceeds u*Z (strict).
+ *   - Temperature divides both target and drafter logits before the softmax.
+ *   - flags bit0: an acceptance test had |u - min(1,rho)| <= 1e-6;
+ *     flags bit1: u*Z lay within 1e-6*Z of an edge of the chosen token's CDF cell.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_F32 0
+#define ORACLE_BF16 1
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG 1
+#define ORACLE_ERR_ALLOC 2
+#define ORACLE_ERR_DATA 3
+
+#define BOUNDARY_EPS 1e-6
+
+static double load_elem(const void *base, int64_t idx, int dtype)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)base)[idx];
+    /* bf16 is the upper half of an IEEE binary32 */
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[idx] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static int pick_threads(int n_threads)
+{
+#ifdef _OPENMP
+    if (n_threads <= 0)
+        n_threads = omp_get_max_threads();
+    return n_threads;
+#else
+    (void)n_threads;
+    return 1;
+#endif
+}
+
+int respec_oracle_max_threads(void)
+{
+    return pick_threads(0);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Verify attention: the plain definition.                                    */
+/*   o[i,h,:] = sum_j softmax_j(sm_scale * <q[i,h,:], k[j,h/G,:]>) v[j,h/G,:]  */
+/*   over the keys j = 0 .. L_b - R_b + i of the row's own sequence.           */
+/* Layouts: q, out [total_q, Hq, D]; k_cache, v_cache [total_kv, Hkv, D];      */
+/* out in fp64; lse [total_q, Hq] fp64 or NULL (natural log of the softmax     */
+/* denominator, in units of the scaled scores).                                */
+/* ------------------------------------------------------------------------- */
+static int attention_one_sequence(const void *q, const void *k_cache, const void *v_cache,
+                                  int32_t q0, int32_t R, int64_t kv0, int64_t L, double *out,
+                                  double *lse, int32_t Hq, int32_t Hkv, int32_t D,
+                                  double sm_scale, int dtype)
+{
+    const int32_t G = Hq / Hkv;
+    double *score = (double *)malloc((size_t)L * sizeof(double));
+    if (!score)
+        return ORACLE_ERR_ALLOC;
+    for (int32_t i = 0; i < R; ++i) {
+        const int64_t last_key = L - R + i; /* inclusive */
+        for (int32_t h = 0; h < Hq; ++h) {
+            const int32_t hk = h / G;
+            const int64_t qoff = ((int64_t)(q0 + i) * Hq + h) * D;
+            double m = -INFINITY;
+            for (int64_t j = 0; j <= last_key; ++j) {
+                const int64_t koff = ((kv0 + j) * Hkv + hk) * D;
+                double dot = 0.0;
+                for (int32_t d = 0; d < D; ++d)
+                    dot += load_elem(q, qoff + d, dtype) * load_elem(k_cache, koff + d, dtype);
+                score[j] = sm_scale * dot;
+                if (score[j] > m)
+                    m = score[j];
+            }
+            double denom = 0.0;
+            for (int64_t j = 0; j <= last_key; ++j) {
+                score[j] = exp(score[j] - m);
+                denom += score[j];
+            }
+            double *o = out + qoff;
+            for (int32_t d = 0; d < D; ++d)
+                o[d] = 0.0;
+            for (int64_t j = 0; j <= last_key; ++j) {
+                const int64_t voff = ((kv0 + j) * Hkv + hk) * D;
+                const double a = score[j] / denom;
+                for (int32_t d = 0; d < D; ++d)
+                    o[d] += a * load_elem(v_cache, voff + d, dtype);
+            }
+            if (lse)
+                lse[(int64_t)(q0 + i) * Hq + h] = m + log(denom);
+        }
+    }
+    free(score);
+    return ORACLE_OK;
+}
+
+int respec_oracle_verify_attention(const void *q, const void *k_cache, const void *v_cache,
+                                   const int32_t *q_indptr, const int64_t *kv_indptr, double *out,
+                                   double *lse, int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
+                                   double sm_scale, int dtype, int n_threads)
+{
+    if (!q || !k_cache || !v_cache || !q_indptr || !kv_indptr || !out)
+        return ORACLE_ERR_ARG;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0)
+        return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16)
+        return ORACLE_ERR_ARG;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t R = q_indptr[b + 1] - q_indptr[b];
+        const int64_t L = kv_indptr[b + 1] - kv_indptr[b];
+        if (R < 1 || L < R)
+            return ORACLE_ERR_DATA;
+    }
+    int status = ORACLE_OK;
+    const int nt = pick_threads(n_threads);
+    (void)nt;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nt)
+    for (int32_t b = 0; b < B; ++b) {
+        const int rc = attention_one_sequence(q, k_cache, v_cache, q_indptr[b],
+                                              q_indptr[b + 1] - q_indptr[b], kv_indptr[b],
+                                              kv_indptr[b + 1] - kv_indptr[b], out, lse, Hq, Hkv,
+                                              D, sm_scale, dtype);
+        if (rc != ORACLE_OK) {
+#pragma omp critical
+            status = rc;
+        }
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Rejection sampling (Section 2.2, Eq. 1 and Eq. 2), one sequence at a time. */
+/* ------------------------------------------------------------------------- */
+
+/* p[x] = softmax(logits[row, :] / T)[x], max-subtracted, all in fp64. */
+static void softmax_row(const void *logits, int64_t row, int64_t ld, int32_t V, double T,
+                        int dtype, double *p)
+{
+    double m = -INFINITY;
+    for (int32_t x = 0; x < V; ++x) {
+        p[x] = load_elem(logits, row * ld + x, dtype) / T;
+        if (p[x] > m)
+            m = p[x];
+    }
+    double s = 0.0;
+    for (int32_t x = 0; x < V; ++x) {
+        p[x] = exp(p[x] - m);
+        s += p[x];
+    }
+    for (int32_t x = 0; x < V; ++x)
+        p[x] /= s;
+}
+
+/* First token whose running sum of w, in ascending id, exceeds u*Z. */
+static int32_t inverse_cdf(const double *w, int32_t V, double Z, double u, int *near_edge)
+{
+    const double t = u * Z;
+    double c = 0.0;
+    int32_t last_positive = -1;
+    for (int32_t x = 0; x < V; ++x) {
+        const double before = c;
+        c += w[x];
+        if (w[x] > 0.0)
+            last_positive = x;
+        if (c > t) {
+            const double lo = fabs(t - before), hi = fabs(c - t);
+            if ((lo < hi ? lo : hi) <= BOUNDARY_EPS * Z)
+                *near_edge = 1;
+            return x;
+        }
+    }
+    /* u*Z rounded up to the total: only reachable through rounding, always flagged */
+    *near_edge = 1;
+    return last_positive >= 0 ? last_positive : V - 1;
+}
+
+static int sample_one_sequence(const void *target_logits, const void *draft_logits,
+                               const int32_t *draft_tokens, int32_t row0, int32_t drow0,
+                               int32_t k, const float *u_accept, float u_final,
+                               int32_t *out_tokens /* [max_k+1] */, int32_t *out_num_accepted,
+                               int32_t *out_flags, int32_t max_k, int32_t V, int64_t ld_t,
+                               int64_t ld_d, double T, int dtype)
+{
+    double *p = (double *)malloc((size_t)V * sizeof(double));
+    double *q = (double *)malloc((size_t)V * sizeof(double));
+    if (!p || !q) {
+        free(p);
+        free(q);
+        return ORACLE_ERR_ALLOC;
+    }
+    int flag_accept = 0, flag_cdf = 0;
+    int32_t n = 0, final_token = -1;
+    int rejected = 0;
+    for (int32_t j = 0; j <= max_k; ++j)
+        out_tokens[j] = -1;
+
+    for (int32_t i = 0; i < k; ++i) {
+        softmax_row(target_logits, row0 + i, ld_t, V, T, dtype, p);
+        softmax_row(draft_logits, drow0 + i, ld_d, V, T, dtype, q);
+        const int32_t x = draft_tokens[drow0 + i];
+        if (x < 0 || x >= V) {
+            free(p);
+            free(q);
+            return ORACLE_ERR_DATA;
+        }
+        double rho;
+        if (q[x] == 0.0)
+            rho = p[x] > 0.0 ? INFINITY : 0.0;
+        else
+            rho = p[x] / q[x];
+        const double thr = rho < 1.0 ? rho : 1.0;
+        const double u = (double)u_accept[drow0 + i];
+        if (fabs(u - thr) <= BOUNDARY_EPS)
+            flag_accept = 1;
+        if (u < thr) { /* Eq. 1: accepted, go on to the next drafted token */
+            out_tokens[i] = x;
+            n = i + 1;
+            continue;
+        }
+        /* first rejection: one sample from the residual, Eq. 2 */
+        double Z = 0.0;
+        for (int32_t y = 0; y < V; ++y) {
+            const double w = p[y] - q[y];
+            q[y] = w > 0.0 ? w : 0.0;
+            Z += q[y];
+        }
+        if (!(Z > 0.0)) { /* cannot happen in exact arithmetic; fall back to p */
+            memcpy(q, p, (size_t)V * sizeof(double));
+            Z = 1.0;
+        }
+        final_token = inverse_cdf(q, V, Z, (double)u_final, &flag_cdf);
+        rejected = 1;
+        break;
+    }
+    if (!rejected) { /* all k accepted (or k == 0): bonus token from target row k */
+        softmax_row(target_logits, row0 + k, ld_t, V, T, dtype, p);
+        final_token = inverse_cdf(p, V, 1.0, (double)u_final, &flag_cdf);
+    }
+    out_tokens[n] = final_token;
+    *out_num_accepted = n;
+    if (out_flags)
+        *out_flags = (flag_accept ? 1 : 0) | (flag_cdf ? 2 : 0);
+    free(p);
+    free(q);
+    return ORACLE_OK;
+}
+
+/*
+ * target_logits [total_q, V] (row stride ld_t), draft_logits [total_q-B, V] (ld_d);
+ * draft rows of sequence b start at q_indptr[b]-b.  out_tokens [B, max_k+1].
+ */
+int respec_oracle_rejection_sample(const void *target_logits, const void *draft_logits,
+                                   const int32_t *draft_tokens, const int32_t *q_indptr,
+                                   const float *u_accept, const float *u_final,
+                                   int32_t *out_tokens, int32_t *out_num_accepted,
+                                   int32_t *out_flags, int32_t B, int32_t max_k, int32_t V,
+                                   int64_t ld_t, int64_t ld_d, double temperature, int dtype,
+                                   int n_threads)
+{
+    if (!target_logits || !q_indptr || !u_final || !out_tokens || !out_num_accepted)
+        return ORACLE_ERR_ARG;
+    if (B <= 0 || V <= 0 || max_k < 0 || ld_t < V || !(temperature > 0.0))
+        return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16)
+        return ORACLE_ERR_ARG;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t k = q_indptr[b + 1] - q_indptr[b] - 1;
+        if (k < 0 || k > max_k)
+            return ORACLE_ERR_DATA;
+        if (k > 0 && (!draft_logits || !draft_tokens || !u_accept || ld_d < V))
+            return ORACLE_ERR_ARG;
+    }
+    int status = ORACLE_OK;
+    const int nt = pick_threads(n_threads);
+    (void)nt;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nt)
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t row0 = q_indptr[b];
+        const int32_t k = q_indptr[b + 1] - row0 - 1;
+        const int rc = sample_one_sequence(
+            target_logits, draft_logits, draft_tokens, row0, row0 - b, k, u_accept, u_final[b],
+            out_tokens + (int64_t)b * (max_k + 1), out_num_accepted + b,
+            out_flags ? out_flags + b : NULL, max_k, V, ld_t, ld_d, temperature, dtype);
+        if (rc != ORACLE_OK) {
+#pragma omp critical
+            status = rc;
+        }
+    }
+    return status;
+}
+
+/* softmax(logits[r,:]/T) for r in [0,n_rows), fp64 out [n_rows, V]; lets tests look inside. */
+int respec_oracle_softmax_rows(const void *logits, int32_t n_rows, int32_t V, int64_t ld,
+                               double temperature, int dtype, double *out)
+{
+    if (!logits || !out || n_rows < 0 || V <= 0 || ld < V || !(temperature > 0.0))
+        return ORACLE_ERR_ARG;
+    for (int32_t r = 0; r < n_rows; ++r)
+        softmax_row(logits, r, ld, V, temperature, dtype, out + (int64_t)r * V);
+    return ORACLE_OK;
+}
