@@ -1,0 +1,152 @@
+/*
+ * respec.h -- C boundary of the MI355X (gfx950) speculative-decoding verify step.
+ *
+ * The verify step is the "Validation" half of the draft/validate cycle of Section 2.2:
+ * the target model scores the k drafted tokens plus one in a single batched forward
+ * (Figure 2), drafted tokens are accepted in order with probability min(1, p/q) (Eq. 1),
+ * the first rejected one is replaced by a sample from the residual distribution
+ * max(0, p-q)/sum (Eq. 2), and when nothing is rejected one more token is drawn from the
+ * target.  This library holds the two data-parallel pieces of that step:
+ *
+ *   respec_verify_attention   the attention of that forward: (k_b+1) causal query rows per
+ *                             sequence, grouped-query heads, ragged per-sequence KV cache;
+ *   respec_rejection_sample   Eq. 1 / Eq. 2 over the vocabulary with supplied uniforms.
+ *
+ * General rules
+ *   - Every data pointer is a DEVICE pointer (HIP global memory) unless it says "host".
+ *     The caller owns all buffers; the library allocates and frees nothing on the device
+ *     and keeps no state between calls.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and never synchronise.  Inputs must stay valid and unchanged until
+ *     the stream has passed the call.
+ *   - The return value reports host-detectable errors only (bad scalars, null pointers,
+ *     misaligned pointers, workspace too small, a failed launch).  On error nothing is
+ *     launched.  respec_last_error() gives a thread-local text for the last failure.
+ *   - Data errors the host cannot see (k_b+1 > L_b, a token id outside [0,V), NaN or +inf
+ *     logits) are undefined behaviour as far as results go, but never read or write
+ *     outside the buffers described by the arguments.
+ *   - No C++ exceptions cross this boundary and nothing is printed.
+ *
+ * Notation: B sequences; sequence b has R_b = k_b+1 query/target rows
+ * (R_b = q_indptr[b+1]-q_indptr[b]) and L_b cached tokens (kv_indptr), the R_b new tokens
+ * included; total_q = sum R_b, total_kv = sum L_b; Hq query heads, Hkv KV heads,
+ * G = Hq/Hkv, head size D, vocabulary V.
+ */
+#ifndef RESPEC_H
+#define RESPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RESPEC_OK = 0,
+    RESPEC_ERR_INVALID_ARG = 1, /* null/misaligned pointer, non-positive size, bad scalar */
+    RESPEC_ERR_UNSUPPORTED = 2, /* valid request outside what the kernels cover         */
+    RESPEC_ERR_WORKSPACE = 3,   /* workspace missing or smaller than *_workspace_bytes  */
+    RESPEC_ERR_HIP = 4          /* the HIP runtime refused a launch                      */
+} respec_status_t;
+
+typedef enum { RESPEC_F32 = 0, RESPEC_BF16 = 1 } respec_dtype_t;
+
+/* Static strings; never NULL. */
+const char *respec_status_string(respec_status_t status);
+/* Thread-local detail text of the calling thread's last failed call ("" if none). */
+const char *respec_last_error(void);
+/* major*10000 + minor*100 + patch */
+int respec_version(void);
+
+/*
+ * Bytes of device workspace respec_verify_attention needs for any batch with these
+ * host-side bounds (split-KV partial results).  All arguments are the same scalars the
+ * call itself takes.  Returns 0 if the arguments are invalid or unsupported.
+ */
+size_t respec_verify_attention_workspace_bytes(int32_t B, int32_t total_q, int64_t total_kv,
+                                               int32_t max_q_per_seq, int32_t max_kv_len,
+                                               int32_t Hq, int32_t Hkv, int32_t D,
+                                               respec_dtype_t dt);
+
+/*
+ * Verify attention (the attention inside the single target forward of Section 2.2 /
+ * Figure 2; the paper fixes no layout, the ones below are this library's).
+ *
+ * For every sequence b, row i in [0,R_b) and query head h:
+ *     out[q_indptr[b]+i, h, :] = sum_j softmax_j(sm_scale * <q[row,h,:], K_b[j,h/G,:]>) V_b[j,h/G,:]
+ * over the keys j = 0 .. L_b-R_b+i of that sequence's cache (row i sits at absolute
+ * position L_b-R_b+i; the cache already holds the K/V of the R_b new tokens; RoPE, if
+ * any, is already applied).  Softmax and accumulation run in fp32; for RESPEC_BF16 the
+ * products run on bf16 MFMA and the result is rounded to nearest-even bf16.
+ *
+ *   q         [total_q, Hq, D]    dt, contiguous, 16-byte aligned
+ *   k_cache   [total_kv, Hkv, D]  dt, token-major, sequences back to back, 16-byte aligned
+ *   v_cache   [total_kv, Hkv, D]  dt, same layout
+ *   q_indptr  [B+1] int32, q_indptr[0] = 0, rows of sequence b = R_b >= 1
+ *   kv_indptr [B+1] int64, kv_indptr[0] = 0, L_b >= R_b
+ *   out       [total_q, Hq, D]    dt (written)
+ *   lse       [total_q, Hq] f32 or NULL: natural log of the softmax denominator plus the
+ *             row maximum, in units of the scaled scores (written when non-NULL)
+ *   max_q_per_seq, max_kv_len   host-side upper bounds of R_b and L_b: they size the grid
+ *             without a device synchronisation.  Rows or keys beyond them are NOT processed.
+ *   D in {64, 128}; Hq % Hkv == 0; G * max_q_per_seq <= 256.
+ *   workspace / workspace_bytes: at least respec_verify_attention_workspace_bytes(...)
+ *             bytes, 256-byte aligned; contents are scratch.
+ */
+respec_status_t respec_verify_attention(const void *q, const void *k_cache, const void *v_cache,
+                                        const int32_t *q_indptr, const int64_t *kv_indptr,
+                                        void *out, float *lse, int32_t B, int32_t total_q,
+                                        int64_t total_kv, int32_t max_q_per_seq,
+                                        int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                        float sm_scale, respec_dtype_t dt, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream);
+
+/* Workspace bytes of respec_rejection_sample (0 = none needed, NULL may be passed). */
+size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t total_q, int32_t V,
+                                               respec_dtype_t logits_dt);
+
+/*
+ * Speculative rejection sampling with supplied randomness (Section 2.2, Eq. 1 and Eq. 2).
+ *
+ * Per sequence b with k_b = R_b-1 drafted tokens, for i = 0 .. k_b-1 in order:
+ *     p = softmax(target_logits[q_indptr[b]+i, :] / T),  q = softmax(draft_logits[q_indptr[b]-b+i, :] / T)
+ *     x = draft_tokens[q_indptr[b]-b+i];  accept iff u_accept[q_indptr[b]-b+i] < min(1, p[x]/q[x])
+ * (q[x] == 0 counts as ratio +inf when p[x] > 0, else 0).  At the first rejection i = n the
+ * token out_tokens[b,n] is drawn from max(0,p-q)/Z (Eq. 2) and the sequence stops; if all
+ * k_b are accepted (or k_b == 0) out_tokens[b,k_b] is drawn from softmax(target row k_b / T).
+ * That one draw is an inverse-CDF walk in ascending token id: the first x whose running
+ * sum exceeds u_final[b]*Z.  Rows after the first rejection are not read.
+ *
+ *   target_logits [total_q, V], row stride ld_t elements (>= V)    logits_dt
+ *   draft_logits  [total_q-B, V], row stride ld_d elements (>= V)  logits_dt; may be NULL
+ *                 when total_q == B.  Rows start 16-byte aligned for the vector path
+ *                 (base and stride); other alignments take a slower scalar path.
+ *   draft_tokens  [total_q-B] int32 in [0,V)
+ *   q_indptr      [B+1] int32 (the same array verify attention takes)
+ *   u_accept      [total_q-B] f32 in [0,1);  u_final [B] f32 in [0,1)
+ *   out_tokens    [B, max_k+1] int32 (written): accepted drafts, then the resampled or
+ *                 bonus token, then -1
+ *   out_num_accepted [B] int32 (written): n_b, the acceptance length (drafts accepted
+ *                 before the first rejection)
+ *   out_flags     [B] int32 or NULL (written): bit0 = an acceptance test had
+ *                 |u - min(1,ratio)| <= 1e-6; bit1 = u_final*Z lay within 1e-6*Z of an edge
+ *                 of the chosen token's CDF cell.  Such draws may legitimately differ from
+ *                 an exact-arithmetic evaluation.
+ *   max_k         host-side upper bound of k_b (row width of out_tokens minus one)
+ *   temperature   T > 0, applied to target and drafter logits alike
+ */
+respec_status_t respec_rejection_sample(const void *target_logits, const void *draft_logits,
+                                        const int32_t *draft_tokens, const int32_t *q_indptr,
+                                        const float *u_accept, const float *u_final,
+                                        int32_t *out_tokens, int32_t *out_num_accepted,
+                                        int32_t *out_flags, int32_t B, int32_t total_q,
+                                        int32_t max_k, int32_t V, int64_t ld_t, int64_t ld_d,
+                                        float temperature, respec_dtype_t logits_dt,
+                                        void *workspace, size_t workspace_bytes,
+                                        void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RESPEC_H */

@@ -1,0 +1,190 @@
+"""ctypes binding of librespec.so: argument marshalling only.
+
+Same names as the C boundary (``include/respec.h``).  Torch tensors are used for device
+memory and the current stream; every step of the verify path runs in the HIP kernels.
+There is no CPU fallback: a missing library or a non-CUDA tensor is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from . import build as _build
+
+RESPEC_F32 = 0
+RESPEC_BF16 = 1
+
+_lib = None
+
+
+class RespecError(RuntimeError):
+    def __init__(self, status: int, text: str, detail: str):
+        super().__init__(f"librespec status {status} ({text}): {detail}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _build.LIB_PATH
+
+
+def load():
+    """Load librespec.so (building it first only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        _build.build()
+    if not os.path.exists(path):
+        raise RuntimeError(f"librespec.so not found at {path}; run python -m paper_2510_26475_amd.build")
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    lib.respec_status_string.restype = c.c_char_p
+    lib.respec_status_string.argtypes = [c.c_int]
+    lib.respec_last_error.restype = c.c_char_p
+    lib.respec_last_error.argtypes = []
+    lib.respec_version.restype = c.c_int
+    lib.respec_version.argtypes = []
+    lib.respec_verify_attention_workspace_bytes.restype = c.c_size_t
+    lib.respec_verify_attention_workspace_bytes.argtypes = [
+        c.c_int32, c.c_int32, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
+        c.c_int]
+    lib.respec_verify_attention.restype = c.c_int
+    lib.respec_verify_attention.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_int32, c.c_int32, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
+        c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_rejection_sample_workspace_bytes.restype = c.c_size_t
+    lib.respec_rejection_sample_workspace_bytes.argtypes = [c.c_int32, c.c_int32, c.c_int32, c.c_int]
+    lib.respec_rejection_sample.restype = c.c_int
+    lib.respec_rejection_sample.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64,
+        c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    _lib = lib
+    return lib
+
+
+EXPORTED_SYMBOLS = [
+    "respec_status_string", "respec_last_error", "respec_version",
+    "respec_verify_attention_workspace_bytes", "respec_verify_attention",
+    "respec_rejection_sample_workspace_bytes", "respec_rejection_sample",
+]
+
+
+def _check(status: int):
+    if status != 0:
+        lib = load()
+        raise RespecError(status, lib.respec_status_string(status).decode(),
+                          lib.respec_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return RESPEC_F32
+    if t.dtype == torch.bfloat16:
+        return RESPEC_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev_ptr(t: Optional[torch.Tensor], name: str):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (got {t.device})")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def respec_version() -> int:
+    return int(load().respec_version())
+
+
+def respec_verify_attention_workspace_bytes(B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq,
+                                            Hkv, D, dt) -> int:
+    return int(load().respec_verify_attention_workspace_bytes(
+        B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, dt))
+
+
+def respec_verify_attention(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, max_q_per_seq,
+                            max_kv_len, sm_scale, workspace, stream=None):
+    """q/out [total_q,Hq,D], k_cache/v_cache [total_kv,Hkv,D], q_indptr int32, kv_indptr int64."""
+    lib = load()
+    total_q, Hq, D = q.shape
+    total_kv, Hkv, _ = k_cache.shape
+    B = q_indptr.numel() - 1
+    if q_indptr.dtype != torch.int32 or kv_indptr.dtype != torch.int64:
+        raise TypeError("q_indptr must be int32 and kv_indptr int64")
+    if lse is not None and lse.dtype != torch.float32:
+        raise TypeError("lse must be float32")
+    if out.dtype != q.dtype or k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise TypeError("q, k_cache, v_cache and out must share one dtype")
+    ws_ptr = _dev_ptr(workspace, "workspace") if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.respec_verify_attention(
+        _dev_ptr(q, "q"), _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
+        _dev_ptr(q_indptr, "q_indptr"), _dev_ptr(kv_indptr, "kv_indptr"), _dev_ptr(out, "out"),
+        _dev_ptr(lse, "lse"), B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D,
+        float(sm_scale), _dtype_code(q), ws_ptr, ws_bytes, _stream_ptr(stream)))
+
+
+def respec_rejection_sample_workspace_bytes(B, total_q, V, logits_dt) -> int:
+    return int(load().respec_rejection_sample_workspace_bytes(B, total_q, V, logits_dt))
+
+
+def respec_rejection_sample(target_logits, draft_logits, draft_tokens, q_indptr, u_accept, u_final,
+                            out_tokens, out_num_accepted, out_flags, max_k, temperature,
+                            workspace=None, stream=None):
+    """target_logits [total_q,V], draft_logits [total_q-B,V]; outputs are written in place."""
+    lib = load()
+    total_q, V = target_logits.shape
+    B = q_indptr.numel() - 1
+    if q_indptr.dtype != torch.int32:
+        raise TypeError("q_indptr must be int32")
+    if out_tokens.dtype != torch.int32 or out_num_accepted.dtype != torch.int32:
+        raise TypeError("out_tokens and out_num_accepted must be int32")
+    if tuple(out_tokens.shape) != (B, max_k + 1) or out_num_accepted.numel() != B:
+        raise ValueError("out_tokens must be [B, max_k+1] and out_num_accepted [B]")
+    if u_final.dtype != torch.float32 or u_final.numel() != B:
+        raise TypeError("u_final must be float32 [B]")
+    n_draft = total_q - B
+    if n_draft > 0:
+        if draft_logits.dtype != target_logits.dtype or tuple(draft_logits.shape) != (n_draft, V):
+            raise ValueError("draft_logits must be [total_q-B, V] in the target's dtype")
+        if draft_tokens.dtype != torch.int32 or draft_tokens.numel() != n_draft:
+            raise TypeError("draft_tokens must be int32 [total_q-B]")
+        if u_accept.dtype != torch.float32 or u_accept.numel() != n_draft:
+            raise TypeError("u_accept must be float32 [total_q-B]")
+        ld_d = draft_logits.stride(0)
+    else:
+        draft_logits = draft_tokens = u_accept = None
+        ld_d = V
+    if target_logits.stride(1) != 1:
+        raise ValueError("logits rows must be unit-stride")
+    ws_ptr = _dev_ptr(workspace, "workspace") if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+
+    def row_ptr(t, name):
+        if t is None:
+            return None
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live on the GPU")
+        return ctypes.c_void_p(t.data_ptr())
+
+    _check(lib.respec_rejection_sample(
+        row_ptr(target_logits, "target_logits"), row_ptr(draft_logits, "draft_logits"),
+        _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(q_indptr, "q_indptr"),
+        _dev_ptr(u_accept, "u_accept"), _dev_ptr(u_final, "u_final"),
+        _dev_ptr(out_tokens, "out_tokens"), _dev_ptr(out_num_accepted, "out_num_accepted"),
+        _dev_ptr(out_flags, "out_flags"), B, total_q, max_k, V, target_logits.stride(0), ld_d,
+        float(temperature), _dtype_code(target_logits), ws_ptr, ws_bytes, _stream_ptr(stream)))

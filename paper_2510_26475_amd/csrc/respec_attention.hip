@@ -1,0 +1,785 @@
+// Verify attention for gfx950: the attention of the single target forward that scores the
+// k drafted tokens plus one (Section 2.2, "Validation"; Figure 2).  (k_b+1) causal query
+// rows per sequence, grouped-query heads, ragged token-major KV cache.
+//
+// bf16 path.  The G*(k_b+1) query rows that share one KV head are the columns of 16-wide
+// MFMA tiles; a work-group of four waves owns one (sequence, KV head, chunk of keys).
+// Each wave streams its own 32-key tiles: 16-byte coalesced global loads -> registers ->
+// wave-private LDS tile -> MFMA operands.  Scores are computed transposed
+// (S^T = K Q^T, v_mfma_f32_16x16x32_bf16) so that a lane's four accumulator rows are keys
+// and its column is one query row: the probabilities then feed the second product
+// (O^T = V^T P^T) straight from registers, and the softmax statistics of a row live in one
+// lane column.  The contraction indices of both products are permuted freely (any order is
+// valid as long as both operands agree), which is what lets K be read from LDS in 16-byte
+// pieces and V in 16-byte pieces along d with a register-level 2-byte regroup.
+// Four waves merge through LDS; a chunk that is the sequence's only one writes the output
+// directly, otherwise it writes an fp32 partial (max, sum, unnormalised O) and a second
+// kernel merges the partials in a fixed order (deterministic, no float atomics).
+//
+// fp32 path.  A plain fp32 kernel (no MFMA; the fp32 workload is the small parity case)
+// producing the same partial format, merged by the same combine kernel.
+#include "respec_common.hpp"
+
+#include <cmath>
+
+namespace respec {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWaves = 4;             // waves per work-group (bf16 path)
+constexpr int kThreads = kWaves * 64;
+constexpr int kTileKeys = 32;         // keys per wave tile
+constexpr int kColTile = 16;          // query rows per MFMA column tile
+constexpr int kMaxColsPerBlock = 64;  // 4 column tiles
+
+struct AttnParams {
+    const void *q;
+    const void *k;
+    const void *v;
+    const int32_t *q_indptr;
+    const int64_t *kv_indptr;
+    void *out;
+    float *lse;
+    float *ws_o;   // [n_slots, Hkv, Mpad, D]
+    float *ws_ml;  // [n_slots, Hkv, Mpad, 2]  (max in log2 units, sum)
+    int32_t B, total_q;
+    int64_t total_kv;
+    int32_t max_q, max_kv_len;
+    int32_t Hq, Hkv, G;
+    int32_t chunk;       // keys per work-group chunk (multiple of kWaves*kTileKeys)
+    int32_t max_chunks;  // ceil(max_kv_len / chunk)
+    int32_t Mpad;        // G*max_q rounded up to kColTile
+    int64_t n_slots;
+    float scale2;  // sm_scale * log2(e)
+};
+
+struct SeqInfo {
+    int32_t q0, R;
+    int64_t kv0;
+    int32_t L;
+    int32_t n_chunks;
+    int64_t slot0;
+};
+
+// Per-sequence bounds, clamped by the host-side totals so that no device data can push an
+// access outside the buffers.
+__device__ inline SeqInfo seq_info(const AttnParams &p, int b) {
+    SeqInfo s;
+    s.q0 = p.q_indptr[b];
+    int32_t R = p.q_indptr[b + 1] - s.q0;
+    s.q0 = max(0, min(s.q0, p.total_q));
+    R = max(0, min(R, min(p.max_q, p.total_q - s.q0)));
+    s.R = R;
+    int64_t kv0 = p.kv_indptr[b];
+    int64_t L = p.kv_indptr[b + 1] - kv0;
+    kv0 = kv0 < 0 ? 0 : (kv0 > p.total_kv ? p.total_kv : kv0);
+    if (L > p.total_kv - kv0) L = p.total_kv - kv0;
+    if (L > p.max_kv_len) L = p.max_kv_len;
+    if (L < 0) L = 0;
+    s.kv0 = kv0;
+    s.L = (int32_t)L;
+    s.n_chunks = (s.L + p.chunk - 1) / p.chunk;
+    s.slot0 = kv0 / p.chunk + b;  // unique, monotone slot range per sequence
+    return s;
+}
+
+__device__ inline float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA kernel
+// ------------------------------------------------------------------------------------------
+template <int D>
+struct Bf16Cfg {
+    static constexpr int kRowElems = D + 8;                 // padded LDS row (bf16 elements)
+    static constexpr int kRowBytes = kRowElems * 2;
+    static constexpr int kTileBytes = kTileKeys * kRowBytes;  // one K or V tile
+    static constexpr int kWaveBytes = 2 * kTileBytes;         // K + V
+    static constexpr int kLanesPerRow = D / 8;                // 16-byte pieces per key row
+    static constexpr int kRowsPerLoad = 64 / kLanesPerRow;
+    static constexpr int kLoads = kTileKeys / kRowsPerLoad;   // global loads per tile per lane
+    static constexpr int kKSteps = D / 32;                    // MFMA k-steps of S^T
+    static constexpr int kDTiles = D / 16;                    // 16-row d tiles of O^T
+    static constexpr int kEpl = D / 16;                       // V elements per lane per key
+    static constexpr int kMergeStride = D + 4;                // fp32 merge row (floats)
+};
+
+template <int D>
+__device__ inline void load_tile(u32x4 (&r)[Bf16Cfg<D>::kLoads], const char *base, int64_t row_bytes,
+                                 int key0, int last_key, int lane) {
+    using C = Bf16Cfg<D>;
+    const int rl = lane / C::kLanesPerRow, cl = lane % C::kLanesPerRow;
+#pragma unroll
+    for (int j = 0; j < C::kLoads; ++j) {
+        int key = key0 + j * C::kRowsPerLoad + rl;
+        key = min(key, last_key);  // rows past the end re-read the last valid row (masked later)
+        r[j] = *reinterpret_cast<const u32x4 *>(base + (int64_t)key * row_bytes + cl * 16);
+    }
+}
+
+template <int D>
+__device__ inline void store_tile(const u32x4 (&r)[Bf16Cfg<D>::kLoads], char *lds, int lane) {
+    using C = Bf16Cfg<D>;
+    const int rl = lane / C::kLanesPerRow, cl = lane % C::kLanesPerRow;
+#pragma unroll
+    for (int j = 0; j < C::kLoads; ++j)
+        *reinterpret_cast<u32x4 *>(lds + (j * C::kRowsPerLoad + rl) * C::kRowBytes + cl * 16) = r[j];
+}
+
+template <int D, int NT, typename OutT>
+__global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_bf16_kernel(AttnParams p) {
+    using C = Bf16Cfg<D>;
+    extern __shared__ __align__(16) char smem[];
+    // layout: [kWaves][kWaveBytes] tiles | stats
+    float *sh_m = reinterpret_cast<float *>(smem + kWaves * C::kWaveBytes);  // [kWaves][64]
+    float *sh_l = sh_m + kWaves * kMaxColsPerBlock;                           // [kWaves][64]
+    float *sh_mt = sh_l + kWaves * kMaxColsPerBlock;                          // [64]
+    float *sh_lt = sh_mt + kMaxColsPerBlock;                                  // [64]
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c16 = lane & 15, g4 = lane >> 4;
+
+    int bid = blockIdx.x;
+    const int kvh = bid % p.Hkv;
+    bid /= p.Hkv;
+    const int chunk = bid % p.max_chunks;
+    const int b = bid / p.max_chunks;
+    const int col0 = blockIdx.y * kMaxColsPerBlock;
+
+    const SeqInfo si = seq_info(p, b);
+    const int k_begin = chunk * p.chunk;
+    const int M = p.G * si.R;
+    if (k_begin >= si.L || col0 >= M || si.R <= 0) return;  // block-uniform
+    const int k_end = min(k_begin + p.chunk, si.L);
+    const int last_key = si.L - 1;
+
+    // query rows of this lane's columns
+    int col_limit[NT];   // last visible key of the column's query row (-1: no row)
+    bf16x8 qreg[NT][C::kKSteps];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int n = col0 + nt * kColTile + c16;
+        const bool valid = n < M;
+        const int i = valid ? n / p.G : 0, gh = valid ? n % p.G : 0;
+        col_limit[nt] = valid ? si.L - si.R + i : -1;
+        const char *qrow = static_cast<const char *>(p.q) +
+                           ((int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh) * (D * 2);
+#pragma unroll
+        for (int t = 0; t < C::kKSteps; ++t) {
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (valid) raw = *reinterpret_cast<const u32x4 *>(qrow + (t * 32 + g4 * 8) * 2);
+            qreg[nt][t] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    float m_run[NT], l_run[NT];
+    floatx4 acc_o[NT][C::kDTiles];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        m_run[nt] = -INFINITY;
+        l_run[nt] = 0.f;
+#pragma unroll
+        for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    char *k_lds = smem + wave * C::kWaveBytes;
+    char *v_lds = k_lds + C::kTileBytes;
+    const int64_t row_bytes = (int64_t)p.Hkv * D * 2;
+    const char *kbase = static_cast<const char *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
+    const char *vbase = static_cast<const char *>(p.v) + (si.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
+    const int first_masked_key = si.L - si.R + 1;  // keys from here on are hidden from some row
+
+    u32x4 kr[C::kLoads], vr[C::kLoads];
+    int key0 = k_begin + wave * kTileKeys;
+    if (key0 < k_end) {
+        load_tile<D>(kr, kbase, row_bytes, key0, last_key, lane);
+        load_tile<D>(vr, vbase, row_bytes, key0, last_key, lane);
+    }
+    for (; key0 < k_end; key0 += kWaves * kTileKeys) {
+        store_tile<D>(kr, k_lds, lane);
+        store_tile<D>(vr, v_lds, lane);
+        const int next0 = key0 + kWaves * kTileKeys;
+        if (next0 < k_end) {  // prefetch the wave's next tile while this one is computed
+            load_tile<D>(kr, kbase, row_bytes, next0, last_key, lane);
+            load_tile<D>(vr, vbase, row_bytes, next0, last_key, lane);
+        }
+
+        // S^T[key, col] = sum_d K[key, d] Q[col, d]; two 16-key sub-tiles
+        floatx4 s_acc[NT][2];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) s_acc[nt][0] = s_acc[nt][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int js = 0; js < 2; ++js) {
+#pragma unroll
+            for (int t = 0; t < C::kKSteps; ++t) {
+                const u32x4 raw = *reinterpret_cast<const u32x4 *>(
+                    k_lds + (js * 16 + c16) * C::kRowBytes + (t * 32 + g4 * 8) * 2);
+                const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    s_acc[nt][js] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[nt][t],
+                                                                            s_acc[nt][js], 0, 0, 0);
+            }
+        }
+
+        // online softmax per column; accumulator element (js, i) is key key0 + 16 js + 4 g4 + i
+        const bool tail = key0 + kTileKeys > first_masked_key;  // wave-uniform
+        bf16x8 pfrag[NT];
+        float alpha[NT];
+        bool rescale = false;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float sv[8];
+#pragma unroll
+            for (int js = 0; js < 2; ++js)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float x = s_acc[nt][js][i] * p.scale2;
+                    if (tail) {
+                        const int key = key0 + js * 16 + g4 * 4 + i;
+                        x = key <= col_limit[nt] ? x : -INFINITY;
+                    }
+                    sv[js * 4 + i] = x;
+                }
+            float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                               fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+            const float mnew = fmaxf(m_run[nt], mloc);
+            const float msafe = mnew == -INFINITY ? 0.f : mnew;
+            alpha[nt] = hw_exp2(m_run[nt] - msafe);
+            rescale |= alpha[nt] != 1.f;
+            float psum = 0.f;
+            float pv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = hw_exp2(sv[e] - msafe);
+                psum += pv[e];
+            }
+            l_run[nt] = l_run[nt] * alpha[nt] + psum;
+            m_run[nt] = mnew;
+            bf16x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const bf16x2 two = __builtin_convertvector(floatx2{pv[e], pv[e + 1]}, bf16x2);
+                pf[e] = two[0];
+                pf[e + 1] = two[1];
+            }
+            pfrag[nt] = pf;
+        }
+        if (__any(rescale)) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= alpha[nt];
+        }
+
+        // O^T[d, col] += sum_key V[key, d] P[key, col]; contraction slot e of lane group g4 is
+        // key 16 (e/4) + 4 g4 + e%4, matching the score accumulators; d tile t holds
+        // d = kEpl * r + t for MFMA row r.
+        uint32_t vw[8][C::kEpl / 2];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int key = 16 * (e / 4) + 4 * g4 + (e % 4);
+            const char *src = v_lds + key * C::kRowBytes + c16 * (C::kEpl * 2);
+            if constexpr (C::kEpl == 8) {
+                const u32x4 raw = *reinterpret_cast<const u32x4 *>(src);
+                vw[e][0] = raw[0];
+                vw[e][1] = raw[1];
+                vw[e][2] = raw[2];
+                vw[e][3] = raw[3];
+            } else {
+                const u32x2 raw = *reinterpret_cast<const u32x2 *>(src);
+                vw[e][0] = raw[0];
+                vw[e][1] = raw[1];
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < C::kDTiles; ++t) {
+            uint32_t aw[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t lo = vw[2 * c][t / 2], hi = vw[2 * c + 1][t / 2];
+                aw[c] = (t & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
+                                : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+            }
+            const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{aw[0], aw[1], aw[2], aw[3]});
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc_o[nt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pfrag[nt], acc_o[nt][t],
+                                                                       0, 0, 0);
+        }
+    }
+
+    // ---- merge the four waves --------------------------------------------------------------
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        float l = l_run[nt];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        l_run[nt] = l;
+        if (g4 == 0) {
+            sh_m[wave * kMaxColsPerBlock + nt * kColTile + c16] = m_run[nt];
+            sh_l[wave * kMaxColsPerBlock + nt * kColTile + c16] = l;
+        }
+    }
+    __syncthreads();  // every wave has left its tile loop: tile memory is free for the merge
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int c = nt * kColTile + c16;
+        float mt = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) mt = fmaxf(mt, sh_m[w * kMaxColsPerBlock + c]);
+        const float msafe = mt == -INFINITY ? 0.f : mt;
+        float lt = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w)
+            lt += sh_l[w * kMaxColsPerBlock + c] * hw_exp2(sh_m[w * kMaxColsPerBlock + c] - msafe);
+        const float own = hw_exp2(m_run[nt] - msafe);
+#pragma unroll
+        for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= own;
+        if (wave == 0 && g4 == 0) {
+            sh_mt[c] = mt;
+            sh_lt[c] = lt;
+        }
+    }
+
+    float *merge = reinterpret_cast<float *>(smem + wave * C::kWaveBytes);
+    const bool single = si.n_chunks == 1;
+    const int64_t slot = si.slot0 + chunk;
+    constexpr int kSeg = D / 8;  // floats per reducing thread
+    const int rc = threadIdx.x / 8, rseg = (threadIdx.x % 8) * kSeg;
+#pragma unroll
+    for (int pp = 0; pp < (NT + 1) / 2; ++pp) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int nt = 2 * pp + h;
+            if (nt < NT) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float *dst = merge + (h * kColTile + c16) * C::kMergeStride + C::kEpl * (4 * g4 + r);
+#pragma unroll
+                    for (int t = 0; t < C::kDTiles; t += 4)
+                        *reinterpret_cast<floatx4 *>(dst + t) =
+                            floatx4{acc_o[nt < NT ? nt : 0][t][r], acc_o[nt < NT ? nt : 0][t + 1][r],
+                                    acc_o[nt < NT ? nt : 0][t + 2][r], acc_o[nt < NT ? nt : 0][t + 3][r]};
+                }
+            }
+        }
+        __syncthreads();
+        const int cl = pp * 32 + rc;  // column within the block
+        const int n = col0 + cl;
+        if (cl < NT * kColTile && n < M) {
+            float sum[kSeg];
+#pragma unroll
+            for (int j = 0; j < kSeg; ++j) sum[j] = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float *src = reinterpret_cast<const float *>(smem + w * C::kWaveBytes) +
+                                   rc * C::kMergeStride + rseg;
+#pragma unroll
+                for (int j = 0; j < kSeg; j += 4) {
+                    const floatx4 x = *reinterpret_cast<const floatx4 *>(src + j);
+                    sum[j] += x[0];
+                    sum[j + 1] += x[1];
+                    sum[j + 2] += x[2];
+                    sum[j + 3] += x[3];
+                }
+            }
+            const float mt = sh_mt[cl], lt = sh_lt[cl];
+            if (single) {
+                const int i = n / p.G, gh = n % p.G;
+                const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
+                const float inv = lt > 0.f ? 1.f / lt : 0.f;
+                OutT *dst = static_cast<OutT *>(p.out) + orow * D + rseg;
+                if constexpr (sizeof(OutT) == 2) {
+                    uint32_t packed[kSeg / 2];
+#pragma unroll
+                    for (int j = 0; j < kSeg; j += 2) {
+                        const bf16x2 two =
+                            __builtin_convertvector(floatx2{sum[j] * inv, sum[j + 1] * inv}, bf16x2);
+                        packed[j / 2] = __builtin_bit_cast(uint32_t, two);
+                    }
+#pragma unroll
+                    for (int j = 0; j < kSeg / 2; j += 4)
+                        *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(dst) + j * 4) =
+                            u32x4{packed[j], packed[j + 1], packed[j + 2], packed[j + 3]};
+                } else {
+#pragma unroll
+                    for (int j = 0; j < kSeg; ++j) dst[j] = sum[j] * inv;
+                }
+                if (p.lse && rseg == 0)
+                    p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
+            } else if (slot < p.n_slots) {
+                const int64_t prow = (slot * p.Hkv + kvh) * p.Mpad + n;
+                float *dst = p.ws_o + prow * D + rseg;
+#pragma unroll
+                for (int j = 0; j < kSeg; j += 4)
+                    *reinterpret_cast<floatx4 *>(dst + j) =
+                        floatx4{sum[j], sum[j + 1], sum[j + 2], sum[j + 3]};
+                if (rseg == 0) {
+                    p.ws_ml[prow * 2] = mt;
+                    p.ws_ml[prow * 2 + 1] = lt;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// fp32 kernel: one work-group per (sequence, query head, query row, chunk)
+// ------------------------------------------------------------------------------------------
+constexpr int kF32Threads = 256;
+
+__device__ inline float block_reduce_max(float x, float *scratch) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) scratch[wave] = x;
+    __syncthreads();
+    float r = scratch[0];
+    for (int w = 1; w < kF32Threads / 64; ++w) r = fmaxf(r, scratch[w]);
+    return r;
+}
+
+__device__ inline float block_reduce_sum(float x, float *scratch) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) scratch[wave] = x;
+    __syncthreads();
+    float r = scratch[0];
+    for (int w = 1; w < kF32Threads / 64; ++w) r += scratch[w];
+    return r;
+}
+
+template <int D>
+__global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
+    __shared__ float sh_q[D];
+    __shared__ float sh_p[kF32Threads];
+    __shared__ float sh_red[kF32Threads / 64];
+    __shared__ float sh_part[kF32Threads];
+    constexpr int kParts = kF32Threads / D;
+
+    int bid = blockIdx.x;
+    const int chunk = bid % p.max_chunks;
+    bid /= p.max_chunks;
+    const int h = bid % p.Hq;
+    const int b = bid / p.Hq;
+    const int i = blockIdx.y;
+    const SeqInfo si = seq_info(p, b);
+    const int k_begin = chunk * p.chunk;
+    if (i >= si.R || k_begin >= si.L) return;
+    const int kvh = h / p.G, gh = h % p.G;
+    const int limit = si.L - si.R + i;                       // last visible key
+    const int k_end = min(min(k_begin + p.chunk, si.L), limit + 1);
+    const int64_t qrow = (int64_t)(si.q0 + i) * p.Hq + h;
+    const float *q = static_cast<const float *>(p.q) + qrow * D;
+    const float *kb = static_cast<const float *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
+    const float *vb = static_cast<const float *>(p.v) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
+    const int64_t rstride = (int64_t)p.Hkv * D;
+    for (int d = threadIdx.x; d < D; d += kF32Threads) sh_q[d] = q[d];
+    __syncthreads();
+
+    const int d_own = threadIdx.x % D, part = threadIdx.x / D;
+    float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
+    for (int t0 = k_begin; t0 < k_end; t0 += kF32Threads) {
+        const int key = t0 + threadIdx.x;
+        float s = -INFINITY;
+        if (key < k_end) {
+            const float4 *kr = reinterpret_cast<const float4 *>(kb + key * rstride);
+            float dot = 0.f;
+#pragma unroll 8
+            for (int d4 = 0; d4 < D / 4; ++d4) {
+                const float4 x = kr[d4];
+                dot = fmaf(x.x, sh_q[4 * d4], dot);
+                dot = fmaf(x.y, sh_q[4 * d4 + 1], dot);
+                dot = fmaf(x.z, sh_q[4 * d4 + 2], dot);
+                dot = fmaf(x.w, sh_q[4 * d4 + 3], dot);
+            }
+            s = dot * p.scale2;
+        }
+        const float m_tile = block_reduce_max(s, sh_red);
+        const float m_new = fmaxf(m_run, m_tile);  // finite: the tile holds at least one key
+        const float pr = key < k_end ? exp2f(s - m_new) : 0.f;
+        const float l_tile = block_reduce_sum(pr, sh_red);
+        const float alpha = exp2f(m_run - m_new);
+        l_run = l_run * alpha + l_tile;
+        acc *= alpha;
+        m_run = m_new;
+        __syncthreads();
+        sh_p[threadIdx.x] = pr;
+        __syncthreads();
+        const int nk = min(kF32Threads, k_end - t0);
+        float a = 0.f;
+        for (int j = part; j < nk; j += kParts) a = fmaf(sh_p[j], vb[(int64_t)(t0 + j) * rstride + d_own], a);
+        acc += a;
+    }
+    __syncthreads();
+    sh_part[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < D) {
+        float o = 0.f;
+        for (int pz = 0; pz < kParts; ++pz) o += sh_part[pz * D + threadIdx.x];
+        const int n = i * p.G + gh;
+        if (si.n_chunks == 1) {
+            static_cast<float *>(p.out)[qrow * D + threadIdx.x] = l_run > 0.f ? o / l_run : 0.f;
+            if (p.lse && threadIdx.x == 0)
+                p.lse[qrow] = l_run > 0.f ? (m_run + log2f(l_run)) * 0.6931471805599453f : -INFINITY;
+        } else {
+            const int64_t slot = si.slot0 + chunk;
+            if (slot < p.n_slots) {
+                const int64_t prow = (slot * p.Hkv + kvh) * p.Mpad + n;
+                p.ws_o[prow * D + threadIdx.x] = o;
+                if (threadIdx.x == 0) {
+                    p.ws_ml[prow * 2] = m_run;   // -inf when this chunk is invisible to the row
+                    p.ws_ml[prow * 2 + 1] = l_run;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// split-KV combine: merge the chunk partials of one (sequence, KV head) in chunk order
+// ------------------------------------------------------------------------------------------
+template <int D, typename OutT>
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
+    constexpr int kTpc = D / 4;             // threads per column (float4 each)
+    constexpr int kCols = 256 / kTpc;       // columns per block
+    const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x % p.Hkv;
+    const SeqInfo si = seq_info(p, b);
+    if (si.n_chunks <= 1 || si.R <= 0) return;
+    const int n = blockIdx.y * kCols + threadIdx.x / kTpc;
+    const int d4 = (threadIdx.x % kTpc) * 4;
+    const int M = p.G * si.R;
+    if (n >= M) return;
+    const int i = n / p.G, gh = n % p.G;
+    const int limit = si.L - si.R + i;
+    // chunks that start beyond the row's last visible key hold nothing for it (and the fp32
+    // kernel never wrote them)
+    int nc = min(si.n_chunks, limit / p.chunk + 1);
+    if (si.slot0 + nc > p.n_slots) nc = (int)max((int64_t)0, p.n_slots - si.slot0);
+    float mt = -INFINITY;
+    for (int c = 0; c < nc; ++c) {
+        const int64_t prow = ((si.slot0 + c) * p.Hkv + kvh) * p.Mpad + n;
+        mt = fmaxf(mt, p.ws_ml[prow * 2]);
+    }
+    const float msafe = mt == -INFINITY ? 0.f : mt;
+    float lt = 0.f;
+    floatx4 o = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < nc; ++c) {
+        const int64_t prow = ((si.slot0 + c) * p.Hkv + kvh) * p.Mpad + n;
+        const float w = exp2f(p.ws_ml[prow * 2] - msafe);
+        lt += p.ws_ml[prow * 2 + 1] * w;
+        const floatx4 x = *reinterpret_cast<const floatx4 *>(p.ws_o + prow * D + d4);
+        o += x * w;
+    }
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+    const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
+    OutT *dst = static_cast<OutT *>(p.out) + orow * D + d4;
+    if constexpr (sizeof(OutT) == 2) {
+        const bf16x2 a = __builtin_convertvector(floatx2{o[0] * inv, o[1] * inv}, bf16x2);
+        const bf16x2 c2 = __builtin_convertvector(floatx2{o[2] * inv, o[3] * inv}, bf16x2);
+        *reinterpret_cast<u32x2 *>(dst) =
+            u32x2{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, c2)};
+    } else {
+        *reinterpret_cast<floatx4 *>(dst) = o * inv;
+    }
+    if (p.lse && d4 == 0)
+        p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+struct Plan {
+    int32_t chunk, max_chunks, Mpad;
+    int64_t n_slots;
+    size_t ws_o_bytes, ws_bytes;
+};
+
+bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, int32_t Hq,
+               int32_t Hkv, int32_t D, respec_dtype_t dt, Plan &pl) {
+    if (B <= 0 || total_kv <= 0 || max_q <= 0 || max_kv_len <= 0 || Hq <= 0 || Hkv <= 0) return false;
+    if (Hq % Hkv != 0 || (D != 64 && D != 128)) return false;
+    if (dt != RESPEC_F32 && dt != RESPEC_BF16) return false;
+    const int32_t G = Hq / Hkv;
+    if ((int64_t)G * max_q > 256) return false;
+    const int unit = kWaves * kTileKeys;  // 128 keys
+    long chunk = env_long("RESPEC_ATTN_CHUNK", 0);
+    if (chunk <= 0) {
+        // largest chunk that still gives the 256 compute units several work-groups each
+        chunk = unit;
+        for (long c = 8192; c >= unit; c /= 2) {
+            const double items = ((double)total_kv / (double)c + 0.5 * B) * Hkv;
+            if (items >= 2048.0) {
+                chunk = c;
+                break;
+            }
+        }
+    }
+    chunk = (chunk + unit - 1) / unit * unit;
+    pl.chunk = (int32_t)chunk;
+    pl.max_chunks = (max_kv_len + pl.chunk - 1) / pl.chunk;
+    pl.Mpad = (G * max_q + kColTile - 1) / kColTile * kColTile;
+    pl.n_slots = total_kv / pl.chunk + B + 1;
+    pl.ws_o_bytes = round_up((size_t)pl.n_slots * Hkv * pl.Mpad * D * sizeof(float), 256);
+    pl.ws_bytes = pl.ws_o_bytes + round_up((size_t)pl.n_slots * Hkv * pl.Mpad * 2 * sizeof(float), 256);
+    return true;
+}
+
+template <int D, int NT, typename OutT>
+hipError_t launch_bf16(const AttnParams &p, dim3 grid, hipStream_t stream) {
+    using C = Bf16Cfg<D>;
+    const size_t smem = kWaves * C::kWaveBytes + (2 * kWaves + 2) * kMaxColsPerBlock * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(&attn_bf16_kernel<D, NT, OutT>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NT, OutT>), grid, dim3(kThreads), smem, stream, p);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_bf16_nt(int nt, const AttnParams &p, dim3 grid, hipStream_t stream) {
+    switch (nt) {
+        case 1: return launch_bf16<D, 1, uint16_t>(p, grid, stream);
+        case 2: return launch_bf16<D, 2, uint16_t>(p, grid, stream);
+        case 3: return launch_bf16<D, 3, uint16_t>(p, grid, stream);
+        default: return launch_bf16<D, 4, uint16_t>(p, grid, stream);
+    }
+}
+
+}  // namespace
+}  // namespace respec
+
+extern "C" {
+
+size_t respec_verify_attention_workspace_bytes(int32_t B, int32_t total_q, int64_t total_kv,
+                                               int32_t max_q_per_seq, int32_t max_kv_len,
+                                               int32_t Hq, int32_t Hkv, int32_t D,
+                                               respec_dtype_t dt) {
+    respec::Plan pl;
+    (void)total_q;
+    if (!respec::make_plan(B, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, dt, pl)) return 0;
+    return pl.ws_bytes;
+}
+
+respec_status_t respec_verify_attention(const void *q, const void *k_cache, const void *v_cache,
+                                        const int32_t *q_indptr, const int64_t *kv_indptr,
+                                        void *out, float *lse, int32_t B, int32_t total_q,
+                                        int64_t total_kv, int32_t max_q_per_seq,
+                                        int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                        float sm_scale, respec_dtype_t dt, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream) {
+    using namespace respec;
+    if (B <= 0 || total_q < B || total_kv < total_q || max_q_per_seq < 1 || max_kv_len < 1)
+        return fail(RESPEC_ERR_INVALID_ARG,
+                    "verify_attention: need B > 0, total_q >= B, total_kv >= total_q, max_q_per_seq >= 1, "
+                    "max_kv_len >= 1 (B=%d total_q=%d total_kv=%lld)", B, total_q, (long long)total_kv);
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0)
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
+    if (dt != RESPEC_F32 && dt != RESPEC_BF16)
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: unknown dtype %d", (int)dt);
+    if (!std::isfinite(sm_scale))
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: sm_scale must be finite");
+    if (D != 64 && D != 128)
+        return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: head size %d not in {64,128}", D);
+    if ((int64_t)(Hq / Hkv) * max_q_per_seq > 256)
+        return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: G*max_q_per_seq = %lld exceeds 256",
+                    (long long)(Hq / Hkv) * max_q_per_seq);
+    if ((int64_t)B * max_q_per_seq < total_q)
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: max_q_per_seq too small for total_q");
+    if (!q || !k_cache || !v_cache || !q_indptr || !kv_indptr || !out)
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: null pointer argument");
+    if (!aligned_to(q, 16) || !aligned_to(k_cache, 16) || !aligned_to(v_cache, 16) || !aligned_to(out, 16))
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: q, k_cache, v_cache and out must be 16-byte aligned");
+    Plan pl;
+    if (!make_plan(B, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, dt, pl))
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: could not plan the launch");
+    if (!workspace || workspace_bytes < pl.ws_bytes || !aligned_to(workspace, 256))
+        return fail(RESPEC_ERR_WORKSPACE, "verify_attention: workspace of %zu bytes (256-byte aligned) needed, got %zu",
+                    pl.ws_bytes, workspace ? workspace_bytes : (size_t)0);
+    const int64_t blocks = (int64_t)B * pl.max_chunks * (dt == RESPEC_BF16 ? Hkv : Hq);
+    if (blocks > 0x7fffffffLL)
+        return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: grid of %lld work-groups is too large", (long long)blocks);
+
+    AttnParams p{};
+    p.q = q;
+    p.k = k_cache;
+    p.v = v_cache;
+    p.q_indptr = q_indptr;
+    p.kv_indptr = kv_indptr;
+    p.out = out;
+    p.lse = lse;
+    p.ws_o = static_cast<float *>(workspace);
+    p.ws_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.ws_o_bytes);
+    p.B = B;
+    p.total_q = total_q;
+    p.total_kv = total_kv;
+    p.max_q = max_q_per_seq;
+    p.max_kv_len = max_kv_len;
+    p.Hq = Hq;
+    p.Hkv = Hkv;
+    p.G = Hq / Hkv;
+    p.chunk = pl.chunk;
+    p.max_chunks = pl.max_chunks;
+    p.Mpad = pl.Mpad;
+    p.n_slots = pl.n_slots;
+    p.scale2 = (float)((double)sm_scale * 1.4426950408889634074);
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t err;
+    const int M = p.G * max_q_per_seq;
+    if (dt == RESPEC_BF16) {
+        const int col_blocks = (M + kMaxColsPerBlock - 1) / kMaxColsPerBlock;
+        const int cols = col_blocks == 1 ? M : kMaxColsPerBlock;
+        const int nt = (cols + kColTile - 1) / kColTile;
+        const dim3 grid((unsigned)blocks, (unsigned)col_blocks);
+        err = D == 128 ? launch_bf16_nt<128>(nt, p, grid, stream) : launch_bf16_nt<64>(nt, p, grid, stream);
+    } else {
+        const dim3 grid((unsigned)blocks, (unsigned)max_q_per_seq);
+        if (D == 128)
+            hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(kF32Threads), 0, stream, p);
+        else
+            hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(kF32Threads), 0, stream, p);
+        err = hipGetLastError();
+    }
+    if (err != hipSuccess)
+        return fail(RESPEC_ERR_HIP, "verify_attention: main launch failed: %s", hipGetErrorString(err));
+    if (pl.max_chunks > 1) {
+        const int cols_per_block = 256 / (D / 4);
+        const dim3 grid((unsigned)(B * Hkv), (unsigned)((M + cols_per_block - 1) / cols_per_block));
+        if (dt == RESPEC_BF16) {
+            if (D == 128)
+                hipLaunchKernelGGL((attn_combine_kernel<128, uint16_t>), grid, dim3(256), 0, stream, p);
+            else
+                hipLaunchKernelGGL((attn_combine_kernel<64, uint16_t>), grid, dim3(256), 0, stream, p);
+        } else {
+            if (D == 128)
+                hipLaunchKernelGGL((attn_combine_kernel<128, float>), grid, dim3(256), 0, stream, p);
+            else
+                hipLaunchKernelGGL((attn_combine_kernel<64, float>), grid, dim3(256), 0, stream, p);
+        }
+        err = hipGetLastError();
+        if (err != hipSuccess)
+            return fail(RESPEC_ERR_HIP, "verify_attention: combine launch failed: %s", hipGetErrorString(err));
+    }
+    clear_error();
+    return RESPEC_OK;
+}
+
+}  // extern "C"

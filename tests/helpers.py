@@ -1,0 +1,134 @@
+"""Test-side glue: run one verify batch through the HIP library and through the oracle."""
+from __future__ import annotations
+
+import math
+import os
+from contextlib import contextmanager
+
+import numpy as np
+import torch
+
+from paper_2510_26475_amd import binding, synth
+
+
+@contextmanager
+def attn_chunk(chunk):
+    """Force the split-KV chunk size (keys per work-group) for the calls inside."""
+    old = os.environ.get("RESPEC_ATTN_CHUNK")
+    if chunk is None:
+        os.environ.pop("RESPEC_ATTN_CHUNK", None)
+    else:
+        os.environ["RESPEC_ATTN_CHUNK"] = str(chunk)
+    try:
+        yield
+    finally:
+        if old is None:
+            os.environ.pop("RESPEC_ATTN_CHUNK", None)
+        else:
+            os.environ["RESPEC_ATTN_CHUNK"] = old
+
+
+def gpu_attention(batch: synth.VerifyBatch, sm_scale=None, want_lse=True, stream=None):
+    wl = batch.wl
+    sm_scale = 1.0 / math.sqrt(wl.D) if sm_scale is None else sm_scale
+    B = len(batch.kv_lens)
+    max_q = max(batch.k_per_seq) + 1
+    dt = binding.RESPEC_F32 if wl.dtype == "f32" else binding.RESPEC_BF16
+    ws_bytes = binding.respec_verify_attention_workspace_bytes(
+        B, batch.total_q, batch.total_kv, max_q, batch.max_kv_len, wl.Hq, wl.Hkv, wl.D, dt)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=batch.q.device)
+    out = torch.full_like(batch.q, float("nan"))
+    lse = torch.full((batch.total_q, wl.Hq), float("nan"), dtype=torch.float32,
+                     device=batch.q.device) if want_lse else None
+    binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                                    batch.kv_indptr, out, lse, max_q, batch.max_kv_len, sm_scale,
+                                    ws, stream=stream)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def oracle_attention(oracle, batch: synth.VerifyBatch, sm_scale=None, n_threads=0):
+    wl = batch.wl
+    sm_scale = 1.0 / math.sqrt(wl.D) if sm_scale is None else sm_scale
+    dt = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+    return oracle.verify_attention(
+        synth.to_host_array(batch.q), synth.to_host_array(batch.k_cache),
+        synth.to_host_array(batch.v_cache), batch.q_indptr.cpu().numpy(),
+        batch.kv_indptr.cpu().numpy(), wl.Hq, wl.Hkv, wl.D, float(np.float32(sm_scale)), dt,
+        want_lse=True, n_threads=n_threads)
+
+
+def sub_batch(batch: synth.VerifyBatch, seqs) -> synth.VerifyBatch:
+    """The sequences ``seqs`` of ``batch`` as a batch of their own (same bytes, same device)."""
+    qi = batch.q_indptr.cpu().tolist()
+    ki = batch.kv_indptr.cpu().tolist()
+    q_rows, kv_rows, d_rows = [], [], []
+    for b in seqs:
+        q_rows += list(range(qi[b], qi[b + 1]))
+        kv_rows += list(range(ki[b], ki[b + 1]))
+        d_rows += list(range(qi[b] - b, qi[b + 1] - (b + 1)))
+    dev = batch.q.device
+    qr = torch.tensor(q_rows, device=dev, dtype=torch.long)
+    kr = torch.tensor(kv_rows, device=dev, dtype=torch.long)
+    dr = torch.tensor(d_rows, device=dev, dtype=torch.long)
+    ks = [batch.k_per_seq[b] for b in seqs]
+    ls = [batch.kv_lens[b] for b in seqs]
+    has_kv = batch.k_cache.shape[0] > 0
+    has_logits = batch.target_logits.shape[1] > 0
+    return synth.VerifyBatch(
+        wl=batch.wl, q=batch.q[qr].contiguous(),
+        k_cache=batch.k_cache[kr].contiguous() if has_kv else batch.k_cache,
+        v_cache=batch.v_cache[kr].contiguous() if has_kv else batch.v_cache,
+        q_indptr=torch.tensor(np.concatenate([[0], np.cumsum([k + 1 for k in ks])]),
+                              dtype=torch.int32, device=dev),
+        kv_indptr=torch.tensor(np.concatenate([[0], np.cumsum(ls)]), dtype=torch.int64, device=dev),
+        target_logits=batch.target_logits[qr].contiguous() if has_logits else batch.target_logits[qr],
+        draft_logits=batch.draft_logits[dr].contiguous() if has_logits else batch.draft_logits[dr],
+        draft_tokens=batch.draft_tokens[dr].contiguous(), u_accept=batch.u_accept[dr].contiguous(),
+        u_final=batch.u_final[torch.tensor(list(seqs), device=dev, dtype=torch.long)].contiguous(),
+        k_per_seq=ks, kv_lens=ls)
+
+
+def gpu_sample(batch: synth.VerifyBatch, temperature=None, max_k=None, stream=None):
+    wl = batch.wl
+    T = wl.temperature if temperature is None else temperature
+    B = len(batch.k_per_seq)
+    max_k = batch.max_k if max_k is None else max_k
+    dev = batch.target_logits.device
+    toks = torch.full((B, max_k + 1), -7, dtype=torch.int32, device=dev)
+    n = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    flags = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    binding.respec_rejection_sample(batch.target_logits, batch.draft_logits, batch.draft_tokens,
+                                    batch.q_indptr, batch.u_accept, batch.u_final, toks, n, flags,
+                                    max_k, T, stream=stream)
+    torch.cuda.synchronize()
+    return toks.cpu().numpy(), n.cpu().numpy(), flags.cpu().numpy()
+
+
+def oracle_sample(oracle, batch: synth.VerifyBatch, temperature=None, max_k=None, n_threads=0):
+    wl = batch.wl
+    T = wl.temperature if temperature is None else temperature
+    max_k = batch.max_k if max_k is None else max_k
+    dt = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+    n_draft = batch.total_q - len(batch.k_per_seq)
+    return oracle.rejection_sample(
+        synth.to_host_array(batch.target_logits),
+        synth.to_host_array(batch.draft_logits) if n_draft else None,
+        batch.draft_tokens.cpu().numpy() if n_draft else None, batch.q_indptr.cpu().numpy(),
+        batch.u_accept.cpu().numpy() if n_draft else None, batch.u_final.cpu().numpy(), max_k, T,
+        dt, n_threads=n_threads)
+
+
+def compare_sampler(gpu, ref):
+    """Exact equality of tokens and counts on unflagged sequences; returns the boundary tally."""
+    g_t, g_n, g_f = gpu
+    r_t, r_n, r_f = ref
+    flagged = r_f != 0
+    same = (g_n == r_n) & (g_t == r_t).all(axis=1)
+    bad = np.flatnonzero(~same & ~flagged)
+    assert bad.size == 0, (
+        f"{bad.size} unflagged sequences differ, first b={bad[0]}: gpu n={g_n[bad[0]]} "
+        f"tokens={g_t[bad[0]].tolist()} vs oracle n={r_n[bad[0]]} tokens={r_t[bad[0]].tolist()}")
+    return {"flagged": int(flagged.sum()), "flagged_mismatch": int((~same & flagged).sum()),
+            "gpu_flagged": int((g_f != 0).sum()), "B": int(len(r_n))}

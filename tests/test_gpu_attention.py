@@ -1,0 +1,222 @@
+"""GPU parity of respec_verify_attention against the CPU oracle (element by element).
+
+Tolerances are the contract's: max abs error 2e-2 for bf16, 1e-5 for fp32.  bf16 cases also
+check a tighter rms bound (the bf16 rounding of the probabilities and of the output keeps
+the rms error near 1e-3 for N(0,1) data), so that a systematic slip cannot hide under 2e-2.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import attn_chunk, gpu_attention, oracle_attention, sub_batch
+from paper_2510_26475_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL, F32_TOL = 2e-2, 1e-5
+
+
+def _wl(name, Hq, Hkv, D, dtype, V=8):
+    return synth.Workload(name, B=0, k=0, Hq=Hq, Hkv=Hkv, D=D, V=V, dtype=dtype,
+                          len_dist="uniform", len_lo=1, len_hi=1)
+
+
+def _check(out, lse, ref, ref_lse, dtype, rms_bound=2.5e-3):
+    got = out.double().cpu().numpy()
+    assert np.isfinite(got).all(), "output holds NaN/inf (a row was not written?)"
+    err = np.abs(got - ref)
+    tol = F32_TOL if dtype == "f32" else BF16_TOL
+    assert err.max() <= tol, f"max abs err {err.max():.3e} > {tol}"
+    if dtype == "bf16":
+        rms = math.sqrt(float((err ** 2).mean()))
+        assert rms <= rms_bound, f"rms err {rms:.3e}"
+    if lse is not None:
+        lerr = np.abs(lse.double().cpu().numpy() - ref_lse)
+        assert lerr.max() <= (1e-4 if dtype == "f32" else 2e-2), f"lse err {lerr.max():.3e}"
+    return float(err.max())
+
+
+def _run(oracle, wl, lens, ks, seed=0, chunk=None, sm_scale=None):
+    batch = synth.make_batch(wl, device="cuda", kv_lens=lens, k_per_seq=ks, seed=seed,
+                             with_logits=False)
+    with attn_chunk(chunk):
+        out, lse = gpu_attention(batch, sm_scale=sm_scale)
+    ref, ref_lse = oracle_attention(oracle, batch, sm_scale=sm_scale)
+    return _check(out, lse, ref, ref_lse, wl.dtype), batch, out
+
+
+def test_tiny_f32_workload(oracle):
+    wl = synth.WORKLOADS["tiny_f32"]
+    batch = synth.make_batch(wl, device="cuda", with_logits=False)
+    out, lse = gpu_attention(batch)
+    ref, ref_lse = oracle_attention(oracle, batch)
+    _check(out, lse, ref, ref_lse, "f32")
+
+
+@pytest.mark.parametrize("chunk", [None, 128, 256])
+def test_f32_split_kv_and_combine(oracle, chunk):
+    wl = _wl("f32_split", 4, 2, 64, "f32")
+    _run(oracle, wl, [300, 129, 5, 1000, 128, 513], [4, 0, 4, 2, 3, 1], seed=3, chunk=chunk)
+    wl = _wl("f32_split_d128", 6, 2, 128, "f32")
+    _run(oracle, wl, [257, 31, 640], [2, 4, 0], seed=4, chunk=chunk)
+
+
+@pytest.mark.parametrize("heads", [(28, 4), (16, 2), (40, 8), (4, 1), (8, 8), (7, 1)])
+@pytest.mark.parametrize("chunk", [None, 128, 512])
+def test_bf16_d128_shapes(oracle, heads, chunk):
+    Hq, Hkv = heads
+    wl = _wl("bf16_shapes", Hq, Hkv, 128, "bf16")
+    lens = [33, 130, 257, 1000, 6, 5, 128, 129, 2049]
+    ks = [3, 4, 0, 4, 4, 4, 1, 2, 3]
+    _run(oracle, wl, lens, ks, seed=Hq + (chunk or 0), chunk=chunk)
+
+
+@pytest.mark.parametrize("chunk", [None, 128])
+def test_bf16_d64(oracle, chunk):
+    wl = _wl("bf16_d64", 8, 2, 64, "bf16")
+    _run(oracle, wl, [33, 130, 700, 9, 257], [3, 4, 0, 8, 2], seed=11, chunk=chunk)
+
+
+@pytest.mark.parametrize("k", [0, 1, 2, 4, 8])
+def test_bf16_draft_lengths_14b_heads(oracle, k):
+    # G = 5: 5, 10, 15, 25, 45 MFMA columns -> 1..3 column tiles
+    wl = _wl("bf16_k", 40, 8, 128, "bf16")
+    _run(oracle, wl, [1500, 64 + k, 333], [k, k, k], seed=20 + k, chunk=256)
+
+
+def test_more_than_64_columns_uses_two_column_blocks(oracle):
+    wl = _wl("bf16_wide", 16, 2, 128, "bf16")            # G = 8, k = 8 -> 72 columns
+    _run(oracle, wl, [400, 90, 1025], [8, 8, 5], seed=31, chunk=256)
+
+
+def test_ragged_draft_lengths_in_one_batch(oracle):
+    wl = _wl("bf16_ragged", 40, 8, 128, "bf16")
+    ks = [0, 8, 3, 1, 7, 0, 5, 2]
+    lens = [700, 9, 1300, 2, 4096, 1, 257, 513]
+    _run(oracle, wl, lens, ks, seed=41)
+    _run(oracle, wl, lens, ks, seed=42, chunk=128)
+
+
+def test_causal_boundary_with_spiked_keys(oracle):
+    """A key with a huge score sits just past each row's horizon: it must capture exactly the
+    rows that may see it (2e-2 would not notice an off-by-one on N(0,1) data)."""
+    wl = _wl("bf16_spike", 8, 2, 128, "bf16")
+    lens, ks = [300, 131, 40, 1029], [4, 3, 4, 2]
+    batch = synth.make_batch(wl, device="cuda", kv_lens=lens, k_per_seq=ks, seed=5,
+                             with_logits=False)
+    qi, ki = batch.q_indptr.tolist(), batch.kv_indptr.tolist()
+    G = wl.Hq // wl.Hkv
+    for b, (L, k) in enumerate(zip(lens, ks)):
+        R = k + 1
+        for i in range(R - 1):
+            key = L - R + i + 1                      # first key row i must NOT see
+            for hk in range(wl.Hkv):
+                # aligned with row i (must stay blind to it) and with row i+1 (must be captured)
+                qv = batch.q[qi[b] + i, hk * G].float() + batch.q[qi[b] + i + 1, hk * G].float()
+                batch.k_cache[ki[b] + key, hk] = (4.0 * qv).to(torch.bfloat16)
+                batch.v_cache[ki[b] + key, hk] = 1.5 + 0.125 * i
+    for chunk in (None, 128):
+        with attn_chunk(chunk):
+            out, lse = gpu_attention(batch)
+        ref, ref_lse = oracle_attention(oracle, batch)
+        _check(out, lse, ref, ref_lse, "bf16", rms_bound=4e-3)
+    # the oracle output really is dominated by the spikes (the test has teeth)
+    assert (np.abs(ref - 1.5) < 1e-3).mean() > 0.02
+
+
+def test_cache_holding_only_the_new_tokens(oracle):
+    wl = _wl("bf16_min", 28, 4, 128, "bf16")
+    err, batch, out = _run(oracle, wl, [4, 1, 5], [3, 0, 4], seed=6)
+    # row 0 of a sequence with L = R sees one key: output equals that value row exactly
+    v0 = batch.v_cache[0].float().cpu().numpy()          # [Hkv, D]
+    got = out[0].float().cpu().numpy().reshape(wl.Hkv, -1, wl.D)
+    assert np.array_equal(got, np.broadcast_to(v0[:, None, :], got.shape))
+
+
+def test_runs_are_bitwise_reproducible(oracle):
+    wl = _wl("bf16_det", 28, 4, 128, "bf16")
+    batch = synth.make_batch(wl, device="cuda", kv_lens=[3000, 700, 129], k_per_seq=[3, 3, 3],
+                             seed=7, with_logits=False)
+    with attn_chunk(256):
+        a, la = gpu_attention(batch)
+        b, lb = gpu_attention(batch)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
+
+
+def test_rows_beyond_the_batch_are_never_read(oracle):
+    wl = _wl("bf16_poison", 16, 2, 128, "bf16")
+    lens, ks = [200, 77], [4, 2]
+    batch = synth.make_batch(wl, device="cuda", kv_lens=lens, k_per_seq=ks, seed=8,
+                             with_logits=False)
+    pad = 64
+    big_k = torch.full((batch.total_kv + pad, wl.Hkv, wl.D), float("nan"), dtype=torch.bfloat16,
+                       device="cuda")
+    big_v = big_k.clone()
+    big_k[:batch.total_kv] = batch.k_cache
+    big_v[:batch.total_kv] = batch.v_cache
+    batch.k_cache, batch.v_cache = big_k[:batch.total_kv], big_v[:batch.total_kv]
+    out, lse = gpu_attention(batch)
+    ref, ref_lse = oracle_attention(oracle, batch)
+    _check(out, lse, ref, ref_lse, "bf16")
+
+
+def test_custom_scale_and_no_lse(oracle):
+    wl = _wl("bf16_scale", 8, 2, 128, "bf16")
+    batch = synth.make_batch(wl, device="cuda", kv_lens=[500, 64], k_per_seq=[2, 4], seed=9,
+                             with_logits=False)
+    out, lse = gpu_attention(batch, sm_scale=0.05, want_lse=False)
+    assert lse is None
+    ref, _ = oracle_attention(oracle, batch, sm_scale=0.05)
+    _check(out, None, ref, None, "bf16")
+
+
+def test_qwen3b_workload_full_batch(oracle):
+    wl = synth.WORKLOADS["qwen3b_b64_k4"]
+    batch = synth.make_batch(wl, device="cuda", with_logits=False)
+    out, lse = gpu_attention(batch)
+    seqs = sorted(set([int(np.argmax(batch.kv_lens)), int(np.argmin(batch.kv_lens)), 0, 17, 63]))
+    sb = sub_batch(batch, seqs)
+    ref, ref_lse = oracle_attention(oracle, sb)
+    qi = batch.q_indptr.tolist()
+    rows = torch.tensor([r for b in seqs for r in range(qi[b], qi[b + 1])], device="cuda")
+    _check(out[rows], lse[rows], ref, ref_lse, "bf16")
+
+
+def test_qwen7b_headline_workload_sampled_sequences(oracle):
+    """Full-size B=256, k=3, 28/4 heads in the launch configuration the benchmark times;
+    the oracle checks a sample of sequences (longest, shortest and a spread)."""
+    wl = synth.WORKLOADS["qwen7b_b256_k3"]
+    batch = synth.make_batch(wl, device="cuda", with_logits=False)
+    out, lse = gpu_attention(batch)
+    assert torch.isfinite(out.float()).all()
+    seqs = sorted(set([int(np.argmax(batch.kv_lens)), int(np.argmin(batch.kv_lens)),
+                       0, 50, 101, 199, 255]))
+    sb = sub_batch(batch, seqs)
+    ref, ref_lse = oracle_attention(oracle, sb)
+    qi = batch.q_indptr.tolist()
+    rows = torch.tensor([r for b in seqs for r in range(qi[b], qi[b + 1])], device="cuda")
+    _check(out[rows], lse[rows], ref, ref_lse, "bf16")
+
+
+def test_bad_arguments_are_rejected_before_any_launch():
+    wl = _wl("bf16_err", 8, 2, 128, "bf16")
+    batch = synth.make_batch(wl, device="cuda", kv_lens=[100], k_per_seq=[3], seed=1,
+                             with_logits=False)
+    out = torch.empty_like(batch.q)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.RespecError) as e:       # workspace too small
+        binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                                        batch.kv_indptr, out, None, 4, 100, 0.1, ws[:16])
+    assert e.value.status == 3
+    with pytest.raises(binding.RespecError) as e:       # max_q_per_seq too small for total_q
+        binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                                        batch.kv_indptr, out, None, 2, 100, 0.1, ws)
+    assert e.value.status == 1
+    q96 = torch.zeros((4, 8, 96), dtype=torch.bfloat16, device="cuda")
+    kv96 = torch.zeros((100, 2, 96), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.RespecError) as e:       # head size outside {64,128}
+        binding.respec_verify_attention(q96, kv96, kv96, batch.q_indptr, batch.kv_indptr,
+                                        torch.empty_like(q96), None, 4, 100, 0.1, ws)
+    assert e.value.status == 2
