@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the speculative-decoding verify step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic batch: verify attention
+(main kernel + split-KV combine, one layer) followed by rejection sampling.  All inputs
+are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sigma S]
+                    [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2510_26475_amd import binding, synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+# HBM bytes per launch of the attention main kernel from rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE runs, scaled by the same counters on a copy kernel of known size); the
+# summaries are under profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def attention_algorithmic_bytes(batch: synth.VerifyBatch) -> int:
+    """K and V of every cached token once, Q in and O out once (split-KV partials excluded)."""
+    wl = batch.wl
+    esz = 4 if wl.dtype == "f32" else 2
+    kv = batch.total_kv * wl.Hkv * wl.D * 2 * esz
+    qo = 2 * batch.total_q * wl.Hq * wl.D * esz
+    return kv + qo
+
+
+def sampler_algorithmic_bytes(batch: synth.VerifyBatch, num_accepted) -> int:
+    """Logit rows the method needs, once each: target rows 0..n_b, drafter rows 0..min(n_b,k_b-1)."""
+    wl = batch.wl
+    esz = 4 if wl.dtype == "f32" else 2
+    rows = 0
+    for n, k in zip(num_accepted, batch.k_per_seq):
+        rows += (n + 1) + min(n + 1, k)
+    return rows * wl.V * esz
+
+
+def run_cpu_baseline(batch: synth.VerifyBatch, n_seqs: int):
+    """The oracle, as it stands, timed on the host cores over the first n_seqs sequences."""
+    import numpy as np
+
+    import oracle  # test infrastructure: allowed here for the cpu_baseline leg only
+    oracle.build()
+    n_seqs = min(n_seqs, len(batch.k_per_seq))
+    sb = synth.sub_batch(batch, list(range(n_seqs)))
+    wl = sb.wl
+    dt = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+    host = dict(
+        q=synth.to_host_array(sb.q), k=synth.to_host_array(sb.k_cache),
+        v=synth.to_host_array(sb.v_cache), qi=sb.q_indptr.cpu().numpy(),
+        ki=sb.kv_indptr.cpu().numpy(), t=synth.to_host_array(sb.target_logits),
+        d=synth.to_host_array(sb.draft_logits), tok=sb.draft_tokens.cpu().numpy(),
+        ua=sb.u_accept.cpu().numpy(), uf=sb.u_final.cpu().numpy())
+    threads = oracle.max_threads()
+    t0 = time.perf_counter()
+    oracle.verify_attention(host["q"], host["k"], host["v"], host["qi"], host["ki"], wl.Hq, wl.Hkv,
+                            wl.D, float(np.float32(1.0 / math.sqrt(wl.D))), dt, n_threads=0)
+    t1 = time.perf_counter()
+    n_draft = sb.total_q - n_seqs
+    toks, n, _ = oracle.rejection_sample(
+        host["t"], host["d"] if n_draft else None, host["tok"] if n_draft else None, host["qi"],
+        host["ua"] if n_draft else None, host["uf"], sb.max_k, wl.temperature, dt, n_threads=0)
+    t2 = time.perf_counter()
+    emitted = int((n + 1).sum())
+    return {
+        "value": emitted / (t2 - t0), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": f"first {n_seqs} of {len(batch.k_per_seq)} sequences of the same workload, "
+                  f"one attention layer + sampler, OpenMP over sequences",
+        "attention_s": t1 - t0, "sampler_s": t2 - t1, "emitted_tokens": emitted,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen7b_b256_k3", choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--sigma", type=float, default=None, help="drafter noise (default: workload's)")
+    ap.add_argument("--batch", type=int, default=None, help="override B (sweeps)")
+    ap.add_argument("--k", type=int, default=None, help="override k (sweeps)")
+    ap.add_argument("--cpu-seqs", type=int, default=32)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the verify step shards over sequences with "
+              "no exchange, so --gpus N > 1 is not measured here", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+
+    import dataclasses
+    wl = synth.WORKLOADS[args.workload]
+    changes = {}
+    if args.sigma is not None:
+        changes["sigma"] = args.sigma
+    if args.batch is not None:
+        changes["B"] = args.batch
+    if args.k is not None:
+        changes["k"] = args.k
+    if changes:
+        wl = dataclasses.replace(wl, **changes)
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    batch = synth.make_batch(wl, device=dev)
+    B = len(batch.k_per_seq)
+    max_q = batch.max_k + 1
+    dt = binding.RESPEC_F32 if wl.dtype == "f32" else binding.RESPEC_BF16
+    ws_bytes = binding.respec_verify_attention_workspace_bytes(
+        B, batch.total_q, batch.total_kv, max_q, batch.max_kv_len, wl.Hq, wl.Hkv, wl.D, dt)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    out = torch.empty_like(batch.q)
+    lse = torch.empty((batch.total_q, wl.Hq), dtype=torch.float32, device=dev)
+    toks = torch.empty((B, batch.max_k + 1), dtype=torch.int32, device=dev)
+    n_acc = torch.empty((B,), dtype=torch.int32, device=dev)
+    flags = torch.empty((B,), dtype=torch.int32, device=dev)
+    sm_scale = 1.0 / math.sqrt(wl.D)
+
+    def attention():
+        binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                                        batch.kv_indptr, out, lse, max_q, batch.max_kv_len,
+                                        sm_scale, ws)
+
+    def sampler():
+        binding.respec_rejection_sample(batch.target_logits, batch.draft_logits,
+                                        batch.draft_tokens, batch.q_indptr, batch.u_accept,
+                                        batch.u_final, toks, n_acc, flags, batch.max_k,
+                                        wl.temperature)
+
+    for _ in range(args.warmup):
+        attention()
+        sampler()
+    torch.cuda.synchronize()
+
+    # timed region: exactly --steps steps, events on the launch stream around every kernel group
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for e4 in ev:
+        e4[1].record()      # create the handle the library will re-record
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e4 in ev:
+        e4[0].record()
+        binding.respec_profile_mark_after_main(e4[1])
+        attention()
+        e4[2].record()
+        sampler()
+        e4[3].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    ms_main = sum(e4[0].elapsed_time(e4[1]) for e4 in ev) / args.steps
+    ms_comb = sum(e4[1].elapsed_time(e4[2]) for e4 in ev) / args.steps
+    ms_samp = sum(e4[2].elapsed_time(e4[3]) for e4 in ev) / args.steps
+
+    n_host = n_acc.cpu().tolist()
+    accepted = int(sum(n_host))
+    emitted = accepted + B
+    attn_bytes = attention_algorithmic_bytes(batch)
+    samp_bytes = sampler_algorithmic_bytes(batch, n_host)
+    esz = 4 if wl.dtype == "f32" else 2
+    samp_all_rows = (batch.total_q + batch.total_q - B) * wl.V * esz
+    achieved = attn_bytes / (ms_main * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name) if not changes else None
+
+    line = {
+        "metric": "accepted tokens/s of the SD verify step (tokens emitted per step = accepted "
+                  "drafts + 1 per sequence; one attention layer + rejection sampling)",
+        "value": emitted / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": wl.name, "B": B, "k": wl.k, "ragged_k": wl.ragged_k, "Hq": wl.Hq,
+            "Hkv": wl.Hkv, "D": wl.D, "V": wl.V, "sigma": wl.sigma, "temperature": wl.temperature,
+            "kv_len": f"{wl.len_dist}[{wl.len_lo},{wl.len_hi}]", "total_kv": batch.total_kv,
+            "seed": wl.seed,
+        },
+        "verify_step_us": ms_step * 1e3,
+        "kernel_us": {"attention_main": ms_main * 1e3, "attention_combine": ms_comb * 1e3,
+                      "rejection_sample": ms_samp * 1e3},
+        "accepted_drafts": accepted, "emitted_tokens": emitted,
+        "emitted_per_seq": emitted / B,
+        "accepted_drafts_per_s": accepted / (ms_step * 1e-3),
+        "boundary_flagged": int((flags != 0).sum().item()),
+        "algorithmic_bytes": {"attention": attn_bytes, "sampler_needed_rows": samp_bytes,
+                              "sampler_all_rows": samp_all_rows},
+        "step_hbm_frac": (attn_bytes + samp_bytes) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "sampler_gbs": samp_bytes / (ms_samp * 1e-3) / 1e9,
+        "roofline": {
+            "kernel": "attn_bf16_kernel" if wl.dtype == "bf16" else "attn_f32_kernel",
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+        },
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = run_cpu_baseline(batch, args.cpu_seqs)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

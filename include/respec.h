@@ -102,6 +102,14 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
                                         float sm_scale, respec_dtype_t dt, void *workspace,
                                         size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Profiling hook (benchmarks only).  If `hip_event` (a hipEvent_t passed as void*) is
+ * non-NULL, the calling thread's next respec_verify_attention records it on the call's
+ * stream after the main kernel and before the split-KV combine kernel, then forgets it.
+ * This is the only state the library keeps, and it is thread-local.
+ */
+void respec_profile_mark_after_main(void *hip_event);
+
 /* Workspace bytes of respec_rejection_sample (0 = none needed, NULL may be passed). */
 size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t total_q, int32_t V,
                                                respec_dtype_t logits_dt);

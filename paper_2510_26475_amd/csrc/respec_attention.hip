@@ -601,6 +601,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+thread_local hipEvent_t g_mark_after_main = nullptr;
+
 struct Plan {
     int32_t chunk, max_chunks, Mpad;
     int64_t n_slots;
@@ -667,6 +669,10 @@ hipError_t launch_bf16_nt(int nt, const AttnParams &p, dim3 grid, hipStream_t st
 }  // namespace respec
 
 extern "C" {
+
+void respec_profile_mark_after_main(void *hip_event) {
+    respec::g_mark_after_main = static_cast<hipEvent_t>(hip_event);
+}
 
 size_t respec_verify_attention_workspace_bytes(int32_t B, int32_t total_q, int64_t total_kv,
                                                int32_t max_q_per_seq, int32_t max_kv_len,
@@ -760,6 +766,10 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     }
     if (err != hipSuccess)
         return fail(RESPEC_ERR_HIP, "verify_attention: main launch failed: %s", hipGetErrorString(err));
+    if (g_mark_after_main) {
+        (void)hipEventRecord(g_mark_after_main, stream);
+        g_mark_after_main = nullptr;
+    }
     if (pl.max_chunks > 1) {
         const int cols_per_block = 256 / (D / 4);
         const dim3 grid((unsigned)(B * Hkv), (unsigned)((M + cols_per_block - 1) / cols_per_block));

@@ -59,35 +59,7 @@ def oracle_attention(oracle, batch: synth.VerifyBatch, sm_scale=None, n_threads=
         want_lse=True, n_threads=n_threads)
 
 
-def sub_batch(batch: synth.VerifyBatch, seqs) -> synth.VerifyBatch:
-    """The sequences ``seqs`` of ``batch`` as a batch of their own (same bytes, same device)."""
-    qi = batch.q_indptr.cpu().tolist()
-    ki = batch.kv_indptr.cpu().tolist()
-    q_rows, kv_rows, d_rows = [], [], []
-    for b in seqs:
-        q_rows += list(range(qi[b], qi[b + 1]))
-        kv_rows += list(range(ki[b], ki[b + 1]))
-        d_rows += list(range(qi[b] - b, qi[b + 1] - (b + 1)))
-    dev = batch.q.device
-    qr = torch.tensor(q_rows, device=dev, dtype=torch.long)
-    kr = torch.tensor(kv_rows, device=dev, dtype=torch.long)
-    dr = torch.tensor(d_rows, device=dev, dtype=torch.long)
-    ks = [batch.k_per_seq[b] for b in seqs]
-    ls = [batch.kv_lens[b] for b in seqs]
-    has_kv = batch.k_cache.shape[0] > 0
-    has_logits = batch.target_logits.shape[1] > 0
-    return synth.VerifyBatch(
-        wl=batch.wl, q=batch.q[qr].contiguous(),
-        k_cache=batch.k_cache[kr].contiguous() if has_kv else batch.k_cache,
-        v_cache=batch.v_cache[kr].contiguous() if has_kv else batch.v_cache,
-        q_indptr=torch.tensor(np.concatenate([[0], np.cumsum([k + 1 for k in ks])]),
-                              dtype=torch.int32, device=dev),
-        kv_indptr=torch.tensor(np.concatenate([[0], np.cumsum(ls)]), dtype=torch.int64, device=dev),
-        target_logits=batch.target_logits[qr].contiguous() if has_logits else batch.target_logits[qr],
-        draft_logits=batch.draft_logits[dr].contiguous() if has_logits else batch.draft_logits[dr],
-        draft_tokens=batch.draft_tokens[dr].contiguous(), u_accept=batch.u_accept[dr].contiguous(),
-        u_final=batch.u_final[torch.tensor(list(seqs), device=dev, dtype=torch.long)].contiguous(),
-        k_per_seq=ks, kv_lens=ls)
+sub_batch = synth.sub_batch
 
 
 def gpu_sample(batch: synth.VerifyBatch, temperature=None, max_k=None, stream=None):
