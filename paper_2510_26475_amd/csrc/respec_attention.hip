@@ -38,6 +38,8 @@ constexpr int kTileKeys = 32;         // keys per wave tile
 constexpr int kColTile = 16;          // query rows per MFMA column tile
 constexpr int kMaxColsPerBlock = 64;  // 4 column tiles
 
+struct WorkItem;
+
 struct AttnParams {
     const void *q;
     const void *k;
@@ -48,6 +50,8 @@ struct AttnParams {
     float *lse;
     float *ws_o;   // [n_slots, Hkv, Mpad, D]
     float *ws_ml;  // [n_slots, Hkv, Mpad, 2]  (max in log2 units, sum)
+    struct WorkItem *items;  // [n_slots] compact list of (sequence, chunk) written by the prep kernel
+    int32_t *n_items;        // [1]
     int32_t B, total_q;
     int64_t total_kv;
     int32_t max_q, max_kv_len;
@@ -90,6 +94,61 @@ __device__ inline SeqInfo seq_info(const AttnParams &p, int b) {
 }
 
 __device__ inline float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// One unit of work of the main kernels: a chunk of keys of one sequence (32 bytes, so that a
+// work-group fetches it in one round trip instead of chasing the two indptr arrays).
+struct __align__(16) WorkItem {
+    int64_t kv0;
+    int32_t L, q0, R, chunk, b, n_chunks;
+};
+
+// Lists every (sequence, chunk) pair that holds keys, in sequence order, so that the main
+// grid has no empty work-groups in its body: with a dense [sequence][max_chunks] grid the
+// work-groups that do have keys land on the eight XCDs unevenly (round-robin by index).
+__global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
+    __shared__ int sh_scan[1024];
+    __shared__ int sh_base;
+    const int tid = threadIdx.x;
+    if (tid == 0) sh_base = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < p.B; b0 += 1024) {
+        const int b = b0 + tid;
+        SeqInfo si{};
+        int nc = 0;
+        if (b < p.B) {
+            si = seq_info(p, b);
+            nc = si.R > 0 ? si.n_chunks : 0;
+        }
+        sh_scan[tid] = nc;
+        __syncthreads();
+        for (int o = 1; o < 1024; o <<= 1) {
+            const int add = tid >= o ? sh_scan[tid - o] : 0;
+            __syncthreads();
+            sh_scan[tid] += add;
+            __syncthreads();
+        }
+        const int base = sh_base;
+        const int64_t first = (int64_t)base + sh_scan[tid] - nc;
+        for (int c = 0; c < nc; ++c) {
+            const int64_t idx = first + c;
+            if (idx < p.n_slots) {
+                WorkItem it;
+                it.kv0 = si.kv0;
+                it.L = si.L;
+                it.q0 = si.q0;
+                it.R = si.R;
+                it.chunk = c;
+                it.b = b;
+                it.n_chunks = si.n_chunks;
+                p.items[idx] = it;
+            }
+        }
+        __syncthreads();
+        if (tid == 1023) sh_base = base + sh_scan[1023];
+        __syncthreads();
+    }
+    if (tid == 0) *p.n_items = (int32_t)min((int64_t)sh_base, p.n_slots);
+}
 
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
@@ -144,19 +203,31 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c16 = lane & 15, g4 = lane >> 4;
 
-    int bid = blockIdx.x;
-    const int kvh = bid % p.Hkv;
-    bid /= p.Hkv;
-    const int chunk = bid % p.max_chunks;
-    const int b = bid / p.max_chunks;
+    const int kvh = blockIdx.x % p.Hkv;
+    const int item_id = blockIdx.x / p.Hkv;
+    if (item_id >= *p.n_items) return;  // block-uniform
+    const WorkItem it = p.items[item_id];
+    const int chunk = it.chunk;
     const int col0 = blockIdx.y * kMaxColsPerBlock;
-
-    const SeqInfo si = seq_info(p, b);
     const int k_begin = chunk * p.chunk;
-    const int M = p.G * si.R;
-    if (k_begin >= si.L || col0 >= M || si.R <= 0) return;  // block-uniform
-    const int k_end = min(k_begin + p.chunk, si.L);
-    const int last_key = si.L - 1;
+    const int M = p.G * it.R;
+    if (col0 >= M) return;  // block-uniform
+    const int k_end = min(k_begin + p.chunk, it.L);
+    const int last_key = it.L - 1;
+
+    // first K/V tile of this wave: issued before anything else that waits on memory
+    char *k_lds = smem + wave * C::kWaveBytes;
+    char *v_lds = k_lds + C::kTileBytes;
+    const int64_t row_bytes = (int64_t)p.Hkv * D * 2;
+    const char *kbase = static_cast<const char *>(p.k) + (it.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
+    const char *vbase = static_cast<const char *>(p.v) + (it.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
+    const int first_masked_key = it.L - it.R + 1;  // keys from here on are hidden from some row
+    u32x4 kr[C::kLoads], vr[C::kLoads];
+    int key0 = k_begin + wave * kTileKeys;
+    if (key0 < k_end) {
+        load_tile<D>(kr, kbase, row_bytes, key0, last_key, lane);
+        load_tile<D>(vr, vbase, row_bytes, key0, last_key, lane);
+    }
 
     // query rows of this lane's columns
     int col_limit[NT];   // last visible key of the column's query row (-1: no row)
@@ -166,9 +237,9 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
         const int n = col0 + nt * kColTile + c16;
         const bool valid = n < M;
         const int i = valid ? n / p.G : 0, gh = valid ? n % p.G : 0;
-        col_limit[nt] = valid ? si.L - si.R + i : -1;
+        col_limit[nt] = valid ? it.L - it.R + i : -1;
         const char *qrow = static_cast<const char *>(p.q) +
-                           ((int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh) * (D * 2);
+                           ((int64_t)(it.q0 + i) * p.Hq + kvh * p.G + gh) * (D * 2);
 #pragma unroll
         for (int t = 0; t < C::kKSteps; ++t) {
             u32x4 raw = {0u, 0u, 0u, 0u};
@@ -187,19 +258,6 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
         for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 
-    char *k_lds = smem + wave * C::kWaveBytes;
-    char *v_lds = k_lds + C::kTileBytes;
-    const int64_t row_bytes = (int64_t)p.Hkv * D * 2;
-    const char *kbase = static_cast<const char *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
-    const char *vbase = static_cast<const char *>(p.v) + (si.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
-    const int first_masked_key = si.L - si.R + 1;  // keys from here on are hidden from some row
-
-    u32x4 kr[C::kLoads], vr[C::kLoads];
-    int key0 = k_begin + wave * kTileKeys;
-    if (key0 < k_end) {
-        load_tile<D>(kr, kbase, row_bytes, key0, last_key, lane);
-        load_tile<D>(vr, vbase, row_bytes, key0, last_key, lane);
-    }
     for (; key0 < k_end; key0 += kWaves * kTileKeys) {
         store_tile<D>(kr, k_lds, lane);
         store_tile<D>(vr, v_lds, lane);
@@ -350,8 +408,8 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
     }
 
     float *merge = reinterpret_cast<float *>(smem + wave * C::kWaveBytes);
-    const bool single = si.n_chunks == 1;
-    const int64_t slot = si.slot0 + chunk;
+    const bool single = it.n_chunks == 1;
+    const int64_t slot = it.kv0 / p.chunk + it.b + chunk;
     constexpr int kSeg = D / 8;  // floats per reducing thread
     const int rc = threadIdx.x / 8, rseg = (threadIdx.x % 8) * kSeg;
 #pragma unroll
@@ -394,7 +452,7 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
             const float mt = sh_mt[cl], lt = sh_lt[cl];
             if (single) {
                 const int i = n / p.G, gh = n % p.G;
-                const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
+                const int64_t orow = (int64_t)(it.q0 + i) * p.Hq + kvh * p.G + gh;
                 const float inv = lt > 0.f ? 1.f / lt : 0.f;
                 OutT *dst = static_cast<OutT *>(p.out) + orow * D + rseg;
                 if constexpr (sizeof(OutT) == 2) {
@@ -469,22 +527,21 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
     __shared__ float sh_part[kF32Threads];
     constexpr int kParts = kF32Threads / D;
 
-    int bid = blockIdx.x;
-    const int chunk = bid % p.max_chunks;
-    bid /= p.max_chunks;
-    const int h = bid % p.Hq;
-    const int b = bid / p.Hq;
+    const int h = blockIdx.x % p.Hq;
+    const int item_id = blockIdx.x / p.Hq;
+    if (item_id >= *p.n_items) return;
+    const WorkItem it = p.items[item_id];
+    const int chunk = it.chunk;
     const int i = blockIdx.y;
-    const SeqInfo si = seq_info(p, b);
     const int k_begin = chunk * p.chunk;
-    if (i >= si.R || k_begin >= si.L) return;
+    if (i >= it.R) return;
     const int kvh = h / p.G, gh = h % p.G;
-    const int limit = si.L - si.R + i;                       // last visible key
-    const int k_end = min(min(k_begin + p.chunk, si.L), limit + 1);
-    const int64_t qrow = (int64_t)(si.q0 + i) * p.Hq + h;
+    const int limit = it.L - it.R + i;                       // last visible key
+    const int k_end = min(min(k_begin + p.chunk, it.L), limit + 1);
+    const int64_t qrow = (int64_t)(it.q0 + i) * p.Hq + h;
     const float *q = static_cast<const float *>(p.q) + qrow * D;
-    const float *kb = static_cast<const float *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
-    const float *vb = static_cast<const float *>(p.v) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
+    const float *kb = static_cast<const float *>(p.k) + (it.kv0 * p.Hkv + kvh) * (int64_t)D;
+    const float *vb = static_cast<const float *>(p.v) + (it.kv0 * p.Hkv + kvh) * (int64_t)D;
     const int64_t rstride = (int64_t)p.Hkv * D;
     for (int d = threadIdx.x; d < D; d += kF32Threads) sh_q[d] = q[d];
     __syncthreads();
@@ -530,12 +587,12 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
         float o = 0.f;
         for (int pz = 0; pz < kParts; ++pz) o += sh_part[pz * D + threadIdx.x];
         const int n = i * p.G + gh;
-        if (si.n_chunks == 1) {
+        if (it.n_chunks == 1) {
             static_cast<float *>(p.out)[qrow * D + threadIdx.x] = l_run > 0.f ? o / l_run : 0.f;
             if (p.lse && threadIdx.x == 0)
                 p.lse[qrow] = l_run > 0.f ? (m_run + log2f(l_run)) * 0.6931471805599453f : -INFINITY;
         } else {
-            const int64_t slot = si.slot0 + chunk;
+            const int64_t slot = it.kv0 / p.chunk + it.b + chunk;
             if (slot < p.n_slots) {
                 const int64_t prow = (slot * p.Hkv + kvh) * p.Mpad + n;
                 p.ws_o[prow * D + threadIdx.x] = o;
@@ -606,7 +663,7 @@ thread_local hipEvent_t g_mark_after_main = nullptr;
 struct Plan {
     int32_t chunk, max_chunks, Mpad;
     int64_t n_slots;
-    size_t ws_o_bytes, ws_bytes;
+    size_t ws_o_bytes, ws_ml_bytes, ws_items_bytes, ws_bytes;
 };
 
 bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, int32_t Hq,
@@ -635,7 +692,9 @@ bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, i
     pl.Mpad = (G * max_q + kColTile - 1) / kColTile * kColTile;
     pl.n_slots = total_kv / pl.chunk + B + 1;
     pl.ws_o_bytes = round_up((size_t)pl.n_slots * Hkv * pl.Mpad * D * sizeof(float), 256);
-    pl.ws_bytes = pl.ws_o_bytes + round_up((size_t)pl.n_slots * Hkv * pl.Mpad * 2 * sizeof(float), 256);
+    pl.ws_ml_bytes = round_up((size_t)pl.n_slots * Hkv * pl.Mpad * 2 * sizeof(float), 256);
+    pl.ws_items_bytes = round_up((size_t)pl.n_slots * sizeof(WorkItem), 256);
+    pl.ws_bytes = pl.ws_o_bytes + pl.ws_ml_bytes + pl.ws_items_bytes + 256;
     return true;
 }
 
@@ -719,7 +778,7 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     if (!workspace || workspace_bytes < pl.ws_bytes || !aligned_to(workspace, 256))
         return fail(RESPEC_ERR_WORKSPACE, "verify_attention: workspace of %zu bytes (256-byte aligned) needed, got %zu",
                     pl.ws_bytes, workspace ? workspace_bytes : (size_t)0);
-    const int64_t blocks = (int64_t)B * pl.max_chunks * (dt == RESPEC_BF16 ? Hkv : Hq);
+    const int64_t blocks = pl.n_slots * (dt == RESPEC_BF16 ? Hkv : Hq);
     if (blocks > 0x7fffffffLL)
         return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: grid of %lld work-groups is too large", (long long)blocks);
 
@@ -733,6 +792,9 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     p.lse = lse;
     p.ws_o = static_cast<float *>(workspace);
     p.ws_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.ws_o_bytes);
+    p.items = reinterpret_cast<WorkItem *>(static_cast<char *>(workspace) + pl.ws_o_bytes + pl.ws_ml_bytes);
+    p.n_items = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + pl.ws_o_bytes + pl.ws_ml_bytes +
+                                            pl.ws_items_bytes);
     p.B = B;
     p.total_q = total_q;
     p.total_kv = total_kv;
@@ -749,6 +811,10 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t err;
+    hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
+    err = hipGetLastError();
+    if (err != hipSuccess)
+        return fail(RESPEC_ERR_HIP, "verify_attention: prep launch failed: %s", hipGetErrorString(err));
     const int M = p.G * max_q_per_seq;
     if (dt == RESPEC_BF16) {
         const int col_blocks = (M + kMaxColsPerBlock - 1) / kMaxColsPerBlock;
