@@ -27,7 +27,8 @@ class RespecError(RuntimeError):
 
 
 def library_path() -> str:
-    return _build.LIB_PATH
+    """Path of librespec.so; RESPEC_LIBRARY_PATH points at another build of it (experiments)."""
+    return os.environ.get("RESPEC_LIBRARY_PATH") or _build.LIB_PATH
 
 
 def load():

@@ -3,21 +3,26 @@
 // rows per sequence, grouped-query heads, ragged token-major KV cache.
 //
 // bf16 path.  The G*(k_b+1) query rows that share one KV head are the columns of 16-wide
-// MFMA tiles; a work-group of four waves owns one (sequence, KV head, chunk of keys).
-// Each wave streams its own 32-key tiles: 16-byte coalesced global loads -> registers ->
-// wave-private LDS tile -> MFMA operands.  Scores are computed transposed
-// (S^T = K Q^T, v_mfma_f32_16x16x32_bf16) so that a lane's four accumulator rows are keys
-// and its column is one query row: the probabilities then feed the second product
+// MFMA tiles.  Work is cut into 128-key tiles (four waves x 32 keys); the tiles of all
+// (KV head, sequence) pairs form one flat list that is split evenly over a fixed number of
+// co-resident work-groups (two per compute unit), so every work-group streams the same
+// number of bytes whatever the mix of sequence lengths.  A work-group walks its range as a
+// list of segments (one sequence each); while it finishes a segment the first tile of the
+// next one is already in flight.  Each wave streams its own 32-key tiles: 16-byte coalesced
+// global loads -> registers -> wave-private LDS tile -> MFMA operands.  Scores are computed
+// transposed (S^T = K Q^T, v_mfma_f32_16x16x32_bf16) so that a lane's four accumulator rows
+// are keys and its column is one query row: the probabilities then feed the second product
 // (O^T = V^T P^T) straight from registers, and the softmax statistics of a row live in one
 // lane column.  The contraction indices of both products are permuted freely (any order is
 // valid as long as both operands agree), which is what lets K be read from LDS in 16-byte
 // pieces and V in 16-byte pieces along d with a register-level 2-byte regroup.
-// Four waves merge through LDS; a chunk that is the sequence's only one writes the output
-// directly, otherwise it writes an fp32 partial (max, sum, unnormalised O) and a second
-// kernel merges the partials in a fixed order (deterministic, no float atomics).
+// The four waves merge through LDS.  A segment that covers a whole sequence writes the
+// output; a sequence cut by a work-group boundary leaves fp32 partials (max, sum,
+// unnormalised O), at most two per work-group, which a second kernel merges in a fixed
+// order (deterministic, no float atomics).
 //
-// fp32 path.  A plain fp32 kernel (no MFMA; the fp32 workload is the small parity case)
-// producing the same partial format, merged by the same combine kernel.
+// fp32 path.  A plain fp32 kernel (no MFMA, no split; the fp32 workload is the small parity
+// case), one work-group per (sequence, query head, query row).
 #include "respec_common.hpp"
 
 #include <cmath>
@@ -35,10 +40,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kWaves = 4;             // waves per work-group (bf16 path)
 constexpr int kThreads = kWaves * 64;
 constexpr int kTileKeys = 32;         // keys per wave tile
+constexpr int kGroupKeys = kWaves * kTileKeys;  // keys per work-group tile (the unit of the split)
 constexpr int kColTile = 16;          // query rows per MFMA column tile
 constexpr int kMaxColsPerBlock = 64;  // 4 column tiles
+constexpr int kMaxWgs = 1024;         // upper bound of the split width (sizes the workspace)
 
-struct WorkItem;
+// Where a work-group's range of the flat tile list starts, and how many tiles it holds.
+struct __align__(16) WgStart {
+    int32_t h, b, t, n;
+};
 
 struct AttnParams {
     const void *q;
@@ -48,27 +58,24 @@ struct AttnParams {
     const int64_t *kv_indptr;
     void *out;
     float *lse;
-    float *ws_o;   // [n_slots, Hkv, Mpad, D]
-    float *ws_ml;  // [n_slots, Hkv, Mpad, 2]  (max in log2 units, sum)
-    struct WorkItem *items;  // [n_slots] compact list of (sequence, chunk) written by the prep kernel
-    int32_t *n_items;        // [1]
+    float *ws_o;           // [2*W, Mpad, D]   unnormalised partial outputs
+    float *ws_ml;          // [2*W, Mpad, 2]   (max in log2 units, sum)
+    int32_t *tile_prefix;  // [B+1] prefix sum of ceil(L_b / kGroupKeys)
+    WgStart *wg_start;     // [W]
     int32_t B, total_q;
     int64_t total_kv;
     int32_t max_q, max_kv_len;
     int32_t Hq, Hkv, G;
-    int32_t chunk;       // keys per work-group chunk (multiple of kWaves*kTileKeys)
-    int32_t max_chunks;  // ceil(max_kv_len / chunk)
-    int32_t Mpad;        // G*max_q rounded up to kColTile
-    int64_t n_slots;
-    float scale2;  // sm_scale * log2(e)
+    int32_t W;             // work-groups the tile list is split over
+    int32_t Mpad;          // G*max_q rounded up to kColTile
+    float scale2;          // sm_scale * log2(e)
 };
 
 struct SeqInfo {
     int32_t q0, R;
     int64_t kv0;
     int32_t L;
-    int32_t n_chunks;
-    int64_t slot0;
+    int32_t tiles;  // ceil(L / kGroupKeys), 0 for a sequence without rows
 };
 
 // Per-sequence bounds, clamped by the host-side totals so that no device data can push an
@@ -88,38 +95,35 @@ __device__ inline SeqInfo seq_info(const AttnParams &p, int b) {
     if (L < 0) L = 0;
     s.kv0 = kv0;
     s.L = (int32_t)L;
-    s.n_chunks = (s.L + p.chunk - 1) / p.chunk;
-    s.slot0 = kv0 / p.chunk + b;  // unique, monotone slot range per sequence
+    s.tiles = R > 0 ? (s.L + kGroupKeys - 1) / kGroupKeys : 0;
     return s;
 }
 
 __device__ inline float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// One unit of work of the main kernels: a chunk of keys of one sequence (32 bytes, so that a
-// work-group fetches it in one round trip instead of chasing the two indptr arrays).
-struct __align__(16) WorkItem {
-    int64_t kv0;
-    int32_t L, q0, R, chunk, b, n_chunks;
-};
+// Work-group w owns flat tiles [w*total/W, (w+1)*total/W); the owner of flat tile x:
+__device__ inline int owner_of_tile(int64_t x, int64_t total, int W) {
+    return (int)(((x + 1) * W - 1) / total);
+}
 
-// Lists every (sequence, chunk) pair that holds keys, in sequence order, so that the main
-// grid has no empty work-groups in its body: with a dense [sequence][max_chunks] grid the
-// work-groups that do have keys land on the eight XCDs unevenly (round-robin by index).
+__device__ inline bool owns_tiles(int w, int64_t total, int W) {
+    return (int64_t)(w + 1) * total / W > (int64_t)w * total / W;
+}
+
+// Builds the tile prefix over sequences and every work-group's starting point.
 __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     __shared__ int sh_scan[1024];
     __shared__ int sh_base;
     const int tid = threadIdx.x;
-    if (tid == 0) sh_base = 0;
+    if (tid == 0) {
+        sh_base = 0;
+        p.tile_prefix[0] = 0;
+    }
     __syncthreads();
     for (int b0 = 0; b0 < p.B; b0 += 1024) {
         const int b = b0 + tid;
-        SeqInfo si{};
-        int nc = 0;
-        if (b < p.B) {
-            si = seq_info(p, b);
-            nc = si.R > 0 ? si.n_chunks : 0;
-        }
-        sh_scan[tid] = nc;
+        const int nt = b < p.B ? seq_info(p, b).tiles : 0;
+        sh_scan[tid] = nt;
         __syncthreads();
         for (int o = 1; o < 1024; o <<= 1) {
             const int add = tid >= o ? sh_scan[tid - o] : 0;
@@ -128,26 +132,30 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
             __syncthreads();
         }
         const int base = sh_base;
-        const int64_t first = (int64_t)base + sh_scan[tid] - nc;
-        for (int c = 0; c < nc; ++c) {
-            const int64_t idx = first + c;
-            if (idx < p.n_slots) {
-                WorkItem it;
-                it.kv0 = si.kv0;
-                it.L = si.L;
-                it.q0 = si.q0;
-                it.R = si.R;
-                it.chunk = c;
-                it.b = b;
-                it.n_chunks = si.n_chunks;
-                p.items[idx] = it;
-            }
-        }
+        if (b < p.B) p.tile_prefix[b + 1] = base + sh_scan[tid];
         __syncthreads();
         if (tid == 1023) sh_base = base + sh_scan[1023];
         __syncthreads();
     }
-    if (tid == 0) *p.n_items = (int32_t)min((int64_t)sh_base, p.n_slots);
+    const int64_t T = sh_base;               // tiles of one KV head
+    const int64_t total = T * p.Hkv;
+    for (int w = tid; w < p.W; w += 1024) {
+        WgStart st{0, 0, 0, 0};
+        if (total > 0) {
+            const int64_t a0 = (int64_t)w * total / p.W, a1 = (int64_t)(w + 1) * total / p.W;
+            st.n = (int32_t)(a1 - a0);
+            st.h = (int32_t)(a0 / T);
+            const int32_t rem = (int32_t)(a0 % T);
+            int lo = 0, hi = p.B - 1;          // last b with tile_prefix[b] <= rem
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (p.tile_prefix[mid] <= rem) lo = mid; else hi = mid - 1;
+            }
+            st.b = lo;
+            st.t = rem - p.tile_prefix[lo];
+        }
+        p.wg_start[w] = st;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -168,16 +176,21 @@ struct Bf16Cfg {
     static constexpr int kMergeStride = D + 4;                // fp32 merge row (floats)
 };
 
+// One 32-key tile of one KV head: kLoads 16-byte loads per lane, rows row_bytes apart.
+// `base` and `key0` are wave-uniform, so a load is (scalar tile base) + (32-bit per-lane
+// offset).  Rows past `last_key` re-read the last valid row (they are masked later): the
+// clamp is on the row index relative to the tile, two VALU operations per load.
 template <int D>
-__device__ inline void load_tile(u32x4 (&r)[Bf16Cfg<D>::kLoads], const char *base, int64_t row_bytes,
+__device__ inline void load_tile(u32x4 (&r)[Bf16Cfg<D>::kLoads], const char *base, int32_t row_bytes,
                                  int key0, int last_key, int lane) {
     using C = Bf16Cfg<D>;
-    const int rl = lane / C::kLanesPerRow, cl = lane % C::kLanesPerRow;
+    const uint32_t rl = lane / C::kLanesPerRow, cl16 = (lane % C::kLanesPerRow) * 16;
+    const char *tile = base + (int64_t)key0 * row_bytes;
+    const uint32_t rows_valid = (uint32_t)(last_key - key0);  // >= 0: the tile starts inside the sequence
 #pragma unroll
     for (int j = 0; j < C::kLoads; ++j) {
-        int key = key0 + j * C::kRowsPerLoad + rl;
-        key = min(key, last_key);  // rows past the end re-read the last valid row (masked later)
-        r[j] = *reinterpret_cast<const u32x4 *>(base + (int64_t)key * row_bytes + cl * 16);
+        const uint32_t row = min(rl + (uint32_t)(j * C::kRowsPerLoad), rows_valid);
+        r[j] = *reinterpret_cast<const u32x4 *>(tile + (row * (uint32_t)row_bytes + cl16));
     }
 }
 
@@ -200,298 +213,352 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
     float *sh_mt = sh_l + kWaves * kMaxColsPerBlock;                          // [64]
     float *sh_lt = sh_mt + kMaxColsPerBlock;                                  // [64]
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform by construction
     const int c16 = lane & 15, g4 = lane >> 4;
-
-    const int kvh = blockIdx.x % p.Hkv;
-    const int item_id = blockIdx.x / p.Hkv;
-    if (item_id >= *p.n_items) return;  // block-uniform
-    const WorkItem it = p.items[item_id];
-    const int chunk = it.chunk;
+    const int wg = blockIdx.x;
     const int col0 = blockIdx.y * kMaxColsPerBlock;
-    const int k_begin = chunk * p.chunk;
-    const int M = p.G * it.R;
-    if (col0 >= M) return;  // block-uniform
-    const int k_end = min(k_begin + p.chunk, it.L);
-    const int last_key = it.L - 1;
 
-    // first K/V tile of this wave: issued before anything else that waits on memory
+    const WgStart st = p.wg_start[wg];
+    int kvh = st.h, b = st.b, t_first = st.t, n_left = st.n;
+    if (n_left <= 0 || kvh >= p.Hkv) return;  // block-uniform
+    SeqInfo si = seq_info(p, b);
+
     char *k_lds = smem + wave * C::kWaveBytes;
     char *v_lds = k_lds + C::kTileBytes;
-    const int64_t row_bytes = (int64_t)p.Hkv * D * 2;
-    const char *kbase = static_cast<const char *>(p.k) + (it.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
-    const char *vbase = static_cast<const char *>(p.v) + (it.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
-    const int first_masked_key = it.L - it.R + 1;  // keys from here on are hidden from some row
+    const int32_t row_bytes = p.Hkv * D * 2;
     u32x4 kr[C::kLoads], vr[C::kLoads];
-    int key0 = k_begin + wave * kTileKeys;
-    if (key0 < k_end) {
-        load_tile<D>(kr, kbase, row_bytes, key0, last_key, lane);
-        load_tile<D>(vr, vbase, row_bytes, key0, last_key, lane);
-    }
+    bool prefetched = false;  // kr/vr hold (or await) this wave's first tile of the segment at hand
 
-    // query rows of this lane's columns
-    int col_limit[NT];   // last visible key of the column's query row (-1: no row)
-    bf16x8 qreg[NT][C::kKSteps];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int n = col0 + nt * kColTile + c16;
-        const bool valid = n < M;
-        const int i = valid ? n / p.G : 0, gh = valid ? n % p.G : 0;
-        col_limit[nt] = valid ? it.L - it.R + i : -1;
-        const char *qrow = static_cast<const char *>(p.q) +
-                           ((int64_t)(it.q0 + i) * p.Hq + kvh * p.G + gh) * (D * 2);
-#pragma unroll
-        for (int t = 0; t < C::kKSteps; ++t) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (valid) raw = *reinterpret_cast<const u32x4 *>(qrow + (t * 32 + g4 * 8) * 2);
-            qreg[nt][t] = __builtin_bit_cast(bf16x8, raw);
+    for (;;) {  // one segment = a run of tiles of one (sequence, KV head)
+        const int seg_tiles = max(0, min(n_left, si.tiles - t_first));
+        const int k_begin = t_first * kGroupKeys;
+        const int k_end = min(si.L, (t_first + seg_tiles) * kGroupKeys);
+        const int last_key = si.L - 1;
+        const bool whole = t_first == 0 && seg_tiles == si.tiles;
+        const char *kbase = static_cast<const char *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
+        const char *vbase = static_cast<const char *>(p.v) + (si.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
+        const int key_first = k_begin + wave * kTileKeys;
+        if (!prefetched && key_first < k_end) {
+            load_tile<D>(kr, kbase, row_bytes, key_first, last_key, lane);
+            load_tile<D>(vr, vbase, row_bytes, key_first, last_key, lane);
         }
-    }
+        prefetched = false;
 
-    float m_run[NT], l_run[NT];
-    floatx4 acc_o[NT][C::kDTiles];
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        m_run[nt] = -INFINITY;
-        l_run[nt] = 0.f;
-#pragma unroll
-        for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    for (; key0 < k_end; key0 += kWaves * kTileKeys) {
-        store_tile<D>(kr, k_lds, lane);
-        store_tile<D>(vr, v_lds, lane);
-        const int next0 = key0 + kWaves * kTileKeys;
-        if (next0 < k_end) {  // prefetch the wave's next tile while this one is computed
-            load_tile<D>(kr, kbase, row_bytes, next0, last_key, lane);
-            load_tile<D>(vr, vbase, row_bytes, next0, last_key, lane);
+        // the segment after this one (same KV head, next sequence with keys; then the next head)
+        const int n_after = n_left - seg_tiles;
+        int nb = b, nh = kvh;
+        SeqInfo ni = si;
+        bool have_next = false;
+        if (n_after > 0) {
+            for (;;) {
+                if (++nb >= p.B) {
+                    nb = 0;
+                    ++nh;
+                }
+                if (nh >= p.Hkv) break;
+                ni = seq_info(p, nb);
+                if (ni.tiles > 0) {
+                    have_next = true;
+                    break;
+                }
+            }
         }
+        const int next_k_end = have_next ? min(ni.L, min(n_after, ni.tiles) * kGroupKeys) : 0;
+        const char *next_kbase =
+            static_cast<const char *>(p.k) + (ni.kv0 * p.Hkv + nh) * (int64_t)(D * 2);
+        const char *next_vbase =
+            static_cast<const char *>(p.v) + (ni.kv0 * p.Hkv + nh) * (int64_t)(D * 2);
+        const bool next_tile_mine = have_next && wave * kTileKeys < next_k_end;
 
-        // S^T[key, col] = sum_d K[key, d] Q[col, d]; two 16-key sub-tiles
-        floatx4 s_acc[NT][2];
+        const int M = p.G * si.R;
+        if (seg_tiles > 0 && col0 < M) {  // block-uniform
+            const int first_masked_key = si.L - si.R + 1;  // keys from here on are hidden from some row
+            // query rows of this lane's columns
+            int col_limit[NT];   // last visible key of the column's query row (-1: no row)
+            bf16x8 qreg[NT][C::kKSteps];
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) s_acc[nt][0] = s_acc[nt][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int nt = 0; nt < NT; ++nt) {
+                const int n = col0 + nt * kColTile + c16;
+                const bool valid = n < M;
+                const int i = valid ? n / p.G : 0, gh = valid ? n % p.G : 0;
+                col_limit[nt] = valid ? si.L - si.R + i : -1;
+                const char *qrow = static_cast<const char *>(p.q) +
+                                   ((int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh) * (D * 2);
 #pragma unroll
-        for (int js = 0; js < 2; ++js) {
+                for (int t = 0; t < C::kKSteps; ++t) {
+                    u32x4 raw = {0u, 0u, 0u, 0u};
+                    if (valid) raw = *reinterpret_cast<const u32x4 *>(qrow + (t * 32 + g4 * 8) * 2);
+                    qreg[nt][t] = __builtin_bit_cast(bf16x8, raw);
+                }
+            }
+
+            float m_run[NT], l_run[NT];
+            floatx4 acc_o[NT][C::kDTiles];
 #pragma unroll
-            for (int t = 0; t < C::kKSteps; ++t) {
-                const u32x4 raw = *reinterpret_cast<const u32x4 *>(
-                    k_lds + (js * 16 + c16) * C::kRowBytes + (t * 32 + g4 * 8) * 2);
-                const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
+            for (int nt = 0; nt < NT; ++nt) {
+                m_run[nt] = -INFINITY;
+                l_run[nt] = 0.f;
+#pragma unroll
+                for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+
+            for (int key0 = key_first; key0 < k_end; key0 += kGroupKeys) {
+                store_tile<D>(kr, k_lds, lane);
+                store_tile<D>(vr, v_lds, lane);
+                // refill the registers: this wave's next tile of the segment, or else its first
+                // tile of the next segment (one load site; the choice is wave-uniform)
+                const int next0 = key0 + kGroupKeys;
+                const bool more_here = next0 < k_end;
+                if (more_here || next_tile_mine) {
+                    const char *src_k = more_here ? kbase : next_kbase;
+                    const char *src_v = more_here ? vbase : next_vbase;
+                    const int src_key = more_here ? next0 : wave * kTileKeys;
+                    const int src_last = more_here ? last_key : ni.L - 1;
+                    load_tile<D>(kr, src_k, row_bytes, src_key, src_last, lane);
+                    load_tile<D>(vr, src_v, row_bytes, src_key, src_last, lane);
+                    prefetched = !more_here;
+                }
+
+            // S^T[key, col] = sum_d K[key, d] Q[col, d]; two 16-key sub-tiles
+            floatx4 s_acc[NT][2];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) s_acc[nt][0] = s_acc[nt][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int js = 0; js < 2; ++js) {
+#pragma unroll
+                for (int t = 0; t < C::kKSteps; ++t) {
+                    const u32x4 raw = *reinterpret_cast<const u32x4 *>(
+                        k_lds + (js * 16 + c16) * C::kRowBytes + (t * 32 + g4 * 8) * 2);
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        s_acc[nt][js] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[nt][t],
+                                                                                s_acc[nt][js], 0, 0, 0);
+                }
+            }
+
+            // online softmax per column; accumulator element (js, i) is key key0 + 16 js + 4 g4 + i
+            const bool tail = key0 + kTileKeys > first_masked_key;  // wave-uniform
+            bf16x8 pfrag[NT];
+            float alpha[NT];
+            bool rescale = false;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                float sv[8];
+#pragma unroll
+                for (int js = 0; js < 2; ++js)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        float x = s_acc[nt][js][i] * p.scale2;
+                        if (tail) {
+                            const int key = key0 + js * 16 + g4 * 4 + i;
+                            x = key <= col_limit[nt] ? x : -INFINITY;
+                        }
+                        sv[js * 4 + i] = x;
+                    }
+                float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                                   fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+                const float mnew = fmaxf(m_run[nt], mloc);
+                const float msafe = mnew == -INFINITY ? 0.f : mnew;
+                alpha[nt] = hw_exp2(m_run[nt] - msafe);
+                rescale |= alpha[nt] != 1.f;
+                float psum = 0.f;
+                float pv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    pv[e] = hw_exp2(sv[e] - msafe);
+                    psum += pv[e];
+                }
+                l_run[nt] = l_run[nt] * alpha[nt] + psum;
+                m_run[nt] = mnew;
+                bf16x8 pf;
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const bf16x2 two = __builtin_convertvector(floatx2{pv[e], pv[e + 1]}, bf16x2);
+                    pf[e] = two[0];
+                    pf[e + 1] = two[1];
+                }
+                pfrag[nt] = pf;
+            }
+            if (__any(rescale)) {
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    s_acc[nt][js] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[nt][t],
-                                                                            s_acc[nt][js], 0, 0, 0);
+#pragma unroll
+                    for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= alpha[nt];
             }
-        }
 
-        // online softmax per column; accumulator element (js, i) is key key0 + 16 js + 4 g4 + i
-        const bool tail = key0 + kTileKeys > first_masked_key;  // wave-uniform
-        bf16x8 pfrag[NT];
-        float alpha[NT];
-        bool rescale = false;
+            // O^T[d, col] += sum_key V[key, d] P[key, col]; contraction slot e of lane group g4 is
+            // key 16 (e/4) + 4 g4 + e%4, matching the score accumulators; d tile t holds
+            // d = kEpl * r + t for MFMA row r.
+            // V is read in 8-byte pieces (4 values of d per key): for D = 128 in two rounds, which
+            // halves the registers the regroup needs
+            constexpr int kRounds = C::kEpl / 4;
+#pragma unroll
+            for (int hf = 0; hf < kRounds; ++hf) {
+                uint32_t vw[8][2];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int key = 16 * (e / 4) + 4 * g4 + (e % 4);
+                    const u32x2 raw = *reinterpret_cast<const u32x2 *>(
+                        v_lds + key * C::kRowBytes + c16 * (C::kEpl * 2) + hf * 8);
+                    vw[e][0] = raw[0];
+                    vw[e][1] = raw[1];
+                }
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    const int t = hf * 4 + tt;
+                    uint32_t aw[4];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const uint32_t lo = vw[2 * c][tt / 2], hi = vw[2 * c + 1][tt / 2];
+                        aw[c] = (tt & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
+                                         : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                    }
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{aw[0], aw[1], aw[2], aw[3]});
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc_o[nt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pfrag[nt], acc_o[nt][t],
+                                                                               0, 0, 0);
+                }
+            }
+            }
+            if (next_tile_mine && !prefetched) {  // this wave had no tile in the segment
+                load_tile<D>(kr, next_kbase, row_bytes, wave * kTileKeys, ni.L - 1, lane);
+                load_tile<D>(vr, next_vbase, row_bytes, wave * kTileKeys, ni.L - 1, lane);
+                prefetched = true;
+            }
+
+        // ---- merge the four waves --------------------------------------------------------------
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            float sv[8];
+            float l = l_run[nt];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            l_run[nt] = l;
+            if (g4 == 0) {
+                sh_m[wave * kMaxColsPerBlock + nt * kColTile + c16] = m_run[nt];
+                sh_l[wave * kMaxColsPerBlock + nt * kColTile + c16] = l;
+            }
+        }
+        __syncthreads();  // every wave has left its tile loop: tile memory is free for the merge
 #pragma unroll
-            for (int js = 0; js < 2; ++js)
+        for (int nt = 0; nt < NT; ++nt) {
+            const int c = nt * kColTile + c16;
+            float mt = -INFINITY;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    float x = s_acc[nt][js][i] * p.scale2;
-                    if (tail) {
-                        const int key = key0 + js * 16 + g4 * 4 + i;
-                        x = key <= col_limit[nt] ? x : -INFINITY;
+            for (int w = 0; w < kWaves; ++w) mt = fmaxf(mt, sh_m[w * kMaxColsPerBlock + c]);
+            const float msafe = mt == -INFINITY ? 0.f : mt;
+            float lt = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w)
+                lt += sh_l[w * kMaxColsPerBlock + c] * hw_exp2(sh_m[w * kMaxColsPerBlock + c] - msafe);
+            const float own = hw_exp2(m_run[nt] - msafe);
+#pragma unroll
+            for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= own;
+            if (wave == 0 && g4 == 0) {
+                sh_mt[c] = mt;
+                sh_lt[c] = lt;
+            }
+        }
+
+        float *merge = reinterpret_cast<float *>(smem + wave * C::kWaveBytes);
+        // a segment that covers its whole sequence writes the output; otherwise it leaves a
+        // partial in one of this work-group's two slots (0: the sequence began in an earlier
+        // work-group, 1: it starts here and continues in the next one)
+        const int64_t slot = 2 * (int64_t)wg + (t_first > 0 ? 0 : 1);
+        constexpr int kSeg = D / 8;  // floats per reducing thread
+        const int rc = threadIdx.x / 8, rseg = (threadIdx.x % 8) * kSeg;
+#pragma unroll
+        for (int pp = 0; pp < (NT + 1) / 2; ++pp) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int nt = 2 * pp + h;
+                if (nt < NT) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float *dst = merge + (h * kColTile + c16) * C::kMergeStride + C::kEpl * (4 * g4 + r);
+#pragma unroll
+                        for (int t = 0; t < C::kDTiles; t += 4)
+                            *reinterpret_cast<floatx4 *>(dst + t) =
+                                floatx4{acc_o[nt < NT ? nt : 0][t][r], acc_o[nt < NT ? nt : 0][t + 1][r],
+                                        acc_o[nt < NT ? nt : 0][t + 2][r], acc_o[nt < NT ? nt : 0][t + 3][r]};
                     }
-                    sv[js * 4 + i] = x;
-                }
-            float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                               fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-            const float mnew = fmaxf(m_run[nt], mloc);
-            const float msafe = mnew == -INFINITY ? 0.f : mnew;
-            alpha[nt] = hw_exp2(m_run[nt] - msafe);
-            rescale |= alpha[nt] != 1.f;
-            float psum = 0.f;
-            float pv[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                pv[e] = hw_exp2(sv[e] - msafe);
-                psum += pv[e];
-            }
-            l_run[nt] = l_run[nt] * alpha[nt] + psum;
-            m_run[nt] = mnew;
-            bf16x8 pf;
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const bf16x2 two = __builtin_convertvector(floatx2{pv[e], pv[e + 1]}, bf16x2);
-                pf[e] = two[0];
-                pf[e + 1] = two[1];
-            }
-            pfrag[nt] = pf;
-        }
-        if (__any(rescale)) {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= alpha[nt];
-        }
-
-        // O^T[d, col] += sum_key V[key, d] P[key, col]; contraction slot e of lane group g4 is
-        // key 16 (e/4) + 4 g4 + e%4, matching the score accumulators; d tile t holds
-        // d = kEpl * r + t for MFMA row r.
-        uint32_t vw[8][C::kEpl / 2];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int key = 16 * (e / 4) + 4 * g4 + (e % 4);
-            const char *src = v_lds + key * C::kRowBytes + c16 * (C::kEpl * 2);
-            if constexpr (C::kEpl == 8) {
-                const u32x4 raw = *reinterpret_cast<const u32x4 *>(src);
-                vw[e][0] = raw[0];
-                vw[e][1] = raw[1];
-                vw[e][2] = raw[2];
-                vw[e][3] = raw[3];
-            } else {
-                const u32x2 raw = *reinterpret_cast<const u32x2 *>(src);
-                vw[e][0] = raw[0];
-                vw[e][1] = raw[1];
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < C::kDTiles; ++t) {
-            uint32_t aw[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint32_t lo = vw[2 * c][t / 2], hi = vw[2 * c + 1][t / 2];
-                aw[c] = (t & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
-                                : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-            }
-            const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{aw[0], aw[1], aw[2], aw[3]});
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc_o[nt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pfrag[nt], acc_o[nt][t],
-                                                                       0, 0, 0);
-        }
-    }
-
-    // ---- merge the four waves --------------------------------------------------------------
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        float l = l_run[nt];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        l_run[nt] = l;
-        if (g4 == 0) {
-            sh_m[wave * kMaxColsPerBlock + nt * kColTile + c16] = m_run[nt];
-            sh_l[wave * kMaxColsPerBlock + nt * kColTile + c16] = l;
-        }
-    }
-    __syncthreads();  // every wave has left its tile loop: tile memory is free for the merge
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int c = nt * kColTile + c16;
-        float mt = -INFINITY;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) mt = fmaxf(mt, sh_m[w * kMaxColsPerBlock + c]);
-        const float msafe = mt == -INFINITY ? 0.f : mt;
-        float lt = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w)
-            lt += sh_l[w * kMaxColsPerBlock + c] * hw_exp2(sh_m[w * kMaxColsPerBlock + c] - msafe);
-        const float own = hw_exp2(m_run[nt] - msafe);
-#pragma unroll
-        for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= own;
-        if (wave == 0 && g4 == 0) {
-            sh_mt[c] = mt;
-            sh_lt[c] = lt;
-        }
-    }
-
-    float *merge = reinterpret_cast<float *>(smem + wave * C::kWaveBytes);
-    const bool single = it.n_chunks == 1;
-    const int64_t slot = it.kv0 / p.chunk + it.b + chunk;
-    constexpr int kSeg = D / 8;  // floats per reducing thread
-    const int rc = threadIdx.x / 8, rseg = (threadIdx.x % 8) * kSeg;
-#pragma unroll
-    for (int pp = 0; pp < (NT + 1) / 2; ++pp) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int nt = 2 * pp + h;
-            if (nt < NT) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float *dst = merge + (h * kColTile + c16) * C::kMergeStride + C::kEpl * (4 * g4 + r);
-#pragma unroll
-                    for (int t = 0; t < C::kDTiles; t += 4)
-                        *reinterpret_cast<floatx4 *>(dst + t) =
-                            floatx4{acc_o[nt < NT ? nt : 0][t][r], acc_o[nt < NT ? nt : 0][t + 1][r],
-                                    acc_o[nt < NT ? nt : 0][t + 2][r], acc_o[nt < NT ? nt : 0][t + 3][r]};
                 }
             }
-        }
-        __syncthreads();
-        const int cl = pp * 32 + rc;  // column within the block
-        const int n = col0 + cl;
-        if (cl < NT * kColTile && n < M) {
-            float sum[kSeg];
+            __syncthreads();
+            const int cl = pp * 32 + rc;  // column within the block
+            const int n = col0 + cl;
+            if (cl < NT * kColTile && n < M) {
+                float sum[kSeg];
 #pragma unroll
-            for (int j = 0; j < kSeg; ++j) sum[j] = 0.f;
+                for (int j = 0; j < kSeg; ++j) sum[j] = 0.f;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                const float *src = reinterpret_cast<const float *>(smem + w * C::kWaveBytes) +
-                                   rc * C::kMergeStride + rseg;
+                for (int w = 0; w < kWaves; ++w) {
+                    const float *src = reinterpret_cast<const float *>(smem + w * C::kWaveBytes) +
+                                       rc * C::kMergeStride + rseg;
 #pragma unroll
-                for (int j = 0; j < kSeg; j += 4) {
-                    const floatx4 x = *reinterpret_cast<const floatx4 *>(src + j);
-                    sum[j] += x[0];
-                    sum[j + 1] += x[1];
-                    sum[j + 2] += x[2];
-                    sum[j + 3] += x[3];
-                }
-            }
-            const float mt = sh_mt[cl], lt = sh_lt[cl];
-            if (single) {
-                const int i = n / p.G, gh = n % p.G;
-                const int64_t orow = (int64_t)(it.q0 + i) * p.Hq + kvh * p.G + gh;
-                const float inv = lt > 0.f ? 1.f / lt : 0.f;
-                OutT *dst = static_cast<OutT *>(p.out) + orow * D + rseg;
-                if constexpr (sizeof(OutT) == 2) {
-                    uint32_t packed[kSeg / 2];
-#pragma unroll
-                    for (int j = 0; j < kSeg; j += 2) {
-                        const bf16x2 two =
-                            __builtin_convertvector(floatx2{sum[j] * inv, sum[j + 1] * inv}, bf16x2);
-                        packed[j / 2] = __builtin_bit_cast(uint32_t, two);
+                    for (int j = 0; j < kSeg; j += 4) {
+                        const floatx4 x = *reinterpret_cast<const floatx4 *>(src + j);
+                        sum[j] += x[0];
+                        sum[j + 1] += x[1];
+                        sum[j + 2] += x[2];
+                        sum[j + 3] += x[3];
                     }
+                }
+                const float mt = sh_mt[cl], lt = sh_lt[cl];
+                if (whole) {
+                    const int i = n / p.G, gh = n % p.G;
+                    const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
+                    const float inv = lt > 0.f ? 1.f / lt : 0.f;
+                    OutT *dst = static_cast<OutT *>(p.out) + orow * D + rseg;
+                    if constexpr (sizeof(OutT) == 2) {
+                        uint32_t packed[kSeg / 2];
 #pragma unroll
-                    for (int j = 0; j < kSeg / 2; j += 4)
-                        *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(dst) + j * 4) =
-                            u32x4{packed[j], packed[j + 1], packed[j + 2], packed[j + 3]};
+                        for (int j = 0; j < kSeg; j += 2) {
+                            const bf16x2 two =
+                                __builtin_convertvector(floatx2{sum[j] * inv, sum[j + 1] * inv}, bf16x2);
+                            packed[j / 2] = __builtin_bit_cast(uint32_t, two);
+                        }
+#pragma unroll
+                        for (int j = 0; j < kSeg / 2; j += 4)
+                            *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(dst) + j * 4) =
+                                u32x4{packed[j], packed[j + 1], packed[j + 2], packed[j + 3]};
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < kSeg; ++j) dst[j] = sum[j] * inv;
+                    }
+                    if (p.lse && rseg == 0)
+                        p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
                 } else {
+                    const int64_t prow = slot * p.Mpad + n;
+                    float *dst = p.ws_o + prow * D + rseg;
 #pragma unroll
-                    for (int j = 0; j < kSeg; ++j) dst[j] = sum[j] * inv;
-                }
-                if (p.lse && rseg == 0)
-                    p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
-            } else if (slot < p.n_slots) {
-                const int64_t prow = (slot * p.Hkv + kvh) * p.Mpad + n;
-                float *dst = p.ws_o + prow * D + rseg;
-#pragma unroll
-                for (int j = 0; j < kSeg; j += 4)
-                    *reinterpret_cast<floatx4 *>(dst + j) =
-                        floatx4{sum[j], sum[j + 1], sum[j + 2], sum[j + 3]};
-                if (rseg == 0) {
-                    p.ws_ml[prow * 2] = mt;
-                    p.ws_ml[prow * 2 + 1] = lt;
+                    for (int j = 0; j < kSeg; j += 4)
+                        *reinterpret_cast<floatx4 *>(dst + j) =
+                            floatx4{sum[j], sum[j + 1], sum[j + 2], sum[j + 3]};
+                    if (rseg == 0) {
+                        p.ws_ml[prow * 2] = mt;
+                        p.ws_ml[prow * 2 + 1] = lt;
+                    }
                 }
             }
+            __syncthreads();
         }
-        __syncthreads();
+        }
+        if (!have_next) break;
+        b = nb;
+        kvh = nh;
+        si = ni;
+        t_first = 0;
+        n_left = n_after;
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// fp32 kernel: one work-group per (sequence, query head, query row, chunk)
+// fp32 kernel: one work-group per (sequence, query head, query row), no split
 // ------------------------------------------------------------------------------------------
 constexpr int kF32Threads = 256;
 
@@ -528,27 +595,23 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
     constexpr int kParts = kF32Threads / D;
 
     const int h = blockIdx.x % p.Hq;
-    const int item_id = blockIdx.x / p.Hq;
-    if (item_id >= *p.n_items) return;
-    const WorkItem it = p.items[item_id];
-    const int chunk = it.chunk;
+    const int b = blockIdx.x / p.Hq;
     const int i = blockIdx.y;
-    const int k_begin = chunk * p.chunk;
-    if (i >= it.R) return;
-    const int kvh = h / p.G, gh = h % p.G;
-    const int limit = it.L - it.R + i;                       // last visible key
-    const int k_end = min(min(k_begin + p.chunk, it.L), limit + 1);
-    const int64_t qrow = (int64_t)(it.q0 + i) * p.Hq + h;
+    const SeqInfo si = seq_info(p, b);
+    if (i >= si.R || si.L <= 0) return;
+    const int kvh = h / p.G;
+    const int k_end = min(si.L, si.L - si.R + i + 1);  // one past the last visible key
+    const int64_t qrow = (int64_t)(si.q0 + i) * p.Hq + h;
     const float *q = static_cast<const float *>(p.q) + qrow * D;
-    const float *kb = static_cast<const float *>(p.k) + (it.kv0 * p.Hkv + kvh) * (int64_t)D;
-    const float *vb = static_cast<const float *>(p.v) + (it.kv0 * p.Hkv + kvh) * (int64_t)D;
+    const float *kb = static_cast<const float *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
+    const float *vb = static_cast<const float *>(p.v) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
     const int64_t rstride = (int64_t)p.Hkv * D;
     for (int d = threadIdx.x; d < D; d += kF32Threads) sh_q[d] = q[d];
     __syncthreads();
 
     const int d_own = threadIdx.x % D, part = threadIdx.x / D;
     float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
-    for (int t0 = k_begin; t0 < k_end; t0 += kF32Threads) {
+    for (int t0 = 0; t0 < k_end; t0 += kF32Threads) {
         const int key = t0 + threadIdx.x;
         float s = -INFINITY;
         if (key < k_end) {
@@ -586,27 +649,14 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
     if (threadIdx.x < D) {
         float o = 0.f;
         for (int pz = 0; pz < kParts; ++pz) o += sh_part[pz * D + threadIdx.x];
-        const int n = i * p.G + gh;
-        if (it.n_chunks == 1) {
-            static_cast<float *>(p.out)[qrow * D + threadIdx.x] = l_run > 0.f ? o / l_run : 0.f;
-            if (p.lse && threadIdx.x == 0)
-                p.lse[qrow] = l_run > 0.f ? (m_run + log2f(l_run)) * 0.6931471805599453f : -INFINITY;
-        } else {
-            const int64_t slot = it.kv0 / p.chunk + it.b + chunk;
-            if (slot < p.n_slots) {
-                const int64_t prow = (slot * p.Hkv + kvh) * p.Mpad + n;
-                p.ws_o[prow * D + threadIdx.x] = o;
-                if (threadIdx.x == 0) {
-                    p.ws_ml[prow * 2] = m_run;   // -inf when this chunk is invisible to the row
-                    p.ws_ml[prow * 2 + 1] = l_run;
-                }
-            }
-        }
+        static_cast<float *>(p.out)[qrow * D + threadIdx.x] = l_run > 0.f ? o / l_run : 0.f;
+        if (p.lse && threadIdx.x == 0)
+            p.lse[qrow] = l_run > 0.f ? (m_run + log2f(l_run)) * 0.6931471805599453f : -INFINITY;
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// split-KV combine: merge the chunk partials of one (sequence, KV head) in chunk order
+// combine: merge the partials of every (sequence, KV head) that a work-group boundary cut
 // ------------------------------------------------------------------------------------------
 template <int D, typename OutT>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
@@ -614,31 +664,35 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     constexpr int kCols = 256 / kTpc;       // columns per block
     const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x % p.Hkv;
     const SeqInfo si = seq_info(p, b);
-    if (si.n_chunks <= 1 || si.R <= 0) return;
+    if (si.tiles <= 0) return;
+    const int64_t T = p.tile_prefix[p.B];
+    const int64_t total = T * p.Hkv;
+    const int64_t first_tile = (int64_t)kvh * T + p.tile_prefix[b];
+    const int w_first = owner_of_tile(first_tile, total, p.W);
+    const int w_last = owner_of_tile(first_tile + si.tiles - 1, total, p.W);
+    if (w_first == w_last) return;          // one work-group saw the whole sequence and wrote it
     const int n = blockIdx.y * kCols + threadIdx.x / kTpc;
     const int d4 = (threadIdx.x % kTpc) * 4;
     const int M = p.G * si.R;
     if (n >= M) return;
     const int i = n / p.G, gh = n % p.G;
-    const int limit = si.L - si.R + i;
-    // chunks that start beyond the row's last visible key hold nothing for it (and the fp32
-    // kernel never wrote them)
-    int nc = min(si.n_chunks, limit / p.chunk + 1);
-    if (si.slot0 + nc > p.n_slots) nc = (int)max((int64_t)0, p.n_slots - si.slot0);
-    float mt = -INFINITY;
-    for (int c = 0; c < nc; ++c) {
-        const int64_t prow = ((si.slot0 + c) * p.Hkv + kvh) * p.Mpad + n;
-        mt = fmaxf(mt, p.ws_ml[prow * 2]);
+    // partials in key order: slot 2*w_first+1, then slot 2*w for w_first < w <= w_last; when
+    // there are fewer tiles than work-groups some of those own no tile and wrote nothing
+    float mt = p.ws_ml[((int64_t)(2 * w_first + 1) * p.Mpad + n) * 2];
+    for (int w = w_first + 1; w <= w_last; ++w) {
+        if (!owns_tiles(w, total, p.W)) continue;
+        mt = fmaxf(mt, p.ws_ml[((int64_t)(2 * w) * p.Mpad + n) * 2]);
     }
     const float msafe = mt == -INFINITY ? 0.f : mt;
     float lt = 0.f;
     floatx4 o = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < nc; ++c) {
-        const int64_t prow = ((si.slot0 + c) * p.Hkv + kvh) * p.Mpad + n;
-        const float w = exp2f(p.ws_ml[prow * 2] - msafe);
-        lt += p.ws_ml[prow * 2 + 1] * w;
+    for (int w = w_first; w <= w_last; ++w) {
+        if (!owns_tiles(w, total, p.W)) continue;
+        const int64_t prow = (int64_t)(w == w_first ? 2 * w + 1 : 2 * w) * p.Mpad + n;
+        const float wgt = exp2f(p.ws_ml[prow * 2] - msafe);
+        lt += p.ws_ml[prow * 2 + 1] * wgt;
         const floatx4 x = *reinterpret_cast<const floatx4 *>(p.ws_o + prow * D + d4);
-        o += x * w;
+        o += x * wgt;
     }
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
@@ -661,9 +715,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
 thread_local hipEvent_t g_mark_after_main = nullptr;
 
 struct Plan {
-    int32_t chunk, max_chunks, Mpad;
-    int64_t n_slots;
-    size_t ws_o_bytes, ws_ml_bytes, ws_items_bytes, ws_bytes;
+    int32_t Mpad;
+    size_t ws_o_bytes, ws_ml_bytes, prefix_bytes, start_bytes, ws_bytes;
 };
 
 bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, int32_t Hq,
@@ -673,29 +726,28 @@ bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, i
     if (dt != RESPEC_F32 && dt != RESPEC_BF16) return false;
     const int32_t G = Hq / Hkv;
     if ((int64_t)G * max_q > 256) return false;
-    const int unit = kWaves * kTileKeys;  // 128 keys
-    long chunk = env_long("RESPEC_ATTN_CHUNK", 0);
-    if (chunk <= 0) {
-        // largest chunk that still gives the 256 compute units several work-groups each
-        chunk = unit;
-        for (long c = 8192; c >= unit; c /= 2) {
-            const double items = ((double)total_kv / (double)c + 0.5 * B) * Hkv;
-            if (items >= 2048.0) {
-                chunk = c;
-                break;
-            }
-        }
-    }
-    chunk = (chunk + unit - 1) / unit * unit;
-    pl.chunk = (int32_t)chunk;
-    pl.max_chunks = (max_kv_len + pl.chunk - 1) / pl.chunk;
     pl.Mpad = (G * max_q + kColTile - 1) / kColTile * kColTile;
-    pl.n_slots = total_kv / pl.chunk + B + 1;
-    pl.ws_o_bytes = round_up((size_t)pl.n_slots * Hkv * pl.Mpad * D * sizeof(float), 256);
-    pl.ws_ml_bytes = round_up((size_t)pl.n_slots * Hkv * pl.Mpad * 2 * sizeof(float), 256);
-    pl.ws_items_bytes = round_up((size_t)pl.n_slots * sizeof(WorkItem), 256);
-    pl.ws_bytes = pl.ws_o_bytes + pl.ws_ml_bytes + pl.ws_items_bytes + 256;
+    // sized for the widest split so that the query needs no device
+    pl.ws_o_bytes = round_up((size_t)2 * kMaxWgs * pl.Mpad * D * sizeof(float), 256);
+    pl.ws_ml_bytes = round_up((size_t)2 * kMaxWgs * pl.Mpad * 2 * sizeof(float), 256);
+    pl.prefix_bytes = round_up((size_t)(B + 1) * sizeof(int32_t), 256);
+    pl.start_bytes = round_up((size_t)kMaxWgs * sizeof(WgStart), 256);
+    pl.ws_bytes = pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes + pl.start_bytes;
     return true;
+}
+
+// Compute units of the current device (cached per device).
+int compute_units() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
 }
 
 template <int D, int NT, typename OutT>
@@ -778,9 +830,8 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     if (!workspace || workspace_bytes < pl.ws_bytes || !aligned_to(workspace, 256))
         return fail(RESPEC_ERR_WORKSPACE, "verify_attention: workspace of %zu bytes (256-byte aligned) needed, got %zu",
                     pl.ws_bytes, workspace ? workspace_bytes : (size_t)0);
-    const int64_t blocks = pl.n_slots * (dt == RESPEC_BF16 ? Hkv : Hq);
-    if (blocks > 0x7fffffffLL)
-        return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: grid of %lld work-groups is too large", (long long)blocks);
+    if (dt == RESPEC_F32 && (int64_t)B * Hq > 0x7fffffffLL)
+        return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: B*Hq too large for the fp32 path");
 
     AttnParams p{};
     p.q = q;
@@ -790,11 +841,11 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     p.kv_indptr = kv_indptr;
     p.out = out;
     p.lse = lse;
-    p.ws_o = static_cast<float *>(workspace);
-    p.ws_ml = reinterpret_cast<float *>(static_cast<char *>(workspace) + pl.ws_o_bytes);
-    p.items = reinterpret_cast<WorkItem *>(static_cast<char *>(workspace) + pl.ws_o_bytes + pl.ws_ml_bytes);
-    p.n_items = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + pl.ws_o_bytes + pl.ws_ml_bytes +
-                                            pl.ws_items_bytes);
+    char *ws = static_cast<char *>(workspace);
+    p.ws_o = reinterpret_cast<float *>(ws);
+    p.ws_ml = reinterpret_cast<float *>(ws + pl.ws_o_bytes);
+    p.tile_prefix = reinterpret_cast<int32_t *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes);
+    p.wg_start = reinterpret_cast<WgStart *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes);
     p.B = B;
     p.total_q = total_q;
     p.total_kv = total_kv;
@@ -803,53 +854,59 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     p.Hq = Hq;
     p.Hkv = Hkv;
     p.G = Hq / Hkv;
-    p.chunk = pl.chunk;
-    p.max_chunks = pl.max_chunks;
     p.Mpad = pl.Mpad;
-    p.n_slots = pl.n_slots;
     p.scale2 = (float)((double)sm_scale * 1.4426950408889634074);
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t err;
-    hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
-    err = hipGetLastError();
-    if (err != hipSuccess)
-        return fail(RESPEC_ERR_HIP, "verify_attention: prep launch failed: %s", hipGetErrorString(err));
     const int M = p.G * max_q_per_seq;
-    if (dt == RESPEC_BF16) {
-        const int col_blocks = (M + kMaxColsPerBlock - 1) / kMaxColsPerBlock;
-        const int cols = col_blocks == 1 ? M : kMaxColsPerBlock;
-        const int nt = (cols + kColTile - 1) / kColTile;
-        const dim3 grid((unsigned)blocks, (unsigned)col_blocks);
-        err = D == 128 ? launch_bf16_nt<128>(nt, p, grid, stream) : launch_bf16_nt<64>(nt, p, grid, stream);
-    } else {
-        const dim3 grid((unsigned)blocks, (unsigned)max_q_per_seq);
+    if (dt == RESPEC_F32) {
+        const dim3 grid((unsigned)(B * Hq), (unsigned)max_q_per_seq);
         if (D == 128)
             hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(kF32Threads), 0, stream, p);
         else
             hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(kF32Threads), 0, stream, p);
         err = hipGetLastError();
+        if (err != hipSuccess)
+            return fail(RESPEC_ERR_HIP, "verify_attention: launch failed: %s", hipGetErrorString(err));
+        if (g_mark_after_main) {
+            (void)hipEventRecord(g_mark_after_main, stream);
+            g_mark_after_main = nullptr;
+        }
+        clear_error();
+        return RESPEC_OK;
     }
+
+    const int col_blocks = (M + kMaxColsPerBlock - 1) / kMaxColsPerBlock;
+    const int cols = col_blocks == 1 ? M : kMaxColsPerBlock;
+    const int nt = (cols + kColTile - 1) / kColTile;
+    // one work-group per resident slot: two per compute unit (one for the wide-column variants)
+    const int per_cu = (D == 128 && nt >= 3) ? 1 : 2;
+    long W = env_long("RESPEC_ATTN_WGS", 0);
+    if (W <= 0) W = (long)per_cu * compute_units() / col_blocks;
+    if (W < 1) W = 1;
+    if (W > kMaxWgs) W = kMaxWgs;
+    p.W = (int32_t)W;
+
+    hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
+    err = hipGetLastError();
+    if (err != hipSuccess)
+        return fail(RESPEC_ERR_HIP, "verify_attention: prep launch failed: %s", hipGetErrorString(err));
+    const dim3 grid((unsigned)W, (unsigned)col_blocks);
+    err = D == 128 ? launch_bf16_nt<128>(nt, p, grid, stream) : launch_bf16_nt<64>(nt, p, grid, stream);
     if (err != hipSuccess)
         return fail(RESPEC_ERR_HIP, "verify_attention: main launch failed: %s", hipGetErrorString(err));
     if (g_mark_after_main) {
         (void)hipEventRecord(g_mark_after_main, stream);
         g_mark_after_main = nullptr;
     }
-    if (pl.max_chunks > 1) {
+    {
         const int cols_per_block = 256 / (D / 4);
-        const dim3 grid((unsigned)(B * Hkv), (unsigned)((M + cols_per_block - 1) / cols_per_block));
-        if (dt == RESPEC_BF16) {
-            if (D == 128)
-                hipLaunchKernelGGL((attn_combine_kernel<128, uint16_t>), grid, dim3(256), 0, stream, p);
-            else
-                hipLaunchKernelGGL((attn_combine_kernel<64, uint16_t>), grid, dim3(256), 0, stream, p);
-        } else {
-            if (D == 128)
-                hipLaunchKernelGGL((attn_combine_kernel<128, float>), grid, dim3(256), 0, stream, p);
-            else
-                hipLaunchKernelGGL((attn_combine_kernel<64, float>), grid, dim3(256), 0, stream, p);
-        }
+        const dim3 cgrid((unsigned)(B * Hkv), (unsigned)((M + cols_per_block - 1) / cols_per_block));
+        if (D == 128)
+            hipLaunchKernelGGL((attn_combine_kernel<128, uint16_t>), cgrid, dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL((attn_combine_kernel<64, uint16_t>), cgrid, dim3(256), 0, stream, p);
         err = hipGetLastError();
         if (err != hipSuccess)
             return fail(RESPEC_ERR_HIP, "verify_attention: combine launch failed: %s", hipGetErrorString(err));

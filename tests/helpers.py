@@ -12,20 +12,22 @@ from paper_2510_26475_amd import binding, synth
 
 
 @contextmanager
-def attn_chunk(chunk):
-    """Force the split-KV chunk size (keys per work-group) for the calls inside."""
-    old = os.environ.get("RESPEC_ATTN_CHUNK")
-    if chunk is None:
-        os.environ.pop("RESPEC_ATTN_CHUNK", None)
+def attn_wgs(wgs):
+    """Force the number of work-groups the key tiles are split over (None = the default,
+    two per compute unit).  Small counts put many sequences in one work-group, large counts
+    cut every sequence into many partials."""
+    old = os.environ.get("RESPEC_ATTN_WGS")
+    if wgs is None:
+        os.environ.pop("RESPEC_ATTN_WGS", None)
     else:
-        os.environ["RESPEC_ATTN_CHUNK"] = str(chunk)
+        os.environ["RESPEC_ATTN_WGS"] = str(wgs)
     try:
         yield
     finally:
         if old is None:
-            os.environ.pop("RESPEC_ATTN_CHUNK", None)
+            os.environ.pop("RESPEC_ATTN_WGS", None)
         else:
-            os.environ["RESPEC_ATTN_CHUNK"] = old
+            os.environ["RESPEC_ATTN_WGS"] = old
 
 
 def gpu_attention(batch: synth.VerifyBatch, sm_scale=None, want_lse=True, stream=None):

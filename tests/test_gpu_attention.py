@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import attn_chunk, gpu_attention, oracle_attention, sub_batch
+from helpers import attn_wgs, gpu_attention, oracle_attention, sub_batch
 from paper_2510_26475_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -38,10 +38,10 @@ def _check(out, lse, ref, ref_lse, dtype, rms_bound=2.5e-3):
     return float(err.max())
 
 
-def _run(oracle, wl, lens, ks, seed=0, chunk=None, sm_scale=None):
+def _run(oracle, wl, lens, ks, seed=0, wgs=None, sm_scale=None):
     batch = synth.make_batch(wl, device="cuda", kv_lens=lens, k_per_seq=ks, seed=seed,
                              with_logits=False)
-    with attn_chunk(chunk):
+    with attn_wgs(wgs):
         out, lse = gpu_attention(batch, sm_scale=sm_scale)
     ref, ref_lse = oracle_attention(oracle, batch, sm_scale=sm_scale)
     return _check(out, lse, ref, ref_lse, wl.dtype), batch, out
@@ -55,40 +55,39 @@ def test_tiny_f32_workload(oracle):
     _check(out, lse, ref, ref_lse, "f32")
 
 
-@pytest.mark.parametrize("chunk", [None, 128, 256])
-def test_f32_split_kv_and_combine(oracle, chunk):
-    wl = _wl("f32_split", 4, 2, 64, "f32")
-    _run(oracle, wl, [300, 129, 5, 1000, 128, 513], [4, 0, 4, 2, 3, 1], seed=3, chunk=chunk)
-    wl = _wl("f32_split_d128", 6, 2, 128, "f32")
-    _run(oracle, wl, [257, 31, 640], [2, 4, 0], seed=4, chunk=chunk)
+def test_f32_longer_contexts(oracle):
+    wl = _wl("f32_long", 4, 2, 64, "f32")
+    _run(oracle, wl, [300, 129, 5, 1000, 128, 513], [4, 0, 4, 2, 3, 1], seed=3)
+    wl = _wl("f32_long_d128", 6, 2, 128, "f32")
+    _run(oracle, wl, [257, 31, 640], [2, 4, 0], seed=4)
 
 
 @pytest.mark.parametrize("heads", [(28, 4), (16, 2), (40, 8), (4, 1), (8, 8), (7, 1)])
-@pytest.mark.parametrize("chunk", [None, 128, 512])
-def test_bf16_d128_shapes(oracle, heads, chunk):
+@pytest.mark.parametrize("wgs", [None, 1, 3, 64])
+def test_bf16_d128_shapes(oracle, heads, wgs):
     Hq, Hkv = heads
     wl = _wl("bf16_shapes", Hq, Hkv, 128, "bf16")
     lens = [33, 130, 257, 1000, 6, 5, 128, 129, 2049]
     ks = [3, 4, 0, 4, 4, 4, 1, 2, 3]
-    _run(oracle, wl, lens, ks, seed=Hq + (chunk or 0), chunk=chunk)
+    _run(oracle, wl, lens, ks, seed=Hq + (wgs or 0), wgs=wgs)
 
 
-@pytest.mark.parametrize("chunk", [None, 128])
-def test_bf16_d64(oracle, chunk):
+@pytest.mark.parametrize("wgs", [None, 5])
+def test_bf16_d64(oracle, wgs):
     wl = _wl("bf16_d64", 8, 2, 64, "bf16")
-    _run(oracle, wl, [33, 130, 700, 9, 257], [3, 4, 0, 8, 2], seed=11, chunk=chunk)
+    _run(oracle, wl, [33, 130, 700, 9, 257], [3, 4, 0, 8, 2], seed=11, wgs=wgs)
 
 
 @pytest.mark.parametrize("k", [0, 1, 2, 4, 8])
 def test_bf16_draft_lengths_14b_heads(oracle, k):
     # G = 5: 5, 10, 15, 25, 45 MFMA columns -> 1..3 column tiles
     wl = _wl("bf16_k", 40, 8, 128, "bf16")
-    _run(oracle, wl, [1500, 64 + k, 333], [k, k, k], seed=20 + k, chunk=256)
+    _run(oracle, wl, [1500, 64 + k, 333], [k, k, k], seed=20 + k, wgs=37)
 
 
 def test_more_than_64_columns_uses_two_column_blocks(oracle):
     wl = _wl("bf16_wide", 16, 2, 128, "bf16")            # G = 8, k = 8 -> 72 columns
-    _run(oracle, wl, [400, 90, 1025], [8, 8, 5], seed=31, chunk=256)
+    _run(oracle, wl, [400, 90, 1025], [8, 8, 5], seed=31, wgs=11)
 
 
 def test_ragged_draft_lengths_in_one_batch(oracle):
@@ -96,7 +95,7 @@ def test_ragged_draft_lengths_in_one_batch(oracle):
     ks = [0, 8, 3, 1, 7, 0, 5, 2]
     lens = [700, 9, 1300, 2, 4096, 1, 257, 513]
     _run(oracle, wl, lens, ks, seed=41)
-    _run(oracle, wl, lens, ks, seed=42, chunk=128)
+    _run(oracle, wl, lens, ks, seed=42, wgs=29)
 
 
 def test_causal_boundary_with_spiked_keys(oracle):
@@ -117,8 +116,8 @@ def test_causal_boundary_with_spiked_keys(oracle):
                 qv = batch.q[qi[b] + i, hk * G].float() + batch.q[qi[b] + i + 1, hk * G].float()
                 batch.k_cache[ki[b] + key, hk] = (4.0 * qv).to(torch.bfloat16)
                 batch.v_cache[ki[b] + key, hk] = 1.5 + 0.125 * i
-    for chunk in (None, 128):
-        with attn_chunk(chunk):
+    for wgs in (None, 2, 13):
+        with attn_wgs(wgs):
             out, lse = gpu_attention(batch)
         ref, ref_lse = oracle_attention(oracle, batch)
         _check(out, lse, ref, ref_lse, "bf16", rms_bound=4e-3)
@@ -139,7 +138,7 @@ def test_runs_are_bitwise_reproducible(oracle):
     wl = _wl("bf16_det", 28, 4, 128, "bf16")
     batch = synth.make_batch(wl, device="cuda", kv_lens=[3000, 700, 129], k_per_seq=[3, 3, 3],
                              seed=7, with_logits=False)
-    with attn_chunk(256):
+    with attn_wgs(100):
         a, la = gpu_attention(batch)
         b, lb = gpu_attention(batch)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
