@@ -95,7 +95,8 @@ def main():
     ap.add_argument("--sigma", type=float, default=None, help="drafter noise (default: workload's)")
     ap.add_argument("--batch", type=int, default=None, help="override B (sweeps)")
     ap.add_argument("--k", type=int, default=None, help="override k (sweeps)")
-    ap.add_argument("--cpu-seqs", type=int, default=32)
+    ap.add_argument("--cpu-seqs", type=int, default=256,
+                    help="sequences the oracle is timed on (cpu_baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
 
@@ -152,14 +153,15 @@ def main():
     torch.cuda.synchronize()
 
     # timed region: exactly --steps steps, events on the launch stream around every kernel group
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     for e4 in ev:
-        e4[1].record()      # create the handle the library will re-record
+        e4[1].record()      # create the handles the library will re-record
+        e4[4].record()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for e4 in ev:
         e4[0].record()
-        binding.respec_profile_mark_after_main(e4[1])
+        binding.respec_profile_mark_main(e4[4], e4[1])
         attention()
         e4[2].record()
         sampler()
@@ -168,7 +170,8 @@ def main():
     t1 = time.perf_counter()
 
     ms_step = (t1 - t0) * 1e3 / args.steps
-    ms_main = sum(e4[0].elapsed_time(e4[1]) for e4 in ev) / args.steps
+    ms_main = sum(e4[4].elapsed_time(e4[1]) for e4 in ev) / args.steps
+    ms_prep = sum(e4[0].elapsed_time(e4[4]) for e4 in ev) / args.steps
     ms_comb = sum(e4[1].elapsed_time(e4[2]) for e4 in ev) / args.steps
     ms_samp = sum(e4[2].elapsed_time(e4[3]) for e4 in ev) / args.steps
 
@@ -201,7 +204,7 @@ def main():
             "seed": wl.seed,
         },
         "verify_step_us": ms_step * 1e3,
-        "kernel_us": {"attention_main": ms_main * 1e3, "attention_combine": ms_comb * 1e3,
+        "kernel_us": {"attention_prep": ms_prep * 1e3, "attention_main": ms_main * 1e3, "attention_combine": ms_comb * 1e3,
                       "rejection_sample": ms_samp * 1e3},
         "accepted_drafts": accepted, "emitted_tokens": emitted,
         "emitted_per_seq": emitted / B,

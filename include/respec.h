@@ -15,7 +15,7 @@
  * General rules
  *   - Every data pointer is a DEVICE pointer (HIP global memory) unless it says "host".
  *     The caller owns all buffers; the library allocates and frees nothing on the device
- *     and keeps no state between calls.
+ *     and keeps no state between calls (the profiling hook below aside).
  *   - Calls are asynchronous on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream) and never synchronise.  Inputs must stay valid and unchanged until
  *     the stream has passed the call.
@@ -103,12 +103,13 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
                                         size_t workspace_bytes, void *hip_stream);
 
 /*
- * Profiling hook (benchmarks only).  If `hip_event` (a hipEvent_t passed as void*) is
- * non-NULL, the calling thread's next respec_verify_attention records it on the call's
- * stream after the main kernel and before the split-KV combine kernel, then forgets it.
- * This is the only state the library keeps, and it is thread-local.
+ * Profiling hook (benchmarks only).  The calling thread's next respec_verify_attention
+ * records `before_main` (if non-NULL) on the call's stream right before its main kernel
+ * (after the small set-up kernel) and `after_main` (if non-NULL) right after it, before
+ * the combine kernel; then it forgets both.  Both are hipEvent_t passed as void*.  This
+ * is the only state the library keeps, and it is thread-local.
  */
-void respec_profile_mark_after_main(void *hip_event);
+void respec_profile_mark_main(void *before_main, void *after_main);
 
 /* Workspace bytes of respec_rejection_sample (0 = none needed, NULL may be passed). */
 size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t total_q, int32_t V,

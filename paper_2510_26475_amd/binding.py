@@ -58,8 +58,8 @@ def load():
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
         c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
-    lib.respec_profile_mark_after_main.restype = None
-    lib.respec_profile_mark_after_main.argtypes = [c.c_void_p]
+    lib.respec_profile_mark_main.restype = None
+    lib.respec_profile_mark_main.argtypes = [c.c_void_p, c.c_void_p]
     lib.respec_rejection_sample_workspace_bytes.restype = c.c_size_t
     lib.respec_rejection_sample_workspace_bytes.argtypes = [c.c_int32, c.c_int32, c.c_int32, c.c_int]
     lib.respec_rejection_sample.restype = c.c_int
@@ -76,7 +76,7 @@ EXPORTED_SYMBOLS = [
     "respec_status_string", "respec_last_error", "respec_version",
     "respec_verify_attention_workspace_bytes", "respec_verify_attention",
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample",
-    "respec_profile_mark_after_main",
+    "respec_profile_mark_main",
 ]
 
 
@@ -142,12 +142,15 @@ def respec_verify_attention(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, 
         float(sm_scale), _dtype_code(q), ws_ptr, ws_bytes, _stream_ptr(stream)))
 
 
-def respec_profile_mark_after_main(event: Optional[torch.cuda.Event]):
-    """Have the next respec_verify_attention record ``event`` between its two kernels."""
-    if event is not None and not event.cuda_event:
-        raise ValueError("the event must have been created (record it once first)")
-    load().respec_profile_mark_after_main(
-        ctypes.c_void_p(event.cuda_event) if event is not None else None)
+def respec_profile_mark_main(before: Optional[torch.cuda.Event], after: Optional[torch.cuda.Event]):
+    """Have the next respec_verify_attention record the two events around its main kernel."""
+    def handle(ev):
+        if ev is None:
+            return None
+        if not ev.cuda_event:
+            raise ValueError("the event must have been created (record it once first)")
+        return ctypes.c_void_p(ev.cuda_event)
+    load().respec_profile_mark_main(handle(before), handle(after))
 
 
 def respec_rejection_sample_workspace_bytes(B, total_q, V, logits_dt) -> int:

@@ -712,6 +712,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+thread_local hipEvent_t g_mark_before_main = nullptr;
 thread_local hipEvent_t g_mark_after_main = nullptr;
 
 struct Plan {
@@ -781,8 +782,9 @@ hipError_t launch_bf16_nt(int nt, const AttnParams &p, dim3 grid, hipStream_t st
 
 extern "C" {
 
-void respec_profile_mark_after_main(void *hip_event) {
-    respec::g_mark_after_main = static_cast<hipEvent_t>(hip_event);
+void respec_profile_mark_main(void *before_main, void *after_main) {
+    respec::g_mark_before_main = static_cast<hipEvent_t>(before_main);
+    respec::g_mark_after_main = static_cast<hipEvent_t>(after_main);
 }
 
 size_t respec_verify_attention_workspace_bytes(int32_t B, int32_t total_q, int64_t total_kv,
@@ -861,6 +863,10 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     hipError_t err;
     const int M = p.G * max_q_per_seq;
     if (dt == RESPEC_F32) {
+        if (g_mark_before_main) {
+            (void)hipEventRecord(g_mark_before_main, stream);
+            g_mark_before_main = nullptr;
+        }
         const dim3 grid((unsigned)(B * Hq), (unsigned)max_q_per_seq);
         if (D == 128)
             hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(kF32Threads), 0, stream, p);
@@ -892,6 +898,10 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     err = hipGetLastError();
     if (err != hipSuccess)
         return fail(RESPEC_ERR_HIP, "verify_attention: prep launch failed: %s", hipGetErrorString(err));
+    if (g_mark_before_main) {
+        (void)hipEventRecord(g_mark_before_main, stream);
+        g_mark_before_main = nullptr;
+    }
     const dim3 grid((unsigned)W, (unsigned)col_blocks);
     err = D == 128 ? launch_bf16_nt<128>(nt, p, grid, stream) : launch_bf16_nt<64>(nt, p, grid, stream);
     if (err != hipSuccess)
