@@ -18,7 +18,7 @@
 namespace respec {
 namespace {
 
-constexpr int kThreads = 1024;
+constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kUnroll = 4;
 constexpr float kRefInit = -1.0e30f;
@@ -36,6 +36,8 @@ struct SamplerParams {
     int32_t *out_flags;
     int32_t B, total_q, max_k, V;
     int64_t ld_t, ld_d;
+    float c_f;         // log2(e)/T rounded to nearest binary32
+    int one_term;      // c_f is close enough to log2(e)/T for the one-fma exponent of the fast pass
     float c_hi, c_lo;  // log2(e)/T = c_hi + c_lo, c_lo > 0
     double c_d;        // log2(e)/T
     double inv_T;
@@ -79,9 +81,12 @@ __device__ inline u32x4 neg_inf_slot() {
 }
 
 // 16 bytes of row `row` starting at element slot*EPV; elements at or beyond V read as -inf.
-template <bool BF16>
+// FULL: every row is 16-byte aligned and V is a whole number of slots (known on the host).
+template <bool BF16, bool FULL = false>
 __device__ inline u32x4 load_slot(const void *row, int slot, int V, bool aligned) {
     constexpr int EPV = Elem<BF16>::EPV;
+    if constexpr (FULL)
+        return *reinterpret_cast<const u32x4 *>(static_cast<const char *>(row) + (size_t)slot * 16);
     const int e0 = slot * EPV;
     if (aligned && e0 + EPV <= V)
         return *reinterpret_cast<const u32x4 *>(static_cast<const char *>(row) + (size_t)slot * 16);
@@ -103,6 +108,9 @@ __device__ inline u32x4 load_slot(const void *row, int slot, int V, bool aligned
 }
 
 __device__ inline float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// fp64 exp2 is only needed a few times per row (reconciling references).
+__device__ inline double exp2_f64(double x) { return exp2(x); }
 
 // exp2 argument of one element: (z - ref) * (c_hi + c_lo).  c_lo > 0 keeps -inf at -inf.
 __device__ inline float exp2_arg(float z, float ref, float c_hi, float c_lo) {
@@ -136,7 +144,7 @@ struct ThreadSum {
                 s += (double)acc[j];
                 acc[j] = 0.f;
             }
-            carry = s * exp2((double)(ref - vmax) * p.c_d);
+            carry = s * exp2_f64((double)(ref - vmax) * p.c_d);
             ref = vmax;
         }
 #pragma unroll
@@ -176,9 +184,11 @@ struct SharedState {
     float m[2][2][kWaves];   // [parity][row p/q][wave]
     double s[2][2][kWaves];
     double wave_total[kWaves];
+    double scan_total[kWaves];
     int token;
     int near_edge;
     int last_positive;
+    int first_thread;
 };
 
 // Combine the per-thread (ref, sum) pairs of the block into one (M, S) with
@@ -187,7 +197,7 @@ __device__ inline void block_combine(float ref, double sum, SharedState &sh, int
                                      const SamplerParams &p, float &M, double &S) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const float mw = wave_max(ref);
-    const double sw = wave_sum(sum * exp2((double)(ref - mw) * p.c_d));
+    const double sw = wave_sum(sum * exp2_f64((double)(ref - mw) * p.c_d));
     if (lane == 0) {
         sh.m[parity][which][wave] = mw;
         sh.s[parity][which][wave] = sw;
@@ -198,14 +208,136 @@ __device__ inline void block_combine(float ref, double sum, SharedState &sh, int
     float mm = my_m;
 #pragma unroll
     for (int o = kWaves / 2; o >= 1; o >>= 1) mm = fmaxf(mm, __shfl_xor(mm, o));
-    double part = sh.s[parity][which][w] * exp2((double)(my_m - mm) * p.c_d);
+    double part = sh.s[parity][which][w] * exp2_f64((double)(my_m - mm) * p.c_d);
 #pragma unroll
     for (int o = kWaves / 2; o >= 1; o >>= 1) part += __shfl_xor(part, o);
     M = mm;
     S = part;
 }
 
-// One streaming pass over a target row (and, if TWO, the matching drafter row).
+// One thread's share of the fast pass: 8 (bf16) or 4 (f32) running sums of
+// exp2(z*c + K) = exp((z - ref)/T), no branches.  ONE_TERM: c = c_f, K = -ref*c_f rounded (the
+// rounding residue is put back in fp64 when threads are combined).
+template <bool BF16, bool ONE_TERM>
+__device__ inline void fast_absorb(const u32x4 &v, float (&acc)[Elem<BF16>::EPV], float ref, float K,
+                                   const SamplerParams &p) {
+    constexpr int EPV = Elem<BF16>::EPV;
+    float z[EPV];
+    unpack<BF16>(v, z);
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) {
+        const float t = ONE_TERM ? fmaf(z[j], p.c_f, K) : exp2_arg(z[j], ref, p.c_hi, p.c_lo);
+        acc[j] += hw_exp2(t);
+    }
+}
+
+template <bool BF16>
+__device__ inline float slot_max(const u32x4 &v) {
+    constexpr int EPV = Elem<BF16>::EPV;
+    float z[EPV];
+    unpack<BF16>(v, z);
+    float m = z[0];
+#pragma unroll
+    for (int j = 1; j < EPV; ++j) m = fmaxf(m, z[j]);
+    return m;
+}
+
+// Fast streaming pass over a target row (and, if TWO, the matching drafter row).  The
+// reference of a wave is the maximum of the first slots it reads, not the row maximum:
+// exp2 keeps full relative precision for any offset, only a logit more than ~88/c above the
+// reference would overflow.  Returns false (every thread alike) when a sum came out
+// non-finite or empty, and the caller then repeats the row with the guarded pass below.
+template <bool BF16, bool TWO, bool ONE_TERM>
+__device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int nslots, SharedState &sh,
+                                      int parity, const SamplerParams &p, float &Mp, double &Sp,
+                                      float &Mq, double &Sq) {
+    constexpr int EPV = Elem<BF16>::EPV;
+    constexpr int kBatch = kThreads * kUnroll;  // slots per block iteration
+    float accp[EPV], accq[EPV];
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) accp[j] = accq[j] = 0.f;
+    float refp = 0.f, refq = 0.f, Kp = 0.f, Kq = 0.f;
+    const int n_iter = (nslots + kBatch - 1) / kBatch;  // block-uniform, >= 1
+    // batch `it` of this thread: slots it*kBatch + tid + u*kThreads; only the last batch can
+    // run past the row (those slots read as -inf)
+    auto load_batch = [&](int it, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) {
+        const int s0 = it * kBatch + threadIdx.x;
+        if (it + 1 < n_iter) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                vp[u] = load_slot<BF16, true>(rowp, s0 + u * kThreads, p.V, true);
+                if constexpr (TWO) vq[u] = load_slot<BF16, true>(rowq, s0 + u * kThreads, p.V, true);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int slot = s0 + u * kThreads;
+                const bool in = slot < nslots;
+                const int safe = in ? slot : 0;
+                const u32x4 a = load_slot<BF16, true>(rowp, safe, p.V, true);
+                vp[u] = in ? a : neg_inf_slot<BF16>();
+                if constexpr (TWO) {
+                    const u32x4 b = load_slot<BF16, true>(rowq, safe, p.V, true);
+                    vq[u] = in ? b : neg_inf_slot<BF16>();
+                }
+            }
+        }
+    };
+    u32x4 vp[kUnroll], vq[kUnroll];
+    load_batch(0, vp, vq);
+    {   // references from the first batch
+        float mp = slot_max<BF16>(vp[0]), mq = -INFINITY;
+#pragma unroll
+        for (int u = 1; u < kUnroll; ++u) mp = fmaxf(mp, slot_max<BF16>(vp[u]));
+        mp = wave_max(mp);
+        refp = (mp > -INFINITY && mp < INFINITY) ? mp : 0.f;
+        Kp = -refp * p.c_f;
+        if constexpr (TWO) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) mq = fmaxf(mq, slot_max<BF16>(vq[u]));
+            mq = wave_max(mq);
+            refq = (mq > -INFINITY && mq < INFINITY) ? mq : 0.f;
+            Kq = -refq * p.c_f;
+        }
+    }
+    for (int it = 0; it < n_iter; ++it) {
+        u32x4 np[kUnroll], nq[kUnroll];
+        const bool more = it + 1 < n_iter;  // block-uniform
+        if (more) load_batch(it + 1, np, nq);  // in flight while this batch is summed
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            fast_absorb<BF16, ONE_TERM>(vp[u], accp, refp, Kp, p);
+            if constexpr (TWO) fast_absorb<BF16, ONE_TERM>(vq[u], accq, refq, Kq, p);
+        }
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                vp[u] = np[u];
+                if constexpr (TWO) vq[u] = nq[u];
+            }
+        }
+    }
+    double sp = 0.0, sq = 0.0;
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) {
+        sp += (double)accp[j];
+        sq += (double)accq[j];
+    }
+    if constexpr (ONE_TERM) {  // exp2(z c + K) = exp2((z - ref) c) * exp2(K + ref c): undo the residue
+        sp *= exp2_f64(-((double)Kp + (double)refp * (double)p.c_f));
+        if constexpr (TWO) sq *= exp2_f64(-((double)Kq + (double)refq * (double)p.c_f));
+    }
+    block_combine(refp, sp, sh, parity, 0, p, Mp, Sp);
+    bool ok = Sp > 0.0 && Sp < 1.0e300;
+    if constexpr (TWO) {
+        block_combine(refq, sq, sh, parity, 1, p, Mq, Sq);
+        ok = ok && Sq > 0.0 && Sq < 1.0e300;
+    }
+    return ok;
+}
+
+// Guarded streaming pass (any finite or -inf logits): per-thread references that follow the
+// running maximum.  Used when the fast pass reports an overflow or an empty sum.
 template <bool BF16, bool TWO>
 __device__ inline void row_stats(const void *rowp, const void *rowq, int nslots, SharedState &sh,
                                  int parity, const SamplerParams &p, float &Mp, double &Sp,
@@ -234,6 +366,18 @@ __device__ inline void row_stats(const void *rowp, const void *rowq, int nslots,
     if constexpr (TWO) block_combine(tq.ref, tq.total(), sh, parity, 1, p, Mq, Sq);
 }
 
+template <bool BF16, bool TWO, bool ONE_TERM, bool FULL>
+__device__ inline void row_stats_any(const void *rowp, const void *rowq, int nslots, SharedState &sh,
+                                     int parity, const SamplerParams &p, float &Mp, double &Sp,
+                                     float &Mq, double &Sq) {
+    if constexpr (FULL) {
+        if (row_stats_fast<BF16, TWO, ONE_TERM>(rowp, rowq, nslots, sh, parity, p, Mp, Sp, Mq, Sq))
+            return;        // block-uniform
+        __syncthreads();   // every thread has read the combine buffers of this parity
+    }
+    row_stats<BF16, TWO>(rowp, rowq, nslots, sh, parity, p, Mp, Sp, Mq, Sq);
+}
+
 // fp64 weights of one slot: p(x) (RESID = false) or max(0, p(x) - q(x)) (Eq. 2).
 template <bool BF16, bool RESID>
 __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, double Cp, float Mq,
@@ -248,8 +392,7 @@ __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, 
         const double pe = (double)hw_exp2(exp2_arg(zp[j], Mp, p.c_hi, p.c_lo)) * Cp;
         if constexpr (RESID) {
             const double qe = (double)hw_exp2(exp2_arg(zq[j], Mq, p.c_hi, p.c_lo)) * Cq;
-            const double d = pe - qe;
-            w[j] = d > 0.0 ? d : 0.0;
+            w[j] = fmax(pe - qe, 0.0);
         } else {
             w[j] = pe;
         }
@@ -257,9 +400,18 @@ __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, 
 }
 
 // The single final draw of a sequence: first token, in ascending id, whose running sum of
-// weights exceeds u*Z.  Each wave owns a contiguous region of the row; regions are summed,
-// the wave holding the crossing rescans its region with the same operations.
-template <bool BF16, bool RESID>
+// weights exceeds u*Z (all sums in fp64).
+//   phase A  each wave owns a contiguous eighth of the row and streams it with coalesced loads;
+//            lanes keep their own fp64 sums, one reduction per wave gives the region total;
+//   choice   every thread takes the ordered prefix over the region totals and finds the
+//            region that holds the crossing;
+//   phase B  the whole block re-reads that one region, each thread a short contiguous run of
+//            slots: thread totals -> one block scan -> the first thread whose running sum
+//            passes u*Z walks its run element by element.
+// Phase B adds the same numbers in another order than phase A, so at the last bit a crossing
+// can fall off the end of the region; that draw then takes the last token with mass and is
+// flagged as a boundary draw (it is within rounding of a CDF edge).
+template <bool BF16, bool RESID, bool FULL>
 __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int nslots, float Mp,
                                        double Sp, float Mq, double Sq, double u, SharedState &sh,
                                        const SamplerParams &p, int &near_edge, double &Z_out) {
@@ -270,37 +422,53 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     const int span = ((nslots + kWaves - 1) / kWaves + 63) / 64 * 64;
     const int beg = min(wave * span, nslots), end = min(beg + span, nslots);
 
-    // phase A: region totals
-    double running = 0.0;
-    for (int s0 = beg; s0 < end; s0 += 64 * kUnroll) {
-        u32x4 vp[kUnroll], vq[kUnroll];
+    // phase A: region totals (the next batch of slots is in flight while one is summed)
+    double lane_sum = 0.0;
+    auto load_batch = [&](int s0, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) {
 #pragma unroll
         for (int c = 0; c < kUnroll; ++c) {
             const int slot = s0 + c * 64 + lane;
-            vp[c] = slot < end ? load_slot<BF16>(rowp, slot, p.V, aligned) : neg_inf_slot<BF16>();
-            if constexpr (RESID)
-                vq[c] = slot < end ? load_slot<BF16>(rowq, slot, p.V, aligned)
-                                   : neg_inf_slot<BF16>();
-            else
+            const bool in = slot < end;
+            const u32x4 a = load_slot<BF16, FULL>(rowp, in ? slot : beg, p.V, aligned);
+            vp[c] = in ? a : neg_inf_slot<BF16>();
+            if constexpr (RESID) {
+                const u32x4 b = load_slot<BF16, FULL>(rowq, in ? slot : beg, p.V, aligned);
+                vq[c] = in ? b : neg_inf_slot<BF16>();
+            } else {
                 vq[c] = vp[c];
+            }
         }
+    };
+    if (beg < end) {  // wave-uniform
+        u32x4 vp[kUnroll], vq[kUnroll];
+        load_batch(beg, vp, vq);
+        for (int s0 = beg; s0 < end; s0 += 64 * kUnroll) {
+            u32x4 np[kUnroll], nq[kUnroll];
+            const bool more = s0 + 64 * kUnroll < end;
+            if (more) load_batch(s0 + 64 * kUnroll, np, nq);
 #pragma unroll
-        for (int c = 0; c < kUnroll; ++c) {
-            if (s0 + c * 64 < end) {  // wave-uniform
+            for (int c = 0; c < kUnroll; ++c) {
                 double w[EPV];
                 slot_weights<BF16, RESID>(vp[c], vq[c], Mp, Cp, Mq, Cq, p, w);
-                double ls = w[0];
 #pragma unroll
-                for (int j = 1; j < EPV; ++j) ls += w[j];
-                const double incl = wave_inclusive_scan(ls, lane);
-                running += __shfl(incl, 63);
+                for (int j = 0; j < EPV; ++j) lane_sum += w[j];
+            }
+            if (more) {
+#pragma unroll
+                for (int c = 0; c < kUnroll; ++c) {
+                    vp[c] = np[c];
+                    vq[c] = nq[c];
+                }
             }
         }
     }
-    if (lane == 0) sh.wave_total[wave] = running;
+    const double region_total = wave_sum(lane_sum);
+    if (lane == 0) sh.wave_total[wave] = region_total;
     if (threadIdx.x == 0) {
         sh.token = -1;
         sh.near_edge = 0;
+        sh.first_thread = kThreads;
+        sh.last_positive = -1;
     }
     __syncthreads();
 
@@ -328,87 +496,84 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         if (tot > 0.0) wlast = w;
         prefix = next;
     }
-    bool forced = false;
-    if (wstar < 0) {  // u*Z rounded up to Z
-        wstar = wlast;
-        forced = true;
-    }
+    const bool forced = wstar < 0;  // u*Z rounded up to Z: take the last token with mass
+    if (forced) wstar = wlast;
 
-    // phase B: the owning wave walks its region again
-    if (wave == wstar) {
-        double run = base;
-        int found = -1, edge = forced ? 1 : 0, last_pos = -1;
-        for (int s0 = beg; s0 < end && found < 0; s0 += 64) {
-            const int slot = s0 + lane;
-            const u32x4 vp = slot < end ? load_slot<BF16>(rowp, slot, p.V, aligned)
-                                        : neg_inf_slot<BF16>();
+    // phase B: the block walks region wstar; thread i owns slots [rb + i*per, rb + (i+1)*per)
+    const int rb = min(wstar * span, nslots), re = min(rb + span, nslots);
+    const int per = (re - rb + kThreads - 1) / kThreads;  // <= 5 for a 151,936-wide bf16 row
+    const int my0 = rb + threadIdx.x * per, my1 = min(my0 + per, re);
+    double my_total = 0.0;
+    int my_last = -1;
+    for (int slot = my0; slot < my1; ++slot) {
+        const u32x4 vp = load_slot<BF16, FULL>(rowp, slot, p.V, aligned);
+        u32x4 vq = vp;
+        if constexpr (RESID) vq = load_slot<BF16, FULL>(rowq, slot, p.V, aligned);
+        double w[EPV];
+        slot_weights<BF16, RESID>(vp, vq, Mp, Cp, Mq, Cq, p, w);
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) {
+            my_total += w[j];
+            if (w[j] > 0.0) my_last = slot * EPV + j;
+        }
+    }
+    const double incl_wave = wave_inclusive_scan(my_total, lane);
+    if (lane == 63) sh.scan_total[wave] = incl_wave;
+    __syncthreads();
+    double before_wave = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w)
+        if (w < wave) before_wave += sh.scan_total[w];
+    const double run_incl = base + (before_wave + incl_wave);
+    const double run_excl = base + (before_wave + (incl_wave - my_total));
+    if (!forced && run_incl > t && my_total > 0.0) atomicMin(&sh.first_thread, (int)threadIdx.x);
+    if (my_last >= 0) atomicMax(&sh.last_positive, my_last);
+    __syncthreads();
+    if ((int)threadIdx.x == sh.first_thread) {  // at most one thread
+        double c = run_excl;
+        int tok = -1, edge = 0;
+        double before = c, after = c;
+        for (int slot = my0; slot < my1 && tok < 0; ++slot) {
+            const u32x4 vp = load_slot<BF16, FULL>(rowp, slot, p.V, aligned);
             u32x4 vq = vp;
-            if constexpr (RESID)
-                vq = slot < end ? load_slot<BF16>(rowq, slot, p.V, aligned) : neg_inf_slot<BF16>();
+            if constexpr (RESID) vq = load_slot<BF16, FULL>(rowq, slot, p.V, aligned);
             double w[EPV];
             slot_weights<BF16, RESID>(vp, vq, Mp, Cp, Mq, Cq, p, w);
-            double ls = w[0];
-            int lp = w[0] > 0.0 ? slot * EPV : -1;
 #pragma unroll
-            for (int j = 1; j < EPV; ++j) {
-                ls += w[j];
-                if (w[j] > 0.0) lp = slot * EPV + j;
-            }
-            const double incl = wave_inclusive_scan(ls, lane);
-            double excl = __shfl_up(incl, 1);
-            if (lane == 0) excl = 0.0;
-            const unsigned long long crossing = __ballot(!forced && (run + incl > t));
-            if (crossing) {
-                const int src = __ffsll((long long)crossing) - 1;
-                if (lane == src) {
-                    double c = run + excl;
-                    int tok = -1;
-                    double before = c, after = c;
-#pragma unroll
-                    for (int j = 0; j < EPV; ++j) {
-                        if (tok < 0) {
-                            const double cn = c + w[j];
-                            if (cn > t) {
-                                tok = slot * EPV + j;
-                                before = c;
-                                after = cn;
-                            }
-                            c = cn;
-                        }
+            for (int j = 0; j < EPV; ++j) {
+                if (tok < 0) {
+                    const double cn = c + w[j];
+                    if (cn > t) {
+                        tok = slot * EPV + j;
+                        before = c;
+                        after = cn;
                     }
-                    if (tok < 0) {  // association differences at the last bit
-                        tok = lp;
-                        edge = 1;
-                    } else {
-                        const double lo = fabs(t - before), hi = fabs(after - t);
-                        if (fmin(lo, hi) <= kBoundaryEps * Z) edge = 1;
-                    }
-                    sh.token = tok;
-                    sh.near_edge = edge;
+                    c = cn;
                 }
-                found = 1;
-            } else {
-                // remember the last token with mass in case the walk ends without a crossing
-                int best = lp;
-#pragma unroll
-                for (int o = 32; o >= 1; o >>= 1) best = max(best, __shfl_xor(best, o));
-                last_pos = max(last_pos, best);
-                run += __shfl(incl, 63);
             }
         }
-        if (found < 0 && lane == 0) {
-            sh.token = last_pos;
-            sh.near_edge = 1;
+        if (tok < 0) {  // the thread's own walk rounds differently from the block scan
+            tok = my_last;
+            edge = 1;
+        } else {
+            const double lo = fabs(t - before), hi = fabs(after - t);
+            if (fmin(lo, hi) <= kBoundaryEps * Z) edge = 1;
         }
+        sh.token = tok;
+        sh.near_edge = edge;
     }
     __syncthreads();
-    const int tok = sh.token;
+    int tok = sh.token;
     near_edge = sh.near_edge;
+    if (tok < 0) {  // no thread saw the crossing (forced, or it fell off the region's end)
+        tok = sh.last_positive;
+        near_edge = 1;
+    }
     __syncthreads();
     return tok;
 }
 
-template <bool BF16>
+template <bool BF16, bool ONE_TERM, bool FULL>
 __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParams p) {
     __shared__ SharedState sh;
     constexpr int EPV = Elem<BF16>::EPV;
@@ -429,12 +594,15 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
 
     int n = 0, flag_accept = 0, flag_cdf = 0, final_token = -1;
     bool rejected = false;
+    const void *scan_row = tbase;  // row, reference and sum of the final inverse-CDF walk over p
+    float scan_M = 0.f;
+    double scan_S = 1.0;
     for (int i = 0; i < k; ++i) {
         const void *rowp = tbase + (size_t)(row0 + i) * p.ld_t * esz;
         const void *rowq = dbase + (size_t)(drow0 + i) * p.ld_d * esz;
         float Mp, Mq;
         double Sp, Sq;
-        row_stats<BF16, true>(rowp, rowq, nslots, sh, i & 1, p, Mp, Sp, Mq, Sq);
+        row_stats_any<BF16, true, ONE_TERM, FULL>(rowp, rowq, nslots, sh, i & 1, p, Mp, Sp, Mq, Sq);
         int x = p.draft_tokens[drow0 + i];
         x = max(0, min(x, p.V - 1));  // memory safety only; ids outside [0,V) are a caller error
         float zpx, zqx;
@@ -463,27 +631,32 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         // first rejection: one draw from the residual distribution (Eq. 2)
         double Z;
         int edge = 0;
-        final_token = inverse_cdf_pass<BF16, true>(rowp, rowq, nslots, Mp, Sp, Mq, Sq, u_fin, sh, p,
-                                                   edge, Z);
-        if (final_token < 0) {  // empty residual (exact tie): fall back to the target itself
-            final_token = inverse_cdf_pass<BF16, false>(rowp, rowp, nslots, Mp, Sp, Mp, Sp, u_fin,
-                                                        sh, p, edge, Z);
-            edge = 1;
-        }
+        final_token = inverse_cdf_pass<BF16, true, FULL>(rowp, rowq, nslots, Mp, Sp, Mq, Sq, u_fin, sh,
+                                                         p, edge, Z);
         flag_cdf = edge;
         rejected = true;
+        scan_row = rowp;
+        scan_M = Mp;
+        scan_S = Sp;
         break;
     }
+    bool scan_target = false;
     if (!rejected) {  // every draft accepted (or none offered): bonus token from target row k
-        const void *rowp = tbase + (size_t)(row0 + k) * p.ld_t * esz;
-        float Mp, Mq;
-        double Sp, Sq;
-        row_stats<BF16, false>(rowp, rowp, nslots, sh, k & 1, p, Mp, Sp, Mq, Sq);
+        scan_row = tbase + (size_t)(row0 + k) * p.ld_t * esz;
+        float Mq;
+        double Sq;
+        row_stats_any<BF16, false, ONE_TERM, FULL>(scan_row, scan_row, nslots, sh, k & 1, p, scan_M, scan_S,
+                                                   Mq, Sq);
+        scan_target = true;
+    } else if (final_token < 0) {  // empty residual (an exact tie): fall back to the target itself
+        scan_target = true;
+    }
+    if (scan_target) {
         double Z;
         int edge = 0;
-        final_token = inverse_cdf_pass<BF16, false>(rowp, rowp, nslots, Mp, Sp, Mp, Sp, u_fin, sh, p,
-                                                    edge, Z);
-        flag_cdf = edge;
+        final_token = inverse_cdf_pass<BF16, false, FULL>(scan_row, scan_row, nslots, scan_M, scan_S,
+                                                          scan_M, scan_S, u_fin, sh, p, edge, Z);
+        flag_cdf = rejected ? 1 : edge;
     }
     if (final_token < 0) final_token = p.V - 1;  // row without any finite logit
     if (threadIdx.x == 0) {
@@ -557,16 +730,28 @@ respec_status_t respec_rejection_sample(const void *target_logits, const void *d
     if ((double)c_hi >= p.c_d) c_hi = std::nextafterf(c_hi, 0.f);  // keep the low term positive
     p.c_hi = c_hi;
     p.c_lo = (float)(p.c_d - (double)c_hi);
+    p.c_f = (float)p.c_d;
+    p.one_term = std::fabs((double)p.c_f / p.c_d - 1.0) <= 2.0e-8 ? 1 : 0;
+    if (env_long("RESPEC_SAMPLER_TWO_TERM", 0) != 0) p.one_term = 0;
     p.inv_T = 1.0 / T;
     p.gap = (float)(40.0 / p.c_d);
     p.aligned = aligned_to(target_logits, 16) && (ld_t * esz) % 16 == 0 &&
                 (!has_drafts || (aligned_to(draft_logits, 16) && (ld_d * esz) % 16 == 0));
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (logits_dt == RESPEC_BF16)
-        hipLaunchKernelGGL(rejection_sample_kernel<true>, dim3(B), dim3(kThreads), 0, stream, p);
-    else
-        hipLaunchKernelGGL(rejection_sample_kernel<false>, dim3(B), dim3(kThreads), 0, stream, p);
+    const int epv = logits_dt == RESPEC_BF16 ? 8 : 4;
+    const bool full = p.aligned && V % epv == 0 && env_long("RESPEC_SAMPLER_GUARDED", 0) == 0;
+    const bool bf = logits_dt == RESPEC_BF16, one = p.one_term != 0;
+#define RESPEC_LAUNCH_SAMPLER(BF, ONE, FULL) \
+    hipLaunchKernelGGL((rejection_sample_kernel<BF, ONE, FULL>), dim3(B), dim3(kThreads), 0, stream, p)
+    if (!full) {
+        if (bf) RESPEC_LAUNCH_SAMPLER(true, false, false); else RESPEC_LAUNCH_SAMPLER(false, false, false);
+    } else if (bf) {
+        if (one) RESPEC_LAUNCH_SAMPLER(true, true, true); else RESPEC_LAUNCH_SAMPLER(true, false, true);
+    } else {
+        if (one) RESPEC_LAUNCH_SAMPLER(false, true, true); else RESPEC_LAUNCH_SAMPLER(false, false, true);
+    }
+#undef RESPEC_LAUNCH_SAMPLER
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess)
         return fail(RESPEC_ERR_HIP, "rejection_sample: launch failed: %s", hipGetErrorString(err));

@@ -82,6 +82,29 @@ def test_identical_drafter_accepts_everything(oracle):
     assert gpu[1].tolist() == ks
 
 
+@pytest.mark.parametrize("env", ["RESPEC_SAMPLER_GUARDED", "RESPEC_SAMPLER_TWO_TERM"])
+def test_alternative_normaliser_passes_agree(oracle, env, monkeypatch):
+    # the guarded pass (running per-thread references) and the two-term exponent are the paths
+    # taken for unaligned rows / temperatures whose log2(e)/T rounds badly; force them here
+    monkeypatch.setenv(env, "1")
+    wl = _wl("alt", 151936, "bf16", sigma=1.0)
+    _parity(oracle, _batch(wl, [3] * 16, seed=21))
+
+
+def test_huge_outlier_logit_takes_the_guarded_pass(oracle):
+    # one logit far above a wave's first slots overflows the fast pass, which must then be
+    # repeated with the guarded one; -inf runs at the row start leave a wave without reference
+    wl = _wl("outlier", 151936, "bf16", sigma=1.0)
+    batch = _batch(wl, [2] * 8, seed=22)
+    batch.target_logits[0, 100000] = 400.0
+    batch.draft_logits[1, 77] = 300.0
+    batch.target_logits[3, :40000] = float("-inf")
+    batch.draft_logits[2, :40000] = float("-inf")
+    batch.target_logits[5, 5] = 250.0
+    batch.draft_logits[4, 5] = 250.0
+    gpu, ref, _ = _parity(oracle, batch)
+
+
 def test_no_drafts_at_all_is_plain_sampling(oracle):
     wl = _wl("k0", 32000, "bf16")
     gpu, ref, _ = _parity(oracle, _batch(wl, [0] * 64, seed=7))
