@@ -101,6 +101,24 @@ __device__ inline SeqInfo seq_info(const AttnParams &p, int b) {
 
 __device__ inline float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Partner values across the four 16-lane rows of a wave, through the gfx950 lane-swap
+// instructions (no LDS round trip).  With both operands equal to x, v_permlane32_swap leaves
+// in the two results the lane's own value and the value of lane ^ 32; v_permlane16_swap does
+// the same for lane ^ 16.
+__device__ inline float max_across_rows(float x) {
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+__device__ inline float sum_across_rows(float x) {
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 // Work-group w owns flat tiles [w*total/W, (w+1)*total/W); the owner of flat tile x:
 __device__ inline int owner_of_tile(int64_t x, int64_t total, int W) {
     return (int)(((x + 1) * W - 1) / total);
@@ -310,15 +328,18 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
                 // tile of the next segment (one load site; the choice is wave-uniform)
                 const int next0 = key0 + kGroupKeys;
                 const bool more_here = next0 < k_end;
-                if (more_here || next_tile_mine) {
-                    const char *src_k = more_here ? kbase : next_kbase;
-                    const char *src_v = more_here ? vbase : next_vbase;
-                    const int src_key = more_here ? next0 : wave * kTileKeys;
-                    const int src_last = more_here ? last_key : ni.L - 1;
+                const bool refill = more_here || next_tile_mine;
+                const char *src_k = more_here ? kbase : next_kbase;
+                const char *src_v = more_here ? vbase : next_vbase;
+                const int src_key = more_here ? next0 : wave * kTileKeys;
+                const int src_last = more_here ? last_key : ni.L - 1;
+                // the K half is requested now, the V half after the score products: two short
+                // bursts keep the memory pipeline fed more evenly than one long one
+                if (refill) {
                     load_tile<D>(kr, src_k, row_bytes, src_key, src_last, lane);
-                    load_tile<D>(vr, src_v, row_bytes, src_key, src_last, lane);
                     prefetched = !more_here;
                 }
+                __builtin_amdgcn_sched_barrier(0);
 
             // S^T[key, col] = sum_d K[key, d] Q[col, d]; two 16-key sub-tiles
             floatx4 s_acc[NT][2];
@@ -338,6 +359,9 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
                 }
             }
 
+            __builtin_amdgcn_sched_barrier(0);
+            if (refill) load_tile<D>(vr, src_v, row_bytes, src_key, src_last, lane);
+            __builtin_amdgcn_sched_barrier(0);
             // online softmax per column; accumulator element (js, i) is key key0 + 16 js + 4 g4 + i
             const bool tail = key0 + kTileKeys > first_masked_key;  // wave-uniform
             bf16x8 pfrag[NT];
@@ -359,8 +383,7 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
                     }
                 float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
                                    fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+                mloc = max_across_rows(mloc);
                 const float mnew = fmaxf(m_run[nt], mloc);
                 const float msafe = mnew == -INFINITY ? 0.f : mnew;
                 alpha[nt] = hw_exp2(m_run[nt] - msafe);
@@ -434,9 +457,7 @@ __global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_
         // ---- merge the four waves --------------------------------------------------------------
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            float l = l_run[nt];
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
+            const float l = sum_across_rows(l_run[nt]);
             l_run[nt] = l;
             if (g4 == 0) {
                 sh_m[wave * kMaxColsPerBlock + nt * kColTile + c16] = m_run[nt];
