@@ -37,16 +37,17 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kWaves = 4;             // waves per work-group (bf16 path)
-constexpr int kThreads = kWaves * 64;
 constexpr int kTileKeys = 32;         // keys per wave tile
-constexpr int kGroupKeys = kWaves * kTileKeys;  // keys per work-group tile (the unit of the split)
 constexpr int kColTile = 16;          // query rows per MFMA column tile
 constexpr int kMaxColsPerBlock = 64;  // 4 column tiles
-constexpr int kMaxWgs = 1024;         // upper bound of the split width (sizes the workspace)
+constexpr float kRescaleSlack = 8.f;  // log2 units
+constexpr int kConsumers = 4;         // computing waves per work-group (one per SIMD), each with a
+                                      // producer wave; one work-group per compute unit
+constexpr int kSlots = 2;             // tiles in a pair's LDS ring = tiles a producer keeps in flight
+constexpr int kMaxWaves = 2048;       // upper bound of the split width (sizes the workspace)
 
-// Where a work-group's range of the flat tile list starts, and how many tiles it holds.
-struct __align__(16) WgStart {
+// Where a wave's range of the flat tile list starts, and how many tiles it holds.
+struct __align__(16) WaveStart {
     int32_t h, b, t, n;
 };
 
@@ -60,13 +61,18 @@ struct AttnParams {
     float *lse;
     float *ws_o;           // [2*W, Mpad, D]   unnormalised partial outputs
     float *ws_ml;          // [2*W, Mpad, 2]   (max in log2 units, sum)
-    int32_t *tile_prefix;  // [B+1] prefix sum of ceil(L_b / kGroupKeys)
-    WgStart *wg_start;     // [W]
+    int32_t *tile_prefix;  // [B+1] prefix sum of ceil(L_b / kTileKeys)
+    WaveStart *wave_start; // [W]
     int32_t B, total_q;
     int64_t total_kv;
     int32_t max_q, max_kv_len;
     int32_t Hq, Hkv, G;
-    int32_t W;             // work-groups the tile list is split over
+    int32_t W;             // waves the tile list is split over
+    int32_t HI;            // KV-head interleave: the HI waves u with equal u / HI (waves of one
+                           // work-group) walk the same keys of different heads, so that the
+                           // pieces of a cache row are requested together (HI divides W, Hkv
+                           // and the waves of a work-group; 1 = one head-major list)
+    int32_t *error_flag;   // set to 1 by a wave whose bounded wait for its partner ran out
     int32_t Mpad;          // G*max_q rounded up to kColTile
     float scale2;          // sm_scale * log2(e)
 };
@@ -75,27 +81,41 @@ struct SeqInfo {
     int32_t q0, R;
     int64_t kv0;
     int32_t L;
-    int32_t tiles;  // ceil(L / kGroupKeys), 0 for a sequence without rows
+    int32_t tiles;  // ceil(L / kTileKeys), 0 for a sequence without rows
 };
+
+// The index arrays are read-only for the whole launch.  Reading them through the constant
+// address space lets a wave-uniform index become a scalar load, which does not count as a
+// vector memory request: a look-up in the middle of the tile stream then waits for itself
+// only, not for every tile request in flight.
+template <typename T>
+using ConstPtr = const T __attribute__((address_space(4))) *;
+
+template <typename T>
+__device__ inline ConstPtr<T> as_constant(const T *ptr) {
+    return (ConstPtr<T>)ptr;
+}
 
 // Per-sequence bounds, clamped by the host-side totals so that no device data can push an
 // access outside the buffers.
 __device__ inline SeqInfo seq_info(const AttnParams &p, int b) {
     SeqInfo s;
-    s.q0 = p.q_indptr[b];
-    int32_t R = p.q_indptr[b + 1] - s.q0;
+    const ConstPtr<int32_t> q_indptr = as_constant(p.q_indptr);
+    const ConstPtr<int64_t> kv_indptr = as_constant(p.kv_indptr);
+    s.q0 = q_indptr[b];
+    int32_t R = q_indptr[b + 1] - s.q0;
     s.q0 = max(0, min(s.q0, p.total_q));
     R = max(0, min(R, min(p.max_q, p.total_q - s.q0)));
     s.R = R;
-    int64_t kv0 = p.kv_indptr[b];
-    int64_t L = p.kv_indptr[b + 1] - kv0;
+    int64_t kv0 = kv_indptr[b];
+    int64_t L = kv_indptr[b + 1] - kv0;
     kv0 = kv0 < 0 ? 0 : (kv0 > p.total_kv ? p.total_kv : kv0);
     if (L > p.total_kv - kv0) L = p.total_kv - kv0;
     if (L > p.max_kv_len) L = p.max_kv_len;
     if (L < 0) L = 0;
     s.kv0 = kv0;
     s.L = (int32_t)L;
-    s.tiles = R > 0 ? (s.L + kGroupKeys - 1) / kGroupKeys : 0;
+    s.tiles = R > 0 ? (s.L + kTileKeys - 1) / kTileKeys : 0;
     return s;
 }
 
@@ -119,16 +139,34 @@ __device__ inline float sum_across_rows(float x) {
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// Work-group w owns flat tiles [w*total/W, (w+1)*total/W); the owner of flat tile x:
-__device__ inline int owner_of_tile(int64_t x, int64_t total, int W) {
-    return (int)(((x + 1) * W - 1) / total);
+// The split.  The KV heads form HI sub-lists of Hkv/HI heads; a sub-list is the flat tile list
+// (head, sequence, tile) of its heads, `sub_total` tiles long, cut evenly into W/HI parts.
+// Wave u takes part u / HI of sub-list u % HI.  Part r owns flat tiles
+// [r*sub_total/parts, (r+1)*sub_total/parts) of its sub-list.
+struct Split {
+    int64_t T;           // tiles of one KV head
+    int64_t sub_total;   // tiles of one sub-list
+    int32_t parts, hps;  // parts per sub-list, heads per sub-list
+};
+
+__device__ inline Split make_split(const AttnParams &p, int64_t T) {
+    Split s;
+    s.T = T;
+    s.hps = p.Hkv / p.HI;
+    s.sub_total = T * s.hps;
+    s.parts = p.W / p.HI;
+    return s;
 }
 
-__device__ inline bool owns_tiles(int w, int64_t total, int W) {
-    return (int64_t)(w + 1) * total / W > (int64_t)w * total / W;
+__device__ inline int part_of_tile(const Split &s, int64_t x) {  // x: flat index in the sub-list
+    return (int)(((x + 1) * s.parts - 1) / s.sub_total);
 }
 
-// Builds the tile prefix over sequences and every work-group's starting point.
+__device__ inline bool part_owns_tiles(const Split &s, int r) {
+    return (int64_t)(r + 1) * s.sub_total / s.parts > (int64_t)r * s.sub_total / s.parts;
+}
+
+// Builds the tile prefix over sequences and every wave's starting point.
 __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     __shared__ int sh_scan[1024];
     __shared__ int sh_base;
@@ -136,6 +174,7 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     if (tid == 0) {
         sh_base = 0;
         p.tile_prefix[0] = 0;
+        *p.error_flag = 0;
     }
     __syncthreads();
     for (int b0 = 0; b0 < p.B; b0 += 1024) {
@@ -155,14 +194,15 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
         if (tid == 1023) sh_base = base + sh_scan[1023];
         __syncthreads();
     }
-    const int64_t T = sh_base;               // tiles of one KV head
-    const int64_t total = T * p.Hkv;
+    const Split sp = make_split(p, sh_base);
+    const int64_t T = sp.T;
     for (int w = tid; w < p.W; w += 1024) {
-        WgStart st{0, 0, 0, 0};
-        if (total > 0) {
-            const int64_t a0 = (int64_t)w * total / p.W, a1 = (int64_t)(w + 1) * total / p.W;
+        WaveStart st{0, 0, 0, 0};
+        if (T > 0) {
+            const int r = w / p.HI, sub = w % p.HI;
+            const int64_t a0 = (int64_t)r * sp.sub_total / sp.parts, a1 = (int64_t)(r + 1) * sp.sub_total / sp.parts;
             st.n = (int32_t)(a1 - a0);
-            st.h = (int32_t)(a0 / T);
+            st.h = sub * sp.hps + (int32_t)(a0 / T);
             const int32_t rem = (int32_t)(a0 % T);
             int lo = 0, hi = p.B - 1;          // last b with tile_prefix[b] <= rem
             while (lo < hi) {
@@ -172,7 +212,7 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
             st.b = lo;
             st.t = rem - p.tile_prefix[lo];
         }
-        p.wg_start[w] = st;
+        p.wave_start[w] = st;
     }
 }
 
@@ -195,20 +235,26 @@ struct Bf16Cfg {
 };
 
 // One 32-key tile of one KV head: kLoads 16-byte loads per lane, rows row_bytes apart.
-// `base` and `key0` are wave-uniform, so a load is (scalar tile base) + (32-bit per-lane
-// offset).  Rows past `last_key` re-read the last valid row (they are masked later): the
-// clamp is on the row index relative to the tile, two VALU operations per load.
+// `tile` (the address of the tile's first row) is wave-uniform, so a load is (scalar base) +
+// (32-bit per-lane offset).  A tile that lies wholly inside its sequence uses the offsets
+// row_off[] computed once per kernel.  In a sequence's last, partial tile the rows past
+// `rows_valid` re-read the last valid row (they are masked later): the clamp is on the row
+// index relative to the tile, two VALU operations per load.  rows_valid = 0 turns the whole
+// request into one 256-byte piece.  Both forms issue the same number of loads.
 template <int D>
-__device__ inline void load_tile(u32x4 (&r)[Bf16Cfg<D>::kLoads], const char *base, int32_t row_bytes,
-                                 int key0, int last_key, int lane) {
+__device__ inline void load_tile(u32x4 (&r)[Bf16Cfg<D>::kLoads], const char *tile, int32_t row_bytes,
+                                 const uint32_t (&row_off)[Bf16Cfg<D>::kLoads], int rows_valid, int lane) {
     using C = Bf16Cfg<D>;
-    const uint32_t rl = lane / C::kLanesPerRow, cl16 = (lane % C::kLanesPerRow) * 16;
-    const char *tile = base + (int64_t)key0 * row_bytes;
-    const uint32_t rows_valid = (uint32_t)(last_key - key0);  // >= 0: the tile starts inside the sequence
+    if (rows_valid >= kTileKeys - 1) {  // wave-uniform
 #pragma unroll
-    for (int j = 0; j < C::kLoads; ++j) {
-        const uint32_t row = min(rl + (uint32_t)(j * C::kRowsPerLoad), rows_valid);
-        r[j] = *reinterpret_cast<const u32x4 *>(tile + (row * (uint32_t)row_bytes + cl16));
+        for (int j = 0; j < C::kLoads; ++j) r[j] = *reinterpret_cast<const u32x4 *>(tile + row_off[j]);
+    } else {
+        const uint32_t rl = lane / C::kLanesPerRow, cl16 = (lane % C::kLanesPerRow) * 16;
+#pragma unroll
+        for (int j = 0; j < C::kLoads; ++j) {
+            const uint32_t row = min(rl + (uint32_t)(j * C::kRowsPerLoad), (uint32_t)rows_valid);
+            r[j] = *reinterpret_cast<const u32x4 *>(tile + (row * (uint32_t)row_bytes + cl16));
+        }
     }
 }
 
@@ -221,360 +267,423 @@ __device__ inline void store_tile(const u32x4 (&r)[Bf16Cfg<D>::kLoads], char *ld
         *reinterpret_cast<u32x4 *>(lds + (j * C::kRowsPerLoad + rl) * C::kRowBytes + cl * 16) = r[j];
 }
 
+// Position of a wave in the flat tile list.  The bounds of the next sequence that has tiles
+// are fetched as soon as a sequence is entered, long before they are needed.
+struct Cursor {
+    int32_t b, h, t;  // sequence, KV head, tile within the sequence
+    SeqInfo si;       // bounds of b
+    int32_t nb, nh;   // next (sequence, KV head) with tiles; nh == Hkv: the list ends
+    SeqInfo nsi;
+};
+
+__device__ inline void cursor_find_next(const AttnParams &p, Cursor &c) {
+    c.nb = c.b;
+    c.nh = c.h;
+    for (;;) {
+        if (++c.nb >= p.B) {
+            c.nb = 0;
+            ++c.nh;
+        }
+        if (c.nh >= p.Hkv) return;
+        c.nsi = seq_info(p, c.nb);
+        if (c.nsi.tiles > 0) return;
+    }
+}
+
+__device__ inline void cursor_advance(const AttnParams &p, Cursor &c) {
+    if (c.t + 1 < c.si.tiles) {
+        ++c.t;
+        return;
+    }
+    c.b = c.nb;
+    c.h = c.nh;
+    c.si = c.nsi;
+    c.t = 0;
+    if (c.h < p.Hkv) cursor_find_next(p, c);
+}
+
+template <int N>
+struct Const {
+    static constexpr int value = N;
+};
+
+// Waits of the tile hand-over.  `flag` is a counter in LDS that only the partner wave
+// advances.  The spin is bounded: when the bound is hit the wave records the failure (the
+// combine kernel then poisons the output) and stops waiting for the rest of the launch, so
+// that every wave reaches its end whatever happens.
+constexpr int kSpinLimit = 1 << 24;
+
+// The counters are addressed as LDS explicitly: through a generic pointer every poll would be
+// a flat load, which counts as (and waits for) vector memory traffic.
+typedef volatile uint32_t __attribute__((address_space(3))) *LdsCounter;
+
+__device__ inline void wait_at_least(LdsCounter flag, uint32_t need, bool &alive, int32_t *error_flag) {
+    if (!alive) return;
+    for (int spin = 0; spin < kSpinLimit; ++spin) {
+        if (*flag >= need) return;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    alive = false;
+    *error_flag = 1;
+}
+
+// One work-group per compute unit: four consumer waves (one per SIMD) and four producer
+// waves.  Consumer i owns an equal range of the flat tile list; producer i walks the same
+// range ahead of it and does nothing but move tiles: global memory -> registers (two tiles in
+// flight) -> the pair's two-slot ring in LDS.  A wave that computes cannot keep the memory
+// pipeline of its compute unit full (a request can only be issued between two tiles' worth of
+// arithmetic, and the unit accepts only a few tiles' worth of requests at a time), a wave that
+// only moves data can.  The pair shares two counters in LDS: `filled` (tiles the producer has
+// written) and `consumed` (tiles the consumer has finished reading).  A wave's LDS operations
+// execute in order, so a counter written after the data (or after the last read) needs no
+// further fence.
 template <int D, int NT, typename OutT>
-__global__ __launch_bounds__(kThreads, (D == 128 && NT >= 3) ? 1 : 2) void attn_bf16_kernel(AttnParams p) {
+__global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnParams p) {
     using C = Bf16Cfg<D>;
-    extern __shared__ __align__(16) char smem[];
-    // layout: [kWaves][kWaveBytes] tiles | stats
-    float *sh_m = reinterpret_cast<float *>(smem + kWaves * C::kWaveBytes);  // [kWaves][64]
-    float *sh_l = sh_m + kWaves * kMaxColsPerBlock;                           // [kWaves][64]
-    float *sh_mt = sh_l + kWaves * kMaxColsPerBlock;                          // [64]
-    float *sh_lt = sh_mt + kMaxColsPerBlock;                                  // [64]
+    extern __shared__ __align__(16) char smem[];  // [kConsumers][kSlots][kWaveBytes] | counters
+    const LdsCounter counters = (LdsCounter)(smem + kConsumers * kSlots * C::kWaveBytes);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform by construction
+    const bool producer = wave >= kConsumers;
+    const int pair = producer ? wave - kConsumers : wave;
     const int c16 = lane & 15, g4 = lane >> 4;
-    const int wg = blockIdx.x;
+    const int u = blockIdx.x * kConsumers + pair;  // index of this pair in the split
     const int col0 = blockIdx.y * kMaxColsPerBlock;
 
-    const WgStart st = p.wg_start[wg];
-    int kvh = st.h, b = st.b, t_first = st.t, n_left = st.n;
-    if (n_left <= 0 || kvh >= p.Hkv) return;  // block-uniform
-    SeqInfo si = seq_info(p, b);
+    if (threadIdx.x < 2 * kConsumers) counters[threadIdx.x] = 0;
+    __syncthreads();  // the only barrier, before any wave can leave
+    const LdsCounter filled = counters + pair;
+    const LdsCounter consumed = counters + kConsumers + pair;
 
-    char *k_lds = smem + wave * C::kWaveBytes;
-    char *v_lds = k_lds + C::kTileBytes;
+    if (u >= p.W) return;  // wave-uniform, and the same for both waves of a pair
+    const ConstPtr<int32_t> start = as_constant(reinterpret_cast<const int32_t *>(p.wave_start + u));
+    const WaveStart st{start[0], start[1], start[2], start[3]};
+    const int n_tiles = st.n;
+    if (n_tiles <= 0 || st.h >= p.Hkv) return;
+
+    char *ring = smem + pair * (kSlots * C::kWaveBytes);
     const int32_t row_bytes = p.Hkv * D * 2;
-    u32x4 kr[C::kLoads], vr[C::kLoads];
-    bool prefetched = false;  // kr/vr hold (or await) this wave's first tile of the segment at hand
+    bool alive = true;
 
-    for (;;) {  // one segment = a run of tiles of one (sequence, KV head)
-        const int seg_tiles = max(0, min(n_left, si.tiles - t_first));
-        const int k_begin = t_first * kGroupKeys;
-        const int k_end = min(si.L, (t_first + seg_tiles) * kGroupKeys);
-        const int last_key = si.L - 1;
-        const bool whole = t_first == 0 && seg_tiles == si.tiles;
-        const char *kbase = static_cast<const char *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
-        const char *vbase = static_cast<const char *>(p.v) + (si.kv0 * p.Hkv + kvh) * (int64_t)(D * 2);
-        const int key_first = k_begin + wave * kTileKeys;
-        if (!prefetched && key_first < k_end) {
-            load_tile<D>(kr, kbase, row_bytes, key_first, last_key, lane);
-            load_tile<D>(vr, vbase, row_bytes, key_first, last_key, lane);
+    Cursor cp;  // position of this wave in its range
+    cp.b = st.b;
+    cp.h = st.h;
+    cp.t = st.t;
+    cp.si = seq_info(p, st.b);
+    cursor_find_next(p, cp);
+
+    if (producer) {
+        // ------------------------------------------------------------------------------------
+        // producer: tile j travels through register buffer j % 2 into ring slot j % 2
+        // ------------------------------------------------------------------------------------
+        uint32_t row_off[C::kLoads];  // byte offset of this lane's piece of each load, full tiles
+#pragma unroll
+        for (int j = 0; j < C::kLoads; ++j)
+            row_off[j] = (uint32_t)(lane / C::kLanesPerRow + j * C::kRowsPerLoad) * (uint32_t)row_bytes +
+                         (uint32_t)(lane % C::kLanesPerRow) * 16u;
+        u32x4 kr[kSlots][C::kLoads], vr[kSlots][C::kLoads];
+        int requested = 0;
+        // Every step issues its tile requests, also when the range has no tile left: the count
+        // of requests behind a buffer's own is then the same on every path, and the wait for a
+        // buffer leaves exactly the younger ones in flight.  An idle request re-reads one
+        // 256-byte piece of the last tile, which the caches hold.
+        auto request = [&](auto S) __attribute__((always_inline)) {
+            constexpr int s = decltype(S)::value;
+            const bool live = requested < n_tiles;
+            const int64_t tile_off = (cp.si.kv0 * p.Hkv + cp.h) * (int64_t)(D * 2) + (int64_t)(cp.t * kTileKeys) * row_bytes;
+            const int rows_valid = live ? cp.si.L - 1 - cp.t * kTileKeys : 0;
+            load_tile<D>(kr[s], static_cast<const char *>(p.k) + tile_off, row_bytes, row_off, rows_valid, lane);
+            load_tile<D>(vr[s], static_cast<const char *>(p.v) + tile_off, row_bytes, row_off, rows_valid, lane);
+            if (live) {
+                if (requested + 1 < n_tiles) cursor_advance(p, cp);
+                ++requested;
+            }
+        };
+        auto move = [&](auto S, const int j) __attribute__((always_inline)) {
+            constexpr int s = decltype(S)::value;
+            if (j < n_tiles) {
+                // slot s is free once tile j - 2 has been read
+                if (j >= kSlots) wait_at_least(consumed, (uint32_t)(j - kSlots + 1), alive, p.error_flag);
+                asm volatile("" ::: "memory");
+                char *slot = ring + s * C::kWaveBytes;
+                store_tile<D>(kr[s], slot, lane);
+                store_tile<D>(vr[s], slot + C::kTileBytes, lane);
+                asm volatile("" ::: "memory");
+                *filled = (uint32_t)(j + 1);
+            }
+            request(S);
+        };
+        request(Const<0>{});
+        request(Const<1>{});
+        for (int j = 0; j < n_tiles; j += kSlots) {
+            move(Const<0>{}, j);
+            move(Const<1>{}, j + 1);
         }
-        prefetched = false;
+        return;
+    }
 
-        // the segment after this one (same KV head, next sequence with keys; then the next head)
-        const int n_after = n_left - seg_tiles;
-        int nb = b, nh = kvh;
-        SeqInfo ni = si;
-        bool have_next = false;
-        if (n_after > 0) {
-            for (;;) {
-                if (++nb >= p.B) {
-                    nb = 0;
-                    ++nh;
-                }
-                if (nh >= p.Hkv) break;
-                ni = seq_info(p, nb);
-                if (ni.tiles > 0) {
-                    have_next = true;
-                    break;
-                }
+    // ----------------------------------------------------------------------------------------
+    // consumer
+    // ----------------------------------------------------------------------------------------
+    // this lane's columns: query row i and head gh within the group, fixed for the kernel
+    int col_i[NT], col_gh[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int n = col0 + nt * kColTile + c16;
+        col_i[nt] = n / p.G;
+        col_gh[nt] = n % p.G;
+    }
+
+    auto load_q = [&](bf16x8(&dst)[NT][C::kKSteps], const SeqInfo &s, int kvh) __attribute__((always_inline)) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const bool valid = col_i[nt] < s.R;
+            const char *qrow = static_cast<const char *>(p.q) +
+                               ((int64_t)(s.q0 + (valid ? col_i[nt] : 0)) * p.Hq + kvh * p.G + col_gh[nt]) * (D * 2);
+#pragma unroll
+            for (int t = 0; t < C::kKSteps; ++t) {
+                u32x4 raw = {0u, 0u, 0u, 0u};
+                if (valid) raw = *reinterpret_cast<const u32x4 *>(qrow + (t * 32 + g4 * 8) * 2);
+                dst[nt][t] = __builtin_bit_cast(bf16x8, raw);
             }
         }
-        const int next_k_end = have_next ? min(ni.L, min(n_after, ni.tiles) * kGroupKeys) : 0;
-        const char *next_kbase =
-            static_cast<const char *>(p.k) + (ni.kv0 * p.Hkv + nh) * (int64_t)(D * 2);
-        const char *next_vbase =
-            static_cast<const char *>(p.v) + (ni.kv0 * p.Hkv + nh) * (int64_t)(D * 2);
-        const bool next_tile_mine = have_next && wave * kTileKeys < next_k_end;
+    };
 
-        const int M = p.G * si.R;
-        if (seg_tiles > 0 && col0 < M) {  // block-uniform
-            const int first_masked_key = si.L - si.R + 1;  // keys from here on are hidden from some row
-            // query rows of this lane's columns
-            int col_limit[NT];   // last visible key of the column's query row (-1: no row)
-            bf16x8 qreg[NT][C::kKSteps];
+    bf16x8 qreg[NT][C::kKSteps];  // query rows of the segment at hand
+    // query rows of the next segment, requested when the current one begins (not kept for the
+    // widest column blocks at D = 128, where the registers do not allow it: a segment then
+    // starts by waiting for its query rows)
+    constexpr bool kPrefetchQ = !(D == 128 && NT >= 3);
+    bf16x8 qnext[kPrefetchQ ? NT : 1][C::kKSteps];
+    bool qnext_valid = false;
+
+    // per-segment state
+    int seg_t_first = 0;
+    int first_masked_key = 0;  // keys from here on are hidden from some query row
+    int col_limit[NT];         // last visible key of the column's query row (-1: no row)
+    float m_run[NT], l_run[NT];
+    floatx4 acc_o[NT][C::kDTiles];
+
+    for (int idx = 0; idx < n_tiles; ++idx) {
+        const int key0 = cp.t * kTileKeys;
+        const int kvh = cp.h;
+        char *k_lds = ring + (idx % kSlots) * C::kWaveBytes;
+        char *v_lds = k_lds + C::kTileBytes;
+        if (idx == 0 || cp.t == 0) {  // a segment begins
+            seg_t_first = cp.t;
+            first_masked_key = cp.si.L - cp.si.R + 1;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const int n = col0 + nt * kColTile + c16;
-                const bool valid = n < M;
-                const int i = valid ? n / p.G : 0, gh = valid ? n % p.G : 0;
-                col_limit[nt] = valid ? si.L - si.R + i : -1;
-                const char *qrow = static_cast<const char *>(p.q) +
-                                   ((int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh) * (D * 2);
-#pragma unroll
-                for (int t = 0; t < C::kKSteps; ++t) {
-                    u32x4 raw = {0u, 0u, 0u, 0u};
-                    if (valid) raw = *reinterpret_cast<const u32x4 *>(qrow + (t * 32 + g4 * 8) * 2);
-                    qreg[nt][t] = __builtin_bit_cast(bf16x8, raw);
-                }
-            }
-
-            float m_run[NT], l_run[NT];
-            floatx4 acc_o[NT][C::kDTiles];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
+                col_limit[nt] = col_i[nt] < cp.si.R ? cp.si.L - cp.si.R + col_i[nt] : -1;
                 m_run[nt] = -INFINITY;
                 l_run[nt] = 0.f;
 #pragma unroll
                 for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
             }
-
-            for (int key0 = key_first; key0 < k_end; key0 += kGroupKeys) {
-                store_tile<D>(kr, k_lds, lane);
-                store_tile<D>(vr, v_lds, lane);
-                // refill the registers: this wave's next tile of the segment, or else its first
-                // tile of the next segment (one load site; the choice is wave-uniform)
-                const int next0 = key0 + kGroupKeys;
-                const bool more_here = next0 < k_end;
-                const bool refill = more_here || next_tile_mine;
-                const char *src_k = more_here ? kbase : next_kbase;
-                const char *src_v = more_here ? vbase : next_vbase;
-                const int src_key = more_here ? next0 : wave * kTileKeys;
-                const int src_last = more_here ? last_key : ni.L - 1;
-                // the K half is requested now, the V half after the score products: two short
-                // bursts keep the memory pipeline fed more evenly than one long one
-                if (refill) {
-                    load_tile<D>(kr, src_k, row_bytes, src_key, src_last, lane);
-                    prefetched = !more_here;
-                }
-                __builtin_amdgcn_sched_barrier(0);
-
-            // S^T[key, col] = sum_d K[key, d] Q[col, d]; two 16-key sub-tiles
-            floatx4 s_acc[NT][2];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) s_acc[nt][0] = s_acc[nt][1] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int js = 0; js < 2; ++js) {
-#pragma unroll
-                for (int t = 0; t < C::kKSteps; ++t) {
-                    const u32x4 raw = *reinterpret_cast<const u32x4 *>(
-                        k_lds + (js * 16 + c16) * C::kRowBytes + (t * 32 + g4 * 8) * 2);
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        s_acc[nt][js] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[nt][t],
-                                                                                s_acc[nt][js], 0, 0, 0);
-                }
-            }
-
-            __builtin_amdgcn_sched_barrier(0);
-            if (refill) load_tile<D>(vr, src_v, row_bytes, src_key, src_last, lane);
-            __builtin_amdgcn_sched_barrier(0);
-            // online softmax per column; accumulator element (js, i) is key key0 + 16 js + 4 g4 + i
-            const bool tail = key0 + kTileKeys > first_masked_key;  // wave-uniform
-            bf16x8 pfrag[NT];
-            float alpha[NT];
-            bool rescale = false;
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                float sv[8];
-#pragma unroll
-                for (int js = 0; js < 2; ++js)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float x = s_acc[nt][js][i] * p.scale2;
-                        if (tail) {
-                            const int key = key0 + js * 16 + g4 * 4 + i;
-                            x = key <= col_limit[nt] ? x : -INFINITY;
-                        }
-                        sv[js * 4 + i] = x;
-                    }
-                float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                                   fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-                mloc = max_across_rows(mloc);
-                const float mnew = fmaxf(m_run[nt], mloc);
-                const float msafe = mnew == -INFINITY ? 0.f : mnew;
-                alpha[nt] = hw_exp2(m_run[nt] - msafe);
-                rescale |= alpha[nt] != 1.f;
-                float psum = 0.f;
-                float pv[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    pv[e] = hw_exp2(sv[e] - msafe);
-                    psum += pv[e];
-                }
-                l_run[nt] = l_run[nt] * alpha[nt] + psum;
-                m_run[nt] = mnew;
-                bf16x8 pf;
-#pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const bf16x2 two = __builtin_convertvector(floatx2{pv[e], pv[e + 1]}, bf16x2);
-                    pf[e] = two[0];
-                    pf[e + 1] = two[1];
-                }
-                pfrag[nt] = pf;
-            }
-            if (__any(rescale)) {
+            if (kPrefetchQ && qnext_valid) {
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= alpha[nt];
+                    for (int t = 0; t < C::kKSteps; ++t) qreg[nt][t] = qnext[kPrefetchQ ? nt : 0][t];
+            } else {
+                load_q(qreg, cp.si, cp.h);
             }
-
-            // O^T[d, col] += sum_key V[key, d] P[key, col]; contraction slot e of lane group g4 is
-            // key 16 (e/4) + 4 g4 + e%4, matching the score accumulators; d tile t holds
-            // d = kEpl * r + t for MFMA row r.
-            // V is read in 8-byte pieces (4 values of d per key): for D = 128 in two rounds, which
-            // halves the registers the regroup needs
-            constexpr int kRounds = C::kEpl / 4;
-#pragma unroll
-            for (int hf = 0; hf < kRounds; ++hf) {
-                uint32_t vw[8][2];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int key = 16 * (e / 4) + 4 * g4 + (e % 4);
-                    const u32x2 raw = *reinterpret_cast<const u32x2 *>(
-                        v_lds + key * C::kRowBytes + c16 * (C::kEpl * 2) + hf * 8);
-                    vw[e][0] = raw[0];
-                    vw[e][1] = raw[1];
-                }
-#pragma unroll
-                for (int tt = 0; tt < 4; ++tt) {
-                    const int t = hf * 4 + tt;
-                    uint32_t aw[4];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const uint32_t lo = vw[2 * c][tt / 2], hi = vw[2 * c + 1][tt / 2];
-                        aw[c] = (tt & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
-                                         : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                    }
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{aw[0], aw[1], aw[2], aw[3]});
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        acc_o[nt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pfrag[nt], acc_o[nt][t],
-                                                                               0, 0, 0);
-                }
-            }
-            }
-            if (next_tile_mine && !prefetched) {  // this wave had no tile in the segment
-                load_tile<D>(kr, next_kbase, row_bytes, wave * kTileKeys, ni.L - 1, lane);
-                load_tile<D>(vr, next_vbase, row_bytes, wave * kTileKeys, ni.L - 1, lane);
-                prefetched = true;
-            }
-
-        // ---- merge the four waves --------------------------------------------------------------
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const float l = sum_across_rows(l_run[nt]);
-            l_run[nt] = l;
-            if (g4 == 0) {
-                sh_m[wave * kMaxColsPerBlock + nt * kColTile + c16] = m_run[nt];
-                sh_l[wave * kMaxColsPerBlock + nt * kColTile + c16] = l;
-            }
-        }
-        __syncthreads();  // every wave has left its tile loop: tile memory is free for the merge
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const int c = nt * kColTile + c16;
-            float mt = -INFINITY;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) mt = fmaxf(mt, sh_m[w * kMaxColsPerBlock + c]);
-            const float msafe = mt == -INFINITY ? 0.f : mt;
-            float lt = 0.f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w)
-                lt += sh_l[w * kMaxColsPerBlock + c] * hw_exp2(sh_m[w * kMaxColsPerBlock + c] - msafe);
-            const float own = hw_exp2(m_run[nt] - msafe);
-#pragma unroll
-            for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= own;
-            if (wave == 0 && g4 == 0) {
-                sh_mt[c] = mt;
-                sh_lt[c] = lt;
+            if constexpr (kPrefetchQ) {
+                qnext_valid = cp.nh < p.Hkv;  // the segment after this one, if the list goes on
+                if (qnext_valid) load_q(qnext, cp.nsi, cp.nh);
             }
         }
 
-        float *merge = reinterpret_cast<float *>(smem + wave * C::kWaveBytes);
-        // a segment that covers its whole sequence writes the output; otherwise it leaves a
-        // partial in one of this work-group's two slots (0: the sequence began in an earlier
-        // work-group, 1: it starts here and continues in the next one)
-        const int64_t slot = 2 * (int64_t)wg + (t_first > 0 ? 0 : 1);
-        constexpr int kSeg = D / 8;  // floats per reducing thread
-        const int rc = threadIdx.x / 8, rseg = (threadIdx.x % 8) * kSeg;
+        wait_at_least(filled, (uint32_t)(idx + 1), alive, p.error_flag);
+        asm volatile("" ::: "memory");
+
+        // S^T[key, col] = sum_d K[key, d] Q[col, d]; two 16-key sub-tiles
+        floatx4 s_acc[NT][2];
 #pragma unroll
-        for (int pp = 0; pp < (NT + 1) / 2; ++pp) {
+        for (int nt = 0; nt < NT; ++nt) s_acc[nt][0] = s_acc[nt][1] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int nt = 2 * pp + h;
-                if (nt < NT) {
+        for (int js = 0; js < 2; ++js) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float *dst = merge + (h * kColTile + c16) * C::kMergeStride + C::kEpl * (4 * g4 + r);
+            for (int t = 0; t < C::kKSteps; ++t) {
+                const u32x4 raw = *reinterpret_cast<const u32x4 *>(
+                    k_lds + (js * 16 + c16) * C::kRowBytes + (t * 32 + g4 * 8) * 2);
+                const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
 #pragma unroll
-                        for (int t = 0; t < C::kDTiles; t += 4)
-                            *reinterpret_cast<floatx4 *>(dst + t) =
-                                floatx4{acc_o[nt < NT ? nt : 0][t][r], acc_o[nt < NT ? nt : 0][t + 1][r],
-                                        acc_o[nt < NT ? nt : 0][t + 2][r], acc_o[nt < NT ? nt : 0][t + 3][r]};
-                    }
-                }
+                for (int nt = 0; nt < NT; ++nt)
+                    s_acc[nt][js] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[nt][t], s_acc[nt][js], 0, 0, 0);
             }
-            __syncthreads();
-            const int cl = pp * 32 + rc;  // column within the block
-            const int n = col0 + cl;
-            if (cl < NT * kColTile && n < M) {
-                float sum[kSeg];
+        }
+
+        // online softmax per column; accumulator element (js, i) is key key0 + 16 js + 4 g4 + i
+        const bool tail = key0 + kTileKeys > first_masked_key;  // wave-uniform
+        bf16x8 pfrag[NT];
+        float alpha[NT];
+        bool rescale = false;
 #pragma unroll
-                for (int j = 0; j < kSeg; ++j) sum[j] = 0.f;
+        for (int nt = 0; nt < NT; ++nt) {
+            float sv[8];
 #pragma unroll
-                for (int w = 0; w < kWaves; ++w) {
-                    const float *src = reinterpret_cast<const float *>(smem + w * C::kWaveBytes) +
-                                       rc * C::kMergeStride + rseg;
+            for (int js = 0; js < 2; ++js)
 #pragma unroll
-                    for (int j = 0; j < kSeg; j += 4) {
-                        const floatx4 x = *reinterpret_cast<const floatx4 *>(src + j);
-                        sum[j] += x[0];
-                        sum[j + 1] += x[1];
-                        sum[j + 2] += x[2];
-                        sum[j + 3] += x[3];
+                for (int i = 0; i < 4; ++i) {
+                    float x = s_acc[nt][js][i] * p.scale2;
+                    if (tail) {
+                        const int key = key0 + js * 16 + g4 * 4 + i;
+                        x = key <= col_limit[nt] ? x : -INFINITY;
                     }
+                    sv[js * 4 + i] = x;
                 }
-                const float mt = sh_mt[cl], lt = sh_lt[cl];
-                if (whole) {
-                    const int i = n / p.G, gh = n % p.G;
-                    const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
-                    const float inv = lt > 0.f ? 1.f / lt : 0.f;
-                    OutT *dst = static_cast<OutT *>(p.out) + orow * D + rseg;
-                    if constexpr (sizeof(OutT) == 2) {
-                        uint32_t packed[kSeg / 2];
+            float mloc = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                               fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+            mloc = max_across_rows(mloc);
+            // The exponent reference m_run follows the running maximum lazily: it moves only
+            // when the maximum has grown by more than kRescaleSlack (probabilities then stay
+            // below 2^kRescaleSlack, harmless in bf16 and fp32), so that rescaling the
+            // accumulators is a rare event instead of one per tile.
+            const bool grow = mloc > m_run[nt] + kRescaleSlack;
+            const float mnew = grow ? mloc : m_run[nt];
+            const float msafe = mnew == -INFINITY ? 0.f : mnew;
+            alpha[nt] = hw_exp2(m_run[nt] - msafe);
+            rescale |= grow;
+            float psum = 0.f;
+            float pv[8];
 #pragma unroll
-                        for (int j = 0; j < kSeg; j += 2) {
-                            const bf16x2 two =
-                                __builtin_convertvector(floatx2{sum[j] * inv, sum[j + 1] * inv}, bf16x2);
-                            packed[j / 2] = __builtin_bit_cast(uint32_t, two);
+            for (int e = 0; e < 8; ++e) {
+                pv[e] = hw_exp2(sv[e] - msafe);
+                psum += pv[e];
+            }
+            l_run[nt] = l_run[nt] * alpha[nt] + psum;
+            m_run[nt] = mnew;
+            bf16x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const bf16x2 two = __builtin_convertvector(floatx2{pv[e], pv[e + 1]}, bf16x2);
+                pf[e] = two[0];
+                pf[e + 1] = two[1];
+            }
+            pfrag[nt] = pf;
+        }
+        if (__any(rescale)) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] *= alpha[nt];
+        }
+
+        // O^T[d, col] += sum_key V[key, d] P[key, col]; contraction slot e of lane group g4 is
+        // key 16 (e/4) + 4 g4 + e%4, matching the score accumulators; d tile t holds
+        // d = kEpl * r + t for MFMA row r.  V is read in 8-byte pieces (4 values of d per key):
+        // for D = 128 in two rounds, which halves the registers the regroup needs
+        constexpr int kRounds = C::kEpl / 4;
+#pragma unroll
+        for (int hf = 0; hf < kRounds; ++hf) {
+            uint32_t vw[8][2];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int key = 16 * (e / 4) + 4 * g4 + (e % 4);
+                const u32x2 raw =
+                    *reinterpret_cast<const u32x2 *>(v_lds + key * C::kRowBytes + c16 * (C::kEpl * 2) + hf * 8);
+                vw[e][0] = raw[0];
+                vw[e][1] = raw[1];
+            }
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                const int t = hf * 4 + tt;
+                uint32_t aw[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t lo = vw[2 * c][tt / 2], hi = vw[2 * c + 1][tt / 2];
+                    aw[c] = (tt & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
+                                     : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                }
+                const bf16x8 a = __builtin_bit_cast(bf16x8, u32x4{aw[0], aw[1], aw[2], aw[3]});
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc_o[nt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pfrag[nt], acc_o[nt][t], 0, 0, 0);
+            }
+        }
+
+        if (idx == n_tiles - 1 || cp.t == cp.si.tiles - 1) {  // the segment ends
+            // A segment that covers its whole sequence writes the output; otherwise it leaves a
+            // partial in one of this pair's two slots (0: the sequence began in an earlier
+            // range, 1: it starts here and continues in the next one).  Lane (c16, g4) holds,
+            // for column c16 of each column tile, d = kEpl * (4 g4 + r) + t in acc_o[nt][t][r]:
+            // written out like that, every store would scatter 16-byte pieces over 64 rows.
+            // The columns go through the ring slot of the tile just finished (still owned by
+            // this wave) instead, 32 at a time, and leave it as whole rows.
+            const bool whole = seg_t_first == 0 && cp.t == cp.si.tiles - 1;
+            const int64_t slot = 2 * (int64_t)u + (seg_t_first > 0 ? 0 : 1);
+            // (the staging reuses memory that other code reads and writes as 32-bit integer
+            // vectors: keep the compiler from moving either across the borders of this block;
+            // the hardware runs a wave's LDS operations in order)
+            asm volatile("" ::: "memory");
+            float *stage = reinterpret_cast<float *>(k_lds);  // [32][kMergeStride]
+            float *stat = stage + 32 * C::kMergeStride;       // [32]: max, sum, output row, -
+            constexpr int kLanesPerOutRow = D / 4;            // lanes that cover a row, 4 floats each
+            constexpr int kRowsPerPass = 64 / kLanesPerOutRow;
+#pragma unroll
+            for (int pp = 0; pp < (NT + 1) / 2; ++pp) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int nt = 2 * pp + h;
+                    if (nt < NT) {
+                        const float lt = sum_across_rows(l_run[nt < NT ? nt : 0]);
+                        float *row = stage + (h * kColTile + c16) * C::kMergeStride;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+#pragma unroll
+                            for (int t = 0; t < C::kEpl; t += 4)
+                                *reinterpret_cast<floatx4 *>(row + C::kEpl * (4 * g4 + r) + t) =
+                                    floatx4{acc_o[nt < NT ? nt : 0][t][r], acc_o[nt < NT ? nt : 0][t + 1][r],
+                                            acc_o[nt < NT ? nt : 0][t + 2][r], acc_o[nt < NT ? nt : 0][t + 3][r]};
+                        if (g4 == 0) {
+                            const int ci = col_i[nt < NT ? nt : 0];
+                            const int orow = ci < cp.si.R
+                                                 ? (cp.si.q0 + ci) * p.Hq + kvh * p.G + col_gh[nt < NT ? nt : 0]
+                                                 : -1;
+                            *reinterpret_cast<floatx4 *>(stat + (h * kColTile + c16) * 4) =
+                                floatx4{m_run[nt < NT ? nt : 0], lt, __int_as_float(orow), 0.f};
                         }
-#pragma unroll
-                        for (int j = 0; j < kSeg / 2; j += 4)
-                            *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(dst) + j * 4) =
-                                u32x4{packed[j], packed[j + 1], packed[j + 2], packed[j + 3]};
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < kSeg; ++j) dst[j] = sum[j] * inv;
-                    }
-                    if (p.lse && rseg == 0)
-                        p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
-                } else {
-                    const int64_t prow = slot * p.Mpad + n;
-                    float *dst = p.ws_o + prow * D + rseg;
-#pragma unroll
-                    for (int j = 0; j < kSeg; j += 4)
-                        *reinterpret_cast<floatx4 *>(dst + j) =
-                            floatx4{sum[j], sum[j + 1], sum[j + 2], sum[j + 3]};
-                    if (rseg == 0) {
-                        p.ws_ml[prow * 2] = mt;
-                        p.ws_ml[prow * 2 + 1] = lt;
                     }
                 }
+                const int n_cols = (NT - 2 * pp) >= 2 ? 32 : 16;  // columns staged in this pass
+#pragma unroll
+                for (int it = 0; it < 32 / kRowsPerPass; ++it) {
+                    if (it * kRowsPerPass >= n_cols) break;
+                    const int cl = it * kRowsPerPass + lane / kLanesPerOutRow;
+                    const int d4 = (lane % kLanesPerOutRow) * 4;
+                    const floatx4 st4 = *reinterpret_cast<const floatx4 *>(stat + cl * 4);
+                    const floatx4 x = *reinterpret_cast<const floatx4 *>(stage + cl * C::kMergeStride + d4);
+                    const float mt = st4[0], lt = st4[1];
+                    const int orow = __float_as_int(st4[2]);
+                    if (orow >= 0) {
+                        if (whole) {
+                            const float inv = lt > 0.f ? 1.f / lt : 0.f;
+                            OutT *dst = static_cast<OutT *>(p.out) + (int64_t)orow * D + d4;
+                            const bf16x2 a = __builtin_convertvector(floatx2{x[0] * inv, x[1] * inv}, bf16x2);
+                            const bf16x2 c2 = __builtin_convertvector(floatx2{x[2] * inv, x[3] * inv}, bf16x2);
+                            *reinterpret_cast<u32x2 *>(dst) =
+                                u32x2{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, c2)};
+                            if (p.lse && d4 == 0)
+                                p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
+                        } else {
+                            const int64_t prow = slot * p.Mpad + col0 + pp * 32 + cl;
+                            *reinterpret_cast<floatx4 *>(p.ws_o + prow * D + d4) = x;
+                            if (d4 == 0) {
+                                p.ws_ml[prow * 2] = mt;
+                                p.ws_ml[prow * 2 + 1] = lt;
+                            }
+                        }
+                    }
+                }
+                asm volatile("" ::: "memory");
             }
-            __syncthreads();
         }
-        }
-        if (!have_next) break;
-        b = nb;
-        kvh = nh;
-        si = ni;
-        t_first = 0;
-        n_left = n_after;
+        // every read of the slot has been issued: hand it back
+        asm volatile("" ::: "memory");
+        *consumed = (uint32_t)(idx + 1);
+        if (idx + 1 < n_tiles) cursor_advance(p, cp);
     }
 }
 
@@ -684,32 +793,39 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     constexpr int kTpc = D / 4;             // threads per column (float4 each)
     constexpr int kCols = 256 / kTpc;       // columns per block
     const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x % p.Hkv;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && *p.error_flag != 0) {
+        // a wave of the main kernel gave up waiting for its partner: the results cannot be
+        // trusted, so make that impossible to miss
+        static_cast<OutT *>(p.out)[0] = sizeof(OutT) == 2 ? (OutT)0x7fc0 : (OutT)0;
+        if (p.lse) p.lse[0] = NAN;
+    }
     const SeqInfo si = seq_info(p, b);
     if (si.tiles <= 0) return;
-    const int64_t T = p.tile_prefix[p.B];
-    const int64_t total = T * p.Hkv;
-    const int64_t first_tile = (int64_t)kvh * T + p.tile_prefix[b];
-    const int w_first = owner_of_tile(first_tile, total, p.W);
-    const int w_last = owner_of_tile(first_tile + si.tiles - 1, total, p.W);
-    if (w_first == w_last) return;          // one work-group saw the whole sequence and wrote it
+    const Split sp = make_split(p, p.tile_prefix[p.B]);
+    const int sub = kvh / sp.hps;
+    const int64_t first_tile = (int64_t)(kvh % sp.hps) * sp.T + p.tile_prefix[b];
+    const int r_first = part_of_tile(sp, first_tile);
+    const int r_last = part_of_tile(sp, first_tile + si.tiles - 1);
+    if (r_first == r_last) return;          // one wave saw the whole sequence and wrote it
     const int n = blockIdx.y * kCols + threadIdx.x / kTpc;
     const int d4 = (threadIdx.x % kTpc) * 4;
     const int M = p.G * si.R;
     if (n >= M) return;
     const int i = n / p.G, gh = n % p.G;
-    // partials in key order: slot 2*w_first+1, then slot 2*w for w_first < w <= w_last; when
-    // there are fewer tiles than work-groups some of those own no tile and wrote nothing
-    float mt = p.ws_ml[((int64_t)(2 * w_first + 1) * p.Mpad + n) * 2];
-    for (int w = w_first + 1; w <= w_last; ++w) {
-        if (!owns_tiles(w, total, p.W)) continue;
-        mt = fmaxf(mt, p.ws_ml[((int64_t)(2 * w) * p.Mpad + n) * 2]);
+    // partials in key order: slot 2*u+1 of the first part's wave u, then slot 2*u of the later
+    // ones; when there are fewer tiles than parts some own no tile and wrote nothing
+    float mt = p.ws_ml[((int64_t)(2 * (r_first * p.HI + sub) + 1) * p.Mpad + n) * 2];
+    for (int r = r_first + 1; r <= r_last; ++r) {
+        if (!part_owns_tiles(sp, r)) continue;
+        mt = fmaxf(mt, p.ws_ml[((int64_t)(2 * (r * p.HI + sub)) * p.Mpad + n) * 2]);
     }
     const float msafe = mt == -INFINITY ? 0.f : mt;
     float lt = 0.f;
     floatx4 o = {0.f, 0.f, 0.f, 0.f};
-    for (int w = w_first; w <= w_last; ++w) {
-        if (!owns_tiles(w, total, p.W)) continue;
-        const int64_t prow = (int64_t)(w == w_first ? 2 * w + 1 : 2 * w) * p.Mpad + n;
+    for (int r = r_first; r <= r_last; ++r) {
+        if (!part_owns_tiles(sp, r)) continue;
+        const int w = r * p.HI + sub;
+        const int64_t prow = (int64_t)(r == r_first ? 2 * w + 1 : 2 * w) * p.Mpad + n;
         const float wgt = exp2f(p.ws_ml[prow * 2] - msafe);
         lt += p.ws_ml[prow * 2 + 1] * wgt;
         const floatx4 x = *reinterpret_cast<const floatx4 *>(p.ws_o + prow * D + d4);
@@ -738,7 +854,7 @@ thread_local hipEvent_t g_mark_after_main = nullptr;
 
 struct Plan {
     int32_t Mpad;
-    size_t ws_o_bytes, ws_ml_bytes, prefix_bytes, start_bytes, ws_bytes;
+    size_t ws_o_bytes, ws_ml_bytes, prefix_bytes, start_bytes, flag_bytes, ws_bytes;
 };
 
 bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, int32_t Hq,
@@ -750,11 +866,12 @@ bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, i
     if ((int64_t)G * max_q > 256) return false;
     pl.Mpad = (G * max_q + kColTile - 1) / kColTile * kColTile;
     // sized for the widest split so that the query needs no device
-    pl.ws_o_bytes = round_up((size_t)2 * kMaxWgs * pl.Mpad * D * sizeof(float), 256);
-    pl.ws_ml_bytes = round_up((size_t)2 * kMaxWgs * pl.Mpad * 2 * sizeof(float), 256);
+    pl.ws_o_bytes = round_up((size_t)2 * kMaxWaves * pl.Mpad * D * sizeof(float), 256);
+    pl.ws_ml_bytes = round_up((size_t)2 * kMaxWaves * pl.Mpad * 2 * sizeof(float), 256);
     pl.prefix_bytes = round_up((size_t)(B + 1) * sizeof(int32_t), 256);
-    pl.start_bytes = round_up((size_t)kMaxWgs * sizeof(WgStart), 256);
-    pl.ws_bytes = pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes + pl.start_bytes;
+    pl.start_bytes = round_up((size_t)kMaxWaves * sizeof(WaveStart), 256);
+    pl.flag_bytes = 256;
+    pl.ws_bytes = pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes + pl.start_bytes + pl.flag_bytes;
     return true;
 }
 
@@ -772,29 +889,28 @@ int compute_units() {
     return cached[dev];
 }
 
-template <int D, int NT, typename OutT>
+template <int D, int NT>
 hipError_t launch_bf16(const AttnParams &p, dim3 grid, hipStream_t stream) {
     using C = Bf16Cfg<D>;
-    const size_t smem = kWaves * C::kWaveBytes + (2 * kWaves + 2) * kMaxColsPerBlock * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(&attn_bf16_kernel<D, NT, OutT>),
-            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    const size_t smem = (size_t)kConsumers * kSlots * C::kWaveBytes + 2 * kConsumers * sizeof(uint32_t);
+    static bool configured = false;  // benign race: the attribute is idempotent
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, NT, uint16_t>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        configured = true;
     }
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NT, OutT>), grid, dim3(kThreads), smem, stream, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NT, uint16_t>), grid, dim3(2 * kConsumers * 64), smem, stream, p);
     return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_bf16_nt(int nt, const AttnParams &p, dim3 grid, hipStream_t stream) {
     switch (nt) {
-        case 1: return launch_bf16<D, 1, uint16_t>(p, grid, stream);
-        case 2: return launch_bf16<D, 2, uint16_t>(p, grid, stream);
-        case 3: return launch_bf16<D, 3, uint16_t>(p, grid, stream);
-        default: return launch_bf16<D, 4, uint16_t>(p, grid, stream);
+        case 1: return launch_bf16<D, 1>(p, grid, stream);
+        case 2: return launch_bf16<D, 2>(p, grid, stream);
+        case 3: return launch_bf16<D, 3>(p, grid, stream);
+        default: return launch_bf16<D, 4>(p, grid, stream);
     }
 }
 
@@ -853,6 +969,8 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     if (!workspace || workspace_bytes < pl.ws_bytes || !aligned_to(workspace, 256))
         return fail(RESPEC_ERR_WORKSPACE, "verify_attention: workspace of %zu bytes (256-byte aligned) needed, got %zu",
                     pl.ws_bytes, workspace ? workspace_bytes : (size_t)0);
+    if ((int64_t)total_q * Hq > 0x7fffffffLL)
+        return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: total_q*Hq exceeds 2^31-1");
     if (dt == RESPEC_F32 && (int64_t)B * Hq > 0x7fffffffLL)
         return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: B*Hq too large for the fp32 path");
 
@@ -868,7 +986,8 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     p.ws_o = reinterpret_cast<float *>(ws);
     p.ws_ml = reinterpret_cast<float *>(ws + pl.ws_o_bytes);
     p.tile_prefix = reinterpret_cast<int32_t *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes);
-    p.wg_start = reinterpret_cast<WgStart *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes);
+    p.wave_start = reinterpret_cast<WaveStart *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes);
+    p.error_flag = reinterpret_cast<int32_t *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes + pl.start_bytes);
     p.B = B;
     p.total_q = total_q;
     p.total_kv = total_kv;
@@ -907,13 +1026,16 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     const int col_blocks = (M + kMaxColsPerBlock - 1) / kMaxColsPerBlock;
     const int cols = col_blocks == 1 ? M : kMaxColsPerBlock;
     const int nt = (cols + kColTile - 1) / kColTile;
-    // one work-group per resident slot: two per compute unit (one for the wide-column variants)
-    const int per_cu = (D == 128 && nt >= 3) ? 1 : 2;
+    // the split width: one wave per SIMD of the device (RESPEC_ATTN_WGS overrides it, for tests
+    // and sweeps)
     long W = env_long("RESPEC_ATTN_WGS", 0);
-    if (W <= 0) W = (long)per_cu * compute_units() / col_blocks;
+    if (W <= 0) W = (long)kConsumers * compute_units() / col_blocks;
     if (W < 1) W = 1;
-    if (W > kMaxWgs) W = kMaxWgs;
+    if (W > kMaxWaves) W = kMaxWaves;
     p.W = (int32_t)W;
+    int hi = Hkv % 4 == 0 ? 4 : (Hkv % 2 == 0 ? 2 : 1);
+    if (W % hi != 0 || env_long("RESPEC_ATTN_HEAD_MAJOR", 0) != 0) hi = 1;
+    p.HI = hi;
 
     hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
     err = hipGetLastError();
@@ -923,7 +1045,7 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
         (void)hipEventRecord(g_mark_before_main, stream);
         g_mark_before_main = nullptr;
     }
-    const dim3 grid((unsigned)W, (unsigned)col_blocks);
+    const dim3 grid((unsigned)((W + kConsumers - 1) / kConsumers), (unsigned)col_blocks);
     err = D == 128 ? launch_bf16_nt<128>(nt, p, grid, stream) : launch_bf16_nt<64>(nt, p, grid, stream);
     if (err != hipSuccess)
         return fail(RESPEC_ERR_HIP, "verify_attention: main launch failed: %s", hipGetErrorString(err));
