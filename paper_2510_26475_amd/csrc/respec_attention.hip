@@ -59,8 +59,9 @@ struct AttnParams {
     const int64_t *kv_indptr;
     void *out;
     float *lse;
-    float *ws_o;           // [2*W, Mpad, D]   unnormalised partial outputs
-    float *ws_ml;          // [2*W, Mpad, 2]   (max in log2 units, sum)
+    int16_t *ws_o;         // [2*W, Mpad, D]   unnormalised partial outputs, 16-bit fixed point
+                           //                  relative to the row's largest magnitude
+    float *ws_ml;          // [2*W, Mpad, 4]   (max in log2 units, sum, largest magnitude, -)
     int32_t *tile_prefix;  // [B+1] prefix sum of ceil(L_b / kTileKeys)
     WaveStart *wave_start; // [W]
     int32_t B, total_q;
@@ -637,13 +638,21 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                                 *reinterpret_cast<floatx4 *>(row + C::kEpl * (4 * g4 + r) + t) =
                                     floatx4{acc_o[nt < NT ? nt : 0][t][r], acc_o[nt < NT ? nt : 0][t + 1][r],
                                             acc_o[nt < NT ? nt : 0][t + 2][r], acc_o[nt < NT ? nt : 0][t + 3][r]};
+                        float amax = 0.f;  // largest magnitude of the column (scale of a partial)
+                        if (!whole) {
+#pragma unroll
+                            for (int t = 0; t < C::kDTiles; ++t)
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) amax = fmaxf(amax, fabsf(acc_o[nt < NT ? nt : 0][t][r]));
+                            amax = max_across_rows(amax);
+                        }
                         if (g4 == 0) {
                             const int ci = col_i[nt < NT ? nt : 0];
                             const int orow = ci < cp.si.R
                                                  ? (cp.si.q0 + ci) * p.Hq + kvh * p.G + col_gh[nt < NT ? nt : 0]
                                                  : -1;
                             *reinterpret_cast<floatx4 *>(stat + (h * kColTile + c16) * 4) =
-                                floatx4{m_run[nt < NT ? nt : 0], lt, __int_as_float(orow), 0.f};
+                                floatx4{m_run[nt < NT ? nt : 0], lt, __int_as_float(orow), amax};
                         }
                     }
                 }
@@ -669,11 +678,20 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                                 p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
                         } else {
                             const int64_t prow = slot * p.Mpad + col0 + pp * 32 + cl;
-                            *reinterpret_cast<floatx4 *>(p.ws_o + prow * D + d4) = x;
-                            if (d4 == 0) {
-                                p.ws_ml[prow * 2] = mt;
-                                p.ws_ml[prow * 2 + 1] = lt;
-                            }
+                            // A partial is written as 16-bit fixed point relative to the row's
+                            // largest magnitude (error below 2^-16 of it, far under the bf16
+                            // rounding of the output): stores into a stream of reads cost several
+                            // times their size in read bandwidth, so bytes count here.  A row
+                            // that has overflowed keeps its inf/NaN in the scale.
+                            const float amax = st4[3];
+                            const float qs = (amax > 0.f && amax < INFINITY) ? 32767.f / amax : 0.f;
+                            const int q0 = (int)__builtin_rintf(x[0] * qs), q1 = (int)__builtin_rintf(x[1] * qs);
+                            const int q2 = (int)__builtin_rintf(x[2] * qs), q3 = (int)__builtin_rintf(x[3] * qs);
+                            *reinterpret_cast<u32x2 *>(p.ws_o + prow * D + d4) =
+                                u32x2{((uint32_t)q0 & 0xffffu) | ((uint32_t)q1 << 16),
+                                      ((uint32_t)q2 & 0xffffu) | ((uint32_t)q3 << 16)};
+                            if (d4 == 0)
+                                *reinterpret_cast<floatx4 *>(p.ws_ml + prow * 4) = floatx4{mt, lt, amax, 0.f};
                         }
                     }
                 }
@@ -814,10 +832,10 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     const int i = n / p.G, gh = n % p.G;
     // partials in key order: slot 2*u+1 of the first part's wave u, then slot 2*u of the later
     // ones; when there are fewer tiles than parts some own no tile and wrote nothing
-    float mt = p.ws_ml[((int64_t)(2 * (r_first * p.HI + sub) + 1) * p.Mpad + n) * 2];
+    float mt = p.ws_ml[((int64_t)(2 * (r_first * p.HI + sub) + 1) * p.Mpad + n) * 4];
     for (int r = r_first + 1; r <= r_last; ++r) {
         if (!part_owns_tiles(sp, r)) continue;
-        mt = fmaxf(mt, p.ws_ml[((int64_t)(2 * (r * p.HI + sub)) * p.Mpad + n) * 2]);
+        mt = fmaxf(mt, p.ws_ml[((int64_t)(2 * (r * p.HI + sub)) * p.Mpad + n) * 4]);
     }
     const float msafe = mt == -INFINITY ? 0.f : mt;
     float lt = 0.f;
@@ -826,10 +844,14 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
         if (!part_owns_tiles(sp, r)) continue;
         const int w = r * p.HI + sub;
         const int64_t prow = (int64_t)(r == r_first ? 2 * w + 1 : 2 * w) * p.Mpad + n;
-        const float wgt = exp2f(p.ws_ml[prow * 2] - msafe);
-        lt += p.ws_ml[prow * 2 + 1] * wgt;
-        const floatx4 x = *reinterpret_cast<const floatx4 *>(p.ws_o + prow * D + d4);
-        o += x * wgt;
+        const floatx4 stats = *reinterpret_cast<const floatx4 *>(p.ws_ml + prow * 4);
+        const float wgt = exp2f(stats[0] - msafe);
+        lt += stats[1] * wgt;
+        const u32x2 q = *reinterpret_cast<const u32x2 *>(p.ws_o + prow * D + d4);
+        const float unit = stats[2] * (1.f / 32767.f) * wgt;
+        const floatx4 x = {(float)(int16_t)(q[0] & 0xffffu), (float)(int16_t)(q[0] >> 16),
+                           (float)(int16_t)(q[1] & 0xffffu), (float)(int16_t)(q[1] >> 16)};
+        o += x * unit;
     }
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
@@ -866,8 +888,8 @@ bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, i
     if ((int64_t)G * max_q > 256) return false;
     pl.Mpad = (G * max_q + kColTile - 1) / kColTile * kColTile;
     // sized for the widest split so that the query needs no device
-    pl.ws_o_bytes = round_up((size_t)2 * kMaxWaves * pl.Mpad * D * sizeof(float), 256);
-    pl.ws_ml_bytes = round_up((size_t)2 * kMaxWaves * pl.Mpad * 2 * sizeof(float), 256);
+    pl.ws_o_bytes = round_up((size_t)2 * kMaxWaves * pl.Mpad * D * sizeof(int16_t), 256);
+    pl.ws_ml_bytes = round_up((size_t)2 * kMaxWaves * pl.Mpad * 4 * sizeof(float), 256);
     pl.prefix_bytes = round_up((size_t)(B + 1) * sizeof(int32_t), 256);
     pl.start_bytes = round_up((size_t)kMaxWaves * sizeof(WaveStart), 256);
     pl.flag_bytes = 256;
@@ -983,7 +1005,7 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     p.out = out;
     p.lse = lse;
     char *ws = static_cast<char *>(workspace);
-    p.ws_o = reinterpret_cast<float *>(ws);
+    p.ws_o = reinterpret_cast<int16_t *>(ws);
     p.ws_ml = reinterpret_cast<float *>(ws + pl.ws_o_bytes);
     p.tile_prefix = reinterpret_cast<int32_t *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes);
     p.wave_start = reinterpret_cast<WaveStart *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes);
