@@ -831,27 +831,46 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     if (n >= M) return;
     const int i = n / p.G, gh = n % p.G;
     // partials in key order: slot 2*u+1 of the first part's wave u, then slot 2*u of the later
-    // ones; when there are fewer tiles than parts some own no tile and wrote nothing
-    float mt = p.ws_ml[((int64_t)(2 * (r_first * p.HI + sub) + 1) * p.Mpad + n) * 4];
-    for (int r = r_first + 1; r <= r_last; ++r) {
-        if (!part_owns_tiles(sp, r)) continue;
-        mt = fmaxf(mt, p.ws_ml[((int64_t)(2 * (r * p.HI + sub)) * p.Mpad + n) * 4]);
-    }
-    const float msafe = mt == -INFINITY ? 0.f : mt;
-    float lt = 0.f;
+    // ones; when there are fewer tiles than parts some own no tile and wrote nothing.  They are
+    // folded in that order, four at a time so that their loads are in flight together.
+    float mt = -INFINITY, lt = 0.f;
     floatx4 o = {0.f, 0.f, 0.f, 0.f};
-    for (int r = r_first; r <= r_last; ++r) {
-        if (!part_owns_tiles(sp, r)) continue;
-        const int w = r * p.HI + sub;
-        const int64_t prow = (int64_t)(r == r_first ? 2 * w + 1 : 2 * w) * p.Mpad + n;
-        const floatx4 stats = *reinterpret_cast<const floatx4 *>(p.ws_ml + prow * 4);
-        const float wgt = exp2f(stats[0] - msafe);
-        lt += stats[1] * wgt;
-        const u32x2 q = *reinterpret_cast<const u32x2 *>(p.ws_o + prow * D + d4);
-        const float unit = stats[2] * (1.f / 32767.f) * wgt;
-        const floatx4 x = {(float)(int16_t)(q[0] & 0xffffu), (float)(int16_t)(q[0] >> 16),
-                           (float)(int16_t)(q[1] & 0xffffu), (float)(int16_t)(q[1] >> 16)};
-        o += x * unit;
+    for (int r = r_first; r <= r_last;) {
+        int64_t prow[4];
+        int cnt = 0;
+        for (; r <= r_last && cnt < 4; ++r) {
+            if (!part_owns_tiles(sp, r)) continue;
+            const int w = r * p.HI + sub;
+            const int64_t row = (int64_t)(r == r_first ? 2 * w + 1 : 2 * w) * p.Mpad + n;
+            if (cnt == 0) prow[0] = row;
+            if (cnt == 1) prow[1] = row;
+            if (cnt == 2) prow[2] = row;
+            if (cnt == 3) prow[3] = row;
+            ++cnt;
+        }
+        floatx4 stats[4];
+        u32x2 q[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j < cnt) {
+                stats[j] = *reinterpret_cast<const floatx4 *>(p.ws_ml + prow[j] * 4);
+                q[j] = *reinterpret_cast<const u32x2 *>(p.ws_o + prow[j] * D + d4);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (j < cnt) {
+                const float mnew = fmaxf(mt, stats[j][0]);
+                const float msafe = mnew == -INFINITY ? 0.f : mnew;
+                const float keep = exp2f(mt - msafe), wgt = exp2f(stats[j][0] - msafe);
+                const float unit = stats[j][2] * (1.f / 32767.f) * wgt;
+                const floatx4 x = {(float)(int16_t)(q[j][0] & 0xffffu), (float)(int16_t)(q[j][0] >> 16),
+                                   (float)(int16_t)(q[j][1] & 0xffffu), (float)(int16_t)(q[j][1] >> 16)};
+                lt = lt * keep + stats[j][1] * wgt;
+                o = o * keep + x * unit;
+                mt = mnew;
+            }
+        }
     }
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
