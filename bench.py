@@ -135,6 +135,9 @@ def main():
     n_acc = torch.empty((B,), dtype=torch.int32, device=dev)
     flags = torch.empty((B,), dtype=torch.int32, device=dev)
     sm_scale = 1.0 / math.sqrt(wl.D)
+    # the sampler's mailbox workspace: zero before its first use, then left to the library
+    samp_ws = torch.zeros(binding.respec_rejection_sample_workspace_bytes(B, batch.total_q, wl.V, dt),
+                          dtype=torch.uint8, device=dev)
 
     def attention():
         binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
@@ -145,7 +148,7 @@ def main():
         binding.respec_rejection_sample(batch.target_logits, batch.draft_logits,
                                         batch.draft_tokens, batch.q_indptr, batch.u_accept,
                                         batch.u_final, toks, n_acc, flags, batch.max_k,
-                                        wl.temperature)
+                                        wl.temperature, workspace=samp_ws)
 
     for _ in range(args.warmup):
         attention()

@@ -111,7 +111,16 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
  */
 void respec_profile_mark_main(void *before_main, void *after_main);
 
-/* Workspace bytes of respec_rejection_sample (0 = none needed, NULL may be passed). */
+/*
+ * Bytes of the optional workspace of respec_rejection_sample.  With a workspace a sequence
+ * can be shared by several work-groups (used for batches small enough to leave compute
+ * units idle); the workspace holds one small mailbox per sequence through which they
+ * exchange partial sums.  Contract: the buffer (device memory, 16-byte aligned) is zero before
+ * the first call that uses it; after that the library keeps it consistent from call to call
+ * (any B up to the one it was sized for), so it is allocated and cleared once.  Calls that
+ * share a workspace must not overlap.  NULL may be passed: one work-group then walks each
+ * sequence and nothing else changes.
+ */
 size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t total_q, int32_t V,
                                                respec_dtype_t logits_dt);
 
@@ -144,6 +153,10 @@ size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t total_q, int32
  *                 an exact-arithmetic evaluation.
  *   max_k         host-side upper bound of k_b (row width of out_tokens minus one)
  *   temperature   T > 0, applied to target and drafter logits alike
+ *   workspace     NULL, or respec_rejection_sample_workspace_bytes bytes (see there)
+ * Errors: RESPEC_ERR_INVALID_ARG / RESPEC_ERR_WORKSPACE before any launch.  If work-groups
+ * that share a sequence ever lose each other (a bounded wait runs out: a device fault or a
+ * workspace that was not zero at first use), out_num_accepted[b] of that sequence is -1.
  */
 respec_status_t respec_rejection_sample(const void *target_logits, const void *draft_logits,
                                         const int32_t *draft_tokens, const int32_t *q_indptr,

@@ -1,16 +1,29 @@
 // Speculative rejection sampling over the vocabulary (Section 2.2, Eq. 1 and Eq. 2) for
-// gfx950.  One 1024-thread work-group walks one sequence: for each drafted position it
-// streams the target row and the drafter row once (16-byte loads, fp32 exp2, sums carried
-// in fp64), takes the acceptance test in fp64, and at the first rejection makes a second
-// pass over that one row pair to draw from max(0, p-q) by an ordered fp64 prefix scan.
-// Rows after the first rejection are never touched.
+// gfx950.  A sequence is walked position by position: for each drafted position the target
+// row and the drafter row are streamed once (16-byte loads, fp32 exp2, sums carried in
+// fp64), the acceptance test is taken in fp64, and at the first rejection a second pass
+// over that one row pair draws from max(0, p-q) by an ordered fp64 prefix scan.  Rows after
+// the first rejection are never touched.
+//
+// Parallelisation.  The chain of positions of one sequence is sequential and its length
+// differs from sequence to sequence, so one work-group per sequence leaves most of the
+// device idle when there are fewer sequences than compute units.  A sequence can therefore
+// be shared by SPLIT work-groups of 512 threads (one per compute unit), each owning a
+// contiguous part of the vocabulary.  After every streaming pass the parts exchange their
+// partial results (a few numbers) through a small mailbox in the workspace and then take
+// the same decision from the same numbers.  An exchange costs a few memory round trips, so
+// sequences are shared only while that fills otherwise idle compute units (batches of at
+// most half as many sequences as the device has compute units).  The mailbox is
+// self-synchronising across calls (an epoch counter per sequence), so it only has to be
+// zero before its first use.  Without a workspace a sequence gets one work-group and no
+// mailbox is touched.
 //
 // Numerics.  Token decisions are discontinuous in the sums, so everything that decides a
 // token is carried in fp64; only exp2 of a single element runs in fp32 (hardware exp2,
 // 1 ulp, argument formed as (z-ref)*log2(e)/T with a two-term constant so that no
 // systematic error enters).  "ref" is a per-thread reference near the row maximum, not
 // necessarily the maximum: fp32 keeps full relative precision for any offset, and the
-// references are reconciled in fp64 when threads are combined.
+// references are reconciled in fp64 when threads (and parts) are combined.
 #include "respec_common.hpp"
 
 #include <cmath>
@@ -21,8 +34,14 @@ namespace {
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kUnroll = 4;
+constexpr int kChunk = 5;   // slots of a thread's run in the inverse-CDF walk that are loaded together
 constexpr float kRefInit = -1.0e30f;
 constexpr double kBoundaryEps = 1e-6;
+constexpr int kMaxSplit = 8;          // work-groups that can share one sequence
+constexpr int kBoxHeaderBytes = 128;                      // epoch at word 0, progress counters at words 16..
+constexpr int kBoxPayload = kMaxSplit * 2 * 8;            // [part][stage parity][8 doubles]
+constexpr size_t kBoxBytes = kBoxHeaderBytes + (size_t)kBoxPayload * 8;
+constexpr int kSpinLimit = 1 << 22;
 
 struct SamplerParams {
     const void *target;
@@ -43,6 +62,8 @@ struct SamplerParams {
     double inv_T;
     float gap;         // logit distance above the reference that forces a re-reference
     int aligned;       // every row starts 16-byte aligned
+    int split;         // work-groups per sequence (1 when there is no workspace)
+    char *boxes;       // [B] mailboxes of kBoxBytes (split > 1)
 };
 
 template <bool BF16>
@@ -185,6 +206,11 @@ struct SharedState {
     double s[2][2][kWaves];
     double wave_total[kWaves];
     double scan_total[kWaves];
+    double all_total[kMaxSplit * kWaves];  // region totals of every part, in vocabulary order
+    double xchg[kMaxSplit][8];             // what the parts published in the current stage
+    float comb_m[2];                       // combined (M, S) of the p row and the q row
+    double comb_s[2];
+    int failed;                            // a bounded wait for a partner ran out
     int token;
     int near_edge;
     int last_positive;
@@ -248,9 +274,9 @@ __device__ inline float slot_max(const u32x4 &v) {
 // reference would overflow.  Returns false (every thread alike) when a sum came out
 // non-finite or empty, and the caller then repeats the row with the guarded pass below.
 template <bool BF16, bool TWO, bool ONE_TERM>
-__device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int nslots, SharedState &sh,
-                                      int parity, const SamplerParams &p, float &Mp, double &Sp,
-                                      float &Mq, double &Sq) {
+__device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int nslots, int Vrow,
+                                      SharedState &sh, int parity, const SamplerParams &p, float &Mp,
+                                      double &Sp, float &Mq, double &Sq) {
     constexpr int EPV = Elem<BF16>::EPV;
     constexpr int kBatch = kThreads * kUnroll;  // slots per block iteration
     float accp[EPV], accq[EPV];
@@ -265,8 +291,8 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
         if (it + 1 < n_iter) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                vp[u] = load_slot<BF16, true>(rowp, s0 + u * kThreads, p.V, true);
-                if constexpr (TWO) vq[u] = load_slot<BF16, true>(rowq, s0 + u * kThreads, p.V, true);
+                vp[u] = load_slot<BF16, true>(rowp, s0 + u * kThreads, Vrow, true);
+                if constexpr (TWO) vq[u] = load_slot<BF16, true>(rowq, s0 + u * kThreads, Vrow, true);
             }
         } else {
 #pragma unroll
@@ -274,10 +300,10 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
                 const int slot = s0 + u * kThreads;
                 const bool in = slot < nslots;
                 const int safe = in ? slot : 0;
-                const u32x4 a = load_slot<BF16, true>(rowp, safe, p.V, true);
+                const u32x4 a = load_slot<BF16, true>(rowp, safe, Vrow, true);
                 vp[u] = in ? a : neg_inf_slot<BF16>();
                 if constexpr (TWO) {
-                    const u32x4 b = load_slot<BF16, true>(rowq, safe, p.V, true);
+                    const u32x4 b = load_slot<BF16, true>(rowq, safe, Vrow, true);
                     vq[u] = in ? b : neg_inf_slot<BF16>();
                 }
             }
@@ -339,7 +365,7 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
 // Guarded streaming pass (any finite or -inf logits): per-thread references that follow the
 // running maximum.  Used when the fast pass reports an overflow or an empty sum.
 template <bool BF16, bool TWO>
-__device__ inline void row_stats(const void *rowp, const void *rowq, int nslots, SharedState &sh,
+__device__ inline void row_stats(const void *rowp, const void *rowq, int nslots, int Vrow, SharedState &sh,
                                  int parity, const SamplerParams &p, float &Mp, double &Sp,
                                  float &Mq, double &Sq) {
     ThreadSum<BF16> tp, tq;
@@ -351,9 +377,9 @@ __device__ inline void row_stats(const void *rowp, const void *rowq, int nslots,
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int slot = s0 + u * kThreads;
-            vp[u] = slot < nslots ? load_slot<BF16>(rowp, slot, p.V, aligned) : neg_inf_slot<BF16>();
+            vp[u] = slot < nslots ? load_slot<BF16>(rowp, slot, Vrow, aligned) : neg_inf_slot<BF16>();
             if constexpr (TWO)
-                vq[u] = slot < nslots ? load_slot<BF16>(rowq, slot, p.V, aligned)
+                vq[u] = slot < nslots ? load_slot<BF16>(rowq, slot, Vrow, aligned)
                                       : neg_inf_slot<BF16>();
         }
 #pragma unroll
@@ -366,16 +392,132 @@ __device__ inline void row_stats(const void *rowp, const void *rowq, int nslots,
     if constexpr (TWO) block_combine(tq.ref, tq.total(), sh, parity, 1, p, Mq, Sq);
 }
 
-template <bool BF16, bool TWO, bool ONE_TERM, bool FULL>
-__device__ inline void row_stats_any(const void *rowp, const void *rowq, int nslots, SharedState &sh,
-                                     int parity, const SamplerParams &p, float &Mp, double &Sp,
-                                     float &Mq, double &Sq) {
-    if constexpr (FULL) {
-        if (row_stats_fast<BF16, TWO, ONE_TERM>(rowp, rowq, nslots, sh, parity, p, Mp, Sp, Mq, Sq))
-            return;        // block-uniform
-        __syncthreads();   // every thread has read the combine buffers of this parity
+// ------------------------------------------------------------------------------------------
+// mailbox: the few numbers the parts of one sequence exchange after a streaming pass
+// ------------------------------------------------------------------------------------------
+// Layout of one box (kBoxBytes): word 0 the epoch (calls that have used the box), words
+// 16.. the progress counter of every part, then [part][stage parity][8] doubles of payload.
+// A part publishes stage s by storing its payload and then progress = epoch*1024 + s + 1; a
+// part that has seen every partner's stage s may publish stage s+1 into the other payload
+// buffer, and nobody can be two stages ahead of the slowest reader.  Part 0 bumps the epoch
+// when it leaves (every partner has read it by then: they publish their first stage after
+// reading it, and part 0 waits for that), so the counters never need resetting and the box
+// only has to be zero before its first use.  All accesses are device-scope atomics: the
+// parts run on compute units whose L2 caches are not coherent with each other.
+struct Mailbox {
+    uint32_t *words;
+    double *payload;
+    uint32_t base;
+    int part, split, stage;
+};
+
+__device__ inline uint32_t load_dev(const uint32_t *ptr) {
+    return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline void store_dev(uint32_t *ptr, uint32_t v) {
+    __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One exchange.  Every thread of the block calls it with the same `mine`; afterwards
+// sh.xchg[j] holds what part j published.  Ends with a barrier.  A wait that runs out of its
+// (very large) spin budget marks the block as failed and goes on, so that every block ends.
+__device__ inline void exchange(Mailbox &mb, const double (&mine)[8], SharedState &sh) {
+    const int parity = mb.stage & 1;
+    const uint32_t mark = mb.base + (uint32_t)mb.stage + 1u;
+    if (threadIdx.x == 0) {
+        double *dst = mb.payload + (mb.part * 2 + parity) * 8;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            __hip_atomic_store(reinterpret_cast<unsigned long long *>(dst + i),
+                               __builtin_bit_cast(unsigned long long, mine[i]), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the stores above have completed
+        store_dev(mb.words + 16 + mb.part, mark);
     }
-    row_stats<BF16, TWO>(rowp, rowq, nslots, sh, parity, p, Mp, Sp, Mq, Sq);
+    if ((int)threadIdx.x < mb.split) {
+        const int j = threadIdx.x;
+        if (j == mb.part) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sh.xchg[j][i] = mine[i];
+        } else {
+            if (!sh.failed) {
+                int spin = 0;
+                while ((int32_t)(load_dev(mb.words + 16 + j) - mark) < 0) {
+                    if (++spin > kSpinLimit) {
+                        sh.failed = 1;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            const double *src = mb.payload + (j * 2 + parity) * 8;
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                sh.xchg[j][i] = __builtin_bit_cast(
+                    double, __hip_atomic_load(reinterpret_cast<const unsigned long long *>(src + i),
+                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+        }
+    }
+    ++mb.stage;
+    __syncthreads();
+}
+
+// (M, S) of a row (and, if TWO, of the drafter row) over the whole vocabulary.  This block
+// streams its own part (`rowp`, `rowq` point at the part's first slot, `nslots` and `Vrow`
+// are the part's); with several parts the partial results are exchanged and combined in part
+// order, so every part holds the same bits afterwards.
+template <bool BF16, bool TWO, bool ONE_TERM, bool FULL, bool SHARED>
+__device__ inline void row_stats_any(const void *rowp, const void *rowq, int nslots, int Vrow, SharedState &sh,
+                                     int parity, Mailbox &mb, const SamplerParams &p, float &Mp,
+                                     double &Sp, float &Mq, double &Sq) {
+    if constexpr (!SHARED) {
+        if constexpr (FULL) {
+            if (row_stats_fast<BF16, TWO, ONE_TERM>(rowp, rowq, nslots, Vrow, sh, parity, p, Mp, Sp, Mq, Sq))
+                return;        // block-uniform
+            __syncthreads();   // every thread has read the combine buffers of this parity
+        }
+        row_stats<BF16, TWO>(rowp, rowq, nslots, Vrow, sh, parity, p, Mp, Sp, Mq, Sq);
+        return;
+    }
+    bool ok = false;
+    if (nslots <= 0) {  // a part without slots (tiny vocabulary): nothing to read, no mass
+        Mp = Mq = kRefInit;
+        Sp = Sq = 0.0;
+        ok = FULL;
+    } else if constexpr (FULL) {
+        ok = row_stats_fast<BF16, TWO, ONE_TERM>(rowp, rowq, nslots, Vrow, sh, parity, p, Mp, Sp, Mq, Sq);
+    }
+    if constexpr (FULL) {
+        const double mine[8] = {(double)Mp, Sp, (double)Mq, Sq, ok ? 1.0 : 0.0, 0.0, 0.0, 0.0};
+        exchange(mb, mine, sh);
+        bool all_ok = true;
+        for (int j = 0; j < mb.split; ++j) all_ok = all_ok && sh.xchg[j][4] != 0.0;
+        ok = all_ok;   // the same in every part
+    }
+    if (!ok) {  // some part saw an overflow or an empty sum: all repeat with the guarded pass
+        __syncthreads();
+        row_stats<BF16, TWO>(rowp, rowq, nslots, Vrow, sh, parity, p, Mp, Sp, Mq, Sq);
+        const double mine[8] = {(double)Mp, Sp, (double)Mq, Sq, 1.0, 0.0, 0.0, 0.0};
+        exchange(mb, mine, sh);
+    }
+    if (threadIdx.x < 2) {  // thread 0: the p row, thread 1: the q row
+        const int r = threadIdx.x;
+        float M = (float)sh.xchg[0][2 * r];
+        for (int j = 1; j < mb.split; ++j) M = fmaxf(M, (float)sh.xchg[j][2 * r]);
+        double S = 0.0;
+        for (int j = 0; j < mb.split; ++j)
+            S += sh.xchg[j][2 * r + 1] * exp2_f64(((double)(float)sh.xchg[j][2 * r] - (double)M) * p.c_d);
+        sh.comb_m[r] = M;
+        sh.comb_s[r] = S;
+    }
+    __syncthreads();
+    Mp = sh.comb_m[0];
+    Sp = sh.comb_s[0];
+    Mq = sh.comb_m[1];
+    Sq = sh.comb_s[1];
+    __syncthreads();  // comb_* and xchg may be rewritten by the next stage
 }
 
 // fp64 weights of one slot: p(x) (RESID = false) or max(0, p(x) - q(x)) (Eq. 2).
@@ -411,10 +553,11 @@ __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, 
 // Phase B adds the same numbers in another order than phase A, so at the last bit a crossing
 // can fall off the end of the region; that draw then takes the last token with mass and is
 // flagged as a boundary draw (it is within rounding of a CDF edge).
-template <bool BF16, bool RESID, bool FULL>
-__device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int nslots, float Mp,
-                                       double Sp, float Mq, double Sq, double u, SharedState &sh,
-                                       const SamplerParams &p, int &near_edge, double &Z_out) {
+template <bool BF16, bool RESID, bool FULL, bool SHARED>
+__device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int nslots, int Vrow, int tok_off,
+                                       float Mp, double Sp, float Mq, double Sq, double u, SharedState &sh,
+                                       Mailbox &mb, const SamplerParams &p, int &near_edge, double &Z_out,
+                                       bool &mine) {
     constexpr int EPV = Elem<BF16>::EPV;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool aligned = p.aligned != 0;
@@ -429,10 +572,10 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         for (int c = 0; c < kUnroll; ++c) {
             const int slot = s0 + c * 64 + lane;
             const bool in = slot < end;
-            const u32x4 a = load_slot<BF16, FULL>(rowp, in ? slot : beg, p.V, aligned);
+            const u32x4 a = load_slot<BF16, FULL>(rowp, in ? slot : beg, Vrow, aligned);
             vp[c] = in ? a : neg_inf_slot<BF16>();
             if constexpr (RESID) {
-                const u32x4 b = load_slot<BF16, FULL>(rowq, in ? slot : beg, p.V, aligned);
+                const u32x4 b = load_slot<BF16, FULL>(rowq, in ? slot : beg, Vrow, aligned);
                 vq[c] = in ? b : neg_inf_slot<BF16>();
             } else {
                 vq[c] = vp[c];
@@ -472,49 +615,90 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     }
     __syncthreads();
 
-    // every thread: ordered prefix over the regions, find the region holding the crossing
-    double Z = 0.0;
+    // the region totals of all parts, in vocabulary order
+    const int n_reg = SHARED ? mb.split * kWaves : kWaves;
+    if constexpr (!SHARED) {
+        // (one part: the wave totals are the region totals)
+    } else {
+        double pub[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) Z += sh.wave_total[w];
+        for (int w = 0; w < kWaves; ++w) pub[w] = sh.wave_total[w];
+        exchange(mb, pub, sh);
+        if ((int)threadIdx.x < n_reg) sh.all_total[threadIdx.x] = sh.xchg[threadIdx.x / kWaves][threadIdx.x % kWaves];
+        __syncthreads();
+    }
+
+    // every thread: ordered prefix over the regions, find the region holding the crossing
+    const double *totals = SHARED ? sh.all_total : sh.wave_total;
+    double Z = 0.0;
+    for (int w = 0; w < n_reg; ++w) Z += totals[w];
     Z_out = Z;
+    mine = false;
     if (!(Z > 0.0)) {  // caller falls back (residual of an exact tie) or reports the last token
         __syncthreads();
         near_edge = 1;
         return -1;
     }
     const double t = u * Z;
-    int wstar = -1, wlast = 0;
+    int rstar = -1, rlast = 0;
     double base = 0.0, prefix = 0.0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        const double tot = sh.wave_total[w];
+    for (int w = 0; w < n_reg; ++w) {
+        const double tot = totals[w];
         const double next = prefix + tot;  // same additions, same order as Z above
-        if (wstar < 0 && next > t) {
-            wstar = w;
+        if (rstar < 0 && next > t) {
+            rstar = w;
             base = prefix;
         }
-        if (tot > 0.0) wlast = w;
+        if (tot > 0.0) rlast = w;
         prefix = next;
     }
-    const bool forced = wstar < 0;  // u*Z rounded up to Z: take the last token with mass
-    if (forced) wstar = wlast;
+    const bool forced = rstar < 0;  // u*Z rounded up to Z: take the last token with mass
+    if (forced) rstar = rlast;
+    if constexpr (SHARED) {
+        __syncthreads();  // all_total and xchg may be rewritten from here on
+        if (rstar / kWaves != mb.part) {  // another part holds the crossing and finishes the draw
+            near_edge = 0;
+            return -1;
+        }
+    }
+    mine = true;
+    const int wstar = rstar % kWaves;
 
     // phase B: the block walks region wstar; thread i owns slots [rb + i*per, rb + (i+1)*per)
     const int rb = min(wstar * span, nslots), re = min(rb + span, nslots);
     const int per = (re - rb + kThreads - 1) / kThreads;  // <= 5 for a 151,936-wide bf16 row
     const int my0 = rb + threadIdx.x * per, my1 = min(my0 + per, re);
+    // a thread's run is read kChunk slots at a time, all loads of a chunk in flight together
+    // (a 151,936-wide bf16 row needs one chunk)
     double my_total = 0.0;
     int my_last = -1;
-    for (int slot = my0; slot < my1; ++slot) {
-        const u32x4 vp = load_slot<BF16, FULL>(rowp, slot, p.V, aligned);
-        u32x4 vq = vp;
-        if constexpr (RESID) vq = load_slot<BF16, FULL>(rowq, slot, p.V, aligned);
-        double w[EPV];
-        slot_weights<BF16, RESID>(vp, vq, Mp, Cp, Mq, Cq, p, w);
+    auto load_chunk = [&](int c0, u32x4 (&vp)[kChunk], u32x4 (&vq)[kChunk]) {
 #pragma unroll
-        for (int j = 0; j < EPV; ++j) {
-            my_total += w[j];
-            if (w[j] > 0.0) my_last = slot * EPV + j;
+        for (int j = 0; j < kChunk; ++j) {
+            const int slot = c0 + j;
+            const bool in = slot < my1;
+            const u32x4 a = load_slot<BF16, FULL>(rowp, in ? slot : rb, Vrow, aligned);
+            vp[j] = in ? a : neg_inf_slot<BF16>();
+            if constexpr (RESID) {
+                const u32x4 b = load_slot<BF16, FULL>(rowq, in ? slot : rb, Vrow, aligned);
+                vq[j] = in ? b : neg_inf_slot<BF16>();
+            } else {
+                vq[j] = vp[j];
+            }
+        }
+    };
+    for (int c0 = my0; c0 < my1; c0 += kChunk) {
+        u32x4 vp[kChunk], vq[kChunk];
+        load_chunk(c0, vp, vq);
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+            double w[EPV];
+            slot_weights<BF16, RESID>(vp[j], vq[j], Mp, Cp, Mq, Cq, p, w);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                my_total += w[e];
+                if (w[e] > 0.0) my_last = tok_off + (c0 + j) * EPV + e;
+            }
         }
     }
     const double incl_wave = wave_inclusive_scan(my_total, lane);
@@ -533,22 +717,24 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         double c = run_excl;
         int tok = -1, edge = 0;
         double before = c, after = c;
-        for (int slot = my0; slot < my1 && tok < 0; ++slot) {
-            const u32x4 vp = load_slot<BF16, FULL>(rowp, slot, p.V, aligned);
-            u32x4 vq = vp;
-            if constexpr (RESID) vq = load_slot<BF16, FULL>(rowq, slot, p.V, aligned);
-            double w[EPV];
-            slot_weights<BF16, RESID>(vp, vq, Mp, Cp, Mq, Cq, p, w);
+        for (int c0 = my0; c0 < my1 && tok < 0; c0 += kChunk) {
+            u32x4 vp[kChunk], vq[kChunk];
+            load_chunk(c0, vp, vq);
 #pragma unroll
-            for (int j = 0; j < EPV; ++j) {
-                if (tok < 0) {
-                    const double cn = c + w[j];
-                    if (cn > t) {
-                        tok = slot * EPV + j;
-                        before = c;
-                        after = cn;
+            for (int j = 0; j < kChunk; ++j) {
+                double w[EPV];
+                slot_weights<BF16, RESID>(vp[j], vq[j], Mp, Cp, Mq, Cq, p, w);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    if (tok < 0) {
+                        const double cn = c + w[e];
+                        if (cn > t) {
+                            tok = tok_off + (c0 + j) * EPV + e;
+                            before = c;
+                            after = cn;
+                        }
+                        c = cn;
                     }
-                    c = cn;
                 }
             }
         }
@@ -573,11 +759,13 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     return tok;
 }
 
-template <bool BF16, bool ONE_TERM, bool FULL>
+template <bool BF16, bool ONE_TERM, bool FULL, bool SHARED>
 __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParams p) {
     __shared__ SharedState sh;
+    __shared__ uint32_t sh_epoch;
     constexpr int EPV = Elem<BF16>::EPV;
-    const int b = blockIdx.x;
+    const int split = SHARED ? p.split : 1;
+    const int b = blockIdx.x / split, part = blockIdx.x % split;
     // bounds come from device data: clamp them by the host-side totals so that no value of
     // q_indptr can push a row outside the logits buffers
     const int row0 = max(0, min(p.q_indptr[b], p.total_q - 1));
@@ -585,34 +773,53 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     k = max(0, min(k, min(p.max_k, p.total_q - 1 - row0)));
     const int drow0 = row0 - b;
     if (drow0 < 0 || drow0 + k > p.total_q - p.B) k = 0;
-    const int nslots = (p.V + EPV - 1) / EPV;
+    const int nslots_row = (p.V + EPV - 1) / EPV;
+    // this block's part of the vocabulary: a whole number of 64-slot groups
+    const int part_span = SHARED ? ((nslots_row + split - 1) / split + 63) / 64 * 64 : nslots_row;
+    const int lo = min(part * part_span, nslots_row);
+    const int nslots = min(lo + part_span, nslots_row) - lo;
+    const int Vrow = p.V - lo * EPV, tok_off = lo * EPV;
     const size_t esz = BF16 ? 2 : 4;
     const char *tbase = static_cast<const char *>(p.target);
     const char *dbase = static_cast<const char *>(p.draft);
     int32_t *out = p.out_tokens + (size_t)b * (p.max_k + 1);
     const double u_fin = (double)p.u_final[b];
 
+    Mailbox mb{nullptr, nullptr, 0u, part, split, 0};
+    if (threadIdx.x == 0) sh.failed = 0;
+    if constexpr (SHARED) {
+        mb.words = reinterpret_cast<uint32_t *>(p.boxes + (size_t)b * kBoxBytes);
+        mb.payload = reinterpret_cast<double *>(p.boxes + (size_t)b * kBoxBytes + kBoxHeaderBytes);
+        if (threadIdx.x == 0) sh_epoch = load_dev(mb.words);
+    }
+    __syncthreads();
+    if constexpr (SHARED) mb.base = sh_epoch * 1024u;
+
     int n = 0, flag_accept = 0, flag_cdf = 0, final_token = -1;
-    bool rejected = false;
-    const void *scan_row = tbase;  // row, reference and sum of the final inverse-CDF walk over p
+    bool rejected = false, mine = false;
+    const char *scan_row = tbase;  // row, reference and sum of the final inverse-CDF walk over p
     float scan_M = 0.f;
     double scan_S = 1.0;
     for (int i = 0; i < k; ++i) {
-        const void *rowp = tbase + (size_t)(row0 + i) * p.ld_t * esz;
-        const void *rowq = dbase + (size_t)(drow0 + i) * p.ld_d * esz;
-        float Mp, Mq;
-        double Sp, Sq;
-        row_stats_any<BF16, true, ONE_TERM, FULL>(rowp, rowq, nslots, sh, i & 1, p, Mp, Sp, Mq, Sq);
+        const char *rowp = tbase + (size_t)(row0 + i) * p.ld_t * esz;
+        const char *rowq = dbase + (size_t)(drow0 + i) * p.ld_d * esz;
+        // the drafted token's two logits and the uniform are requested before the streaming
+        // pass, so that the acceptance test does not start with a chain of dependent loads
         int x = p.draft_tokens[drow0 + i];
         x = max(0, min(x, p.V - 1));  // memory safety only; ids outside [0,V) are a caller error
         float zpx, zqx;
         if constexpr (BF16) {
-            zpx = as_f32((uint32_t) static_cast<const uint16_t *>(rowp)[x] << 16);
-            zqx = as_f32((uint32_t) static_cast<const uint16_t *>(rowq)[x] << 16);
+            zpx = as_f32((uint32_t) reinterpret_cast<const uint16_t *>(rowp)[x] << 16);
+            zqx = as_f32((uint32_t) reinterpret_cast<const uint16_t *>(rowq)[x] << 16);
         } else {
-            zpx = static_cast<const float *>(rowp)[x];
-            zqx = static_cast<const float *>(rowq)[x];
+            zpx = reinterpret_cast<const float *>(rowp)[x];
+            zqx = reinterpret_cast<const float *>(rowq)[x];
         }
+        const double u = (double)p.u_accept[drow0 + i];
+        float Mp, Mq;
+        double Sp, Sq;
+        row_stats_any<BF16, true, ONE_TERM, FULL, SHARED>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16, nslots, Vrow, sh,
+                                                  i & 1, mb, p, Mp, Sp, Mq, Sq);
         // Eq. 1 in fp64: rho = p(x)/q(x) = exp(((zp-Mp) - (zq-Mq))/T) * Sq/Sp
         double rho;
         if (zqx == -INFINITY)
@@ -621,23 +828,24 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
             rho = exp((((double)zpx - (double)Mp) - ((double)zqx - (double)Mq)) * p.inv_T) *
                   (Sq / Sp);
         const double thr = rho < 1.0 ? rho : 1.0;
-        const double u = (double)p.u_accept[drow0 + i];
         if (fabs(u - thr) <= kBoundaryEps) flag_accept = 1;
         if (u < thr) {
-            if (threadIdx.x == 0) out[i] = x;
+            if (threadIdx.x == 0 && part == 0) out[i] = x;
             n = i + 1;
             continue;
         }
         // first rejection: one draw from the residual distribution (Eq. 2)
         double Z;
         int edge = 0;
-        final_token = inverse_cdf_pass<BF16, true, FULL>(rowp, rowq, nslots, Mp, Sp, Mq, Sq, u_fin, sh,
-                                                         p, edge, Z);
+        final_token = inverse_cdf_pass<BF16, true, FULL, SHARED>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16, nslots, Vrow,
+                                                         tok_off, Mp, Sp, Mq, Sq, u_fin, sh, mb, p, edge, Z, mine);
         flag_cdf = edge;
         rejected = true;
         scan_row = rowp;
         scan_M = Mp;
         scan_S = Sp;
+        // an empty residual (an exact tie, Z = 0 in every part) falls back to the target itself
+        if (!(Z > 0.0)) final_token = -2;
         break;
     }
     bool scan_target = false;
@@ -645,25 +853,38 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         scan_row = tbase + (size_t)(row0 + k) * p.ld_t * esz;
         float Mq;
         double Sq;
-        row_stats_any<BF16, false, ONE_TERM, FULL>(scan_row, scan_row, nslots, sh, k & 1, p, scan_M, scan_S,
-                                                   Mq, Sq);
+        row_stats_any<BF16, false, ONE_TERM, FULL, SHARED>(scan_row + (size_t)lo * 16, scan_row + (size_t)lo * 16, nslots, Vrow,
+                                                   sh, k & 1, mb, p, scan_M, scan_S, Mq, Sq);
         scan_target = true;
-    } else if (final_token < 0) {  // empty residual (an exact tie): fall back to the target itself
+    } else if (final_token == -2) {
         scan_target = true;
     }
     if (scan_target) {
         double Z;
         int edge = 0;
-        final_token = inverse_cdf_pass<BF16, false, FULL>(scan_row, scan_row, nslots, scan_M, scan_S,
-                                                          scan_M, scan_S, u_fin, sh, p, edge, Z);
+        final_token = inverse_cdf_pass<BF16, false, FULL, SHARED>(scan_row + (size_t)lo * 16, scan_row + (size_t)lo * 16, nslots,
+                                                          Vrow, tok_off, scan_M, scan_S, scan_M, scan_S, u_fin, sh,
+                                                          mb, p, edge, Z, mine);
         flag_cdf = rejected ? 1 : edge;
+        if (!(Z > 0.0)) {  // row without any finite logit: part 0 reports the last token
+            mine = part == 0;
+            final_token = p.V - 1;
+        }
     }
-    if (final_token < 0) final_token = p.V - 1;  // row without any finite logit
+    // the part that made the final draw writes the sequence's results
     if (threadIdx.x == 0) {
-        out[n] = final_token;
-        for (int j = n + 1; j <= p.max_k; ++j) out[j] = -1;
-        p.out_num_accepted[b] = n;
-        if (p.out_flags) p.out_flags[b] = (flag_accept ? 1 : 0) | (flag_cdf ? 2 : 0);
+        const bool failed = sh.failed != 0;
+        if (mine) {
+            out[n] = final_token;
+            for (int j = n + 1; j <= p.max_k; ++j) out[j] = -1;
+            p.out_num_accepted[b] = failed ? -1 : n;
+            if (p.out_flags) p.out_flags[b] = (flag_accept ? 1 : 0) | (flag_cdf ? 2 : 0);
+        } else if (failed) {
+            p.out_num_accepted[b] = -1;  // a wait for a partner ran out: make it impossible to miss
+        }
+        if constexpr (SHARED) {
+            if (part == 0) store_dev(mb.words, sh_epoch + 1u);
+        }
     }
 }
 
@@ -672,8 +893,8 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
 
 extern "C" {
 
-size_t respec_rejection_sample_workspace_bytes(int32_t, int32_t, int32_t, respec_dtype_t) {
-    return 0;
+size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t, int32_t, respec_dtype_t) {
+    return B > 0 ? (size_t)B * respec::kBoxBytes : 0;
 }
 
 respec_status_t respec_rejection_sample(const void *target_logits, const void *draft_logits,
@@ -686,8 +907,6 @@ respec_status_t respec_rejection_sample(const void *target_logits, const void *d
                                         void *workspace, size_t workspace_bytes,
                                         void *hip_stream) {
     using namespace respec;
-    (void)workspace;
-    (void)workspace_bytes;
     if (B <= 0 || total_q < B || max_k < 0 || V <= 0)
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: need B > 0, total_q >= B, max_k >= 0, V > 0 "
                     "(B=%d total_q=%d max_k=%d V=%d)", B, total_q, max_k, V);
@@ -738,12 +957,39 @@ respec_status_t respec_rejection_sample(const void *target_logits, const void *d
     p.aligned = aligned_to(target_logits, 16) && (ld_t * esz) % 16 == 0 &&
                 (!has_drafts || (aligned_to(draft_logits, 16) && (ld_d * esz) % 16 == 0));
 
+    // work-groups per sequence: as many as there are otherwise idle compute units, as long as a
+    // part keeps a useful share of the row; one (and no mailbox) without a workspace
+    int split = 1;
+    if (workspace) {
+        if (workspace_bytes < (size_t)B * kBoxBytes || !aligned_to(workspace, 16))
+            return fail(RESPEC_ERR_WORKSPACE, "rejection_sample: workspace of %zu bytes (16-byte aligned) needed, got %zu",
+                        (size_t)B * kBoxBytes, workspace_bytes);
+        int cus = 256, dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        const int epv0 = logits_dt == RESPEC_BF16 ? 8 : 4;
+        const long slots_row = ((long)V + epv0 - 1) / epv0;
+        while (split < kMaxSplit && (long)B * split * 2 <= cus && slots_row / (split * 2) >= 2048) split *= 2;
+        const long forced = env_long("RESPEC_SAMPLER_SPLIT", 0);
+        if (forced == 1 || forced == 2 || forced == 4 || forced == 8) split = (int)forced;
+    }
+    if ((int64_t)B * split > 0x7fffffffLL)
+        return fail(RESPEC_ERR_UNSUPPORTED, "rejection_sample: too many work-groups");
+    p.split = split;
+    p.boxes = static_cast<char *>(workspace);
+
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int epv = logits_dt == RESPEC_BF16 ? 8 : 4;
     const bool full = p.aligned && V % epv == 0 && env_long("RESPEC_SAMPLER_GUARDED", 0) == 0;
     const bool bf = logits_dt == RESPEC_BF16, one = p.one_term != 0;
-#define RESPEC_LAUNCH_SAMPLER(BF, ONE, FULL) \
-    hipLaunchKernelGGL((rejection_sample_kernel<BF, ONE, FULL>), dim3(B), dim3(kThreads), 0, stream, p)
+#define RESPEC_LAUNCH_SAMPLER(BF, ONE, FULL)                                                                        \
+    do {                                                                                                           \
+        if (split > 1)                                                                                             \
+            hipLaunchKernelGGL((rejection_sample_kernel<BF, ONE, FULL, true>), dim3((unsigned)(B * split)),        \
+                               dim3(kThreads), 0, stream, p);                                                      \
+        else                                                                                                       \
+            hipLaunchKernelGGL((rejection_sample_kernel<BF, ONE, FULL, false>), dim3((unsigned)B), dim3(kThreads), \
+                               0, stream, p);                                                                      \
+    } while (0)
     if (!full) {
         if (bf) RESPEC_LAUNCH_SAMPLER(true, false, false); else RESPEC_LAUNCH_SAMPLER(false, false, false);
     } else if (bf) {

@@ -64,7 +64,39 @@ def oracle_attention(oracle, batch: synth.VerifyBatch, sm_scale=None, n_threads=
 sub_batch = synth.sub_batch
 
 
-def gpu_sample(batch: synth.VerifyBatch, temperature=None, max_k=None, stream=None):
+_SAMPLER_WORKSPACES = {}
+
+
+def sampler_workspace(B, V, dtype_code, device):
+    """The sampler's mailbox workspace: zero once, then reused by every later call (the
+    library keeps it consistent from call to call)."""
+    need = binding.respec_rejection_sample_workspace_bytes(B, B, V, dtype_code)
+    key = (str(device), B)
+    ws = _SAMPLER_WORKSPACES.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.zeros(need, dtype=torch.uint8, device=device)
+        _SAMPLER_WORKSPACES[key] = ws
+    return ws
+
+
+@contextmanager
+def sampler_split(split):
+    """Force the number of work-groups that share a sequence (None: the library's choice)."""
+    old = os.environ.get("RESPEC_SAMPLER_SPLIT")
+    if split is None:
+        os.environ.pop("RESPEC_SAMPLER_SPLIT", None)
+    else:
+        os.environ["RESPEC_SAMPLER_SPLIT"] = str(split)
+    try:
+        yield
+    finally:
+        if old is None:
+            os.environ.pop("RESPEC_SAMPLER_SPLIT", None)
+        else:
+            os.environ["RESPEC_SAMPLER_SPLIT"] = old
+
+
+def gpu_sample(batch: synth.VerifyBatch, temperature=None, max_k=None, stream=None, workspace="shared"):
     wl = batch.wl
     T = wl.temperature if temperature is None else temperature
     B = len(batch.k_per_seq)
@@ -73,9 +105,12 @@ def gpu_sample(batch: synth.VerifyBatch, temperature=None, max_k=None, stream=No
     toks = torch.full((B, max_k + 1), -7, dtype=torch.int32, device=dev)
     n = torch.full((B,), -7, dtype=torch.int32, device=dev)
     flags = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    if isinstance(workspace, str):
+        dt = binding.RESPEC_F32 if batch.target_logits.dtype == torch.float32 else binding.RESPEC_BF16
+        workspace = sampler_workspace(B, batch.target_logits.shape[1], dt, dev)
     binding.respec_rejection_sample(batch.target_logits, batch.draft_logits, batch.draft_tokens,
                                     batch.q_indptr, batch.u_accept, batch.u_final, toks, n, flags,
-                                    max_k, T, stream=stream)
+                                    max_k, T, workspace=workspace, stream=stream)
     torch.cuda.synchronize()
     return toks.cpu().numpy(), n.cpu().numpy(), flags.cpu().numpy()
 

@@ -9,7 +9,7 @@ import pytest
 import torch
 from scipy import stats
 
-from helpers import compare_sampler, gpu_sample, oracle_sample
+from helpers import compare_sampler, gpu_sample, oracle_sample, sampler_split
 from paper_2510_26475_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -103,6 +103,39 @@ def test_huge_outlier_logit_takes_the_guarded_pass(oracle):
     batch.target_logits[5, 5] = 250.0
     batch.draft_logits[4, 5] = 250.0
     gpu, ref, _ = _parity(oracle, batch)
+
+
+@pytest.mark.parametrize("split", [1, 2, 4, 8])
+def test_sequences_shared_by_several_work_groups(oracle, split):
+    # the vocabulary of a sequence is cut into `split` parts that exchange partial sums; the
+    # mailbox workspace is reused from call to call without being cleared
+    wl = _wl("shared", 151936, "bf16", sigma=1.0)
+    ks = [3, 0, 4, 1, 2, 4, 3, 3, 0, 2, 4, 1]
+    batch = _batch(wl, ks, seed=31)
+    ref = oracle_sample(oracle, batch)
+    with sampler_split(split):
+        for _ in range(3):
+            gpu = gpu_sample(batch)
+            tally = compare_sampler(gpu, ref)
+            assert tally["flagged"] <= 3, tally
+
+
+@pytest.mark.parametrize("V", [1000, 70, 4099])
+def test_shared_sequences_with_small_and_ragged_vocabularies(oracle, V):
+    # parts without any slot, unaligned rows, a partial last slot
+    wl = _wl("shared_small", V, "bf16")
+    ks = [2, 0, 3, 1] * 4
+    batch = _batch(wl, ks, seed=V + 1)
+    ref = oracle_sample(oracle, batch)
+    for split in (2, 8):
+        with sampler_split(split):
+            compare_sampler(gpu_sample(batch), ref)
+
+
+def test_without_a_workspace_one_work_group_walks_a_sequence(oracle):
+    wl = _wl("nows", 151936, "bf16")
+    batch = _batch(wl, [3, 1, 0, 2], seed=33)
+    compare_sampler(gpu_sample(batch, workspace=None), oracle_sample(oracle, batch))
 
 
 def test_no_drafts_at_all_is_plain_sampling(oracle):

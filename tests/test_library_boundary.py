@@ -44,7 +44,9 @@ def test_workspace_query(lib):
     assert f(256, 1024, 668000, 4, 8192, 28, 5, 128, binding.RESPEC_BF16) == 0     # Hq % Hkv
     assert f(256, 1024, 668000, 4, 8192, 28, 4, 96, binding.RESPEC_BF16) == 0      # head size
     assert f(0, 0, 0, 4, 8192, 28, 4, 128, binding.RESPEC_BF16) == 0
-    assert lib.respec_rejection_sample_workspace_bytes(256, 1024, 151936, binding.RESPEC_BF16) == 0
+    w = lib.respec_rejection_sample_workspace_bytes(256, 1024, 151936, binding.RESPEC_BF16)
+    assert w > 0 and w % 256 == 0                  # one mailbox per sequence
+    assert lib.respec_rejection_sample_workspace_bytes(0, 0, 151936, binding.RESPEC_BF16) == 0
 
 
 def test_attention_argument_errors_need_no_gpu(lib):
