@@ -3,22 +3,21 @@
 // rows per sequence, grouped-query heads, ragged token-major KV cache.
 //
 // bf16 path.  The G*(k_b+1) query rows that share one KV head are the columns of 16-wide
-// MFMA tiles.  Work is cut into 128-key tiles (four waves x 32 keys); the tiles of all
-// (KV head, sequence) pairs form one flat list that is split evenly over a fixed number of
-// co-resident work-groups (two per compute unit), so every work-group streams the same
-// number of bytes whatever the mix of sequence lengths.  A work-group walks its range as a
-// list of segments (one sequence each); while it finishes a segment the first tile of the
-// next one is already in flight.  Each wave streams its own 32-key tiles: 16-byte coalesced
-// global loads -> registers -> wave-private LDS tile -> MFMA operands.  Scores are computed
+// MFMA tiles.  Work is cut into 32-key tiles of one (KV head, sequence); the tiles form flat
+// lists ordered (head, sequence, tile) that are split evenly over a fixed number of ranges
+// (four per compute unit), so every range streams the same number of bytes whatever the mix of
+// sequence lengths.  One work-group per compute unit holds four pairs of waves: the consumer
+// of a pair computes its range, the producer walks the same range ahead of it and only moves
+// tiles (global memory -> registers -> a two-slot ring in LDS).  Scores are computed
 // transposed (S^T = K Q^T, v_mfma_f32_16x16x32_bf16) so that a lane's four accumulator rows
 // are keys and its column is one query row: the probabilities then feed the second product
 // (O^T = V^T P^T) straight from registers, and the softmax statistics of a row live in one
 // lane column.  The contraction indices of both products are permuted freely (any order is
 // valid as long as both operands agree), which is what lets K be read from LDS in 16-byte
-// pieces and V in 16-byte pieces along d with a register-level 2-byte regroup.
-// The four waves merge through LDS.  A segment that covers a whole sequence writes the
-// output; a sequence cut by a work-group boundary leaves fp32 partials (max, sum,
-// unnormalised O), at most two per work-group, which a second kernel merges in a fixed
+// pieces and V in 8-byte pieces along d with a register-level 2-byte regroup.
+// A range is walked as segments (one sequence each).  A segment that covers a whole sequence
+// writes the output; a sequence cut by a range border leaves partials (max, sum, unnormalised
+// O as 16-bit fixed point), at most two per range, which a second kernel folds in a fixed
 // order (deterministic, no float atomics).
 //
 // fp32 path.  A plain fp32 kernel (no MFMA, no split; the fp32 workload is the small parity
@@ -232,7 +231,7 @@ struct Bf16Cfg {
     static constexpr int kKSteps = D / 32;                    // MFMA k-steps of S^T
     static constexpr int kDTiles = D / 16;                    // 16-row d tiles of O^T
     static constexpr int kEpl = D / 16;                       // V elements per lane per key
-    static constexpr int kMergeStride = D + 4;                // fp32 merge row (floats)
+    static constexpr int kMergeStride = D + 4;                // fp32 row of the write-out staging (floats)
 };
 
 // One 32-key tile of one KV head: kLoads 16-byte loads per lane, rows row_bytes apart.
@@ -620,7 +619,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             // the hardware runs a wave's LDS operations in order)
             asm volatile("" ::: "memory");
             float *stage = reinterpret_cast<float *>(k_lds);  // [32][kMergeStride]
-            float *stat = stage + 32 * C::kMergeStride;       // [32]: max, sum, output row, -
+            float *stat = stage + 32 * C::kMergeStride;       // [32]: max, sum, output row, largest magnitude
             constexpr int kLanesPerOutRow = D / 4;            // lanes that cover a row, 4 floats each
             constexpr int kRowsPerPass = 64 / kLanesPerOutRow;
 #pragma unroll

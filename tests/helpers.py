@@ -13,9 +13,9 @@ from paper_2510_26475_amd import binding, synth
 
 @contextmanager
 def attn_wgs(wgs):
-    """Force the number of work-groups the key tiles are split over (None = the default,
-    two per compute unit).  Small counts put many sequences in one work-group, large counts
-    cut every sequence into many partials."""
+    """Force the number of ranges the key tiles are split over (None = the default, four per
+    compute unit).  Small counts put many sequences in one range, large counts cut every
+    sequence into many partials."""
     old = os.environ.get("RESPEC_ATTN_WGS")
     if wgs is None:
         os.environ.pop("RESPEC_ATTN_WGS", None)
