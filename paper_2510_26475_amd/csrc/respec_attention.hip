@@ -45,9 +45,14 @@ constexpr int kConsumers = 4;         // computing waves per work-group (one per
 constexpr int kSlots = 2;             // tiles in a pair's LDS ring = tiles a producer keeps in flight
 constexpr int kMaxWaves = 2048;       // upper bound of the split width (sizes the workspace)
 
-// Where a wave's range of the flat tile list starts, and how many tiles it holds.
+// Where a wave's range of the flat tile list starts and how many tiles it holds, with the
+// bounds of its first sequence already resolved (one look-up instead of a chain of them before
+// the first tile can be requested).
 struct __align__(16) WaveStart {
     int32_t h, b, t, n;
+    int32_t q0, R, L, tiles;
+    int64_t kv0;
+    int64_t pad;
 };
 
 struct AttnParams {
@@ -142,7 +147,9 @@ __device__ inline float sum_across_rows(float x) {
 // The split.  The KV heads form HI sub-lists of Hkv/HI heads; a sub-list is the flat tile list
 // (head, sequence, tile) of its heads, `sub_total` tiles long, cut evenly into W/HI parts.
 // Wave u takes part u / HI of sub-list u % HI.  Part r owns flat tiles
-// [r*sub_total/parts, (r+1)*sub_total/parts) of its sub-list.
+// [range_begin(r), range_begin(r+1)) of its sub-list.  (Unequal parts were tried, to make up
+// for the odd-numbered dies being served about 5 % slower under saturation; the kernel did not
+// get faster: the dies share one memory system and the early finishers' share is not taken up.)
 struct Split {
     int64_t T;           // tiles of one KV head
     int64_t sub_total;   // tiles of one sub-list
@@ -158,12 +165,14 @@ __device__ inline Split make_split(const AttnParams &p, int64_t T) {
     return s;
 }
 
+__device__ inline int64_t range_begin(const Split &s, int r) { return (int64_t)r * s.sub_total / s.parts; }
+
 __device__ inline int part_of_tile(const Split &s, int64_t x) {  // x: flat index in the sub-list
     return (int)(((x + 1) * s.parts - 1) / s.sub_total);
 }
 
 __device__ inline bool part_owns_tiles(const Split &s, int r) {
-    return (int64_t)(r + 1) * s.sub_total / s.parts > (int64_t)r * s.sub_total / s.parts;
+    return range_begin(s, r + 1) > range_begin(s, r);
 }
 
 // Builds the tile prefix over sequences and every wave's starting point.
@@ -197,10 +206,10 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     const Split sp = make_split(p, sh_base);
     const int64_t T = sp.T;
     for (int w = tid; w < p.W; w += 1024) {
-        WaveStart st{0, 0, 0, 0};
+        WaveStart st{0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         if (T > 0) {
             const int r = w / p.HI, sub = w % p.HI;
-            const int64_t a0 = (int64_t)r * sp.sub_total / sp.parts, a1 = (int64_t)(r + 1) * sp.sub_total / sp.parts;
+            const int64_t a0 = range_begin(sp, r), a1 = range_begin(sp, r + 1);
             st.n = (int32_t)(a1 - a0);
             st.h = sub * sp.hps + (int32_t)(a0 / T);
             const int32_t rem = (int32_t)(a0 % T);
@@ -211,6 +220,12 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
             }
             st.b = lo;
             st.t = rem - p.tile_prefix[lo];
+            const SeqInfo si = seq_info(p, lo);
+            st.q0 = si.q0;
+            st.R = si.R;
+            st.L = si.L;
+            st.tiles = si.tiles;
+            st.kv0 = si.kv0;
         }
         p.wave_start[w] = st;
     }
@@ -358,20 +373,27 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
 
     if (u >= p.W) return;  // wave-uniform, and the same for both waves of a pair
     const ConstPtr<int32_t> start = as_constant(reinterpret_cast<const int32_t *>(p.wave_start + u));
-    const WaveStart st{start[0], start[1], start[2], start[3]};
-    const int n_tiles = st.n;
-    if (n_tiles <= 0 || st.h >= p.Hkv) return;
+    const int n_tiles = start[3];
+    if (n_tiles <= 0 || start[0] >= p.Hkv) return;
 
     char *ring = smem + pair * (kSlots * C::kWaveBytes);
     const int32_t row_bytes = p.Hkv * D * 2;
     bool alive = true;
 
-    Cursor cp;  // position of this wave in its range
-    cp.b = st.b;
-    cp.h = st.h;
-    cp.t = st.t;
-    cp.si = seq_info(p, st.b);
-    cursor_find_next(p, cp);
+    // Position of this wave in its range.  The bounds of the sequence after the first are
+    // looked up only after the first requests (tile or query rows) have gone out.
+    Cursor cp;
+    cp.h = start[0];
+    cp.b = start[1];
+    cp.t = start[2];
+    cp.si.q0 = start[4];
+    cp.si.R = start[5];
+    cp.si.L = start[6];
+    cp.si.tiles = start[7];
+    cp.si.kv0 = (int64_t)(uint32_t)start[8] | ((int64_t)start[9] << 32);
+    cp.nb = cp.b;
+    cp.nh = cp.h;
+    cp.nsi = cp.si;
 
     if (producer) {
         // ------------------------------------------------------------------------------------
@@ -388,6 +410,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
         // of requests behind a buffer's own is then the same on every path, and the wait for a
         // buffer leaves exactly the younger ones in flight.  An idle request re-reads one
         // 256-byte piece of the last tile, which the caches hold.
+        bool next_known = false;  // cp.nb / cp.nh / cp.nsi have been looked up
         auto request = [&](auto S) __attribute__((always_inline)) {
             constexpr int s = decltype(S)::value;
             const bool live = requested < n_tiles;
@@ -395,6 +418,10 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             const int rows_valid = live ? cp.si.L - 1 - cp.t * kTileKeys : 0;
             load_tile<D>(kr[s], static_cast<const char *>(p.k) + tile_off, row_bytes, row_off, rows_valid, lane);
             load_tile<D>(vr[s], static_cast<const char *>(p.v) + tile_off, row_bytes, row_off, rows_valid, lane);
+            if (!next_known) {  // once, with the first tile already on its way
+                cursor_find_next(p, cp);
+                next_known = true;
+            }
             if (live) {
                 if (requested + 1 < n_tiles) cursor_advance(p, cp);
                 ++requested;
@@ -451,6 +478,8 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     };
 
     bf16x8 qreg[NT][C::kKSteps];  // query rows of the segment at hand
+    load_q(qreg, cp.si, cp.h);    // of the first segment, requested before anything else
+    cursor_find_next(p, cp);
     // query rows of the next segment, requested when the current one begins (not kept for the
     // widest column blocks at D = 128, where the registers do not allow it: a segment then
     // starts by waiting for its query rows)
@@ -486,7 +515,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                     for (int t = 0; t < C::kKSteps; ++t) qreg[nt][t] = qnext[kPrefetchQ ? nt : 0][t];
-            } else {
+            } else if (idx > 0) {
                 load_q(qreg, cp.si, cp.h);
             }
             if constexpr (kPrefetchQ) {
