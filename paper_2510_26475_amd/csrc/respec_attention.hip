@@ -78,6 +78,8 @@ struct AttnParams {
                            // pieces of a cache row are requested together (HI divides W, Hkv
                            // and the waves of a work-group; 1 = one head-major list)
     int32_t *error_flag;   // set to 1 by a wave whose bounded wait for its partner ran out
+    int32_t *cuts;         // [B][Hkv][4] first and last part that hold tiles of the (sequence,
+                           // head), first query row, query rows; error_flag[1]: every part owns tiles
     int32_t Mpad;          // G*max_q rounded up to kColTile
     float scale2;          // sm_scale * log2(e)
 };
@@ -175,14 +177,21 @@ __device__ inline bool part_owns_tiles(const Split &s, int r) {
     return range_begin(s, r + 1) > range_begin(s, r);
 }
 
-// Builds the tile prefix over sequences and every wave's starting point.
+// Builds the tile prefix over sequences, every wave's starting point and, for every
+// (sequence, KV head), the first and the last part that hold its tiles (the 64-bit divisions
+// behind them are done once here, not by every thread of the combine kernel).
+constexpr int kPrepLdsSeqs = 8192;  // batches up to this size keep the prefix in LDS for the searches
+
 __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     __shared__ int sh_scan[1024];
+    __shared__ int sh_prefix[kPrepLdsSeqs + 1];
     __shared__ int sh_base;
     const int tid = threadIdx.x;
+    const bool in_lds = p.B <= kPrepLdsSeqs;
     if (tid == 0) {
         sh_base = 0;
         p.tile_prefix[0] = 0;
+        sh_prefix[0] = 0;
         *p.error_flag = 0;
     }
     __syncthreads();
@@ -198,11 +207,15 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
             __syncthreads();
         }
         const int base = sh_base;
-        if (b < p.B) p.tile_prefix[b + 1] = base + sh_scan[tid];
+        if (b < p.B) {
+            p.tile_prefix[b + 1] = base + sh_scan[tid];
+            if (in_lds) sh_prefix[b + 1] = base + sh_scan[tid];
+        }
         __syncthreads();
         if (tid == 1023) sh_base = base + sh_scan[1023];
         __syncthreads();
     }
+    auto prefix = [&](int i) { return in_lds ? sh_prefix[i] : p.tile_prefix[i]; };
     const Split sp = make_split(p, sh_base);
     const int64_t T = sp.T;
     for (int w = tid; w < p.W; w += 1024) {
@@ -213,13 +226,13 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
             st.n = (int32_t)(a1 - a0);
             st.h = sub * sp.hps + (int32_t)(a0 / T);
             const int32_t rem = (int32_t)(a0 % T);
-            int lo = 0, hi = p.B - 1;          // last b with tile_prefix[b] <= rem
+            int lo = 0, hi = p.B - 1;          // last b with prefix[b] <= rem
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
-                if (p.tile_prefix[mid] <= rem) lo = mid; else hi = mid - 1;
+                if (prefix(mid) <= rem) lo = mid; else hi = mid - 1;
             }
             st.b = lo;
-            st.t = rem - p.tile_prefix[lo];
+            st.t = rem - prefix(lo);
             const SeqInfo si = seq_info(p, lo);
             st.q0 = si.q0;
             st.R = si.R;
@@ -229,6 +242,19 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
         }
         p.wave_start[w] = st;
     }
+    for (int idx = tid; idx < p.B * p.Hkv; idx += 1024) {
+        const int b = idx / p.Hkv, kvh = idx % p.Hkv;
+        const int tiles = prefix(b + 1) - prefix(b);
+        int r_first = 0, r_last = 0;
+        if (tiles > 0) {
+            const int64_t first_tile = (int64_t)(kvh % sp.hps) * T + prefix(b);
+            r_first = part_of_tile(sp, first_tile);
+            r_last = part_of_tile(sp, first_tile + tiles - 1);
+        }
+        const SeqInfo si = seq_info(p, b);
+        *reinterpret_cast<int4 *>(p.cuts + 4 * (int64_t)idx) = int4{r_first, r_last, si.q0, si.R};
+    }
+    if (tid == 0) p.error_flag[1] = sp.sub_total >= sp.parts ? 1 : 0;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -838,21 +864,23 @@ template <int D, typename OutT>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     constexpr int kTpc = D / 4;             // threads per column (float4 each)
     constexpr int kCols = 256 / kTpc;       // columns per block
-    const int b = blockIdx.x / p.Hkv, kvh = blockIdx.x % p.Hkv;
+    const int kvh = blockIdx.x % p.Hkv;  // blockIdx.x = sequence * Hkv + KV head
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && *p.error_flag != 0) {
         // a wave of the main kernel gave up waiting for its partner: the results cannot be
         // trusted, so make that impossible to miss
         static_cast<OutT *>(p.out)[0] = sizeof(OutT) == 2 ? (OutT)0x7fc0 : (OutT)0;
         if (p.lse) p.lse[0] = NAN;
     }
-    const SeqInfo si = seq_info(p, b);
-    if (si.tiles <= 0) return;
-    const Split sp = make_split(p, p.tile_prefix[p.B]);
-    const int sub = kvh / sp.hps;
-    const int64_t first_tile = (int64_t)(kvh % sp.hps) * sp.T + p.tile_prefix[b];
-    const int r_first = part_of_tile(sp, first_tile);
-    const int r_last = part_of_tile(sp, first_tile + si.tiles - 1);
-    if (r_first == r_last) return;          // one wave saw the whole sequence and wrote it
+    const int4 cut = *reinterpret_cast<const int4 *>(p.cuts + 4 * (int64_t)blockIdx.x);
+    const bool dense = p.error_flag[1] != 0;  // every part owns tiles
+    const int r_first = cut.x, r_last = cut.y;
+    if (r_first == r_last) return;          // one wave saw the whole sequence and wrote it (or no tiles)
+    SeqInfo si{};
+    si.q0 = cut.z;
+    si.R = cut.w;
+    Split sp{};
+    if (!dense) sp = make_split(p, p.tile_prefix[p.B]);
+    const int sub = kvh / (p.Hkv / p.HI);
     const int n = blockIdx.y * kCols + threadIdx.x / kTpc;
     const int d4 = (threadIdx.x % kTpc) * 4;
     const int M = p.G * si.R;
@@ -867,7 +895,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
         int64_t prow[4];
         int cnt = 0;
         for (; r <= r_last && cnt < 4; ++r) {
-            if (!part_owns_tiles(sp, r)) continue;
+            if (!dense && !part_owns_tiles(sp, r)) continue;
             const int w = r * p.HI + sub;
             const int64_t row = (int64_t)(r == r_first ? 2 * w + 1 : 2 * w) * p.Mpad + n;
             if (cnt == 0) prow[0] = row;
@@ -923,7 +951,7 @@ thread_local hipEvent_t g_mark_after_main = nullptr;
 
 struct Plan {
     int32_t Mpad;
-    size_t ws_o_bytes, ws_ml_bytes, prefix_bytes, start_bytes, flag_bytes, ws_bytes;
+    size_t ws_o_bytes, ws_ml_bytes, prefix_bytes, start_bytes, flag_bytes, cut_bytes, ws_bytes;
 };
 
 bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, int32_t Hq,
@@ -940,7 +968,8 @@ bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, i
     pl.prefix_bytes = round_up((size_t)(B + 1) * sizeof(int32_t), 256);
     pl.start_bytes = round_up((size_t)kMaxWaves * sizeof(WaveStart), 256);
     pl.flag_bytes = 256;
-    pl.ws_bytes = pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes + pl.start_bytes + pl.flag_bytes;
+    pl.cut_bytes = round_up((size_t)B * Hkv * 4 * sizeof(int32_t), 256);
+    pl.ws_bytes = pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes + pl.start_bytes + pl.flag_bytes + pl.cut_bytes;
     return true;
 }
 
@@ -1038,6 +1067,8 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     if (!workspace || workspace_bytes < pl.ws_bytes || !aligned_to(workspace, 256))
         return fail(RESPEC_ERR_WORKSPACE, "verify_attention: workspace of %zu bytes (256-byte aligned) needed, got %zu",
                     pl.ws_bytes, workspace ? workspace_bytes : (size_t)0);
+    if ((int64_t)B * Hkv > 0x0fffffffLL)
+        return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: B*Hkv exceeds 2^28-1");
     if ((int64_t)total_q * Hq > 0x7fffffffLL)
         return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention: total_q*Hq exceeds 2^31-1");
     if (dt == RESPEC_F32 && (int64_t)B * Hq > 0x7fffffffLL)
@@ -1057,6 +1088,7 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     p.tile_prefix = reinterpret_cast<int32_t *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes);
     p.wave_start = reinterpret_cast<WaveStart *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes);
     p.error_flag = reinterpret_cast<int32_t *>(ws + pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes + pl.start_bytes);
+    p.cuts = p.error_flag + pl.flag_bytes / sizeof(int32_t);
     p.B = B;
     p.total_q = total_q;
     p.total_kv = total_kv;
