@@ -687,6 +687,13 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
             }
         }
     };
+    // the totals of the slots of the first chunk are kept for the walk, and (when the registers
+    // allow: one work-group per sequence) so are the slots themselves
+    constexpr bool kKeepSlots = !SHARED;
+    double slot_total[kChunk];
+    u32x4 keep_p[kKeepSlots ? kChunk : 1], keep_q[kKeepSlots ? kChunk : 1];
+#pragma unroll
+    for (int j = 0; j < kChunk; ++j) slot_total[j] = 0.0;
     for (int c0 = my0; c0 < my1; c0 += kChunk) {
         u32x4 vp[kChunk], vq[kChunk];
         load_chunk(c0, vp, vq);
@@ -694,10 +701,19 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         for (int j = 0; j < kChunk; ++j) {
             double w[EPV];
             slot_weights<BF16, RESID>(vp[j], vq[j], Mp, Cp, Mq, Cq, p, w);
+            double st = 0.0;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
-                my_total += w[e];
+                st += w[e];
                 if (w[e] > 0.0) my_last = tok_off + (c0 + j) * EPV + e;
+            }
+            my_total += st;
+            if (c0 == my0) {
+                slot_total[j] = st;
+                if constexpr (kKeepSlots) {
+                    keep_p[j] = vp[j];
+                    keep_q[j] = vq[j];
+                }
             }
         }
     }
@@ -717,26 +733,47 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         double c = run_excl;
         int tok = -1, edge = 0;
         double before = c, after = c;
-        for (int c0 = my0; c0 < my1 && tok < 0; c0 += kChunk) {
+        auto walk_slot = [&](int slot, const u32x4 &vp, const u32x4 &vq) {
+            double w[EPV];
+            slot_weights<BF16, RESID>(vp, vq, Mp, Cp, Mq, Cq, p, w);
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) {
+                if (tok < 0) {
+                    const double cn = c + w[e];
+                    if (cn > t) {
+                        tok = tok_off + slot * EPV + e;
+                        before = c;
+                        after = cn;
+                    }
+                    c = cn;
+                }
+            }
+        };
+        // first chunk: skip whole slots by their totals, walk only the slot of the crossing
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+            if (tok < 0 && my0 + j < my1) {
+                const double cn = c + slot_total[j];
+                if (cn > t) {
+                    if constexpr (kKeepSlots) {
+                        walk_slot(my0 + j, keep_p[j], keep_q[j]);
+                    } else {
+                        const u32x4 vp = load_slot<BF16, FULL>(rowp, my0 + j, Vrow, aligned);
+                        u32x4 vq = vp;
+                        if constexpr (RESID) vq = load_slot<BF16, FULL>(rowq, my0 + j, Vrow, aligned);
+                        walk_slot(my0 + j, vp, vq);
+                    }
+                    // (a crossing lost to rounding inside the slot carries on with the next one)
+                } else {
+                    c = cn;
+                }
+            }
+        }
+        for (int c0 = my0 + kChunk; c0 < my1 && tok < 0; c0 += kChunk) {
             u32x4 vp[kChunk], vq[kChunk];
             load_chunk(c0, vp, vq);
 #pragma unroll
-            for (int j = 0; j < kChunk; ++j) {
-                double w[EPV];
-                slot_weights<BF16, RESID>(vp[j], vq[j], Mp, Cp, Mq, Cq, p, w);
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) {
-                    if (tok < 0) {
-                        const double cn = c + w[e];
-                        if (cn > t) {
-                            tok = tok_off + (c0 + j) * EPV + e;
-                            before = c;
-                            after = cn;
-                        }
-                        c = cn;
-                    }
-                }
-            }
+            for (int j = 0; j < kChunk; ++j) walk_slot(c0 + j, vp[j], vq[j]);
         }
         if (tok < 0) {  // the thread's own walk rounds differently from the block scan
             tok = my_last;
