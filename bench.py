@@ -78,7 +78,24 @@ def run_cpu_baseline(batch: synth.VerifyBatch, n_seqs: int):
         host["ua"] if n_draft else None, host["uf"], sb.max_k, wl.temperature, dt, n_threads=0)
     t2 = time.perf_counter()
     emitted = int((n + 1).sum())
+    # one thread, on the first sequences only (it is about `threads` times slower)
+    n1 = max(1, min(n_seqs, n_seqs // max(1, threads)))
+    s1 = synth.sub_batch(batch, list(range(n1)))
+    h1 = dict(q=synth.to_host_array(s1.q), k=synth.to_host_array(s1.k_cache), v=synth.to_host_array(s1.v_cache),
+              qi=s1.q_indptr.cpu().numpy(), ki=s1.kv_indptr.cpu().numpy(), t=synth.to_host_array(s1.target_logits),
+              d=synth.to_host_array(s1.draft_logits), tok=s1.draft_tokens.cpu().numpy(),
+              ua=s1.u_accept.cpu().numpy(), uf=s1.u_final.cpu().numpy())
+    t3 = time.perf_counter()
+    oracle.verify_attention(h1["q"], h1["k"], h1["v"], h1["qi"], h1["ki"], wl.Hq, wl.Hkv, wl.D,
+                            float(np.float32(1.0 / math.sqrt(wl.D))), dt, n_threads=1)
+    nd1 = s1.total_q - n1
+    _, n_1, _ = oracle.rejection_sample(
+        h1["t"], h1["d"] if nd1 else None, h1["tok"] if nd1 else None, h1["qi"],
+        h1["ua"] if nd1 else None, h1["uf"], s1.max_k, wl.temperature, dt, n_threads=1)
+    t4 = time.perf_counter()
     return {
+        "one_thread": {"value": int((n_1 + 1).sum()) / (t4 - t3), "unit": "tokens/s",
+                       "sample": f"first {n1} sequences"},
         "value": emitted / (t2 - t0), "unit": "tokens/s", "cores": threads, "kind": "oracle",
         "sample": f"first {n_seqs} of {len(batch.k_per_seq)} sequences of the same workload, "
                   f"one attention layer + sampler, OpenMP over sequences",
@@ -97,6 +114,8 @@ def main():
     ap.add_argument("--k", type=int, default=None, help="override k (sweeps)")
     ap.add_argument("--probe-every", type=int, default=4,
                     help="in the timed region, bracket the main attention kernel with events on every n-th step")
+    ap.add_argument("--layers", type=int, default=None,
+                    help="attention layers of the modelled full-depth figure (default: the model's public card)")
     ap.add_argument("--cpu-seqs", type=int, default=256,
                     help="sequences the oracle is timed on (cpu_baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -200,6 +219,21 @@ def main():
     ms_comb = sum(e4[1].elapsed_time(e4[2]) for e4 in ev) / n_pass
     ms_samp = sum(e4[2].elapsed_time(e4[3]) for e4 in ev) / n_pass
 
+    # a device copy of 1 GiB, timed live: what this device's memory system gives a trivial kernel
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * src.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+    main_sorted = sorted(a.elapsed_time(b) for a, b in probes)
+    layers = args.layers or {"qwen3b": 36, "qwen7b": 28, "qwen14b": 48}.get(wl.name.split("_")[0], 1)
+
     n_host = n_acc.cpu().tolist()
     accepted = int(sum(n_host))
     emitted = accepted + B
@@ -243,6 +277,13 @@ def main():
                               "sampler_all_rows": samp_all_rows},
         "step_hbm_frac": (attn_bytes + samp_bytes) / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "sampler_gbs": samp_bytes / (ms_samp * 1e-3) / 1e9,
+        "t_attn_us": (ms_prep + ms_main_pass + ms_comb) * 1e3, "t_samp_us": ms_samp * 1e3,
+        "tokens_per_s_kernels": emitted / ((ms_prep + ms_main_pass + ms_comb + ms_samp) * 1e-3),
+        "modelled_full_depth": {"layers": layers, "note": "MODELLED, not measured: emitted / (layers * t_attn + t_samp)",
+                                "tokens_per_s": emitted / ((layers * (ms_prep + ms_main_pass + ms_comb) + ms_samp) * 1e-3)},
+        "attention_main_us_median_min": [main_sorted[len(main_sorted) // 2] * 1e3, main_sorted[0] * 1e3],
+        "measured_copy_gbs": copy_gbs,
+        "attention_frac_of_measured_copy": achieved / copy_gbs,
         "roofline": {
             "kernel": "attn_bf16_kernel" if wl.dtype == "bf16" else "attn_f32_kernel",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
