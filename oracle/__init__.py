@@ -48,6 +48,15 @@ def _load():
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
             c.c_void_p, c.c_void_p, c.c_void_p,
             c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_double, c.c_int, c.c_int]
+        lib.respec_oracle_verify_attention_tree.restype = c.c_int
+        lib.respec_oracle_verify_attention_tree.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_double, c.c_int, c.c_int]
+        lib.respec_oracle_tree_rejection_sample.restype = c.c_int
+        lib.respec_oracle_tree_rejection_sample.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_double, c.c_int, c.c_int]
         lib.respec_oracle_softmax_rows.restype = c.c_int
         lib.respec_oracle_softmax_rows.argtypes = [
             c.c_void_p, c.c_int32, c.c_int32, c.c_int64, c.c_double, c.c_int, c.c_void_p]
@@ -95,6 +104,59 @@ def verify_attention(q, k_cache, v_cache, q_indptr, kv_indptr, Hq, Hkv, D, sm_sc
     if rc != 0:
         raise RuntimeError(f"respec_oracle_verify_attention failed with code {rc}")
     return (out, lse) if want_lse else out
+
+
+def verify_attention_tree(q, k_cache, v_cache, q_indptr, kv_indptr, tree_mask, Hq, Hkv, D, sm_scale,
+                          dtype, want_lse=False, n_threads=1):
+    """As verify_attention, with tree_mask [total_q] uint64: bit j of row i's word says that the
+    sequence's j-th new token is visible to row i (its ancestors and itself)."""
+    q = _check_elems(q, dtype, "q")
+    k_cache = _check_elems(k_cache, dtype, "k_cache")
+    v_cache = _check_elems(v_cache, dtype, "v_cache")
+    q_indptr = np.ascontiguousarray(q_indptr, dtype=np.int32)
+    kv_indptr = np.ascontiguousarray(kv_indptr, dtype=np.int64)
+    tree_mask = np.ascontiguousarray(tree_mask, dtype=np.uint64)
+    B = q_indptr.shape[0] - 1
+    total_q = int(q_indptr[-1])
+    assert tree_mask.shape == (total_q,)
+    out = np.zeros((total_q, Hq, D), dtype=np.float64)
+    lse = np.zeros((total_q, Hq), dtype=np.float64) if want_lse else None
+    rc = _load().respec_oracle_verify_attention_tree(
+        _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(q_indptr), _ptr(kv_indptr), _ptr(tree_mask),
+        _ptr(out), _ptr(lse), B, Hq, Hkv, D, float(sm_scale), dtype, n_threads)
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_verify_attention_tree failed with code {rc}")
+    return (out, lse) if want_lse else out
+
+
+def tree_rejection_sample(target_logits, draft_logits, node_tokens, parent, q_indptr, u_accept,
+                          u_final, max_depth, temperature, dtype, n_threads=1):
+    """target_logits, draft_logits [total_q,V]; node_tokens, parent, u_accept [total_q].
+
+    Returns (out_tokens [B,max_depth+1], out_path [B,max(max_depth,1)], num_accepted [B], flags [B]).
+    """
+    target_logits = _check_elems(target_logits, dtype, "target_logits")
+    draft_logits = _check_elems(draft_logits, dtype, "draft_logits")
+    q_indptr = np.ascontiguousarray(q_indptr, dtype=np.int32)
+    B = q_indptr.shape[0] - 1
+    total_q, V = target_logits.shape
+    assert total_q == int(q_indptr[-1]) and draft_logits.shape == (total_q, V)
+    node_tokens = np.ascontiguousarray(node_tokens, dtype=np.int32)
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    u_accept = np.ascontiguousarray(u_accept, dtype=np.float32)
+    u_final = np.ascontiguousarray(u_final, dtype=np.float32)
+    assert node_tokens.shape == parent.shape == u_accept.shape == (total_q,) and u_final.shape == (B,)
+    out_tokens = np.empty((B, max_depth + 1), dtype=np.int32)
+    out_path = np.empty((B, max(max_depth, 1)), dtype=np.int32)
+    num_accepted = np.empty((B,), dtype=np.int32)
+    flags = np.empty((B,), dtype=np.int32)
+    rc = _load().respec_oracle_tree_rejection_sample(
+        _ptr(target_logits), _ptr(draft_logits), _ptr(node_tokens), _ptr(parent), _ptr(q_indptr),
+        _ptr(u_accept), _ptr(u_final), _ptr(out_tokens), _ptr(out_path), _ptr(num_accepted),
+        _ptr(flags), B, max_depth, V, V, V, float(np.float32(temperature)), dtype, n_threads)
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_tree_rejection_sample failed with code {rc}")
+    return out_tokens, out_path, num_accepted, flags
 
 
 def rejection_sample(target_logits, draft_logits, draft_tokens, q_indptr, u_accept, u_final,

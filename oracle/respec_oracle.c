@@ -18,6 +18,13 @@
  *                 marginal against p over 10^6 draws, acceptance rate against
  *                 1 - TV(p,q), disjoint supports, exact enumeration over a
  *                 stratified uniform grid.
+ *   tree attention -- the chain mask reproduces the chain function bit for bit, dense
+ *                 numpy with an explicit visibility matrix, invariance of a row to
+ *                 nodes off its path.
+ *   tree sampler -- a chain-shaped tree reproduces the chain function exactly, a
+ *                 hand-worked case (tests/golden/tree_hand_case.json), chi-square of
+ *                 the emitted token against p with three sibling candidates, the
+ *                 closed-form probability that every sibling is rejected.
  *
  * Conventions (the paper fixes Eq. 1 and Eq. 2 only; the rest are this build's
  * stated readings):
@@ -90,22 +97,30 @@ int respec_oracle_max_threads(void)
 /* out in fp64; lse [total_q, Hq] fp64 or NULL (natural log of the softmax     */
 /* denominator, in units of the scaled scores).                                */
 /* ------------------------------------------------------------------------- */
+/* With a tree of drafts (tree_mask != NULL) row i sees every key before the new tokens and,    */
+/* among the R_b new tokens, exactly those whose bit is set in tree_mask[q0+i] (its ancestors  */
+/* and itself); the chain is the mask with bits 0..i.                                          */
 static int attention_one_sequence(const void *q, const void *k_cache, const void *v_cache,
                                   int32_t q0, int32_t R, int64_t kv0, int64_t L, double *out,
                                   double *lse, int32_t Hq, int32_t Hkv, int32_t D,
-                                  double sm_scale, int dtype)
+                                  double sm_scale, int dtype, const uint64_t *tree_mask)
 {
     const int32_t G = Hq / Hkv;
     double *score = (double *)malloc((size_t)L * sizeof(double));
     if (!score)
         return ORACLE_ERR_ALLOC;
     for (int32_t i = 0; i < R; ++i) {
-        const int64_t last_key = L - R + i; /* inclusive */
+        const int64_t last_key = tree_mask ? L - 1 : L - R + i; /* inclusive */
+        const int64_t first_new = L - R;
         for (int32_t h = 0; h < Hq; ++h) {
             const int32_t hk = h / G;
             const int64_t qoff = ((int64_t)(q0 + i) * Hq + h) * D;
             double m = -INFINITY;
             for (int64_t j = 0; j <= last_key; ++j) {
+                if (tree_mask && j >= first_new && !((tree_mask[q0 + i] >> (j - first_new)) & 1u)) {
+                    score[j] = -INFINITY; /* hidden from this row */
+                    continue;
+                }
                 const int64_t koff = ((kv0 + j) * Hkv + hk) * D;
                 double dot = 0.0;
                 for (int32_t d = 0; d < D; ++d)
@@ -116,13 +131,15 @@ static int attention_one_sequence(const void *q, const void *k_cache, const void
             }
             double denom = 0.0;
             for (int64_t j = 0; j <= last_key; ++j) {
-                score[j] = exp(score[j] - m);
+                score[j] = score[j] == -INFINITY ? 0.0 : exp(score[j] - m);
                 denom += score[j];
             }
             double *o = out + qoff;
             for (int32_t d = 0; d < D; ++d)
                 o[d] = 0.0;
             for (int64_t j = 0; j <= last_key; ++j) {
+                if (score[j] == 0.0)
+                    continue;
                 const int64_t voff = ((kv0 + j) * Hkv + hk) * D;
                 const double a = score[j] / denom;
                 for (int32_t d = 0; d < D; ++d)
@@ -136,10 +153,10 @@ static int attention_one_sequence(const void *q, const void *k_cache, const void
     return ORACLE_OK;
 }
 
-int respec_oracle_verify_attention(const void *q, const void *k_cache, const void *v_cache,
-                                   const int32_t *q_indptr, const int64_t *kv_indptr, double *out,
-                                   double *lse, int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
-                                   double sm_scale, int dtype, int n_threads)
+static int verify_attention_any(const void *q, const void *k_cache, const void *v_cache,
+                                const int32_t *q_indptr, const int64_t *kv_indptr, double *out,
+                                double *lse, int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
+                                double sm_scale, int dtype, int n_threads, const uint64_t *tree_mask)
 {
     if (!q || !k_cache || !v_cache || !q_indptr || !kv_indptr || !out)
         return ORACLE_ERR_ARG;
@@ -150,7 +167,7 @@ int respec_oracle_verify_attention(const void *q, const void *k_cache, const voi
     for (int32_t b = 0; b < B; ++b) {
         const int32_t R = q_indptr[b + 1] - q_indptr[b];
         const int64_t L = kv_indptr[b + 1] - kv_indptr[b];
-        if (R < 1 || L < R)
+        if (R < 1 || L < R || (tree_mask && R > 64))
             return ORACLE_ERR_DATA;
     }
     int status = ORACLE_OK;
@@ -161,13 +178,36 @@ int respec_oracle_verify_attention(const void *q, const void *k_cache, const voi
         const int rc = attention_one_sequence(q, k_cache, v_cache, q_indptr[b],
                                               q_indptr[b + 1] - q_indptr[b], kv_indptr[b],
                                               kv_indptr[b + 1] - kv_indptr[b], out, lse, Hq, Hkv,
-                                              D, sm_scale, dtype);
+                                              D, sm_scale, dtype, tree_mask);
         if (rc != ORACLE_OK) {
 #pragma omp critical
             status = rc;
         }
     }
     return status;
+}
+
+int respec_oracle_verify_attention(const void *q, const void *k_cache, const void *v_cache,
+                                   const int32_t *q_indptr, const int64_t *kv_indptr, double *out,
+                                   double *lse, int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
+                                   double sm_scale, int dtype, int n_threads)
+{
+    return verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, B, Hq, Hkv, D,
+                                sm_scale, dtype, n_threads, NULL);
+}
+
+/* Verify attention over a tree of drafts (Section 3.1: candidate branches validated in
+ * parallel); tree_mask [total_q] as described above, at most 64 rows per sequence. */
+int respec_oracle_verify_attention_tree(const void *q, const void *k_cache, const void *v_cache,
+                                        const int32_t *q_indptr, const int64_t *kv_indptr,
+                                        const uint64_t *tree_mask, double *out, double *lse,
+                                        int32_t B, int32_t Hq, int32_t Hkv, int32_t D,
+                                        double sm_scale, int dtype, int n_threads)
+{
+    if (!tree_mask)
+        return ORACLE_ERR_ARG;
+    return verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, B, Hq, Hkv, D,
+                                sm_scale, dtype, n_threads, tree_mask);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -323,6 +363,157 @@ int respec_oracle_rejection_sample(const void *target_logits, const void *draft_
             target_logits, draft_logits, draft_tokens, row0, row0 - b, k, u_accept, u_final[b],
             out_tokens + (int64_t)b * (max_k + 1), out_num_accepted + b,
             out_flags ? out_flags + b : NULL, max_k, V, ld_t, ld_d, temperature, dtype);
+        if (rc != ORACLE_OK) {
+#pragma omp critical
+            status = rc;
+        }
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Rejection sampling over a tree of drafts.                                   */
+/* The paper names the tree (branching factor t, Section 3.1) and refers to    */
+/* its drafting method for the rest; this build's reading is the multi-round   */
+/* form of Eq. 1 / Eq. 2 for sibling candidates drawn independently from the   */
+/* same drafter distribution q:                                                */
+/*   at a node, p_0 = p (target row of the node); its children are tried in    */
+/*   ascending row order; child c with token x is accepted iff                 */
+/*   u_c < min(1, p_r(x)/q(x)); a rejection replaces p_r by                    */
+/*   p_{r+1} = max(0, p_r - q) / Z_{r+1}  (Eq. 2 applied again);               */
+/*   an accepted child becomes the node (r back to 0); when no child is left   */
+/*   one token is drawn from the current p_r and validation stops.             */
+/* A chain (every node one child) is exactly the procedure above.              */
+/* Rows of sequence b: q_indptr[b] .. , row 0 the root (last committed token), */
+/* parent[row] the local index of the parent row (-1 for the root, < the row's */
+/* own index otherwise).  target_logits, draft_logits [total_q, V]: row i is   */
+/* the target / drafter distribution of the token that follows row i (drafter  */
+/* rows of leaves are not read).  u_accept [total_q] (entry of the root        */
+/* unused), u_final [B].  out_tokens [B, max_depth+1]; out_path [B, max_depth]  */
+/* the local rows of the accepted nodes (-1 beyond).                           */
+/* ------------------------------------------------------------------------- */
+static int sample_one_tree(const void *target_logits, const void *draft_logits,
+                           const int32_t *node_tokens, const int32_t *parent, int32_t row0,
+                           int32_t R, const float *u_accept, float u_final, int32_t *out_tokens,
+                           int32_t *out_path, int32_t *out_num_accepted, int32_t *out_flags,
+                           int32_t max_depth, int32_t V, int64_t ld_t, int64_t ld_d, double T,
+                           int dtype)
+{
+    double *p = (double *)malloc((size_t)V * sizeof(double));
+    double *q = (double *)malloc((size_t)V * sizeof(double));
+    if (!p || !q) {
+        free(p);
+        free(q);
+        return ORACLE_ERR_ALLOC;
+    }
+    int flag_accept = 0, flag_cdf = 0;
+    int32_t n = 0, cur = 0;
+    for (int32_t j = 0; j <= max_depth; ++j)
+        out_tokens[j] = -1;
+    for (int32_t j = 0; j < max_depth; ++j)
+        out_path[j] = -1;
+    for (;;) {
+        softmax_row(target_logits, row0 + cur, ld_t, V, T, dtype, p);
+        int have_q = 0;
+        int32_t next = -1;
+        for (int32_t c = cur + 1; c < R && next < 0; ++c) {
+            if (parent[row0 + c] != cur)
+                continue;
+            if (!have_q) {
+                softmax_row(draft_logits, row0 + cur, ld_d, V, T, dtype, q);
+                have_q = 1;
+            }
+            const int32_t x = node_tokens[row0 + c];
+            if (x < 0 || x >= V || n >= max_depth) {
+                free(p);
+                free(q);
+                return ORACLE_ERR_DATA;
+            }
+            double rho;
+            if (q[x] == 0.0)
+                rho = p[x] > 0.0 ? INFINITY : 0.0;
+            else
+                rho = p[x] / q[x];
+            const double thr = rho < 1.0 ? rho : 1.0;
+            const double u = (double)u_accept[row0 + c];
+            if (fabs(u - thr) <= BOUNDARY_EPS)
+                flag_accept = 1;
+            if (u < thr) { /* accepted: the child becomes the node */
+                out_tokens[n] = x;
+                out_path[n] = c;
+                n += 1;
+                next = c;
+                break;
+            }
+            /* rejected: p <- max(0, p - q) / Z  (Eq. 2 applied to the current p) */
+            double Z = 0.0;
+            for (int32_t y = 0; y < V; ++y) {
+                const double w = p[y] - q[y];
+                p[y] = w > 0.0 ? w : 0.0;
+                Z += p[y];
+            }
+            if (!(Z > 0.0)) { /* cannot happen in exact arithmetic; keep the target itself */
+                softmax_row(target_logits, row0 + cur, ld_t, V, T, dtype, p);
+                flag_cdf = 1;
+            } else {
+                for (int32_t y = 0; y < V; ++y)
+                    p[y] /= Z;
+            }
+        }
+        if (next >= 0) {
+            cur = next;
+            continue;
+        }
+        /* no child left (or none offered): one draw from the current p */
+        double Zp = 0.0;
+        for (int32_t y = 0; y < V; ++y)
+            Zp += p[y];
+        out_tokens[n] = inverse_cdf(p, V, Zp, (double)u_final, &flag_cdf);
+        break;
+    }
+    *out_num_accepted = n;
+    if (out_flags)
+        *out_flags = (flag_accept ? 1 : 0) | (flag_cdf ? 2 : 0);
+    free(p);
+    free(q);
+    return ORACLE_OK;
+}
+
+int respec_oracle_tree_rejection_sample(const void *target_logits, const void *draft_logits,
+                                        const int32_t *node_tokens, const int32_t *parent,
+                                        const int32_t *q_indptr, const float *u_accept,
+                                        const float *u_final, int32_t *out_tokens,
+                                        int32_t *out_path, int32_t *out_num_accepted,
+                                        int32_t *out_flags, int32_t B, int32_t max_depth,
+                                        int32_t V, int64_t ld_t, int64_t ld_d,
+                                        double temperature, int dtype, int n_threads)
+{
+    if (!target_logits || !draft_logits || !node_tokens || !parent || !q_indptr || !u_accept ||
+        !u_final || !out_tokens || !out_path || !out_num_accepted)
+        return ORACLE_ERR_ARG;
+    if (B <= 0 || V <= 0 || max_depth < 0 || ld_t < V || ld_d < V || !(temperature > 0.0))
+        return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16)
+        return ORACLE_ERR_ARG;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t row0 = q_indptr[b], R = q_indptr[b + 1] - row0;
+        if (R < 1 || parent[row0] != -1)
+            return ORACLE_ERR_DATA;
+        for (int32_t i = 1; i < R; ++i)
+            if (parent[row0 + i] < 0 || parent[row0 + i] >= i)
+                return ORACLE_ERR_DATA;
+    }
+    int status = ORACLE_OK;
+    const int nt = pick_threads(n_threads);
+    (void)nt;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nt)
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t row0 = q_indptr[b];
+        const int rc = sample_one_tree(
+            target_logits, draft_logits, node_tokens, parent, row0, q_indptr[b + 1] - row0,
+            u_accept, u_final[b], out_tokens + (int64_t)b * (max_depth + 1),
+            out_path + (int64_t)b * (max_depth > 0 ? max_depth : 1), out_num_accepted + b,
+            out_flags ? out_flags + b : NULL, max_depth, V, ld_t, ld_d, temperature, dtype);
         if (rc != ORACLE_OK) {
 #pragma omp critical
             status = rc;

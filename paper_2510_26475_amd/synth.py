@@ -242,6 +242,140 @@ def make_batch(wl: Workload, device="cpu", kv_lens: Optional[Sequence[int]] = No
         u_accept=u_accept, u_final=u_final, k_per_seq=k_per_seq, kv_lens=kv_lens)
 
 
+@dataclass
+class TreeBatch:
+    """One verify step over trees of drafts.  Row 0 of a sequence is the root (the last committed
+    token), the other rows are draft nodes in an order in which parents come first."""
+    wl: Workload
+    q: torch.Tensor               # [total_q, Hq, D]
+    k_cache: torch.Tensor         # [total_kv, Hkv, D]
+    v_cache: torch.Tensor         # [total_kv, Hkv, D]
+    q_indptr: torch.Tensor        # [B+1] int32
+    kv_indptr: torch.Tensor       # [B+1] int64
+    parent: torch.Tensor          # [total_q] int32, local row of the parent (-1 for the root)
+    tree_mask: torch.Tensor       # [total_q] int64 holding 64 mask bits: bit j = new token j visible
+    target_logits: torch.Tensor   # [total_q, V]
+    draft_logits: torch.Tensor    # [total_q, V]  row i: what row i's children were drawn from
+    node_tokens: torch.Tensor     # [total_q] int32 (-1 for the root)
+    u_accept: torch.Tensor        # [total_q] f32 (the root's entry is unused)
+    u_final: torch.Tensor         # [B] f32
+    parents_per_seq: list = field(default_factory=list)
+    kv_lens: list = field(default_factory=list)
+
+    @property
+    def total_q(self) -> int:
+        return int(self.q.shape[0])
+
+    @property
+    def total_kv(self) -> int:
+        return int(self.k_cache.shape[0])
+
+    @property
+    def max_rows(self) -> int:
+        return max(len(p) for p in self.parents_per_seq)
+
+    @property
+    def max_kv_len(self) -> int:
+        return max(self.kv_lens)
+
+    @property
+    def max_depth(self) -> int:
+        best = 0
+        for par in self.parents_per_seq:
+            depth = [0] * len(par)
+            for i in range(1, len(par)):
+                depth[i] = depth[par[i]] + 1
+            best = max(best, max(depth))
+        return best
+
+
+def caterpillar_parents(depth: int, branch: int) -> list:
+    """A main chain of `depth` draft nodes in which every node of the chain (and the root) has
+    `branch` children: the first continues the chain, the others are leaves.  1 + depth*branch rows."""
+    par = [-1]
+    spine = 0
+    for _ in range(depth):
+        first = len(par)
+        for _ in range(branch):
+            par.append(spine)
+        spine = first
+    return par
+
+
+def random_parents(n_nodes: int, gen: torch.Generator, max_children: int = 3) -> list:
+    """A random tree: every node picks a parent among the earlier rows that still has room."""
+    par = [-1]
+    kids = [0]
+    for i in range(1, n_nodes + 1):
+        room = [j for j in range(i) if kids[j] < max_children]
+        j = room[int(torch.randint(0, len(room), (1,), generator=gen))]
+        par.append(j)
+        kids[j] += 1
+        kids.append(0)
+    return par
+
+
+def make_tree_batch(wl: Workload, parents_per_seq: Sequence[Sequence[int]], device="cpu",
+                    kv_lens: Optional[Sequence[int]] = None, seed: Optional[int] = None,
+                    with_attention: bool = True, with_logits: bool = True) -> TreeBatch:
+    """Inputs of one tree verify step.  The children of a row are drawn independently from the
+    softmax of that row's drafter logits (Gumbel-max, no softmax evaluated)."""
+    seed = wl.seed if seed is None else seed
+    cgen = torch.Generator(device="cpu").manual_seed(seed)
+    B = len(parents_per_seq)
+    if kv_lens is None:
+        wl_b = Workload(**{**wl.__dict__, "B": B})
+        kv_lens = draw_lengths(wl_b, cgen)
+    kv_lens = [max(int(L), len(par)) for L, par in zip(kv_lens, parents_per_seq)]
+    dgen = torch.Generator(device=device).manual_seed(seed + 1000003)
+    dt = torch_dtype(wl.dtype)
+    q_indptr, kv_indptr, parent, mask = [0], [0], [], []
+    for L, par in zip(kv_lens, parents_per_seq):
+        assert par[0] == -1 and len(par) <= 64
+        q_indptr.append(q_indptr[-1] + len(par))
+        kv_indptr.append(kv_indptr[-1] + L)
+        bits = []
+        for i, pi in enumerate(par):
+            assert i == 0 or 0 <= pi < i
+            bits.append((1 << i) | (bits[pi] if pi >= 0 else 0))
+        parent.extend(par)
+        mask.extend(b - (1 << 64) if b >= (1 << 63) else b for b in bits)
+    total_q, total_kv = q_indptr[-1], kv_indptr[-1]
+    if with_attention:
+        q = _randn((total_q, wl.Hq, wl.D), dgen, device, dt)
+        k_cache = _randn((total_kv, wl.Hkv, wl.D), dgen, device, dt)
+        v_cache = _randn((total_kv, wl.Hkv, wl.D), dgen, device, dt)
+    else:
+        q = torch.empty((total_q, wl.Hq, wl.D), device=device, dtype=dt)
+        k_cache = torch.empty((0, wl.Hkv, wl.D), device=device, dtype=dt)
+        v_cache = torch.empty((0, wl.Hkv, wl.D), device=device, dtype=dt)
+    parent_t = torch.tensor(parent, dtype=torch.int32, device=device)
+    if with_logits:
+        rows = torch.arange(total_q, dtype=torch.int64)
+        sig = torch.full((total_q,), float(wl.sigma), dtype=torch.float32)
+        target, draft = make_logits(total_q, sig, rows, wl.V, dt, dgen, device)
+        # the token of row i comes from the drafter row of its parent
+        base = torch.repeat_interleave(torch.tensor(q_indptr[:-1], dtype=torch.int64),
+                                       torch.tensor([len(p) for p in parents_per_seq]))
+        src = (base + torch.tensor(parent, dtype=torch.int64).clamp_min(0)).to(device)
+        node_tokens = sample_draft_tokens(draft[src], wl.temperature, dgen)
+        node_tokens[parent_t < 0] = -1
+    else:
+        target = torch.empty((total_q, 0), device=device, dtype=dt)
+        draft = torch.empty((total_q, 0), device=device, dtype=dt)
+        node_tokens = torch.zeros((total_q,), device=device, dtype=torch.int32)
+    u_accept = torch.rand((total_q,), generator=dgen, device=device, dtype=torch.float32)
+    u_final = torch.rand((B,), generator=dgen, device=device, dtype=torch.float32)
+    return TreeBatch(
+        wl=wl, q=q, k_cache=k_cache, v_cache=v_cache,
+        q_indptr=torch.tensor(q_indptr, dtype=torch.int32, device=device),
+        kv_indptr=torch.tensor(kv_indptr, dtype=torch.int64, device=device),
+        parent=parent_t, tree_mask=torch.tensor(mask, dtype=torch.int64, device=device),
+        target_logits=target, draft_logits=draft, node_tokens=node_tokens,
+        u_accept=u_accept, u_final=u_final, parents_per_seq=[list(p) for p in parents_per_seq],
+        kv_lens=list(kv_lens))
+
+
 import numpy as _np  # noqa: E402  (index bookkeeping only)
 
 
