@@ -103,6 +103,27 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
                                         size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Verify attention over a tree of drafts (Section 3.1: candidate branches, branching factor
+ * t, validated in parallel).  As respec_verify_attention, except for which of a sequence's
+ * own new tokens a row sees: row i of sequence b (rows in an order in which parents come
+ * first, row 0 the root = the last committed token; the R_b new tokens are the last R_b
+ * entries of the sequence's KV range, in row order) sees every key before the new tokens
+ * and the new token j iff bit j of tree_mask[q_indptr[b]+i] is set (its ancestors and
+ * itself; the chain is the mask with bits 0..i).
+ *   tree_mask   [total_q] uint64, device memory
+ *   max_q_per_seq <= 64 (RESPEC_ERR_UNSUPPORTED otherwise); everything else as above,
+ *   the same workspace size.
+ */
+respec_status_t respec_verify_attention_tree(const void *q, const void *k_cache, const void *v_cache,
+                                             const int32_t *q_indptr, const int64_t *kv_indptr,
+                                             const uint64_t *tree_mask, void *out, float *lse,
+                                             int32_t B, int32_t total_q, int64_t total_kv,
+                                             int32_t max_q_per_seq, int32_t max_kv_len, int32_t Hq,
+                                             int32_t Hkv, int32_t D, float sm_scale,
+                                             respec_dtype_t dt, void *workspace,
+                                             size_t workspace_bytes, void *hip_stream);
+
+/*
  * Profiling hook (benchmarks only).  The calling thread's next respec_verify_attention
  * records `before_main` (if non-NULL) on the call's stream right before its main kernel
  * (after the small set-up kernel) and `after_main` (if non-NULL) right after it, before

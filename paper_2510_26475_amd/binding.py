@@ -58,6 +58,11 @@ def load():
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
         c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_verify_attention_tree.restype = c.c_int
+    lib.respec_verify_attention_tree.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_int32, c.c_int32, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
+        c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.respec_profile_mark_main.restype = None
     lib.respec_profile_mark_main.argtypes = [c.c_void_p, c.c_void_p]
     lib.respec_rejection_sample_workspace_bytes.restype = c.c_size_t
@@ -74,7 +79,7 @@ def load():
 
 EXPORTED_SYMBOLS = [
     "respec_status_string", "respec_last_error", "respec_version",
-    "respec_verify_attention_workspace_bytes", "respec_verify_attention",
+    "respec_verify_attention_workspace_bytes", "respec_verify_attention", "respec_verify_attention_tree",
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample",
     "respec_profile_mark_main",
 ]
@@ -140,6 +145,30 @@ def respec_verify_attention(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, 
         _dev_ptr(q_indptr, "q_indptr"), _dev_ptr(kv_indptr, "kv_indptr"), _dev_ptr(out, "out"),
         _dev_ptr(lse, "lse"), B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D,
         float(sm_scale), _dtype_code(q), ws_ptr, ws_bytes, _stream_ptr(stream)))
+
+
+def respec_verify_attention_tree(q, k_cache, v_cache, q_indptr, kv_indptr, tree_mask, out, lse,
+                                 max_q_per_seq, max_kv_len, sm_scale, workspace, stream=None):
+    """As respec_verify_attention; tree_mask [total_q] int64 (or uint64) holding the 64 mask bits."""
+    lib = load()
+    total_q, Hq, D = q.shape
+    total_kv, Hkv, _ = k_cache.shape
+    B = q_indptr.numel() - 1
+    if q_indptr.dtype != torch.int32 or kv_indptr.dtype != torch.int64:
+        raise TypeError("q_indptr must be int32 and kv_indptr int64")
+    if tree_mask.element_size() != 8 or tree_mask.numel() != total_q:
+        raise TypeError("tree_mask must hold one 64-bit word per query row")
+    if lse is not None and lse.dtype != torch.float32:
+        raise TypeError("lse must be float32")
+    if out.dtype != q.dtype or k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise TypeError("q, k_cache, v_cache and out must share one dtype")
+    ws_ptr = _dev_ptr(workspace, "workspace") if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.respec_verify_attention_tree(
+        _dev_ptr(q, "q"), _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
+        _dev_ptr(q_indptr, "q_indptr"), _dev_ptr(kv_indptr, "kv_indptr"), _dev_ptr(tree_mask, "tree_mask"),
+        _dev_ptr(out, "out"), _dev_ptr(lse, "lse"), B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq,
+        Hkv, D, float(sm_scale), _dtype_code(q), ws_ptr, ws_bytes, _stream_ptr(stream)))
 
 
 def respec_profile_mark_main(before: Optional[torch.cuda.Event], after: Optional[torch.cuda.Event]):

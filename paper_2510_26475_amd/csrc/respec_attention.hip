@@ -61,6 +61,8 @@ struct AttnParams {
     const void *v;
     const int32_t *q_indptr;
     const int64_t *kv_indptr;
+    const uint64_t *tree_mask;  // [total_q] or NULL (chain): bit j = the sequence's j-th new token is
+                                // visible to the row (its ancestors in the draft tree and itself)
     void *out;
     float *lse;
     int16_t *ws_o;         // [2*W, Mpad, D]   unnormalised partial outputs, 16-bit fixed point
@@ -517,6 +519,8 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     int seg_t_first = 0;
     int first_masked_key = 0;  // keys from here on are hidden from some query row
     int col_limit[NT];         // last visible key of the column's query row (-1: no row)
+    uint64_t col_mask[NT];     // draft tree: which of the sequence's new tokens the row sees
+    const bool tree = p.tree_mask != nullptr;
     float m_run[NT], l_run[NT];
     floatx4 acc_o[NT][C::kDTiles];
 
@@ -530,7 +534,8 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             first_masked_key = cp.si.L - cp.si.R + 1;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                col_limit[nt] = col_i[nt] < cp.si.R ? cp.si.L - cp.si.R + col_i[nt] : -1;
+                col_limit[nt] = col_i[nt] < cp.si.R ? (tree ? cp.si.L - 1 : cp.si.L - cp.si.R + col_i[nt]) : -1;
+                col_mask[nt] = tree && col_i[nt] < cp.si.R ? p.tree_mask[cp.si.q0 + col_i[nt]] : 0;
                 m_run[nt] = -INFINITY;
                 l_run[nt] = 0.f;
 #pragma unroll
@@ -585,7 +590,12 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                     float x = s_acc[nt][js][i] * p.scale2;
                     if (tail) {
                         const int key = key0 + js * 16 + g4 * 4 + i;
-                        x = key <= col_limit[nt] ? x : -INFINITY;
+                        bool seen = key <= col_limit[nt];
+                        if (tree) {
+                            const int j = key - (first_masked_key - 1);  // index among the new tokens
+                            seen = seen && (j < 0 || ((col_mask[nt] >> (j & 63)) & 1u));
+                        }
+                        x = seen ? x : -INFINITY;
                     }
                     sv[js * 4 + i] = x;
                 }
@@ -802,7 +812,10 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
     const SeqInfo si = seq_info(p, b);
     if (i >= si.R || si.L <= 0) return;
     const int kvh = h / p.G;
-    const int k_end = min(si.L, si.L - si.R + i + 1);  // one past the last visible key
+    const bool tree = p.tree_mask != nullptr;
+    const uint64_t row_mask = tree ? p.tree_mask[si.q0 + i] : 0;
+    const int first_new = si.L - si.R;
+    const int k_end = tree ? si.L : min(si.L, si.L - si.R + i + 1);  // one past the last visible key
     const int64_t qrow = (int64_t)(si.q0 + i) * p.Hq + h;
     const float *q = static_cast<const float *>(p.q) + qrow * D;
     const float *kb = static_cast<const float *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
@@ -816,7 +829,8 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
     for (int t0 = 0; t0 < k_end; t0 += kF32Threads) {
         const int key = t0 + threadIdx.x;
         float s = -INFINITY;
-        if (key < k_end) {
+        const bool seen = key < k_end && (!tree || key < first_new || ((row_mask >> (key - first_new)) & 1u));
+        if (seen) {
             const float4 *kr = reinterpret_cast<const float4 *>(kb + key * rstride);
             float dot = 0.f;
 #pragma unroll 8
@@ -831,7 +845,7 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
         }
         const float m_tile = block_reduce_max(s, sh_red);
         const float m_new = fmaxf(m_run, m_tile);  // finite: the tile holds at least one key
-        const float pr = key < k_end ? exp2f(s - m_new) : 0.f;
+        const float pr = seen ? exp2f(s - m_new) : 0.f;
         const float l_tile = block_reduce_sum(pr, sh_red);
         const float alpha = exp2f(m_run - m_new);
         l_run = l_run * alpha + l_tile;
@@ -1032,14 +1046,21 @@ size_t respec_verify_attention_workspace_bytes(int32_t B, int32_t total_q, int64
     return pl.ws_bytes;
 }
 
-respec_status_t respec_verify_attention(const void *q, const void *k_cache, const void *v_cache,
-                                        const int32_t *q_indptr, const int64_t *kv_indptr,
-                                        void *out, float *lse, int32_t B, int32_t total_q,
-                                        int64_t total_kv, int32_t max_q_per_seq,
-                                        int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D,
-                                        float sm_scale, respec_dtype_t dt, void *workspace,
-                                        size_t workspace_bytes, void *hip_stream) {
-    using namespace respec;
+}  // extern "C"
+
+namespace respec {
+namespace {
+
+respec_status_t verify_attention_any(const void *q, const void *k_cache, const void *v_cache,
+                                     const int32_t *q_indptr, const int64_t *kv_indptr,
+                                     const uint64_t *tree_mask, void *out, float *lse, int32_t B,
+                                     int32_t total_q, int64_t total_kv, int32_t max_q_per_seq,
+                                     int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D, float sm_scale,
+                                     respec_dtype_t dt, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream) {
+    if (tree_mask && max_q_per_seq > 64)
+        return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention_tree: at most 64 rows per sequence, got %d",
+                    max_q_per_seq);
     if (B <= 0 || total_q < B || total_kv < total_q || max_q_per_seq < 1 || max_kv_len < 1)
         return fail(RESPEC_ERR_INVALID_ARG,
                     "verify_attention: need B > 0, total_q >= B, total_kv >= total_q, max_q_per_seq >= 1, "
@@ -1080,6 +1101,7 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     p.v = v_cache;
     p.q_indptr = q_indptr;
     p.kv_indptr = kv_indptr;
+    p.tree_mask = tree_mask;
     p.out = out;
     p.lse = lse;
     char *ws = static_cast<char *>(workspace);
@@ -1167,6 +1189,37 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     }
     clear_error();
     return RESPEC_OK;
+}
+
+}  // namespace
+}  // namespace respec
+
+extern "C" {
+
+respec_status_t respec_verify_attention(const void *q, const void *k_cache, const void *v_cache,
+                                        const int32_t *q_indptr, const int64_t *kv_indptr,
+                                        void *out, float *lse, int32_t B, int32_t total_q,
+                                        int64_t total_kv, int32_t max_q_per_seq,
+                                        int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                        float sm_scale, respec_dtype_t dt, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream) {
+    return respec::verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, nullptr, out, lse, B, total_q,
+                                        total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt, workspace,
+                                        workspace_bytes, hip_stream);
+}
+
+respec_status_t respec_verify_attention_tree(const void *q, const void *k_cache, const void *v_cache,
+                                             const int32_t *q_indptr, const int64_t *kv_indptr,
+                                             const uint64_t *tree_mask, void *out, float *lse, int32_t B,
+                                             int32_t total_q, int64_t total_kv, int32_t max_q_per_seq,
+                                             int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                             float sm_scale, respec_dtype_t dt, void *workspace,
+                                             size_t workspace_bytes, void *hip_stream) {
+    if (!tree_mask)
+        return respec::fail(RESPEC_ERR_INVALID_ARG, "verify_attention_tree: null tree_mask");
+    return respec::verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, tree_mask, out, lse, B, total_q,
+                                        total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt, workspace,
+                                        workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -141,3 +141,32 @@ def compare_sampler(gpu, ref):
         f"tokens={g_t[bad[0]].tolist()} vs oracle n={r_n[bad[0]]} tokens={r_t[bad[0]].tolist()}")
     return {"flagged": int(flagged.sum()), "flagged_mismatch": int((~same & flagged).sum()),
             "gpu_flagged": int((g_f != 0).sum()), "B": int(len(r_n))}
+
+
+def gpu_tree_attention(tb: synth.TreeBatch, sm_scale=None, want_lse=True):
+    wl = tb.wl
+    sm_scale = 1.0 / math.sqrt(wl.D) if sm_scale is None else sm_scale
+    B = len(tb.kv_lens)
+    dt = binding.RESPEC_F32 if wl.dtype == "f32" else binding.RESPEC_BF16
+    ws_bytes = binding.respec_verify_attention_workspace_bytes(
+        B, tb.total_q, tb.total_kv, tb.max_rows, tb.max_kv_len, wl.Hq, wl.Hkv, wl.D, dt)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=tb.q.device)
+    out = torch.full_like(tb.q, float("nan"))
+    lse = torch.full((tb.total_q, wl.Hq), float("nan"), dtype=torch.float32,
+                     device=tb.q.device) if want_lse else None
+    binding.respec_verify_attention_tree(tb.q, tb.k_cache, tb.v_cache, tb.q_indptr, tb.kv_indptr,
+                                         tb.tree_mask, out, lse, tb.max_rows, tb.max_kv_len, sm_scale, ws)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def oracle_tree_attention(oracle, tb: synth.TreeBatch, sm_scale=None, n_threads=0):
+    wl = tb.wl
+    sm_scale = 1.0 / math.sqrt(wl.D) if sm_scale is None else sm_scale
+    dt = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+    return oracle.verify_attention_tree(
+        synth.to_host_array(tb.q), synth.to_host_array(tb.k_cache), synth.to_host_array(tb.v_cache),
+        tb.q_indptr.cpu().numpy(), tb.kv_indptr.cpu().numpy(),
+        tb.tree_mask.cpu().numpy().view(np.uint64), wl.Hq, wl.Hkv, wl.D, float(np.float32(sm_scale)), dt,
+        want_lse=True, n_threads=n_threads)
