@@ -10,7 +10,9 @@
  *
  *   respec_verify_attention   the attention of that forward: (k_b+1) causal query rows per
  *                             sequence, grouped-query heads, ragged per-sequence KV cache;
- *   respec_rejection_sample   Eq. 1 / Eq. 2 over the vocabulary with supplied uniforms.
+ *   respec_rejection_sample   Eq. 1 / Eq. 2 over the vocabulary with supplied uniforms;
+ * and their counterparts for a tree of drafts (Section 3.1), respec_verify_attention_tree
+ * and respec_tree_rejection_sample.
  *
  * General rules
  *   - Every data pointer is a DEVICE pointer (HIP global memory) unless it says "host".
@@ -188,6 +190,50 @@ respec_status_t respec_rejection_sample(const void *target_logits, const void *d
                                         float temperature, respec_dtype_t logits_dt,
                                         void *workspace, size_t workspace_bytes,
                                         void *hip_stream);
+
+/*
+ * Rejection sampling over a tree of drafts (Section 3.1: candidate branches with branching
+ * factor t validated in parallel; Section 2.2, Eq. 1 and Eq. 2 applied to sibling candidates
+ * one after the other).  The paper states the rule for a chain only; this is the reading
+ * that keeps the result distributed as the target model when the children of a node are
+ * independent draws from the drafter at that node.
+ *
+ * Sequence b owns rows q_indptr[b] .. q_indptr[b+1]-1, the rows verify attention over a tree
+ * takes: row 0 is the root (the last committed token), parent[row] < row is the row's
+ * parent within the sequence (-1 for the root).  With cur = 0 and
+ *     p = softmax(target_logits[q_indptr[b]+cur, :] / T),  q = softmax(draft_logits[q_indptr[b]+cur, :] / T)
+ * the children c of cur are tried in row order: x = node_tokens[q_indptr[b]+c] is accepted
+ * iff u_accept[q_indptr[b]+c] < min(1, p[x]/q[x]) (q[x] == 0: ratio +inf if p[x] > 0, else 0);
+ * accepted, c becomes cur and the walk goes on from its own rows; rejected, p is replaced by
+ * max(0, p-q)/Z (Eq. 2) before the next child is tried.  When no child is left (or cur has
+ * none) one token is drawn from the current p by the inverse-CDF walk of
+ * respec_rejection_sample with u_final[b].  Rows off the accepted path are never read.
+ *
+ *   target_logits [total_q, V], row stride ld_t  logits_dt
+ *   draft_logits  [total_q, V], row stride ld_d  logits_dt: row r holds the drafter's logits
+ *                 for the children of row r (rows of leaves are never read)
+ *   node_tokens   [total_q] int32 in [0,V) (the root's entry is never read)
+ *   parent        [total_q] int32
+ *   u_accept      [total_q] f32 in [0,1) (one per node; the root's is never read)
+ *   u_final       [B] f32 in [0,1)
+ *   out_tokens    [B, max_depth+1] int32 (written): accepted tokens along the path, then the
+ *                 final token, then -1
+ *   out_path      [B, max(max_depth,1)] int32 (written): rows of the accepted nodes, then -1
+ *   out_num_accepted [B] int32 (written); out_flags [B] or NULL as in respec_rejection_sample
+ *                 (bit1 is also set when a residual came out empty and the target was used)
+ *   max_q_per_seq host-side bound of the rows of a sequence, <= 64 (RESPEC_ERR_UNSUPPORTED)
+ *   max_depth     host-side bound of the depth of any tree (root = depth 0)
+ * A chain-shaped tree gives the tokens of respec_rejection_sample bit for bit.
+ */
+respec_status_t respec_tree_rejection_sample(const void *target_logits, const void *draft_logits,
+                                             const int32_t *node_tokens, const int32_t *parent,
+                                             const int32_t *q_indptr, const float *u_accept,
+                                             const float *u_final, int32_t *out_tokens,
+                                             int32_t *out_path, int32_t *out_num_accepted,
+                                             int32_t *out_flags, int32_t B, int32_t total_q,
+                                             int32_t max_q_per_seq, int32_t max_depth, int32_t V,
+                                             int64_t ld_t, int64_t ld_d, float temperature,
+                                             respec_dtype_t logits_dt, void *hip_stream);
 
 #ifdef __cplusplus
 }

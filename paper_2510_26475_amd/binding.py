@@ -73,6 +73,12 @@ def load():
         c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64,
         c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_tree_rejection_sample.restype = c.c_int
+    lib.respec_tree_rejection_sample.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64,
+        c.c_float, c.c_int, c.c_void_p]
     _lib = lib
     return lib
 
@@ -81,6 +87,7 @@ EXPORTED_SYMBOLS = [
     "respec_status_string", "respec_last_error", "respec_version",
     "respec_verify_attention_workspace_bytes", "respec_verify_attention", "respec_verify_attention_tree",
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample",
+    "respec_tree_rejection_sample",
     "respec_profile_mark_main",
 ]
 
@@ -232,3 +239,43 @@ def respec_rejection_sample(target_logits, draft_logits, draft_tokens, q_indptr,
         _dev_ptr(out_tokens, "out_tokens"), _dev_ptr(out_num_accepted, "out_num_accepted"),
         _dev_ptr(out_flags, "out_flags"), B, total_q, max_k, V, target_logits.stride(0), ld_d,
         float(temperature), _dtype_code(target_logits), ws_ptr, ws_bytes, _stream_ptr(stream)))
+
+
+def respec_tree_rejection_sample(target_logits, draft_logits, node_tokens, parent, q_indptr, u_accept,
+                                 u_final, out_tokens, out_path, out_num_accepted, out_flags,
+                                 max_q_per_seq, max_depth, temperature, stream=None):
+    """target_logits and draft_logits [total_q,V] (one row per tree node); outputs are written in place."""
+    lib = load()
+    total_q, V = target_logits.shape
+    B = q_indptr.numel() - 1
+    if q_indptr.dtype != torch.int32:
+        raise TypeError("q_indptr must be int32")
+    if draft_logits.dtype != target_logits.dtype or tuple(draft_logits.shape) != (total_q, V):
+        raise ValueError("draft_logits must be [total_q, V] in the target's dtype")
+    for t, name in ((node_tokens, "node_tokens"), (parent, "parent")):
+        if t.dtype != torch.int32 or t.numel() != total_q:
+            raise TypeError(f"{name} must be int32 [total_q]")
+    if u_accept.dtype != torch.float32 or u_accept.numel() != total_q:
+        raise TypeError("u_accept must be float32 [total_q]")
+    if u_final.dtype != torch.float32 or u_final.numel() != B:
+        raise TypeError("u_final must be float32 [B]")
+    for t, name in ((out_tokens, "out_tokens"), (out_path, "out_path"), (out_num_accepted, "out_num_accepted")):
+        if t.dtype != torch.int32:
+            raise TypeError(f"{name} must be int32")
+    if tuple(out_tokens.shape) != (B, max_depth + 1) or tuple(out_path.shape) != (B, max(max_depth, 1)):
+        raise ValueError("out_tokens must be [B, max_depth+1] and out_path [B, max(max_depth,1)]")
+    if out_num_accepted.numel() != B:
+        raise ValueError("out_num_accepted must be [B]")
+    if target_logits.stride(1) != 1 or draft_logits.stride(1) != 1:
+        raise ValueError("logits rows must be unit-stride")
+    for t, name in ((target_logits, "target_logits"), (draft_logits, "draft_logits")):
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live on the GPU")
+    _check(lib.respec_tree_rejection_sample(
+        ctypes.c_void_p(target_logits.data_ptr()), ctypes.c_void_p(draft_logits.data_ptr()),
+        _dev_ptr(node_tokens, "node_tokens"), _dev_ptr(parent, "parent"), _dev_ptr(q_indptr, "q_indptr"),
+        _dev_ptr(u_accept, "u_accept"), _dev_ptr(u_final, "u_final"), _dev_ptr(out_tokens, "out_tokens"),
+        _dev_ptr(out_path, "out_path"), _dev_ptr(out_num_accepted, "out_num_accepted"),
+        _dev_ptr(out_flags, "out_flags"), B, total_q, max_q_per_seq, max_depth, V,
+        target_logits.stride(0), draft_logits.stride(0), float(temperature), _dtype_code(target_logits),
+        _stream_ptr(stream)))

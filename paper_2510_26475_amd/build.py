@@ -15,7 +15,7 @@ CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "librespec.so")
 
-SOURCES = ["respec_common.hip", "respec_sampler.hip", "respec_attention.hip"]
+SOURCES = ["respec_common.hip", "respec_sampler.hip", "respec_tree_sampler.hip", "respec_attention.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -30,7 +30,8 @@ FLAGS = [
 
 def _inputs():
     files = [os.path.join(CSRC, s) for s in SOURCES]
-    files += [os.path.join(CSRC, "respec_common.hpp"), os.path.join(INCLUDE, "respec.h")]
+    files += [os.path.join(CSRC, "respec_common.hpp"), os.path.join(CSRC, "respec_sampler_rows.hpp"),
+              os.path.join(INCLUDE, "respec.h")]
     return files
 
 

@@ -24,26 +24,12 @@
 // systematic error enters).  "ref" is a per-thread reference near the row maximum, not
 // necessarily the maximum: fp32 keeps full relative precision for any offset, and the
 // references are reconciled in fp64 when threads (and parts) are combined.
-#include "respec_common.hpp"
-
-#include <cmath>
+#include "respec_sampler_rows.hpp"
 
 namespace respec {
 namespace {
 
-constexpr int kThreads = 512;
-constexpr int kWaves = kThreads / 64;
-constexpr int kUnroll = 4;
-constexpr int kChunk = 5;   // slots of a thread's run in the inverse-CDF walk that are loaded together
-constexpr float kRefInit = -1.0e30f;
-constexpr double kBoundaryEps = 1e-6;
-constexpr int kMaxSplit = 8;          // work-groups that can share one sequence
-constexpr int kBoxHeaderBytes = 128;                      // epoch at word 0, progress counters at words 16..
-constexpr int kBoxPayload = kMaxSplit * 2 * 8;            // [part][stage parity][8 doubles]
-constexpr size_t kBoxBytes = kBoxHeaderBytes + (size_t)kBoxPayload * 8;
-constexpr int kSpinLimit = 1 << 22;
-
-struct SamplerParams {
+struct SamplerParams : RowMath {
     const void *target;
     const void *draft;
     const int32_t *draft_tokens;
@@ -55,342 +41,10 @@ struct SamplerParams {
     int32_t *out_flags;
     int32_t B, total_q, max_k, V;
     int64_t ld_t, ld_d;
-    float c_f;         // log2(e)/T rounded to nearest binary32
-    int one_term;      // c_f is close enough to log2(e)/T for the one-fma exponent of the fast pass
-    float c_hi, c_lo;  // log2(e)/T = c_hi + c_lo, c_lo > 0
-    double c_d;        // log2(e)/T
-    double inv_T;
-    float gap;         // logit distance above the reference that forces a re-reference
-    int aligned;       // every row starts 16-byte aligned
     int split;         // work-groups per sequence (1 when there is no workspace)
     char *boxes;       // [B] mailboxes of kBoxBytes (split > 1)
 };
 
-template <bool BF16>
-struct Elem {
-    static constexpr int EPV = BF16 ? 8 : 4;  // elements per 16-byte slot
-};
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ inline float as_f32(uint32_t u) { return __uint_as_float(u); }
-
-template <bool BF16>
-__device__ inline void unpack(const u32x4 &v, float (&z)[Elem<BF16>::EPV]) {
-    if constexpr (BF16) {
-        z[0] = as_f32(v[0] << 16);
-        z[1] = as_f32(v[0] & 0xffff0000u);
-        z[2] = as_f32(v[1] << 16);
-        z[3] = as_f32(v[1] & 0xffff0000u);
-        z[4] = as_f32(v[2] << 16);
-        z[5] = as_f32(v[2] & 0xffff0000u);
-        z[6] = as_f32(v[3] << 16);
-        z[7] = as_f32(v[3] & 0xffff0000u);
-    } else {
-        z[0] = as_f32(v[0]);
-        z[1] = as_f32(v[1]);
-        z[2] = as_f32(v[2]);
-        z[3] = as_f32(v[3]);
-    }
-}
-
-// A slot filled with -inf: inert in every sum and never chosen.
-template <bool BF16>
-__device__ inline u32x4 neg_inf_slot() {
-    const uint32_t w = BF16 ? 0xff80ff80u : 0xff800000u;
-    return u32x4{w, w, w, w};
-}
-
-// 16 bytes of row `row` starting at element slot*EPV; elements at or beyond V read as -inf.
-// FULL: every row is 16-byte aligned and V is a whole number of slots (known on the host).
-template <bool BF16, bool FULL = false>
-__device__ inline u32x4 load_slot(const void *row, int slot, int V, bool aligned) {
-    constexpr int EPV = Elem<BF16>::EPV;
-    if constexpr (FULL)
-        return *reinterpret_cast<const u32x4 *>(static_cast<const char *>(row) + (size_t)slot * 16);
-    const int e0 = slot * EPV;
-    if (aligned && e0 + EPV <= V)
-        return *reinterpret_cast<const u32x4 *>(static_cast<const char *>(row) + (size_t)slot * 16);
-    uint32_t w[4];
-    if constexpr (BF16) {
-        const uint16_t *r = static_cast<const uint16_t *>(row);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const uint32_t lo = (e0 + 2 * j < V) ? r[e0 + 2 * j] : 0xff80u;
-            const uint32_t hi = (e0 + 2 * j + 1 < V) ? r[e0 + 2 * j + 1] : 0xff80u;
-            w[j] = lo | (hi << 16);
-        }
-    } else {
-        const uint32_t *r = static_cast<const uint32_t *>(row);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = (e0 + j < V) ? r[e0 + j] : 0xff800000u;
-    }
-    return u32x4{w[0], w[1], w[2], w[3]};
-}
-
-__device__ inline float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// fp64 exp2 is only needed a few times per row (reconciling references).
-__device__ inline double exp2_f64(double x) { return exp2(x); }
-
-// exp2 argument of one element: (z - ref) * (c_hi + c_lo).  c_lo > 0 keeps -inf at -inf.
-__device__ inline float exp2_arg(float z, float ref, float c_hi, float c_lo) {
-    const float d = z - ref;
-    return fmaf(d, c_hi, d * c_lo);
-}
-
-// Running sum of exp((z-ref)/T) of one thread: fp32 lanes per slot position, fp64 carry.
-template <bool BF16>
-struct ThreadSum {
-    float ref = kRefInit;
-    double carry = 0.0;
-    float acc[Elem<BF16>::EPV];
-
-    __device__ inline void init() {
-#pragma unroll
-        for (int j = 0; j < Elem<BF16>::EPV; ++j) acc[j] = 0.f;
-    }
-
-    __device__ inline void absorb(const u32x4 &v, const SamplerParams &p) {
-        constexpr int EPV = Elem<BF16>::EPV;
-        float z[EPV];
-        unpack<BF16>(v, z);
-        float vmax = z[0];
-#pragma unroll
-        for (int j = 1; j < EPV; ++j) vmax = fmaxf(vmax, z[j]);
-        if (vmax - ref > p.gap) {  // first finite slot, or an element far above the reference
-            double s = carry;
-#pragma unroll
-            for (int j = 0; j < EPV; ++j) {
-                s += (double)acc[j];
-                acc[j] = 0.f;
-            }
-            carry = s * exp2_f64((double)(ref - vmax) * p.c_d);
-            ref = vmax;
-        }
-#pragma unroll
-        for (int j = 0; j < EPV; ++j) acc[j] += hw_exp2(exp2_arg(z[j], ref, p.c_hi, p.c_lo));
-    }
-
-    __device__ inline double total() const {
-        double s = carry;
-#pragma unroll
-        for (int j = 0; j < Elem<BF16>::EPV; ++j) s += (double)acc[j];
-        return s;
-    }
-};
-
-__device__ inline float wave_max(float x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
-    return x;
-}
-
-__device__ inline double wave_sum(double x) {
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
-    return x;
-}
-
-__device__ inline double wave_inclusive_scan(double x, int lane) {
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const double y = __shfl_up(x, o);
-        if (lane >= o) x += y;
-    }
-    return x;
-}
-
-struct SharedState {
-    float m[2][2][kWaves];   // [parity][row p/q][wave]
-    double s[2][2][kWaves];
-    double wave_total[kWaves];
-    double scan_total[kWaves];
-    double all_total[kMaxSplit * kWaves];  // region totals of every part, in vocabulary order
-    double xchg[kMaxSplit][8];             // what the parts published in the current stage
-    float comb_m[2];                       // combined (M, S) of the p row and the q row
-    double comb_s[2];
-    int failed;                            // a bounded wait for a partner ran out
-    int token;
-    int near_edge;
-    int last_positive;
-    int first_thread;
-};
-
-// Combine the per-thread (ref, sum) pairs of the block into one (M, S) with
-// S = sum_x exp((z_x - M)/T).  Every thread returns the same bits.
-__device__ inline void block_combine(float ref, double sum, SharedState &sh, int parity, int which,
-                                     const SamplerParams &p, float &M, double &S) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const float mw = wave_max(ref);
-    const double sw = wave_sum(sum * exp2_f64((double)(ref - mw) * p.c_d));
-    if (lane == 0) {
-        sh.m[parity][which][wave] = mw;
-        sh.s[parity][which][wave] = sw;
-    }
-    __syncthreads();
-    const int w = lane & (kWaves - 1);
-    const float my_m = sh.m[parity][which][w];
-    float mm = my_m;
-#pragma unroll
-    for (int o = kWaves / 2; o >= 1; o >>= 1) mm = fmaxf(mm, __shfl_xor(mm, o));
-    double part = sh.s[parity][which][w] * exp2_f64((double)(my_m - mm) * p.c_d);
-#pragma unroll
-    for (int o = kWaves / 2; o >= 1; o >>= 1) part += __shfl_xor(part, o);
-    M = mm;
-    S = part;
-}
-
-// One thread's share of the fast pass: 8 (bf16) or 4 (f32) running sums of
-// exp2(z*c + K) = exp((z - ref)/T), no branches.  ONE_TERM: c = c_f, K = -ref*c_f rounded (the
-// rounding residue is put back in fp64 when threads are combined).
-template <bool BF16, bool ONE_TERM>
-__device__ inline void fast_absorb(const u32x4 &v, float (&acc)[Elem<BF16>::EPV], float ref, float K,
-                                   const SamplerParams &p) {
-    constexpr int EPV = Elem<BF16>::EPV;
-    float z[EPV];
-    unpack<BF16>(v, z);
-#pragma unroll
-    for (int j = 0; j < EPV; ++j) {
-        const float t = ONE_TERM ? fmaf(z[j], p.c_f, K) : exp2_arg(z[j], ref, p.c_hi, p.c_lo);
-        acc[j] += hw_exp2(t);
-    }
-}
-
-template <bool BF16>
-__device__ inline float slot_max(const u32x4 &v) {
-    constexpr int EPV = Elem<BF16>::EPV;
-    float z[EPV];
-    unpack<BF16>(v, z);
-    float m = z[0];
-#pragma unroll
-    for (int j = 1; j < EPV; ++j) m = fmaxf(m, z[j]);
-    return m;
-}
-
-// Fast streaming pass over a target row (and, if TWO, the matching drafter row).  The
-// reference of a wave is the maximum of the first slots it reads, not the row maximum:
-// exp2 keeps full relative precision for any offset, only a logit more than ~88/c above the
-// reference would overflow.  Returns false (every thread alike) when a sum came out
-// non-finite or empty, and the caller then repeats the row with the guarded pass below.
-template <bool BF16, bool TWO, bool ONE_TERM>
-__device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int nslots, int Vrow,
-                                      SharedState &sh, int parity, const SamplerParams &p, float &Mp,
-                                      double &Sp, float &Mq, double &Sq) {
-    constexpr int EPV = Elem<BF16>::EPV;
-    constexpr int kBatch = kThreads * kUnroll;  // slots per block iteration
-    float accp[EPV], accq[EPV];
-#pragma unroll
-    for (int j = 0; j < EPV; ++j) accp[j] = accq[j] = 0.f;
-    float refp = 0.f, refq = 0.f, Kp = 0.f, Kq = 0.f;
-    const int n_iter = (nslots + kBatch - 1) / kBatch;  // block-uniform, >= 1
-    // batch `it` of this thread: slots it*kBatch + tid + u*kThreads; only the last batch can
-    // run past the row (those slots read as -inf)
-    auto load_batch = [&](int it, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) {
-        const int s0 = it * kBatch + threadIdx.x;
-        if (it + 1 < n_iter) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                vp[u] = load_slot<BF16, true>(rowp, s0 + u * kThreads, Vrow, true);
-                if constexpr (TWO) vq[u] = load_slot<BF16, true>(rowq, s0 + u * kThreads, Vrow, true);
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int slot = s0 + u * kThreads;
-                const bool in = slot < nslots;
-                const int safe = in ? slot : 0;
-                const u32x4 a = load_slot<BF16, true>(rowp, safe, Vrow, true);
-                vp[u] = in ? a : neg_inf_slot<BF16>();
-                if constexpr (TWO) {
-                    const u32x4 b = load_slot<BF16, true>(rowq, safe, Vrow, true);
-                    vq[u] = in ? b : neg_inf_slot<BF16>();
-                }
-            }
-        }
-    };
-    u32x4 vp[kUnroll], vq[kUnroll];
-    load_batch(0, vp, vq);
-    {   // references from the first batch
-        float mp = slot_max<BF16>(vp[0]), mq = -INFINITY;
-#pragma unroll
-        for (int u = 1; u < kUnroll; ++u) mp = fmaxf(mp, slot_max<BF16>(vp[u]));
-        mp = wave_max(mp);
-        refp = (mp > -INFINITY && mp < INFINITY) ? mp : 0.f;
-        Kp = -refp * p.c_f;
-        if constexpr (TWO) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) mq = fmaxf(mq, slot_max<BF16>(vq[u]));
-            mq = wave_max(mq);
-            refq = (mq > -INFINITY && mq < INFINITY) ? mq : 0.f;
-            Kq = -refq * p.c_f;
-        }
-    }
-    for (int it = 0; it < n_iter; ++it) {
-        u32x4 np[kUnroll], nq[kUnroll];
-        const bool more = it + 1 < n_iter;  // block-uniform
-        if (more) load_batch(it + 1, np, nq);  // in flight while this batch is summed
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            fast_absorb<BF16, ONE_TERM>(vp[u], accp, refp, Kp, p);
-            if constexpr (TWO) fast_absorb<BF16, ONE_TERM>(vq[u], accq, refq, Kq, p);
-        }
-        if (more) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                vp[u] = np[u];
-                if constexpr (TWO) vq[u] = nq[u];
-            }
-        }
-    }
-    double sp = 0.0, sq = 0.0;
-#pragma unroll
-    for (int j = 0; j < EPV; ++j) {
-        sp += (double)accp[j];
-        sq += (double)accq[j];
-    }
-    if constexpr (ONE_TERM) {  // exp2(z c + K) = exp2((z - ref) c) * exp2(K + ref c): undo the residue
-        sp *= exp2_f64(-((double)Kp + (double)refp * (double)p.c_f));
-        if constexpr (TWO) sq *= exp2_f64(-((double)Kq + (double)refq * (double)p.c_f));
-    }
-    block_combine(refp, sp, sh, parity, 0, p, Mp, Sp);
-    bool ok = Sp > 0.0 && Sp < 1.0e300;
-    if constexpr (TWO) {
-        block_combine(refq, sq, sh, parity, 1, p, Mq, Sq);
-        ok = ok && Sq > 0.0 && Sq < 1.0e300;
-    }
-    return ok;
-}
-
-// Guarded streaming pass (any finite or -inf logits): per-thread references that follow the
-// running maximum.  Used when the fast pass reports an overflow or an empty sum.
-template <bool BF16, bool TWO>
-__device__ inline void row_stats(const void *rowp, const void *rowq, int nslots, int Vrow, SharedState &sh,
-                                 int parity, const SamplerParams &p, float &Mp, double &Sp,
-                                 float &Mq, double &Sq) {
-    ThreadSum<BF16> tp, tq;
-    tp.init();
-    tq.init();
-    const bool aligned = p.aligned != 0;
-    for (int s0 = threadIdx.x; s0 < nslots; s0 += kThreads * kUnroll) {
-        u32x4 vp[kUnroll], vq[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int slot = s0 + u * kThreads;
-            vp[u] = slot < nslots ? load_slot<BF16>(rowp, slot, Vrow, aligned) : neg_inf_slot<BF16>();
-            if constexpr (TWO)
-                vq[u] = slot < nslots ? load_slot<BF16>(rowq, slot, Vrow, aligned)
-                                      : neg_inf_slot<BF16>();
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            tp.absorb(vp[u], p);
-            if constexpr (TWO) tq.absorb(vq[u], p);
-        }
-    }
-    block_combine(tp.ref, tp.total(), sh, parity, 0, p, Mp, Sp);
-    if constexpr (TWO) block_combine(tq.ref, tq.total(), sh, parity, 1, p, Mq, Sq);
-}
 
 // ------------------------------------------------------------------------------------------
 // mailbox: the few numbers the parts of one sequence exchange after a streaming pass
@@ -980,17 +634,7 @@ respec_status_t respec_rejection_sample(const void *target_logits, const void *d
     p.V = V;
     p.ld_t = ld_t;
     p.ld_d = has_drafts ? ld_d : ld_t;
-    const double T = (double)temperature;
-    p.c_d = 1.4426950408889634074 / T;
-    float c_hi = (float)p.c_d;
-    if ((double)c_hi >= p.c_d) c_hi = std::nextafterf(c_hi, 0.f);  // keep the low term positive
-    p.c_hi = c_hi;
-    p.c_lo = (float)(p.c_d - (double)c_hi);
-    p.c_f = (float)p.c_d;
-    p.one_term = std::fabs((double)p.c_f / p.c_d - 1.0) <= 2.0e-8 ? 1 : 0;
-    if (env_long("RESPEC_SAMPLER_TWO_TERM", 0) != 0) p.one_term = 0;
-    p.inv_T = 1.0 / T;
-    p.gap = (float)(40.0 / p.c_d);
+    set_row_math(p, temperature);
     p.aligned = aligned_to(target_logits, 16) && (ld_t * esz) % 16 == 0 &&
                 (!has_drafts || (aligned_to(draft_logits, 16) && (ld_d * esz) % 16 == 0));
 

@@ -170,3 +170,44 @@ def oracle_tree_attention(oracle, tb: synth.TreeBatch, sm_scale=None, n_threads=
         tb.q_indptr.cpu().numpy(), tb.kv_indptr.cpu().numpy(),
         tb.tree_mask.cpu().numpy().view(np.uint64), wl.Hq, wl.Hkv, wl.D, float(np.float32(sm_scale)), dt,
         want_lse=True, n_threads=n_threads)
+
+
+def gpu_tree_sample(tb: synth.TreeBatch, temperature=None, max_depth=None):
+    T = tb.wl.temperature if temperature is None else temperature
+    B = len(tb.kv_lens)
+    max_depth = tb.max_depth if max_depth is None else max_depth
+    dev = tb.target_logits.device
+    toks = torch.full((B, max_depth + 1), -7, dtype=torch.int32, device=dev)
+    path = torch.full((B, max(max_depth, 1)), -7, dtype=torch.int32, device=dev)
+    n = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    flags = torch.full((B,), -7, dtype=torch.int32, device=dev)
+    binding.respec_tree_rejection_sample(tb.target_logits, tb.draft_logits, tb.node_tokens, tb.parent,
+                                         tb.q_indptr, tb.u_accept, tb.u_final, toks, path, n, flags,
+                                         tb.max_rows, max_depth, T)
+    torch.cuda.synchronize()
+    return toks.cpu().numpy(), path.cpu().numpy(), n.cpu().numpy(), flags.cpu().numpy()
+
+
+def oracle_tree_sample(oracle, tb: synth.TreeBatch, temperature=None, max_depth=None, n_threads=0):
+    T = tb.wl.temperature if temperature is None else temperature
+    max_depth = tb.max_depth if max_depth is None else max_depth
+    dt = oracle.F32 if tb.wl.dtype == "f32" else oracle.BF16
+    return oracle.tree_rejection_sample(
+        synth.to_host_array(tb.target_logits), synth.to_host_array(tb.draft_logits),
+        tb.node_tokens.cpu().numpy(), tb.parent.cpu().numpy(), tb.q_indptr.cpu().numpy(),
+        tb.u_accept.cpu().numpy(), tb.u_final.cpu().numpy(), max_depth, T, dt, n_threads=n_threads)
+
+
+def compare_tree_sampler(gpu, ref):
+    """Exact equality of tokens, path and counts on unflagged sequences; returns the boundary tally."""
+    g_t, g_p, g_n, g_f = gpu
+    r_t, r_p, r_n, r_f = ref
+    flagged = r_f != 0
+    same = (g_n == r_n) & (g_t == r_t).all(axis=1) & (g_p == r_p).all(axis=1)
+    bad = np.flatnonzero(~same & ~flagged)
+    assert bad.size == 0, (
+        f"{bad.size} unflagged sequences differ, first b={bad[0]}: gpu n={g_n[bad[0]]} "
+        f"tokens={g_t[bad[0]].tolist()} path={g_p[bad[0]].tolist()} vs oracle n={r_n[bad[0]]} "
+        f"tokens={r_t[bad[0]].tolist()} path={r_p[bad[0]].tolist()}")
+    return {"flagged": int(flagged.sum()), "flagged_mismatch": int((~same & flagged).sum()),
+            "gpu_flagged": int((g_f != 0).sum()), "B": int(len(r_n))}

@@ -1,0 +1,176 @@
+"""GPU parity of respec_tree_rejection_sample against the CPU oracle.
+
+Tokens, the accepted path and its length must match bit-exactly given the same uniforms,
+except for sequences the oracle flags as boundary draws, which are counted.
+"""
+import numpy as np
+import pytest
+import torch
+from scipy import stats
+
+from helpers import compare_tree_sampler, gpu_sample, gpu_tree_sample, oracle_tree_sample
+from paper_2510_26475_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _wl(name, V, dtype, sigma=1.0, T=1.0):
+    return synth.Workload(name, B=0, k=0, Hq=1, Hkv=1, D=64, V=V, dtype=dtype,
+                          len_dist="uniform", len_lo=1, len_hi=1, sigma=sigma, temperature=T)
+
+
+def _mixed_trees(n, seed, max_nodes=12):
+    gen = torch.Generator().manual_seed(seed)
+    out = []
+    for i in range(n):
+        kind = i % 5
+        if kind == 0:
+            out.append(synth.random_parents(2 + int(torch.randint(0, max_nodes, (1,), generator=gen)), gen))
+        elif kind == 1:
+            out.append(synth.caterpillar_parents(1 + i % 4, 2 + i % 3))
+        elif kind == 2:
+            out.append(list(range(-1, 1 + i % 5)))          # a chain
+        elif kind == 3:
+            out.append([-1] + [0] * (1 + i % 7))            # a star: siblings only
+        else:
+            out.append([-1])                                 # no drafts at all
+    return out
+
+
+def _batch(wl, parents, seed):
+    return synth.make_tree_batch(wl, parents, device="cuda", kv_lens=[len(p) for p in parents], seed=seed,
+                                 with_attention=False)
+
+
+def _parity(oracle, tb, **kw):
+    gpu = gpu_tree_sample(tb, **kw)
+    ref = oracle_tree_sample(oracle, tb, **kw)
+    tally = compare_tree_sampler(gpu, ref)
+    assert tally["flagged"] <= max(3, 0.25 * tally["B"]), tally
+    return gpu, ref, tally
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V", [1024, 1000, 1001, 7, 4099])
+def test_small_vocab_sizes_and_ragged_tails(oracle, dtype, V):
+    wl = _wl("tree_small", V, dtype)
+    _, ref, _ = _parity(oracle, _batch(wl, _mixed_trees(80, V), seed=V))
+    assert len(set(ref[2].tolist())) >= 3          # a mix of accepted path lengths
+
+
+@pytest.mark.parametrize("sigma", [0.5, 1.0, 3.0])
+def test_full_vocab_bf16(oracle, sigma):
+    wl = _wl("tree_full", 151936, "bf16", sigma=sigma)
+    gpu, ref, tally = _parity(oracle, _batch(wl, _mixed_trees(40, 7), seed=int(10 * sigma)))
+    print("tree sampler tally", sigma, tally, "accepted", ref[2].tolist())
+
+
+def test_full_vocab_f32_with_temperature(oracle):
+    wl = _wl("tree_f32_T", 151936, "f32", sigma=1.5, T=0.7)
+    _parity(oracle, _batch(wl, _mixed_trees(16, 9), seed=21))
+
+
+def test_many_rejected_siblings_in_a_row(oracle):
+    # stars with up to 12 children and a poor drafter: long runs of Eq. 2 applied to itself
+    wl = _wl("tree_star", 4096, "f32", sigma=4.0)
+    parents = [[-1] + [0] * m for m in (12, 9, 6, 5, 4, 3, 12, 8)] * 8
+    gpu, ref, tally = _parity(oracle, _batch(wl, parents, seed=5))
+    assert (ref[2] == 0).sum() >= 8                # plenty of sequences rejected every child
+
+
+def test_chain_shaped_tree_gives_the_chain_samplers_tokens_bit_for_bit():
+    wl = _wl("tree_chain", 151936, "bf16")
+    ks = [3, 0, 4, 1, 2, 4, 3, 3] * 4
+    tb = _batch(wl, [list(range(-1, k)) for k in ks], seed=12)
+    qi = tb.q_indptr.cpu().tolist()
+    d_rows = [r for b, k in enumerate(ks) for r in range(qi[b], qi[b] + k)]        # nodes with a child
+    c_rows = [r + 1 for r in d_rows]                                              # those children
+    d_idx = torch.tensor(d_rows, device="cuda", dtype=torch.long)
+    c_idx = torch.tensor(c_rows, device="cuda", dtype=torch.long)
+    chain = synth.VerifyBatch(
+        wl=wl, q=torch.empty(0), k_cache=torch.empty(0), v_cache=torch.empty(0), q_indptr=tb.q_indptr,
+        kv_indptr=torch.empty(0), target_logits=tb.target_logits, draft_logits=tb.draft_logits[d_idx].contiguous(),
+        draft_tokens=tb.node_tokens[c_idx].contiguous(), u_accept=tb.u_accept[c_idx].contiguous(),
+        u_final=tb.u_final, k_per_seq=ks, kv_lens=[k + 1 for k in ks])
+    t_tok, t_path, t_n, t_flags = gpu_tree_sample(tb)
+    c_tok, c_n, c_flags = gpu_sample(chain, workspace=None)
+    np.testing.assert_array_equal(t_tok, c_tok)
+    np.testing.assert_array_equal(t_n, c_n)
+    np.testing.assert_array_equal(t_flags, c_flags)
+    for b, n in enumerate(t_n):
+        assert t_path[b, :n].tolist() == list(range(1, n + 1))
+
+
+def test_identical_drafter_accepts_the_first_child_everywhere(oracle):
+    wl = _wl("tree_same", 2048, "f32")
+    tb = _batch(wl, [synth.caterpillar_parents(3, 2)] * 16, seed=3)
+    tb.draft_logits.copy_(tb.target_logits)
+    # tokens must come from the (new) drafter rows for q[x] > 0 to hold: redraw them
+    dg = torch.Generator(device="cuda").manual_seed(8)
+    qi = tb.q_indptr.cpu().tolist()
+    src = torch.tensor([qi[b] + max(p, 0) for b, par in enumerate(tb.parents_per_seq) for p in par], device="cuda")
+    tb.node_tokens.copy_(synth.sample_draft_tokens(tb.draft_logits[src], 1.0, dg))
+    gpu, ref, _ = _parity(oracle, tb)
+    assert (gpu[2] == 3).all() and (gpu[1] == np.array([1, 3, 5])).all()
+
+
+def test_runs_are_bitwise_reproducible():
+    wl = _wl("tree_det", 151936, "bf16", sigma=2.0)
+    tb = _batch(wl, _mixed_trees(32, 4), seed=10)
+    a, b = gpu_tree_sample(tb), gpu_tree_sample(tb)
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
+
+
+def test_chi_square_emitted_marginal_is_target_on_gpu(oracle):
+    """Losslessness with sibling candidates: 10^6 stars of 3 children, tiny vocabulary; the first
+    emitted token is distributed as the target."""
+    V, N, m = 12, 1_000_000, 3
+    g = torch.Generator(device="cpu").manual_seed(3)
+    t_row = 1.5 * torch.randn(V, generator=g)
+    d_row = t_row + torch.randn(V, generator=g)
+    wl = _wl("tree_chi", V, "f32")
+    R = m + 1
+    target = t_row.repeat(R * N, 1).cuda()
+    draft = d_row.repeat(R * N, 1).cuda()
+    dg = torch.Generator(device="cuda").manual_seed(4)
+    node_tokens = synth.sample_draft_tokens(draft, 1.0, dg, chunk_rows=1 << 18)
+    parent = torch.tensor([-1] + [0] * m, dtype=torch.int32).repeat(N).cuda()
+    tb = synth.TreeBatch(
+        wl=wl, q=torch.empty((R * N, 0)), k_cache=torch.empty(0), v_cache=torch.empty(0),
+        q_indptr=torch.arange(0, R * N + 1, R, dtype=torch.int32, device="cuda"), kv_indptr=torch.empty(0),
+        parent=parent, tree_mask=torch.empty(0), target_logits=target, draft_logits=draft,
+        node_tokens=node_tokens, u_accept=torch.rand(R * N, generator=dg, device="cuda"),
+        u_final=torch.rand(N, generator=dg, device="cuda"), parents_per_seq=[[-1] + [0] * m], kv_lens=[R] * N)
+    toks, path, n, _ = gpu_tree_sample(tb, max_depth=1)
+    p = oracle.softmax_rows(t_row.numpy()[None].astype(np.float32), 1.0, oracle.F32)[0]
+    counts = np.bincount(toks[:, 0], minlength=V)
+    assert stats.chisquare(counts, p * N)[1] > 1e-3
+    # more candidates accept more often than one: P(accept first) = sum min(p, q)
+    q = oracle.softmax_rows(d_row.numpy()[None].astype(np.float32), 1.0, oracle.F32)[0]
+    alpha1 = np.minimum(p, q).sum()
+    assert n.mean() > alpha1 + 0.01
+
+
+def test_bad_arguments_are_rejected_before_any_launch():
+    wl = _wl("tree_err", 1024, "f32")
+    tb = _batch(wl, [[-1, 0, 0], [-1, 0]], seed=1)
+    toks = torch.empty((2, 2), dtype=torch.int32, device="cuda")
+    path = torch.empty((2, 1), dtype=torch.int32, device="cuda")
+    n = torch.empty(2, dtype=torch.int32, device="cuda")
+
+    def call(max_rows=3, T=1.0):
+        binding.respec_tree_rejection_sample(tb.target_logits, tb.draft_logits, tb.node_tokens, tb.parent,
+                                             tb.q_indptr, tb.u_accept, tb.u_final, toks, path, n, None,
+                                             max_rows, 1, T)
+    with pytest.raises(binding.RespecError) as e:
+        call(T=0.0)
+    assert e.value.status == 1
+    with pytest.raises(binding.RespecError) as e:
+        call(max_rows=2)            # 2 sequences * 2 rows < 5 rows
+    assert e.value.status == 1
+    with pytest.raises(binding.RespecError) as e:
+        call(max_rows=65)
+    assert e.value.status == 2
+    call()
+    torch.cuda.synchronize()

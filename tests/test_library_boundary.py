@@ -103,3 +103,38 @@ def test_sampler_argument_errors_need_no_gpu(lib):
     assert run(V=0) == 1
     assert run(dt=7) == 1
     assert run(B=0) == 1
+
+
+def test_tree_entry_points_argument_errors_need_no_gpu(lib):
+    null = ctypes.c_void_p(None)
+    bogus = ctypes.c_void_p(0x1000)
+    attn = lib.respec_verify_attention_tree
+    # more rows per sequence than the mask has bits
+    st = attn(bogus, bogus, bogus, bogus, bogus, bogus, bogus, null, 1, 65, 100, 65, 100, 8, 2, 128, 0.1,
+              binding.RESPEC_BF16, bogus, 1 << 30, null)
+    assert st == 2
+    # no mask
+    st = attn(bogus, bogus, bogus, bogus, bogus, null, bogus, null, 1, 4, 100, 4, 100, 8, 2, 128, 0.1,
+              binding.RESPEC_BF16, bogus, 1 << 30, null)
+    assert st == 1
+    call = lib.respec_tree_rejection_sample
+
+    def run(**kw):
+        a = dict(t=bogus, d=bogus, tok=bogus, par=bogus, qi=bogus, ua=bogus, uf=bogus, ot=bogus, op=bogus,
+                 on=bogus, of=null, B=2, total_q=8, max_rows=4, max_depth=3, V=1024, ld_t=1024, ld_d=1024,
+                 T=1.0, dt=binding.RESPEC_F32)
+        a.update(kw)
+        return call(a["t"], a["d"], a["tok"], a["par"], a["qi"], a["ua"], a["uf"], a["ot"], a["op"], a["on"],
+                    a["of"], a["B"], a["total_q"], a["max_rows"], a["max_depth"], a["V"], a["ld_t"], a["ld_d"],
+                    a["T"], a["dt"], null)
+
+    assert run(T=0.0) == 1
+    assert run(T=float("inf")) == 1
+    assert run(d=null) == 1
+    assert run(par=null) == 1
+    assert run(op=null) == 1
+    assert run(ld_d=1000) == 1
+    assert run(max_rows=3) == 1              # 2 sequences * 3 rows < 8 rows
+    assert run(max_rows=65, total_q=100) == 2
+    assert run(max_depth=-1) == 1
+    assert run(dt=7) == 1
