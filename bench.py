@@ -6,7 +6,11 @@ A "step" is one pass of the whole hot path over one synthetic batch: verify atte
 are resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sigma S]
-                    [--no-cpu-baseline]
+                    [--tree DEPTHxBRANCH] [--no-cpu-baseline]
+
+--tree times the tree-of-drafts variant of the step on the same workload (every sequence
+drafts a main chain of DEPTH nodes with BRANCH candidates per position); the default is the
+chain of k drafts the workload names.
 """
 from __future__ import annotations
 
@@ -49,6 +53,58 @@ def sampler_algorithmic_bytes(batch: synth.VerifyBatch, num_accepted) -> int:
     for n, k in zip(num_accepted, batch.k_per_seq):
         rows += (n + 1) + min(n + 1, k)
     return rows * wl.V * esz
+
+
+def tree_sampler_algorithmic_bytes(tb: synth.TreeBatch, num_accepted, path) -> int:
+    """Logit rows the method needs, once each: the target row of every node on the accepted path
+    (root included) and the drafter row of those of them that have children."""
+    esz = 4 if tb.wl.dtype == "f32" else 2
+    rows = 0
+    for b, par in enumerate(tb.parents_per_seq):
+        has_child = set(par[1:])
+        visited = [0] + [int(r) for r in path[b][:num_accepted[b]]]
+        rows += len(visited) + sum(1 for r in visited if r in has_child)
+    return rows * tb.wl.V * esz
+
+
+def run_cpu_baseline_tree(tb: synth.TreeBatch, n_seqs: int):
+    """The oracle's tree entry points timed on the host cores over the first n_seqs sequences."""
+    import numpy as np
+
+    import oracle  # test infrastructure: allowed here for the cpu_baseline leg only
+    oracle.build()
+    wl = tb.wl
+    dt = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+    n_all = len(tb.parents_per_seq)
+    threads = oracle.max_threads()
+
+    def run(n, n_threads):
+        n = max(1, min(n, n_all))
+        rq, rk = int(tb.q_indptr[n]), int(tb.kv_indptr[n])
+        h = dict(q=synth.to_host_array(tb.q[:rq]), k=synth.to_host_array(tb.k_cache[:rk]),
+                 v=synth.to_host_array(tb.v_cache[:rk]), qi=tb.q_indptr[:n + 1].cpu().numpy(),
+                 ki=tb.kv_indptr[:n + 1].cpu().numpy(), mask=tb.tree_mask[:rq].cpu().numpy().view(np.uint64),
+                 t=synth.to_host_array(tb.target_logits[:rq]), d=synth.to_host_array(tb.draft_logits[:rq]),
+                 tok=tb.node_tokens[:rq].cpu().numpy(), par=tb.parent[:rq].cpu().numpy(),
+                 ua=tb.u_accept[:rq].cpu().numpy(), uf=tb.u_final[:n].cpu().numpy())
+        t0 = time.perf_counter()
+        oracle.verify_attention_tree(h["q"], h["k"], h["v"], h["qi"], h["ki"], h["mask"], wl.Hq, wl.Hkv, wl.D,
+                                     float(np.float32(1.0 / math.sqrt(wl.D))), dt, n_threads=n_threads)
+        t1 = time.perf_counter()
+        _, _, n_acc, _ = oracle.tree_rejection_sample(h["t"], h["d"], h["tok"], h["par"], h["qi"], h["ua"], h["uf"],
+                                                      tb.max_depth, wl.temperature, dt, n_threads=n_threads)
+        t2 = time.perf_counter()
+        return n, int((n_acc + 1).sum()), t1 - t0, t2 - t1
+
+    n, emitted, ta, ts = run(n_seqs, 0)
+    n1, emitted1, ta1, ts1 = run(n_seqs // max(1, threads), 1)
+    return {
+        "one_thread": {"value": emitted1 / (ta1 + ts1), "unit": "tokens/s", "sample": f"first {n1} sequences"},
+        "value": emitted / (ta + ts), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+        "sample": f"first {n} of {n_all} sequences of the same workload, one attention layer + sampler, "
+                  f"OpenMP over sequences",
+        "attention_s": ta, "sampler_s": ts, "emitted_tokens": emitted,
+    }
 
 
 def run_cpu_baseline(batch: synth.VerifyBatch, n_seqs: int):
@@ -112,6 +168,8 @@ def main():
     ap.add_argument("--sigma", type=float, default=None, help="drafter noise (default: workload's)")
     ap.add_argument("--batch", type=int, default=None, help="override B (sweeps)")
     ap.add_argument("--k", type=int, default=None, help="override k (sweeps)")
+    ap.add_argument("--tree", default=None, metavar="DEPTHxBRANCH",
+                    help="time the tree-of-drafts entry points: a chain of DEPTH nodes, BRANCH candidates per position")
     ap.add_argument("--probe-every", type=int, default=4,
                     help="in the timed region, bracket the main attention kernel with events on every n-th step")
     ap.add_argument("--layers", type=int, default=None,
@@ -143,16 +201,26 @@ def main():
 
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    batch = synth.make_batch(wl, device=dev)
-    B = len(batch.k_per_seq)
-    max_q = batch.max_k + 1
+    tree = None
+    if args.tree:
+        depth, branch = (int(x) for x in args.tree.lower().split("x"))
+        tree = synth.caterpillar_parents(depth, branch)
+        cgen = torch.Generator(device="cpu").manual_seed(wl.seed)
+        batch = synth.make_tree_batch(wl, [tree] * wl.B, device=dev, kv_lens=synth.draw_lengths(wl, cgen))
+        B, max_q, max_out = wl.B, batch.max_rows, batch.max_depth
+    else:
+        batch = synth.make_batch(wl, device=dev)
+        B = len(batch.k_per_seq)
+        max_q = batch.max_k + 1
+        max_out = batch.max_k
     dt = binding.RESPEC_F32 if wl.dtype == "f32" else binding.RESPEC_BF16
     ws_bytes = binding.respec_verify_attention_workspace_bytes(
         B, batch.total_q, batch.total_kv, max_q, batch.max_kv_len, wl.Hq, wl.Hkv, wl.D, dt)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     out = torch.empty_like(batch.q)
     lse = torch.empty((batch.total_q, wl.Hq), dtype=torch.float32, device=dev)
-    toks = torch.empty((B, batch.max_k + 1), dtype=torch.int32, device=dev)
+    toks = torch.empty((B, max_out + 1), dtype=torch.int32, device=dev)
+    path = torch.empty((B, max(max_out, 1)), dtype=torch.int32, device=dev)
     n_acc = torch.empty((B,), dtype=torch.int32, device=dev)
     flags = torch.empty((B,), dtype=torch.int32, device=dev)
     sm_scale = 1.0 / math.sqrt(wl.D)
@@ -160,16 +228,27 @@ def main():
     samp_ws = torch.zeros(binding.respec_rejection_sample_workspace_bytes(B, batch.total_q, wl.V, dt),
                           dtype=torch.uint8, device=dev)
 
-    def attention():
-        binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
-                                        batch.kv_indptr, out, lse, max_q, batch.max_kv_len,
-                                        sm_scale, ws)
+    if tree is not None:
+        def attention():
+            binding.respec_verify_attention_tree(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                                                 batch.kv_indptr, batch.tree_mask, out, lse, max_q,
+                                                 batch.max_kv_len, sm_scale, ws)
 
-    def sampler():
-        binding.respec_rejection_sample(batch.target_logits, batch.draft_logits,
-                                        batch.draft_tokens, batch.q_indptr, batch.u_accept,
-                                        batch.u_final, toks, n_acc, flags, batch.max_k,
-                                        wl.temperature, workspace=samp_ws)
+        def sampler():
+            binding.respec_tree_rejection_sample(batch.target_logits, batch.draft_logits, batch.node_tokens,
+                                                 batch.parent, batch.q_indptr, batch.u_accept, batch.u_final,
+                                                 toks, path, n_acc, flags, max_q, max_out, wl.temperature)
+    else:
+        def attention():
+            binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                                            batch.kv_indptr, out, lse, max_q, batch.max_kv_len,
+                                            sm_scale, ws)
+
+        def sampler():
+            binding.respec_rejection_sample(batch.target_logits, batch.draft_logits,
+                                            batch.draft_tokens, batch.q_indptr, batch.u_accept,
+                                            batch.u_final, toks, n_acc, flags, batch.max_k,
+                                            wl.temperature, workspace=samp_ws)
 
     for _ in range(args.warmup):
         attention()
@@ -238,11 +317,15 @@ def main():
     accepted = int(sum(n_host))
     emitted = accepted + B
     attn_bytes = attention_algorithmic_bytes(batch)
-    samp_bytes = sampler_algorithmic_bytes(batch, n_host)
     esz = 4 if wl.dtype == "f32" else 2
-    samp_all_rows = (batch.total_q + batch.total_q - B) * wl.V * esz
+    if tree is not None:
+        samp_bytes = tree_sampler_algorithmic_bytes(batch, n_host, path.cpu().tolist())
+        samp_all_rows = 2 * batch.total_q * wl.V * esz
+    else:
+        samp_bytes = sampler_algorithmic_bytes(batch, n_host)
+        samp_all_rows = (batch.total_q + batch.total_q - B) * wl.V * esz
     achieved = attn_bytes / (ms_main * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name) if not changes else None
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name) if not changes and tree is None else None
 
     line = {
         "metric": "accepted tokens/s of the SD verify step (tokens emitted per step = accepted "
@@ -257,7 +340,10 @@ def main():
         "dtype": wl.dtype,
         "data": "synthetic",
         "config": {
-            "workload": wl.name, "B": B, "k": wl.k, "ragged_k": wl.ragged_k, "Hq": wl.Hq,
+            "workload": wl.name if tree is None else f"{wl.name}+tree{args.tree}",
+            "drafts": f"chain of k={wl.k}" if tree is None else
+                      f"tree: chain of {depth} nodes, {branch} candidates per position, {len(tree)} rows per sequence",
+            "B": B, "k": wl.k, "ragged_k": wl.ragged_k, "Hq": wl.Hq,
             "Hkv": wl.Hkv, "D": wl.D, "V": wl.V, "sigma": wl.sigma, "temperature": wl.temperature,
             "kv_len": f"{wl.len_dist}[{wl.len_lo},{wl.len_hi}]", "total_kv": batch.total_kv,
             "seed": wl.seed,
@@ -291,7 +377,8 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = run_cpu_baseline(batch, args.cpu_seqs)
+        line["cpu_baseline"] = (run_cpu_baseline_tree(batch, args.cpu_seqs) if tree is not None
+                                else run_cpu_baseline(batch, args.cpu_seqs))
     print(json.dumps(line))
 
 

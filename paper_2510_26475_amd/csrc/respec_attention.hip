@@ -380,31 +380,43 @@ __device__ inline void wait_at_least(LdsCounter flag, uint32_t need, bool &alive
 // written) and `consumed` (tiles the consumer has finished reading).  A wave's LDS operations
 // execute in order, so a counter written after the data (or after the last read) needs no
 // further fence.
-template <int D, int NT, typename OutT>
+//
+// CW ("column ways") = 2 is the form for wide column blocks (more than 32 query columns): the
+// accumulators of 64 columns do not fit a wave's registers, so two consumers share one range,
+// each with half of the columns, and the two producers of the range move its tiles in turn
+// (producer w the tiles j = w mod 2, each into its own ring).  A work-group then walks two
+// ranges instead of four.  Each consumer keeps its own `consumed`; a producer reuses a slot once
+// both have passed it.
+template <int D, int NT, typename OutT, int CW>
 __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnParams p) {
     using C = Bf16Cfg<D>;
+    static_assert(CW == 1 || CW == 2, "one or two consumers per range");
+    constexpr int kStreams = kConsumers / CW;     // ranges per work-group
     extern __shared__ __align__(16) char smem[];  // [kConsumers][kSlots][kWaveBytes] | counters
     const LdsCounter counters = (LdsCounter)(smem + kConsumers * kSlots * C::kWaveBytes);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform by construction
     const bool producer = wave >= kConsumers;
-    const int pair = producer ? wave - kConsumers : wave;
+    const int role = producer ? wave - kConsumers : wave;  // index among the producers / consumers
+    const int stream = role / CW, way = role % CW;
     const int c16 = lane & 15, g4 = lane >> 4;
-    const int u = blockIdx.x * kConsumers + pair;  // index of this pair in the split
-    const int col0 = blockIdx.y * kMaxColsPerBlock;
+    const int u = blockIdx.x * kStreams + stream;  // index of this range in the split
+    const int col0 = blockIdx.y * kMaxColsPerBlock + (producer ? 0 : way * NT * kColTile);
 
-    if (threadIdx.x < 2 * kConsumers) counters[threadIdx.x] = 0;
+    if (threadIdx.x < 3 * kConsumers) counters[threadIdx.x] = 0;
     __syncthreads();  // the only barrier, before any wave can leave
-    const LdsCounter filled = counters + pair;
-    const LdsCounter consumed = counters + kConsumers + pair;
+    // filled[r]: tiles producer r has written to its ring; consumed[r]: tiles of the range that
+    // consumer r has finished with; read_done[r]: tiles whose K and V consumer r has read (CW = 2)
+    const LdsCounter filled = counters;
+    const LdsCounter consumed = counters + kConsumers;
+    const LdsCounter read_done = counters + 2 * kConsumers;
 
-    if (u >= p.W) return;  // wave-uniform, and the same for both waves of a pair
+    if (u >= p.W) return;  // wave-uniform, and the same for all waves of a range
     const ConstPtr<int32_t> start = as_constant(reinterpret_cast<const int32_t *>(p.wave_start + u));
     const int n_tiles = start[3];
     if (n_tiles <= 0 || start[0] >= p.Hkv) return;
 
-    char *ring = smem + pair * (kSlots * C::kWaveBytes);
     const int32_t row_bytes = p.Hkv * D * 2;
     bool alive = true;
 
@@ -433,15 +445,24 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             row_off[j] = (uint32_t)(lane / C::kLanesPerRow + j * C::kRowsPerLoad) * (uint32_t)row_bytes +
                          (uint32_t)(lane % C::kLanesPerRow) * 16u;
         u32x4 kr[kSlots][C::kLoads], vr[kSlots][C::kLoads];
-        int requested = 0;
+        char *ring = smem + role * (kSlots * C::kWaveBytes);
+        // this producer moves the range's tiles way, way + CW, ...: `pos` is the tile the cursor
+        // points at, n_local the number of tiles that are this producer's
+        int pos = way;
+        const int n_local = (n_tiles - way + CW - 1) / CW;
         // Every step issues its tile requests, also when the range has no tile left: the count
         // of requests behind a buffer's own is then the same on every path, and the wait for a
         // buffer leaves exactly the younger ones in flight.  An idle request re-reads one
         // 256-byte piece of the last tile, which the caches hold.
         bool next_known = false;  // cp.nb / cp.nh / cp.nsi have been looked up
+        if (CW > 1 && way > 0 && way < n_tiles) {  // the second producer starts one tile in
+            cursor_find_next(p, cp);
+            next_known = true;
+            cursor_advance(p, cp);
+        }
         auto request = [&](auto S) __attribute__((always_inline)) {
             constexpr int s = decltype(S)::value;
-            const bool live = requested < n_tiles;
+            const bool live = pos < n_tiles;
             const int64_t tile_off = (cp.si.kv0 * p.Hkv + cp.h) * (int64_t)(D * 2) + (int64_t)(cp.t * kTileKeys) * row_bytes;
             const int rows_valid = live ? cp.si.L - 1 - cp.t * kTileKeys : 0;
             load_tile<D>(kr[s], static_cast<const char *>(p.k) + tile_off, row_bytes, row_off, rows_valid, lane);
@@ -451,27 +472,37 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                 next_known = true;
             }
             if (live) {
-                if (requested + 1 < n_tiles) cursor_advance(p, cp);
-                ++requested;
+                if (pos + CW < n_tiles) {
+#pragma unroll
+                    for (int c = 0; c < CW; ++c) cursor_advance(p, cp);
+                }
+                pos += CW;
             }
         };
+        // j: index among this producer's own tiles (tile CW * j + way of the range)
         auto move = [&](auto S, const int j) __attribute__((always_inline)) {
             constexpr int s = decltype(S)::value;
-            if (j < n_tiles) {
-                // slot s is free once tile j - 2 has been read
-                if (j >= kSlots) wait_at_least(consumed, (uint32_t)(j - kSlots + 1), alive, p.error_flag);
+            if (j < n_local) {
+                // slot s is free once every consumer of the range has finished with the tile
+                // that was in it, this producer's tile j - 2
+                if (j >= kSlots) {
+                    const uint32_t need = (uint32_t)(CW * (j - kSlots) + way + 1);
+#pragma unroll
+                    for (int c = 0; c < CW; ++c)
+                        wait_at_least(consumed + stream * CW + c, need, alive, p.error_flag);
+                }
                 asm volatile("" ::: "memory");
                 char *slot = ring + s * C::kWaveBytes;
                 store_tile<D>(kr[s], slot, lane);
                 store_tile<D>(vr[s], slot + C::kTileBytes, lane);
                 asm volatile("" ::: "memory");
-                *filled = (uint32_t)(j + 1);
+                filled[role] = (uint32_t)(j + 1);
             }
             request(S);
         };
         request(Const<0>{});
         request(Const<1>{});
-        for (int j = 0; j < n_tiles; j += kSlots) {
+        for (int j = 0; j < n_local; j += kSlots) {
             move(Const<0>{}, j);
             move(Const<1>{}, j + 1);
         }
@@ -527,7 +558,9 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     for (int idx = 0; idx < n_tiles; ++idx) {
         const int key0 = cp.t * kTileKeys;
         const int kvh = cp.h;
-        char *k_lds = ring + (idx % kSlots) * C::kWaveBytes;
+        // tile idx of the range is tile idx / CW of producer idx % CW of this range
+        const int src = stream * CW + idx % CW;
+        char *k_lds = smem + src * (kSlots * C::kWaveBytes) + ((idx / CW) % kSlots) * C::kWaveBytes;
         char *v_lds = k_lds + C::kTileBytes;
         if (idx == 0 || cp.t == 0) {  // a segment begins
             seg_t_first = cp.t;
@@ -555,7 +588,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             }
         }
 
-        wait_at_least(filled, (uint32_t)(idx + 1), alive, p.error_flag);
+        wait_at_least(filled + src, (uint32_t)(idx / CW + 1), alive, p.error_flag);
         asm volatile("" ::: "memory");
 
         // S^T[key, col] = sum_d K[key, d] Q[col, d]; two 16-key sub-tiles
@@ -676,22 +709,32 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             // for column c16 of each column tile, d = kEpl * (4 g4 + r) + t in acc_o[nt][t][r]:
             // written out like that, every store would scatter 16-byte pieces over 64 rows.
             // The columns go through the ring slot of the tile just finished (still owned by
-            // this wave) instead, 32 at a time, and leave it as whole rows.
+            // the consumers of the range) instead, 32 at a time, and leave it as whole rows.
+            // Two consumers that share the range take half of the slot each, 16 columns at a
+            // time, once both have read the tile.
             const bool whole = seg_t_first == 0 && cp.t == cp.si.tiles - 1;
             const int64_t slot = 2 * (int64_t)u + (seg_t_first > 0 ? 0 : 1);
             // (the staging reuses memory that other code reads and writes as 32-bit integer
             // vectors: keep the compiler from moving either across the borders of this block;
             // the hardware runs a wave's LDS operations in order)
             asm volatile("" ::: "memory");
-            float *stage = reinterpret_cast<float *>(k_lds);  // [32][kMergeStride]
-            float *stat = stage + 32 * C::kMergeStride;       // [32]: max, sum, output row, largest magnitude
+            if constexpr (CW > 1) {
+                read_done[role] = (uint32_t)(idx + 1);
+                wait_at_least(read_done + (role ^ 1), (uint32_t)(idx + 1), alive, p.error_flag);
+                asm volatile("" ::: "memory");
+            }
+            constexpr int kTilesPerPass = 2 / CW;             // column tiles staged together
+            constexpr int kStageCols = kTilesPerPass * kColTile;
+            float *stage = reinterpret_cast<float *>(k_lds + (CW > 1 ? way * C::kTileBytes : 0));  // [kStageCols][kMergeStride]
+            float *stat = stage + kStageCols * C::kMergeStride;  // [kStageCols]: max, sum, output row, largest magnitude
+            static_assert((kStageCols * C::kMergeStride + kStageCols * 4) * 4 <= C::kWaveBytes / CW, "staging fits its share of a slot");
             constexpr int kLanesPerOutRow = D / 4;            // lanes that cover a row, 4 floats each
             constexpr int kRowsPerPass = 64 / kLanesPerOutRow;
 #pragma unroll
-            for (int pp = 0; pp < (NT + 1) / 2; ++pp) {
+            for (int pp = 0; pp < (NT + kTilesPerPass - 1) / kTilesPerPass; ++pp) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int nt = 2 * pp + h;
+                for (int h = 0; h < kTilesPerPass; ++h) {
+                    const int nt = kTilesPerPass * pp + h;
                     if (nt < NT) {
                         const float lt = sum_across_rows(l_run[nt < NT ? nt : 0]);
                         float *row = stage + (h * kColTile + c16) * C::kMergeStride;
@@ -720,9 +763,9 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                         }
                     }
                 }
-                const int n_cols = (NT - 2 * pp) >= 2 ? 32 : 16;  // columns staged in this pass
+                const int n_cols = (NT - kTilesPerPass * pp) >= kTilesPerPass ? kStageCols : kColTile;  // columns staged in this pass
 #pragma unroll
-                for (int it = 0; it < 32 / kRowsPerPass; ++it) {
+                for (int it = 0; it < kStageCols / kRowsPerPass; ++it) {
                     if (it * kRowsPerPass >= n_cols) break;
                     const int cl = it * kRowsPerPass + lane / kLanesPerOutRow;
                     const int d4 = (lane % kLanesPerOutRow) * 4;
@@ -741,7 +784,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                             if (p.lse && d4 == 0)
                                 p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
                         } else {
-                            const int64_t prow = slot * p.Mpad + col0 + pp * 32 + cl;
+                            const int64_t prow = slot * p.Mpad + col0 + pp * kStageCols + cl;
                             // A partial is written as 16-bit fixed point relative to the row's
                             // largest magnitude (error below 2^-16 of it, far under the bf16
                             // rounding of the output): stores into a stream of reads cost several
@@ -764,7 +807,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
         }
         // every read of the slot has been issued: hand it back
         asm volatile("" ::: "memory");
-        *consumed = (uint32_t)(idx + 1);
+        consumed[role] = (uint32_t)(idx + 1);
         if (idx + 1 < n_tiles) cursor_advance(p, cp);
     }
 }
@@ -1001,28 +1044,30 @@ int compute_units() {
     return cached[dev];
 }
 
-template <int D, int NT>
+template <int D, int NT, int CW>
 hipError_t launch_bf16(const AttnParams &p, dim3 grid, hipStream_t stream) {
     using C = Bf16Cfg<D>;
-    const size_t smem = (size_t)kConsumers * kSlots * C::kWaveBytes + 2 * kConsumers * sizeof(uint32_t);
+    const size_t smem = (size_t)kConsumers * kSlots * C::kWaveBytes + 3 * kConsumers * sizeof(uint32_t);
     static bool configured = false;  // benign race: the attribute is idempotent
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, NT, uint16_t>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, NT, uint16_t, CW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((attn_bf16_kernel<D, NT, uint16_t>), grid, dim3(2 * kConsumers * 64), smem, stream, p);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, NT, uint16_t, CW>), grid, dim3(2 * kConsumers * 64), smem, stream, p);
     return hipGetLastError();
 }
 
+// nt: column tiles of a column block; cw: consumers that share a range
 template <int D>
-hipError_t launch_bf16_nt(int nt, const AttnParams &p, dim3 grid, hipStream_t stream) {
+hipError_t launch_bf16_nt(int nt, int cw, const AttnParams &p, dim3 grid, hipStream_t stream) {
+    if (cw == 2) return launch_bf16<D, 2, 2>(p, grid, stream);
     switch (nt) {
-        case 1: return launch_bf16<D, 1>(p, grid, stream);
-        case 2: return launch_bf16<D, 2>(p, grid, stream);
-        case 3: return launch_bf16<D, 3>(p, grid, stream);
-        default: return launch_bf16<D, 4>(p, grid, stream);
+        case 1: return launch_bf16<D, 1, 1>(p, grid, stream);
+        case 2: return launch_bf16<D, 2, 1>(p, grid, stream);
+        case 3: return launch_bf16<D, 3, 1>(p, grid, stream);
+        default: return launch_bf16<D, 4, 1>(p, grid, stream);
     }
 }
 
@@ -1149,14 +1194,23 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     const int col_blocks = (M + kMaxColsPerBlock - 1) / kMaxColsPerBlock;
     const int cols = col_blocks == 1 ? M : kMaxColsPerBlock;
     const int nt = (cols + kColTile - 1) / kColTile;
-    // the split width: one wave per SIMD of the device (RESPEC_ATTN_WGS overrides it, for tests
-    // and sweeps)
+    // a column block of four column tiles at D = 128 is more than one wave's registers hold
+    // (400 bytes of spills per lane, measured 1.5x slower): two consumers share each range then.
+    // Three tiles still run faster with one consumer per range and a few spills.
+    // RESPEC_ATTN_WIDE = 0 / 1 overrides the choice for any block of more than two tiles (tests,
+    // comparisons).
+    const long wide = env_long("RESPEC_ATTN_WIDE", -1);
+    const int cw = nt > 2 && (wide < 0 ? (D == 128 && nt == 4) : wide != 0) ? 2 : 1;
+    const int streams = kConsumers / cw;  // ranges per work-group
+    // the split width: one range per consumer (or pair of consumers) of the device
+    // (RESPEC_ATTN_WGS overrides it, for tests and sweeps)
     long W = env_long("RESPEC_ATTN_WGS", 0);
-    if (W <= 0) W = (long)kConsumers * compute_units() / col_blocks;
+    if (W <= 0) W = (long)streams * compute_units() / col_blocks;
     if (W < 1) W = 1;
     if (W > kMaxWaves) W = kMaxWaves;
     p.W = (int32_t)W;
     int hi = Hkv % 4 == 0 ? 4 : (Hkv % 2 == 0 ? 2 : 1);
+    if (hi > streams) hi = streams;
     if (W % hi != 0 || env_long("RESPEC_ATTN_HEAD_MAJOR", 0) != 0) hi = 1;
     p.HI = hi;
 
@@ -1168,8 +1222,8 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
         (void)hipEventRecord(g_mark_before_main, stream);
         g_mark_before_main = nullptr;
     }
-    const dim3 grid((unsigned)((W + kConsumers - 1) / kConsumers), (unsigned)col_blocks);
-    err = D == 128 ? launch_bf16_nt<128>(nt, p, grid, stream) : launch_bf16_nt<64>(nt, p, grid, stream);
+    const dim3 grid((unsigned)((W + streams - 1) / streams), (unsigned)col_blocks);
+    err = D == 128 ? launch_bf16_nt<128>(nt, cw, p, grid, stream) : launch_bf16_nt<64>(nt, cw, p, grid, stream);
     if (err != hipSuccess)
         return fail(RESPEC_ERR_HIP, "verify_attention: main launch failed: %s", hipGetErrorString(err));
     if (g_mark_after_main) {

@@ -12,6 +12,23 @@ from paper_2510_26475_amd import binding, synth
 
 
 @contextmanager
+def env_setting(name, value):
+    """Set (or, with None, unset) one environment knob of the library for the duration."""
+    old = os.environ.get(name)
+    if value is None:
+        os.environ.pop(name, None)
+    else:
+        os.environ[name] = str(value)
+    try:
+        yield
+    finally:
+        if old is None:
+            os.environ.pop(name, None)
+        else:
+            os.environ[name] = old
+
+
+@contextmanager
 def attn_wgs(wgs):
     """Force the number of ranges the key tiles are split over (None = the default, four per
     compute unit).  Small counts put many sequences in one range, large counts cut every

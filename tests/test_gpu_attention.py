@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import attn_wgs, gpu_attention, oracle_attention, sub_batch
+from helpers import attn_wgs, env_setting, gpu_attention, oracle_attention, sub_batch
 from paper_2510_26475_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -88,6 +88,26 @@ def test_bf16_draft_lengths_14b_heads(oracle, k):
 def test_more_than_64_columns_uses_two_column_blocks(oracle):
     wl = _wl("bf16_wide", 16, 2, 128, "bf16")            # G = 8, k = 8 -> 72 columns
     _run(oracle, wl, [400, 90, 1025], [8, 8, 5], seed=31, wgs=11)
+
+
+@pytest.mark.parametrize("wgs", [None, 1, 2, 3, 7, 64, 500])
+@pytest.mark.parametrize("heads", [(28, 4, 6), (28, 4, 8), (40, 8, 8), (16, 2, 8), (7, 1, 5)])
+def test_wide_column_blocks_share_a_range_between_two_consumers(oracle, heads, wgs):
+    # 33..72 MFMA columns at D = 128: two consumers per range, each with half of the columns
+    Hq, Hkv, k = heads
+    wl = _wl("bf16_two_way", Hq, Hkv, 128, "bf16")
+    lens = [33, 130, 257, 1000, 9, 10, 128, 129, 2049, 64, 65]
+    ks = [k, k, 0, k, k, k - 1, 1, 2, k, k, 3]
+    _run(oracle, wl, lens, ks, seed=Hq + k + (wgs or 0), wgs=wgs)
+
+
+@pytest.mark.parametrize("wide", [0, 1])
+@pytest.mark.parametrize("D", [64, 128])
+def test_both_forms_of_a_wide_column_block_agree_with_the_oracle(oracle, D, wide):
+    wl = _wl("bf16_forms", 40, 8, D, "bf16")            # G = 5, k = 8 -> 45 columns
+    with env_setting("RESPEC_ATTN_WIDE", wide):
+        _run(oracle, wl, [700, 9, 1300, 12, 4096, 257], [8, 8, 8, 7, 8, 8], seed=50 + D + wide)
+        _run(oracle, wl, [700, 9, 1300, 12, 4096, 257], [8, 8, 8, 7, 8, 8], seed=60 + D + wide, wgs=13)
 
 
 def test_ragged_draft_lengths_in_one_batch(oracle):
