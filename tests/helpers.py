@@ -228,3 +228,23 @@ def compare_tree_sampler(gpu, ref):
         f"tokens={r_t[bad[0]].tolist()} path={r_p[bad[0]].tolist()}")
     return {"flagged": int(flagged.sum()), "flagged_mismatch": int((~same & flagged).sum()),
             "gpu_flagged": int((g_f != 0).sum()), "B": int(len(r_n))}
+
+
+def sub_tree_batch(tb: synth.TreeBatch, seqs) -> synth.TreeBatch:
+    """The sequences ``seqs`` of a tree batch as a batch of their own (attention inputs only)."""
+    qi, ki = tb.q_indptr.cpu().tolist(), tb.kv_indptr.cpu().tolist()
+    q_rows = [r for b in seqs for r in range(qi[b], qi[b + 1])]
+    kv_rows = [r for b in seqs for r in range(ki[b], ki[b + 1])]
+    dev = tb.q.device
+    qr = torch.tensor(q_rows, device=dev, dtype=torch.long)
+    kr = torch.tensor(kv_rows, device=dev, dtype=torch.long)
+    pars = [tb.parents_per_seq[b] for b in seqs]
+    lens = [tb.kv_lens[b] for b in seqs]
+    return synth.TreeBatch(
+        wl=tb.wl, q=tb.q[qr].contiguous(), k_cache=tb.k_cache[kr].contiguous(), v_cache=tb.v_cache[kr].contiguous(),
+        q_indptr=torch.tensor(np.concatenate([[0], np.cumsum([len(p) for p in pars])]), dtype=torch.int32, device=dev),
+        kv_indptr=torch.tensor(np.concatenate([[0], np.cumsum(lens)]), dtype=torch.int64, device=dev),
+        parent=tb.parent[qr].contiguous(), tree_mask=tb.tree_mask[qr].contiguous(),
+        target_logits=tb.target_logits[:0], draft_logits=tb.draft_logits[:0], node_tokens=tb.node_tokens[qr].contiguous(),
+        u_accept=tb.u_accept[qr].contiguous(), u_final=tb.u_final[torch.tensor(list(seqs), device=dev)].contiguous(),
+        parents_per_seq=pars, kv_lens=lens)

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import attn_wgs, gpu_attention, gpu_tree_attention, oracle_tree_attention
+from helpers import attn_wgs, gpu_attention, gpu_tree_attention, oracle_tree_attention, sub_tree_batch
 from paper_2510_26475_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -93,6 +93,21 @@ def test_wide_trees_use_two_column_blocks(oracle):
     out, lse = gpu_tree_attention(tb)
     ref, ref_lse = oracle_tree_attention(oracle, tb)
     _check(out, lse, ref, ref_lse, "bf16")
+
+
+def test_headline_tree_workload_sampled_sequences(oracle):
+    """B=256, 28/4 heads, a chain of 3 nodes with 2 candidates per position (49 columns) in the
+    launch configuration the benchmark times; the oracle checks a sample of sequences."""
+    wl = synth.WORKLOADS["qwen7b_b256_k3"]
+    tb = synth.make_tree_batch(wl, [synth.caterpillar_parents(3, 2)] * wl.B, device="cuda", with_logits=False)
+    out, lse = gpu_tree_attention(tb)
+    assert torch.isfinite(out.float()).all()
+    seqs = sorted(set([int(np.argmax(tb.kv_lens)), int(np.argmin(tb.kv_lens)), 0, 50, 101, 199, 255]))
+    sb = sub_tree_batch(tb, seqs)
+    ref, ref_lse = oracle_tree_attention(oracle, sb)
+    qi = tb.q_indptr.tolist()
+    rows = torch.tensor([r for b in seqs for r in range(qi[b], qi[b + 1])], device="cuda")
+    _check(out[rows], lse[rows], ref, ref_lse, "bf16")
 
 
 def test_more_than_64_rows_is_refused():

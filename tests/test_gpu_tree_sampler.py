@@ -152,6 +152,17 @@ def test_chi_square_emitted_marginal_is_target_on_gpu(oracle):
     assert n.mean() > alpha1 + 0.01
 
 
+def test_headline_tree_workload_full_batch(oracle):
+    """B=256, V=151936 bf16, a chain of 3 nodes with 2 candidates per position, in the launch
+    configuration the benchmark times; the oracle walks the whole batch."""
+    wl = synth.WORKLOADS["qwen7b_b256_k3"]
+    tb = synth.make_tree_batch(wl, [synth.caterpillar_parents(3, 2)] * wl.B, device="cuda", with_attention=False)
+    gpu, ref, tally = _parity(oracle, tb)
+    emitted = float((ref[2] + 1).mean())
+    assert 2.2 < emitted < 2.9, emitted           # two candidates per position beat the chain's 2.27
+    print("tree sampler tally", tally, "emitted/seq", emitted)
+
+
 def test_bad_arguments_are_rejected_before_any_launch():
     wl = _wl("tree_err", 1024, "f32")
     tb = _batch(wl, [[-1, 0, 0], [-1, 0]], seed=1)
