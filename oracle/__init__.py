@@ -57,6 +57,15 @@ def _load():
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
             c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_double, c.c_int, c.c_int]
+        lib.respec_oracle_verify_attention_paged.restype = c.c_int
+        lib.respec_oracle_verify_attention_paged.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_double, c.c_int, c.c_int]
+        lib.respec_oracle_commit_accepted_paged.restype = c.c_int
+        lib.respec_oracle_commit_accepted_paged.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int]
         lib.respec_oracle_softmax_rows.restype = c.c_int
         lib.respec_oracle_softmax_rows.argtypes = [
             c.c_void_p, c.c_int32, c.c_int32, c.c_int64, c.c_double, c.c_int, c.c_void_p]
@@ -127,6 +136,64 @@ def verify_attention_tree(q, k_cache, v_cache, q_indptr, kv_indptr, tree_mask, H
     if rc != 0:
         raise RuntimeError(f"respec_oracle_verify_attention_tree failed with code {rc}")
     return (out, lse) if want_lse else out
+
+
+def verify_attention_paged(q, k_pages, v_pages, q_indptr, page_indptr, page_table, kv_len, Hq, Hkv, D,
+                           sm_scale, dtype, tree_mask=None, want_lse=False, n_threads=1):
+    """k_pages, v_pages [num_pages, page_size, Hkv, D]; sequence b owns the pages
+    page_table[page_indptr[b]:page_indptr[b+1]] in token order and holds kv_len[b] tokens."""
+    q = _check_elems(q, dtype, "q")
+    k_pages = _check_elems(k_pages, dtype, "k_pages")
+    v_pages = _check_elems(v_pages, dtype, "v_pages")
+    assert k_pages.ndim == 4 and k_pages.shape == v_pages.shape and k_pages.shape[2:] == (Hkv, D)
+    num_pages, page_size = k_pages.shape[:2]
+    q_indptr = np.ascontiguousarray(q_indptr, dtype=np.int32)
+    page_indptr = np.ascontiguousarray(page_indptr, dtype=np.int32)
+    page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+    kv_len = np.ascontiguousarray(kv_len, dtype=np.int32)
+    B = q_indptr.shape[0] - 1
+    total_q = int(q_indptr[-1])
+    assert page_indptr.shape == (B + 1,) and kv_len.shape == (B,) and page_table.shape[0] >= int(page_indptr[-1])
+    if tree_mask is not None:
+        tree_mask = np.ascontiguousarray(tree_mask, dtype=np.uint64)
+        assert tree_mask.shape == (total_q,)
+    out = np.zeros((total_q, Hq, D), dtype=np.float64)
+    lse = np.zeros((total_q, Hq), dtype=np.float64) if want_lse else None
+    rc = _load().respec_oracle_verify_attention_paged(
+        _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(q_indptr), _ptr(page_indptr), _ptr(page_table),
+        _ptr(kv_len), _ptr(tree_mask), _ptr(out), _ptr(lse), B, num_pages, page_size, Hq, Hkv, D,
+        float(sm_scale), dtype, n_threads)
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_verify_attention_paged failed with code {rc}")
+    return (out, lse) if want_lse else out
+
+
+def commit_accepted_paged(k_pages, v_pages, q_indptr, page_indptr, page_table, kv_len, num_accepted, dtype,
+                          path=None):
+    """Moves the K/V of the accepted rows behind the last committed token and cuts the lengths.
+    k_pages, v_pages and kv_len are changed IN PLACE (they must be C-contiguous arrays of the right type)."""
+    want = np.float32 if dtype == F32 else np.uint16
+    for a, name in ((k_pages, "k_pages"), (v_pages, "v_pages")):
+        if a.dtype != want or not a.flags["C_CONTIGUOUS"]:
+            raise TypeError(f"{name} must be a C-contiguous {want.__name__} array")
+    if kv_len.dtype != np.int32 or not kv_len.flags["C_CONTIGUOUS"]:
+        raise TypeError("kv_len must be a C-contiguous int32 array")
+    num_pages, page_size, Hkv, D = k_pages.shape
+    q_indptr = np.ascontiguousarray(q_indptr, dtype=np.int32)
+    page_indptr = np.ascontiguousarray(page_indptr, dtype=np.int32)
+    page_table = np.ascontiguousarray(page_table, dtype=np.int32)
+    num_accepted = np.ascontiguousarray(num_accepted, dtype=np.int32)
+    B = q_indptr.shape[0] - 1
+    stride = 0
+    if path is not None:
+        path = np.ascontiguousarray(path, dtype=np.int32)
+        assert path.ndim == 2 and path.shape[0] == B
+        stride = path.shape[1]
+    rc = _load().respec_oracle_commit_accepted_paged(
+        _ptr(k_pages), _ptr(v_pages), _ptr(q_indptr), _ptr(page_indptr), _ptr(page_table), _ptr(kv_len),
+        _ptr(path), stride, _ptr(num_accepted), B, num_pages, page_size, Hkv, D, dtype)
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_commit_accepted_paged failed with code {rc}")
 
 
 def tree_rejection_sample(target_logits, draft_logits, node_tokens, parent, q_indptr, u_accept,

@@ -21,6 +21,11 @@
  *   tree attention -- the chain mask reproduces the chain function bit for bit, dense
  *                 numpy with an explicit visibility matrix, invariance of a row to
  *                 nodes off its path.
+ *   paged attention / commit -- dense numpy over a cache gathered by the test's own
+ *                 indexing, invariance to a permutation of the physical pages and to
+ *                 the page size, poisoned unused slots, a chain commit equals cutting
+ *                 the length, a committed tree path attends like a cache built from
+ *                 the accepted tokens only.
  *   tree sampler -- a chain-shaped tree reproduces the chain function exactly, a
  *                 hand-worked case (tests/golden/tree_hand_case.json), chi-square of
  *                 the emitted token against p with three sibling candidates, the
@@ -208,6 +213,118 @@ int respec_oracle_verify_attention_tree(const void *q, const void *k_cache, cons
         return ORACLE_ERR_ARG;
     return verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, B, Hq, Hkv, D,
                                 sm_scale, dtype, n_threads, tree_mask);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Paged KV cache (the cache the serving side manages, Sections 4.2 and 4.3;   */
+/* the paper fixes no layout).  K and V live in pages of page_size tokens,     */
+/* [num_pages, page_size, Hkv, D]; sequence b owns the page ids                */
+/* page_table[page_indptr[b] .. page_indptr[b+1]) in token order and holds     */
+/* kv_len[b] tokens (the R_b new ones included).  Attention over it is the     */
+/* plain definition applied to the sequence's tokens gathered in order.        */
+/* ------------------------------------------------------------------------- */
+static size_t elem_bytes(int dtype) { return dtype == ORACLE_F32 ? 4u : 2u; }
+
+int respec_oracle_verify_attention_paged(const void *q, const void *k_pages, const void *v_pages,
+                                         const int32_t *q_indptr, const int32_t *page_indptr,
+                                         const int32_t *page_table, const int32_t *kv_len,
+                                         const uint64_t *tree_mask, double *out, double *lse,
+                                         int32_t B, int32_t num_pages, int32_t page_size,
+                                         int32_t Hq, int32_t Hkv, int32_t D, double sm_scale,
+                                         int dtype, int n_threads)
+{
+    if (!q || !k_pages || !v_pages || !q_indptr || !page_indptr || !page_table || !kv_len || !out)
+        return ORACLE_ERR_ARG;
+    if (B <= 0 || num_pages <= 0 || page_size <= 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv != 0)
+        return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16)
+        return ORACLE_ERR_ARG;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t R = q_indptr[b + 1] - q_indptr[b];
+        const int64_t pages = page_indptr[b + 1] - page_indptr[b];
+        if (R < 1 || kv_len[b] < R || (int64_t)kv_len[b] > pages * page_size || (tree_mask && R > 64))
+            return ORACLE_ERR_DATA;
+        for (int64_t i = 0; i * page_size < kv_len[b]; ++i) {
+            const int32_t pg = page_table[page_indptr[b] + i];
+            if (pg < 0 || pg >= num_pages)
+                return ORACLE_ERR_DATA;
+        }
+    }
+    int status = ORACLE_OK;
+    const size_t tok_bytes = (size_t)Hkv * D * elem_bytes(dtype);
+    const int nt = pick_threads(n_threads);
+    (void)nt;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nt)
+    for (int32_t b = 0; b < B; ++b) {
+        const int64_t L = kv_len[b];
+        char *kseq = (char *)malloc((size_t)L * tok_bytes);
+        char *vseq = (char *)malloc((size_t)L * tok_bytes);
+        int rc = ORACLE_OK;
+        if (!kseq || !vseq) {
+            rc = ORACLE_ERR_ALLOC;
+        } else {
+            for (int64_t j = 0; j < L; ++j) { /* token j lives in slot j % page_size of page j / page_size */
+                const int64_t pg = page_table[page_indptr[b] + j / page_size];
+                const size_t src = ((size_t)pg * page_size + (size_t)(j % page_size)) * tok_bytes;
+                memcpy(kseq + (size_t)j * tok_bytes, (const char *)k_pages + src, tok_bytes);
+                memcpy(vseq + (size_t)j * tok_bytes, (const char *)v_pages + src, tok_bytes);
+            }
+            rc = attention_one_sequence(q, kseq, vseq, q_indptr[b], q_indptr[b + 1] - q_indptr[b], 0, L,
+                                        out, lse, Hq, Hkv, D, sm_scale, dtype, tree_mask);
+        }
+        free(kseq);
+        free(vseq);
+        if (rc != ORACLE_OK) {
+#pragma omp critical
+            status = rc;
+        }
+    }
+    return status;
+}
+
+/* After validation (Section 2.2) the accepted drafts become part of the sequence and the rest
+ * of the speculative tokens are dropped.  The new tokens of sequence b sit at positions
+ * first_new + r (r = their row, first_new = kv_len[b] - R_b; row 0 is the last committed
+ * token).  The accepted nodes are rows path[0] < path[1] < ... (a chain: 1, 2, ..., n_b; pass
+ * path == NULL): the K/V of row path[j] moves to position first_new + 1 + j, and the length
+ * becomes first_new + 1 + n_b.  The token drawn last has no K/V yet.  k_pages and v_pages are
+ * changed in place; positions at or beyond the new length keep whatever they held. */
+int respec_oracle_commit_accepted_paged(void *k_pages, void *v_pages, const int32_t *q_indptr,
+                                        const int32_t *page_indptr, const int32_t *page_table,
+                                        int32_t *kv_len, const int32_t *path, int32_t path_stride,
+                                        const int32_t *num_accepted, int32_t B, int32_t num_pages,
+                                        int32_t page_size, int32_t Hkv, int32_t D, int dtype)
+{
+    if (!k_pages || !v_pages || !q_indptr || !page_indptr || !page_table || !kv_len || !num_accepted)
+        return ORACLE_ERR_ARG;
+    if (B <= 0 || num_pages <= 0 || page_size <= 0 || Hkv <= 0 || D <= 0 || (path && path_stride < 1))
+        return ORACLE_ERR_ARG;
+    const size_t tok_bytes = (size_t)Hkv * D * elem_bytes(dtype);
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t R = q_indptr[b + 1] - q_indptr[b];
+        const int32_t n = num_accepted[b];
+        const int64_t first_new = (int64_t)kv_len[b] - R;
+        if (R < 1 || first_new < 0 || n < 0 || n > R - 1 || (path && n > path_stride))
+            return ORACLE_ERR_DATA;
+        for (int32_t j = 0; j < n; ++j) {
+            const int32_t r = path ? path[(int64_t)b * path_stride + j] : j + 1;
+            if (r < j + 1 || r >= R || (j > 0 && path && r <= path[(int64_t)b * path_stride + j - 1]))
+                return ORACLE_ERR_DATA;
+            const int64_t from = first_new + r, to = first_new + 1 + j;
+            if (from == to)
+                continue;
+            const int64_t pf = page_table[page_indptr[b] + from / page_size];
+            const int64_t pt = page_table[page_indptr[b] + to / page_size];
+            if (pf < 0 || pf >= num_pages || pt < 0 || pt >= num_pages)
+                return ORACLE_ERR_DATA;
+            const size_t src = ((size_t)pf * page_size + (size_t)(from % page_size)) * tok_bytes;
+            const size_t dst = ((size_t)pt * page_size + (size_t)(to % page_size)) * tok_bytes;
+            memmove((char *)k_pages + dst, (const char *)k_pages + src, tok_bytes);
+            memmove((char *)v_pages + dst, (const char *)v_pages + src, tok_bytes);
+        }
+        kv_len[b] = (int32_t)(first_new + 1 + n);
+    }
+    return ORACLE_OK;
 }
 
 /* ------------------------------------------------------------------------- */

@@ -417,3 +417,47 @@ def to_host_array(t: torch.Tensor):
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view(np.uint16)
     return t.numpy()
+
+
+@dataclass
+class PagedKV:
+    """A KV cache cut into pages of ``page_size`` tokens (layout only, no arithmetic)."""
+    k_pages: torch.Tensor       # [num_pages, page_size, Hkv, D]
+    v_pages: torch.Tensor
+    page_indptr: torch.Tensor   # [B+1] int32: pages of sequence b in page_table
+    page_table: torch.Tensor    # [sum pages] int32 physical page ids, token order within a sequence
+    kv_len: torch.Tensor        # [B] int32 tokens held by sequence b
+    page_size: int
+
+    @property
+    def num_pages(self) -> int:
+        return int(self.k_pages.shape[0])
+
+
+def paginate(k_cache: torch.Tensor, v_cache: torch.Tensor, kv_lens: Sequence[int], page_size: int,
+             seed: int = 0, spare_pages: int = 3, extra_pages_per_seq: int = 0, poison: bool = True) -> PagedKV:
+    """Scatters a contiguous cache [total_kv, Hkv, D] into pages handed out in a seeded random
+    order (plus ``spare_pages`` owned by nobody and ``extra_pages_per_seq`` allocated but unused
+    pages behind every sequence).  With ``poison`` every slot no token lives in holds NaN."""
+    dev = k_cache.device
+    gen = torch.Generator(device="cpu").manual_seed(seed + 77)
+    pages_per_seq = [(int(L) + page_size - 1) // page_size + extra_pages_per_seq for L in kv_lens]
+    total_pages = sum(pages_per_seq)
+    num_pages = total_pages + spare_pages
+    order = torch.randperm(num_pages, generator=gen)[:total_pages].to(torch.int32)
+    page_indptr = torch.tensor(_np.concatenate([[0], _np.cumsum(pages_per_seq)]), dtype=torch.int32)
+    shape = (num_pages, page_size) + tuple(k_cache.shape[1:])
+    fill = float("nan") if poison else 0.0
+    k_pages = torch.full(shape, fill, dtype=k_cache.dtype, device=dev)
+    v_pages = torch.full(shape, fill, dtype=v_cache.dtype, device=dev)
+    # destination slot (page * page_size + offset) of every cached token
+    dst = []
+    for b, L in enumerate(kv_lens):
+        j = torch.arange(int(L), dtype=torch.int64)
+        pg = order[int(page_indptr[b]) + j // page_size].to(torch.int64)
+        dst.append(pg * page_size + j % page_size)
+    dst = torch.cat(dst).to(dev)
+    k_pages.view((num_pages * page_size,) + tuple(k_cache.shape[1:]))[dst] = k_cache
+    v_pages.view((num_pages * page_size,) + tuple(v_cache.shape[1:]))[dst] = v_cache
+    return PagedKV(k_pages=k_pages, v_pages=v_pages, page_indptr=page_indptr.to(dev), page_table=order.to(dev),
+                   kv_len=torch.tensor([int(L) for L in kv_lens], dtype=torch.int32, device=dev), page_size=page_size)
