@@ -11,8 +11,9 @@
  *   respec_verify_attention   the attention of that forward: (k_b+1) causal query rows per
  *                             sequence, grouped-query heads, ragged per-sequence KV cache;
  *   respec_rejection_sample   Eq. 1 / Eq. 2 over the vocabulary with supplied uniforms;
- * and their counterparts for a tree of drafts (Section 3.1), respec_verify_attention_tree
- * and respec_tree_rejection_sample.
+ * their counterparts for a tree of drafts (Section 3.1), respec_verify_attention_tree and
+ * respec_tree_rejection_sample, and the paged-cache forms respec_verify_attention_paged and
+ * respec_commit_accepted_paged.
  *
  * General rules
  *   - Every data pointer is a DEVICE pointer (HIP global memory) unless it says "host".
@@ -124,6 +125,64 @@ respec_status_t respec_verify_attention_tree(const void *q, const void *k_cache,
                                              int32_t Hkv, int32_t D, float sm_scale,
                                              respec_dtype_t dt, void *workspace,
                                              size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Verify attention over a paged KV cache (the cache the serving side manages while it moves
+ * sequences between speculative and plain decoding, Sections 4.2 and 4.3; the paper fixes no
+ * layout, this one is the library's).  The result is that of respec_verify_attention (or, with
+ * a tree_mask, of respec_verify_attention_tree) on the sequence's tokens taken in order:
+ * token j of sequence b lives in slot j % page_size of page
+ * page_table[page_indptr[b] + j / page_size].
+ *
+ *   k_pages, v_pages [num_pages, page_size, Hkv, D] dt, 16-byte aligned
+ *   page_indptr   [B+1] int32: the entries of page_table that belong to sequence b
+ *   page_table    [page_table_len] int32 page ids in [0, num_pages), token order per sequence;
+ *                 a sequence may own more pages than it uses
+ *   kv_len        [B] int32: L_b, tokens held by sequence b, the R_b new ones included
+ *                 (L_b <= page_size * pages of b; larger values are cut to that)
+ *   tree_mask     [total_q] uint64 or NULL (chain)
+ *   page_size     a power of two in [16, 1024] (RESPEC_ERR_UNSUPPORTED otherwise)
+ *   workspace     respec_verify_attention_workspace_bytes(B, total_q, num_pages*page_size, ...)
+ * Everything else as respec_verify_attention.  Page ids outside [0, num_pages) are a caller
+ * error; they are clamped, so they cannot cause an access outside the pools.
+ */
+respec_status_t respec_verify_attention_paged(const void *q, const void *k_pages, const void *v_pages,
+                                              const int32_t *q_indptr, const int32_t *page_indptr,
+                                              const int32_t *page_table, const int32_t *kv_len,
+                                              const uint64_t *tree_mask, void *out, float *lse,
+                                              int32_t B, int32_t total_q, int32_t num_pages,
+                                              int32_t page_table_len, int32_t page_size,
+                                              int32_t max_q_per_seq, int32_t max_kv_len, int32_t Hq,
+                                              int32_t Hkv, int32_t D, float sm_scale,
+                                              respec_dtype_t dt, void *workspace,
+                                              size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Commit of a verify step in a paged cache (Section 2.2, "Validation": accepted drafts are
+ * kept, the rest of the speculative tokens are dropped; Section 4.3: sequences move between
+ * speculative and plain decoding with their cache in place).  Before the call sequence b holds
+ * kv_len[b] tokens of which the last R_b are the new ones, row r at position
+ * first_new + r (first_new = kv_len[b] - R_b; row 0 is the last committed token).  With
+ * n_b = num_accepted[b] accepted nodes, rows path[b, 0] < path[b, 1] < ... (path == NULL: a
+ * chain, rows 1..n_b), the K/V of row path[b, j] is moved to position first_new + 1 + j and
+ * kv_len[b] becomes first_new + 1 + n_b.  The token drawn last has no K/V yet: the next
+ * forward writes it at position kv_len[b].  Slots at or beyond the new length keep whatever
+ * they held.  A path entry that is not an increasing row in [j+1, R_b) ends the commit of that
+ * sequence at the entries before it.
+ *
+ *   k_pages, v_pages, page_indptr, page_table, page_size   as respec_verify_attention_paged
+ *   kv_len        [B] int32, read and written
+ *   path          [B, path_stride] int32 (out_path of respec_tree_rejection_sample) or NULL
+ *   num_accepted  [B] int32 (out_num_accepted of either sampler)
+ *   Hkv*D*sizeof(element) must be a multiple of 16.
+ */
+respec_status_t respec_commit_accepted_paged(void *k_pages, void *v_pages, const int32_t *q_indptr,
+                                             const int32_t *page_indptr, const int32_t *page_table,
+                                             int32_t *kv_len, const int32_t *path, int32_t path_stride,
+                                             const int32_t *num_accepted, int32_t B, int32_t total_q,
+                                             int32_t max_q_per_seq, int32_t num_pages,
+                                             int32_t page_table_len, int32_t page_size, int32_t Hkv,
+                                             int32_t D, respec_dtype_t dt, void *hip_stream);
 
 /*
  * Profiling hook (benchmarks only).  The calling thread's next respec_verify_attention

@@ -79,6 +79,17 @@ def load():
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64,
         c.c_float, c.c_int, c.c_void_p]
+    lib.respec_verify_attention_paged.restype = c.c_int
+    lib.respec_verify_attention_paged.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_void_p,
+        c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
+        c.c_int32, c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_commit_accepted_paged.restype = c.c_int
+    lib.respec_commit_accepted_paged.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
+        c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
+        c.c_int, c.c_void_p]
     _lib = lib
     return lib
 
@@ -87,7 +98,7 @@ EXPORTED_SYMBOLS = [
     "respec_status_string", "respec_last_error", "respec_version",
     "respec_verify_attention_workspace_bytes", "respec_verify_attention", "respec_verify_attention_tree",
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample",
-    "respec_tree_rejection_sample",
+    "respec_tree_rejection_sample", "respec_verify_attention_paged", "respec_commit_accepted_paged",
     "respec_profile_mark_main",
 ]
 
@@ -279,3 +290,61 @@ def respec_tree_rejection_sample(target_logits, draft_logits, node_tokens, paren
         _dev_ptr(out_flags, "out_flags"), B, total_q, max_q_per_seq, max_depth, V,
         target_logits.stride(0), draft_logits.stride(0), float(temperature), _dtype_code(target_logits),
         _stream_ptr(stream)))
+
+
+def respec_verify_attention_paged(q, k_pages, v_pages, q_indptr, page_indptr, page_table, kv_len, out, lse,
+                                  max_q_per_seq, max_kv_len, sm_scale, workspace, tree_mask=None, stream=None):
+    """k_pages, v_pages [num_pages, page_size, Hkv, D]; out is written in place."""
+    lib = load()
+    total_q, Hq, D = q.shape
+    num_pages, page_size, Hkv, Dk = k_pages.shape
+    if Dk != D or tuple(v_pages.shape) != tuple(k_pages.shape):
+        raise ValueError("k_pages and v_pages must be [num_pages, page_size, Hkv, D] with q's D")
+    if k_pages.dtype != q.dtype or v_pages.dtype != q.dtype or out.dtype != q.dtype:
+        raise TypeError("q, k_pages, v_pages and out must share one dtype")
+    if tuple(out.shape) != tuple(q.shape):
+        raise ValueError("out must have q's shape")
+    B = q_indptr.numel() - 1
+    for t, name, n in ((q_indptr, "q_indptr", B + 1), (page_indptr, "page_indptr", B + 1), (kv_len, "kv_len", B)):
+        if t.dtype != torch.int32 or t.numel() != n:
+            raise TypeError(f"{name} must be int32 [{n}]")
+    if page_table.dtype != torch.int32:
+        raise TypeError("page_table must be int32")
+    if tree_mask is not None and (tree_mask.dtype != torch.int64 or tree_mask.numel() != total_q):
+        raise TypeError("tree_mask must be int64 [total_q] (the bits of a uint64 per row)")
+    if lse is not None and (lse.dtype != torch.float32 or tuple(lse.shape) != (total_q, Hq)):
+        raise TypeError("lse must be float32 [total_q, Hq]")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.respec_verify_attention_paged(
+        _dev_ptr(q, "q"), _dev_ptr(k_pages, "k_pages"), _dev_ptr(v_pages, "v_pages"), _dev_ptr(q_indptr, "q_indptr"),
+        _dev_ptr(page_indptr, "page_indptr"), _dev_ptr(page_table, "page_table"), _dev_ptr(kv_len, "kv_len"),
+        _dev_ptr(tree_mask, "tree_mask"), _dev_ptr(out, "out"), _dev_ptr(lse, "lse"), B, total_q, num_pages,
+        page_table.numel(), page_size, max_q_per_seq, max_kv_len, Hq, Hkv, D, float(sm_scale), _dtype_code(q),
+        _dev_ptr(workspace, "workspace"), ws_bytes, _stream_ptr(stream)))
+
+
+def respec_commit_accepted_paged(k_pages, v_pages, q_indptr, page_indptr, page_table, kv_len, num_accepted,
+                                 total_q, max_q_per_seq, path=None, stream=None):
+    """Moves the K/V of the accepted rows behind the last committed token; k_pages, v_pages and
+    kv_len are changed in place."""
+    lib = load()
+    num_pages, page_size, Hkv, D = k_pages.shape
+    if tuple(v_pages.shape) != tuple(k_pages.shape) or v_pages.dtype != k_pages.dtype:
+        raise ValueError("k_pages and v_pages must have one shape and dtype")
+    B = q_indptr.numel() - 1
+    for t, name, n in ((q_indptr, "q_indptr", B + 1), (page_indptr, "page_indptr", B + 1), (kv_len, "kv_len", B),
+                       (num_accepted, "num_accepted", B)):
+        if t.dtype != torch.int32 or t.numel() != n:
+            raise TypeError(f"{name} must be int32 [{n}]")
+    if page_table.dtype != torch.int32:
+        raise TypeError("page_table must be int32")
+    stride = 0
+    if path is not None:
+        if path.dtype != torch.int32 or path.dim() != 2 or path.shape[0] != B:
+            raise TypeError("path must be int32 [B, stride]")
+        stride = path.shape[1]
+    _check(lib.respec_commit_accepted_paged(
+        _dev_ptr(k_pages, "k_pages"), _dev_ptr(v_pages, "v_pages"), _dev_ptr(q_indptr, "q_indptr"),
+        _dev_ptr(page_indptr, "page_indptr"), _dev_ptr(page_table, "page_table"), _dev_ptr(kv_len, "kv_len"),
+        _dev_ptr(path, "path"), stride, _dev_ptr(num_accepted, "num_accepted"), B, total_q, max_q_per_seq,
+        num_pages, page_table.numel(), page_size, Hkv, D, _dtype_code(k_pages), _stream_ptr(stream)))

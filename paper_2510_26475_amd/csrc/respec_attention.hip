@@ -63,6 +63,12 @@ struct AttnParams {
     const int64_t *kv_indptr;
     const uint64_t *tree_mask;  // [total_q] or NULL (chain): bit j = the sequence's j-th new token is
                                 // visible to the row (its ancestors in the draft tree and itself)
+    // paged cache (page_table != NULL): k and v are [num_pages, page_size, Hkv, D], sequence b
+    // owns the page ids page_table[page_indptr[b] .. page_indptr[b+1]) and holds kv_len[b] tokens
+    const int32_t *page_table;
+    const int32_t *page_indptr;
+    const int32_t *kv_len;
+    int32_t num_pages, table_len, page_size, page_shift;  // page_size = 1 << page_shift, >= 16
     void *out;
     float *lse;
     int16_t *ws_o;         // [2*W, Mpad, D]   unnormalised partial outputs, 16-bit fixed point
@@ -88,7 +94,7 @@ struct AttnParams {
 
 struct SeqInfo {
     int32_t q0, R;
-    int64_t kv0;
+    int64_t kv0;    // first token of the sequence in the cache; paged: its first entry in page_table
     int32_t L;
     int32_t tiles;  // ceil(L / kTileKeys), 0 for a sequence without rows
 };
@@ -116,6 +122,20 @@ __device__ inline SeqInfo seq_info(const AttnParams &p, int b) {
     s.q0 = max(0, min(s.q0, p.total_q));
     R = max(0, min(R, min(p.max_q, p.total_q - s.q0)));
     s.R = R;
+    if (p.page_table) {
+        const ConstPtr<int32_t> page_indptr = as_constant(p.page_indptr);
+        int32_t e0 = page_indptr[b];
+        int32_t pages = page_indptr[b + 1] - e0;
+        e0 = max(0, min(e0, p.table_len));
+        pages = max(0, min(pages, p.table_len - e0));
+        int64_t L = as_constant(p.kv_len)[b];
+        L = min(L, (int64_t)pages << p.page_shift);
+        L = max((int64_t)0, min(L, (int64_t)p.max_kv_len));
+        s.kv0 = e0;
+        s.L = (int32_t)L;
+        s.tiles = R > 0 ? (s.L + kTileKeys - 1) / kTileKeys : 0;
+        return s;
+    }
     int64_t kv0 = kv_indptr[b];
     int64_t L = kv_indptr[b + 1] - kv0;
     kv0 = kv0 < 0 ? 0 : (kv0 > p.total_kv ? p.total_kv : kv0);
@@ -284,21 +304,52 @@ struct Bf16Cfg {
 // `rows_valid` re-read the last valid row (they are masked later): the clamp is on the row
 // index relative to the tile, two VALU operations per load.  rows_valid = 0 turns the whole
 // request into one 256-byte piece.  Both forms issue the same number of loads.
+// With 16-token pages a tile spans two pages: `tile` is then the address of the first page's
+// rows and `tile_hi` the address the second page's rows would have if row 16 followed row 15
+// (second page's base minus 16 rows), so that the same offsets serve both halves; each load
+// lies in one half.  Everywhere else tile_hi == tile.
 template <int D>
-__device__ inline void load_tile(u32x4 (&r)[Bf16Cfg<D>::kLoads], const char *tile, int32_t row_bytes,
-                                 const uint32_t (&row_off)[Bf16Cfg<D>::kLoads], int rows_valid, int lane) {
+__device__ inline void load_tile(u32x4 (&r)[Bf16Cfg<D>::kLoads], const char *tile, const char *tile_hi,
+                                 int32_t row_bytes, const uint32_t (&row_off)[Bf16Cfg<D>::kLoads],
+                                 int rows_valid, int lane) {
     using C = Bf16Cfg<D>;
+    static_assert(C::kLoads % 2 == 0 && (C::kLoads / 2) * C::kRowsPerLoad == 16, "a load lies in one 16-row half");
     if (rows_valid >= kTileKeys - 1) {  // wave-uniform
 #pragma unroll
-        for (int j = 0; j < C::kLoads; ++j) r[j] = *reinterpret_cast<const u32x4 *>(tile + row_off[j]);
+        for (int j = 0; j < C::kLoads; ++j)
+            r[j] = *reinterpret_cast<const u32x4 *>((j < C::kLoads / 2 ? tile : tile_hi) + row_off[j]);
     } else {
         const uint32_t rl = lane / C::kLanesPerRow, cl16 = (lane % C::kLanesPerRow) * 16;
 #pragma unroll
         for (int j = 0; j < C::kLoads; ++j) {
             const uint32_t row = min(rl + (uint32_t)(j * C::kRowsPerLoad), (uint32_t)rows_valid);
-            r[j] = *reinterpret_cast<const u32x4 *>(tile + (row * (uint32_t)row_bytes + cl16));
+            const char *base = row < 16u ? tile : tile_hi;
+            r[j] = *reinterpret_cast<const u32x4 *>(base + (row * (uint32_t)row_bytes + cl16));
         }
     }
+}
+
+// Byte offsets, in the K or V pool, of the two 16-row halves of tile t of a paged sequence
+// (head h): lo = rows 0..15, hi = what rows 16..31 are addressed from (see load_tile).  The
+// page ids come from device memory and are clamped to the pool.
+struct TileOffsets {
+    int64_t lo, hi;
+};
+
+__device__ inline TileOffsets paged_tile_offsets(const AttnParams &p, const SeqInfo &si, int t, int h, int D2,
+                                                 int32_t row_bytes) {
+    const ConstPtr<int32_t> table = as_constant(p.page_table);
+    const int key0 = t * kTileKeys;
+    const int last_entry = max(si.L - 1, 0) >> p.page_shift;  // the sequence's last page that holds tokens
+    const int e_lo = min(key0 >> p.page_shift, last_entry);
+    const int e_hi = min((key0 + 16) >> p.page_shift, last_entry);
+    const int64_t pg_lo = max(0, min(table[si.kv0 + e_lo], p.num_pages - 1));
+    const int64_t pg_hi = max(0, min(table[si.kv0 + e_hi], p.num_pages - 1));
+    const int in_lo = key0 & (p.page_size - 1), in_hi = (key0 + 16) & (p.page_size - 1);
+    TileOffsets o;
+    o.lo = ((pg_lo << p.page_shift) + in_lo) * (int64_t)row_bytes + (int64_t)h * D2;
+    o.hi = ((pg_hi << p.page_shift) + in_hi - 16) * (int64_t)row_bytes + (int64_t)h * D2;
+    return o;
 }
 
 template <int D>
@@ -460,13 +511,24 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             next_known = true;
             cursor_advance(p, cp);
         }
+        const bool paged = p.page_table != nullptr;
+        TileOffsets next_off{0, 0};
+        if (paged) next_off = paged_tile_offsets(p, cp.si, cp.t, cp.h, D * 2, row_bytes);
         auto request = [&](auto S) __attribute__((always_inline)) {
             constexpr int s = decltype(S)::value;
             const bool live = pos < n_tiles;
-            const int64_t tile_off = (cp.si.kv0 * p.Hkv + cp.h) * (int64_t)(D * 2) + (int64_t)(cp.t * kTileKeys) * row_bytes;
+            TileOffsets off;
+            if (paged) {
+                off = next_off;  // looked up when the cursor moved here
+            } else {
+                off.lo = (cp.si.kv0 * p.Hkv + cp.h) * (int64_t)(D * 2) + (int64_t)(cp.t * kTileKeys) * row_bytes;
+                off.hi = off.lo;
+            }
             const int rows_valid = live ? cp.si.L - 1 - cp.t * kTileKeys : 0;
-            load_tile<D>(kr[s], static_cast<const char *>(p.k) + tile_off, row_bytes, row_off, rows_valid, lane);
-            load_tile<D>(vr[s], static_cast<const char *>(p.v) + tile_off, row_bytes, row_off, rows_valid, lane);
+            load_tile<D>(kr[s], static_cast<const char *>(p.k) + off.lo, static_cast<const char *>(p.k) + off.hi,
+                         row_bytes, row_off, rows_valid, lane);
+            load_tile<D>(vr[s], static_cast<const char *>(p.v) + off.lo, static_cast<const char *>(p.v) + off.hi,
+                         row_bytes, row_off, rows_valid, lane);
             if (!next_known) {  // once, with the first tile already on its way
                 cursor_find_next(p, cp);
                 next_known = true;
@@ -475,6 +537,9 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                 if (pos + CW < n_tiles) {
 #pragma unroll
                     for (int c = 0; c < CW; ++c) cursor_advance(p, cp);
+                    // the page ids of the tile after this one: a scalar look-up that has a whole
+                    // step to arrive
+                    if (paged) next_off = paged_tile_offsets(p, cp.si, cp.t, cp.h, D * 2, row_bytes);
                 }
                 pos += CW;
             }
@@ -861,9 +926,15 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
     const int k_end = tree ? si.L : min(si.L, si.L - si.R + i + 1);  // one past the last visible key
     const int64_t qrow = (int64_t)(si.q0 + i) * p.Hq + h;
     const float *q = static_cast<const float *>(p.q) + qrow * D;
-    const float *kb = static_cast<const float *>(p.k) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
-    const float *vb = static_cast<const float *>(p.v) + (si.kv0 * p.Hkv + kvh) * (int64_t)D;
-    const int64_t rstride = (int64_t)p.Hkv * D;
+    const bool paged = p.page_table != nullptr;
+    // element offset of key j's row of this KV head in the K or V buffer
+    auto key_row = [&](int j) __attribute__((always_inline)) -> int64_t {
+        if (!paged) return ((si.kv0 + j) * p.Hkv + kvh) * (int64_t)D;
+        const int64_t pg = max(0, min(p.page_table[si.kv0 + (j >> p.page_shift)], p.num_pages - 1));
+        return (((pg << p.page_shift) + (j & (p.page_size - 1))) * p.Hkv + kvh) * (int64_t)D;
+    };
+    const float *kb = static_cast<const float *>(p.k);
+    const float *vb = static_cast<const float *>(p.v);
     for (int d = threadIdx.x; d < D; d += kF32Threads) sh_q[d] = q[d];
     __syncthreads();
 
@@ -874,7 +945,7 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
         float s = -INFINITY;
         const bool seen = key < k_end && (!tree || key < first_new || ((row_mask >> (key - first_new)) & 1u));
         if (seen) {
-            const float4 *kr = reinterpret_cast<const float4 *>(kb + key * rstride);
+            const float4 *kr = reinterpret_cast<const float4 *>(kb + key_row(key));
             float dot = 0.f;
 #pragma unroll 8
             for (int d4 = 0; d4 < D / 4; ++d4) {
@@ -899,7 +970,7 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
         __syncthreads();
         const int nk = min(kF32Threads, k_end - t0);
         float a = 0.f;
-        for (int j = part; j < nk; j += kParts) a = fmaf(sh_p[j], vb[(int64_t)(t0 + j) * rstride + d_own], a);
+        for (int j = part; j < nk; j += kParts) a = fmaf(sh_p[j], vb[key_row(t0 + j) + d_own], a);
         acc += a;
     }
     __syncthreads();
@@ -1001,6 +1072,64 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
 }
 
 // ------------------------------------------------------------------------------------------
+// commit of the accepted tokens in a paged cache
+// ------------------------------------------------------------------------------------------
+struct CommitParams {
+    void *k;
+    void *v;
+    const int32_t *q_indptr;
+    const int32_t *page_indptr;
+    const int32_t *page_table;
+    int32_t *kv_len;
+    const int32_t *path;          // [B, path_stride] rows of the accepted nodes, or NULL (chain: 1..n)
+    const int32_t *num_accepted;
+    int32_t B, total_q, max_q, path_stride;
+    int32_t num_pages, table_len, page_size, page_shift;
+    int32_t token_bytes;          // Hkv * D * sizeof(element), a multiple of 16
+};
+
+// One work-group per sequence.  The new tokens sit at positions first_new + row; the K/V of
+// accepted node j (row path[j] >= j + 1) moves to position first_new + 1 + j, in ascending j,
+// and the length becomes first_new + 1 + n.  A thread always handles the same 16-byte pieces
+// of a token, and a later move never reads what an earlier one wrote over (rows increase along
+// the path), so program order within the thread is all the ordering the moves need.
+__global__ __launch_bounds__(256) void commit_accepted_kernel(CommitParams p) {
+    const int b = blockIdx.x;
+    const int q0 = max(0, min(p.q_indptr[b], p.total_q));
+    const int R = max(0, min(p.q_indptr[b + 1] - q0, min(p.max_q, p.total_q - q0)));
+    int e0 = p.page_indptr[b];
+    int pages = p.page_indptr[b + 1] - e0;
+    e0 = max(0, min(e0, p.table_len));
+    pages = max(0, min(pages, p.table_len - e0));
+    const int64_t cap = (int64_t)pages << p.page_shift;
+    const int64_t L = max((int64_t)0, min((int64_t)p.kv_len[b], cap));
+    if (R < 1 || L < R) return;  // nothing that could be committed: the length stays
+    const int first_new = (int)(L - R);
+    int n = max(0, min(p.num_accepted[b], R - 1));
+    if (p.path) n = min(n, p.path_stride);
+    const int pieces = p.token_bytes / 16;
+    auto slot = [&](int pos) __attribute__((always_inline)) -> int64_t {  // byte offset of a token's K or V
+        const int64_t pg = max(0, min(p.page_table[e0 + (pos >> p.page_shift)], p.num_pages - 1));
+        return ((pg << p.page_shift) + (pos & (p.page_size - 1))) * (int64_t)p.token_bytes;
+    };
+    int done = 0;
+    for (int j = 0; j < n; ++j) {
+        const int r = p.path ? p.path[(int64_t)b * p.path_stride + j] : j + 1;
+        if (r < j + 1 || r >= R) break;  // not a path: keep what has been committed so far
+        done = j + 1;
+        if (r == j + 1) continue;        // already in place
+        const int64_t src = slot(first_new + r), dst = slot(first_new + 1 + j);
+        for (int i = threadIdx.x; i < pieces; i += blockDim.x) {
+            const u32x4 a = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(p.k) + src + (int64_t)i * 16);
+            const u32x4 c = *reinterpret_cast<const u32x4 *>(static_cast<const char *>(p.v) + src + (int64_t)i * 16);
+            *reinterpret_cast<u32x4 *>(static_cast<char *>(p.k) + dst + (int64_t)i * 16) = a;
+            *reinterpret_cast<u32x4 *>(static_cast<char *>(p.v) + dst + (int64_t)i * 16) = c;
+        }
+    }
+    if (threadIdx.x == 0) p.kv_len[b] = first_new + 1 + done;
+}
+
+// ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
 thread_local hipEvent_t g_mark_before_main = nullptr;
@@ -1096,17 +1225,44 @@ size_t respec_verify_attention_workspace_bytes(int32_t B, int32_t total_q, int64
 namespace respec {
 namespace {
 
+// The page table of a paged cache (all NULL / 0 for the contiguous layout).
+struct Pages {
+    const int32_t *page_indptr;
+    const int32_t *page_table;
+    const int32_t *kv_len;
+    int32_t num_pages, table_len, page_size;
+};
+
+int page_shift_of(int32_t page_size) {  // log2 of a supported page size, -1 otherwise
+    for (int s = 4; s <= 10; ++s)
+        if (page_size == (1 << s)) return s;
+    return -1;
+}
+
 respec_status_t verify_attention_any(const void *q, const void *k_cache, const void *v_cache,
-                                     const int32_t *q_indptr, const int64_t *kv_indptr,
+                                     const int32_t *q_indptr, const int64_t *kv_indptr, const Pages &pg,
                                      const uint64_t *tree_mask, void *out, float *lse, int32_t B,
                                      int32_t total_q, int64_t total_kv, int32_t max_q_per_seq,
                                      int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D, float sm_scale,
                                      respec_dtype_t dt, void *workspace, size_t workspace_bytes,
                                      void *hip_stream) {
+    const bool paged = pg.page_table != nullptr;
     if (tree_mask && max_q_per_seq > 64)
         return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention_tree: at most 64 rows per sequence, got %d",
                     max_q_per_seq);
-    if (B <= 0 || total_q < B || total_kv < total_q || max_q_per_seq < 1 || max_kv_len < 1)
+    if (paged) {
+        if (!pg.page_indptr || !pg.kv_len)
+            return fail(RESPEC_ERR_INVALID_ARG, "verify_attention_paged: null pointer argument");
+        if (pg.num_pages < 1 || pg.table_len < 1)
+            return fail(RESPEC_ERR_INVALID_ARG, "verify_attention_paged: need num_pages >= 1 and page_table_len >= 1");
+        if (page_shift_of(pg.page_size) < 0)
+            return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention_paged: page size %d is not a power of two in [16, 1024]",
+                        pg.page_size);
+        total_kv = (int64_t)pg.num_pages * pg.page_size;
+    } else if (!kv_indptr) {
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: null pointer argument");
+    }
+    if (B <= 0 || total_q < B || total_kv < (paged ? 1 : total_q) || max_q_per_seq < 1 || max_kv_len < 1)
         return fail(RESPEC_ERR_INVALID_ARG,
                     "verify_attention: need B > 0, total_q >= B, total_kv >= total_q, max_q_per_seq >= 1, "
                     "max_kv_len >= 1 (B=%d total_q=%d total_kv=%lld)", B, total_q, (long long)total_kv);
@@ -1123,7 +1279,7 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
                     (long long)(Hq / Hkv) * max_q_per_seq);
     if ((int64_t)B * max_q_per_seq < total_q)
         return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: max_q_per_seq too small for total_q");
-    if (!q || !k_cache || !v_cache || !q_indptr || !kv_indptr || !out)
+    if (!q || !k_cache || !v_cache || !q_indptr || !out)
         return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: null pointer argument");
     if (!aligned_to(q, 16) || !aligned_to(k_cache, 16) || !aligned_to(v_cache, 16) || !aligned_to(out, 16))
         return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: q, k_cache, v_cache and out must be 16-byte aligned");
@@ -1147,6 +1303,13 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     p.q_indptr = q_indptr;
     p.kv_indptr = kv_indptr;
     p.tree_mask = tree_mask;
+    p.page_table = pg.page_table;
+    p.page_indptr = pg.page_indptr;
+    p.kv_len = pg.kv_len;
+    p.num_pages = pg.num_pages;
+    p.table_len = pg.table_len;
+    p.page_size = paged ? pg.page_size : 0;
+    p.page_shift = paged ? page_shift_of(pg.page_size) : 0;
     p.out = out;
     p.lse = lse;
     char *ws = static_cast<char *>(workspace);
@@ -1257,9 +1420,9 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
                                         int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D,
                                         float sm_scale, respec_dtype_t dt, void *workspace,
                                         size_t workspace_bytes, void *hip_stream) {
-    return respec::verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, nullptr, out, lse, B, total_q,
-                                        total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt, workspace,
-                                        workspace_bytes, hip_stream);
+    return respec::verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, respec::Pages{}, nullptr, out, lse,
+                                        B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt,
+                                        workspace, workspace_bytes, hip_stream);
 }
 
 respec_status_t respec_verify_attention_tree(const void *q, const void *k_cache, const void *v_cache,
@@ -1271,9 +1434,77 @@ respec_status_t respec_verify_attention_tree(const void *q, const void *k_cache,
                                              size_t workspace_bytes, void *hip_stream) {
     if (!tree_mask)
         return respec::fail(RESPEC_ERR_INVALID_ARG, "verify_attention_tree: null tree_mask");
-    return respec::verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, tree_mask, out, lse, B, total_q,
-                                        total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt, workspace,
+    return respec::verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, respec::Pages{}, tree_mask, out,
+                                        lse, B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale,
+                                        dt, workspace, workspace_bytes, hip_stream);
+}
+
+respec_status_t respec_verify_attention_paged(const void *q, const void *k_pages, const void *v_pages,
+                                              const int32_t *q_indptr, const int32_t *page_indptr,
+                                              const int32_t *page_table, const int32_t *kv_len,
+                                              const uint64_t *tree_mask, void *out, float *lse, int32_t B,
+                                              int32_t total_q, int32_t num_pages, int32_t page_table_len,
+                                              int32_t page_size, int32_t max_q_per_seq, int32_t max_kv_len,
+                                              int32_t Hq, int32_t Hkv, int32_t D, float sm_scale,
+                                              respec_dtype_t dt, void *workspace, size_t workspace_bytes,
+                                              void *hip_stream) {
+    if (!page_table)
+        return respec::fail(RESPEC_ERR_INVALID_ARG, "verify_attention_paged: null page_table");
+    const respec::Pages pg{page_indptr, page_table, kv_len, num_pages, page_table_len, page_size};
+    return respec::verify_attention_any(q, k_pages, v_pages, q_indptr, nullptr, pg, tree_mask, out, lse, B, total_q,
+                                        0, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt, workspace,
                                         workspace_bytes, hip_stream);
+}
+
+respec_status_t respec_commit_accepted_paged(void *k_pages, void *v_pages, const int32_t *q_indptr,
+                                             const int32_t *page_indptr, const int32_t *page_table,
+                                             int32_t *kv_len, const int32_t *path, int32_t path_stride,
+                                             const int32_t *num_accepted, int32_t B, int32_t total_q,
+                                             int32_t max_q_per_seq, int32_t num_pages, int32_t page_table_len,
+                                             int32_t page_size, int32_t Hkv, int32_t D, respec_dtype_t dt,
+                                             void *hip_stream) {
+    using namespace respec;
+    if (!k_pages || !v_pages || !q_indptr || !page_indptr || !page_table || !kv_len || !num_accepted)
+        return fail(RESPEC_ERR_INVALID_ARG, "commit_accepted_paged: null pointer argument");
+    if (B <= 0 || total_q < B || max_q_per_seq < 1 || num_pages < 1 || page_table_len < 1 || Hkv <= 0 || D <= 0)
+        return fail(RESPEC_ERR_INVALID_ARG, "commit_accepted_paged: sizes must be positive (B=%d total_q=%d)", B, total_q);
+    if (path && path_stride < 1)
+        return fail(RESPEC_ERR_INVALID_ARG, "commit_accepted_paged: path_stride must be >= 1 with a path");
+    if (dt != RESPEC_F32 && dt != RESPEC_BF16)
+        return fail(RESPEC_ERR_INVALID_ARG, "commit_accepted_paged: unknown dtype %d", (int)dt);
+    const int shift = page_shift_of(page_size);
+    if (shift < 0)
+        return fail(RESPEC_ERR_UNSUPPORTED, "commit_accepted_paged: page size %d is not a power of two in [16, 1024]",
+                    page_size);
+    const int64_t token_bytes = (int64_t)Hkv * D * (dt == RESPEC_BF16 ? 2 : 4);
+    if (token_bytes % 16 != 0 || token_bytes > 0x7fffffffLL)
+        return fail(RESPEC_ERR_UNSUPPORTED, "commit_accepted_paged: Hkv*D*sizeof(element) must be a multiple of 16");
+    if (!aligned_to(k_pages, 16) || !aligned_to(v_pages, 16))
+        return fail(RESPEC_ERR_INVALID_ARG, "commit_accepted_paged: k_pages and v_pages must be 16-byte aligned");
+    CommitParams p{};
+    p.k = k_pages;
+    p.v = v_pages;
+    p.q_indptr = q_indptr;
+    p.page_indptr = page_indptr;
+    p.page_table = page_table;
+    p.kv_len = kv_len;
+    p.path = path;
+    p.num_accepted = num_accepted;
+    p.B = B;
+    p.total_q = total_q;
+    p.max_q = max_q_per_seq;
+    p.path_stride = path_stride;
+    p.num_pages = num_pages;
+    p.table_len = page_table_len;
+    p.page_size = page_size;
+    p.page_shift = shift;
+    p.token_bytes = (int32_t)token_bytes;
+    hipLaunchKernelGGL(commit_accepted_kernel, dim3((unsigned)B), dim3(256), 0, static_cast<hipStream_t>(hip_stream), p);
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess)
+        return fail(RESPEC_ERR_HIP, "commit_accepted_paged: launch failed: %s", hipGetErrorString(err));
+    clear_error();
+    return RESPEC_OK;
 }
 
 }  // extern "C"

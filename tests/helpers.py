@@ -248,3 +248,36 @@ def sub_tree_batch(tb: synth.TreeBatch, seqs) -> synth.TreeBatch:
         target_logits=tb.target_logits[:0], draft_logits=tb.draft_logits[:0], node_tokens=tb.node_tokens[qr].contiguous(),
         u_accept=tb.u_accept[qr].contiguous(), u_final=tb.u_final[torch.tensor(list(seqs), device=dev)].contiguous(),
         parents_per_seq=pars, kv_lens=lens)
+
+
+def gpu_paged_attention(batch, pk: synth.PagedKV, sm_scale=None, tree_mask=None, max_rows=None):
+    """batch: a VerifyBatch or TreeBatch (q, q_indptr); the cache comes from ``pk``."""
+    wl = batch.wl
+    sm_scale = 1.0 / math.sqrt(wl.D) if sm_scale is None else sm_scale
+    B = pk.kv_len.numel()
+    max_rows = max_rows if max_rows is not None else int((batch.q_indptr[1:] - batch.q_indptr[:-1]).max())
+    max_kv_len = int(pk.kv_len.max())
+    dt = binding.RESPEC_F32 if wl.dtype == "f32" else binding.RESPEC_BF16
+    ws_bytes = binding.respec_verify_attention_workspace_bytes(
+        B, batch.total_q, pk.num_pages * pk.page_size, max_rows, max_kv_len, wl.Hq, wl.Hkv, wl.D, dt)
+    assert ws_bytes > 0
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=batch.q.device)
+    out = torch.full_like(batch.q, float("nan"))
+    lse = torch.full((batch.total_q, wl.Hq), float("nan"), dtype=torch.float32, device=batch.q.device)
+    binding.respec_verify_attention_paged(batch.q, pk.k_pages, pk.v_pages, batch.q_indptr, pk.page_indptr,
+                                          pk.page_table, pk.kv_len, out, lse, max_rows, max_kv_len, sm_scale, ws,
+                                          tree_mask=tree_mask)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def oracle_paged_attention(oracle, batch, pk: synth.PagedKV, sm_scale=None, tree_mask=None, n_threads=0):
+    wl = batch.wl
+    sm_scale = 1.0 / math.sqrt(wl.D) if sm_scale is None else sm_scale
+    dt = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+    return oracle.verify_attention_paged(
+        synth.to_host_array(batch.q), synth.to_host_array(pk.k_pages), synth.to_host_array(pk.v_pages),
+        batch.q_indptr.cpu().numpy(), pk.page_indptr.cpu().numpy(), pk.page_table.cpu().numpy(),
+        pk.kv_len.cpu().numpy(), wl.Hq, wl.Hkv, wl.D, float(np.float32(sm_scale)), dt,
+        tree_mask=None if tree_mask is None else tree_mask.cpu().numpy().view(np.uint64),
+        want_lse=True, n_threads=n_threads)
