@@ -6,11 +6,13 @@ A "step" is one pass of the whole hot path over one synthetic batch: verify atte
 are resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sigma S]
-                    [--tree DEPTHxBRANCH] [--no-cpu-baseline]
+                    [--tree DEPTHxBRANCH] [--page-size P] [--no-cpu-baseline]
 
 --tree times the tree-of-drafts variant of the step on the same workload (every sequence
 drafts a main chain of DEPTH nodes with BRANCH candidates per position); the default is the
-chain of k drafts the workload names.
+chain of k drafts the workload names.  --page-size scatters the KV cache over pages of P tokens
+handed out in random order, runs attention through the page table and adds the commit of the
+accepted tokens to the step.
 """
 from __future__ import annotations
 
@@ -170,6 +172,8 @@ def main():
     ap.add_argument("--k", type=int, default=None, help="override k (sweeps)")
     ap.add_argument("--tree", default=None, metavar="DEPTHxBRANCH",
                     help="time the tree-of-drafts entry points: a chain of DEPTH nodes, BRANCH candidates per position")
+    ap.add_argument("--page-size", type=int, default=None,
+                    help="run on a paged KV cache with pages of this many tokens (adds the commit kernel to the step)")
     ap.add_argument("--probe-every", type=int, default=4,
                     help="in the timed region, bracket the main attention kernel with events on every n-th step")
     ap.add_argument("--layers", type=int, default=None,
@@ -228,22 +232,46 @@ def main():
     samp_ws = torch.zeros(binding.respec_rejection_sample_workspace_bytes(B, batch.total_q, wl.V, dt),
                           dtype=torch.uint8, device=dev)
 
-    if tree is not None:
-        def attention():
-            binding.respec_verify_attention_tree(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
-                                                 batch.kv_indptr, batch.tree_mask, out, lse, max_q,
-                                                 batch.max_kv_len, sm_scale, ws)
+    paged = None
+    if args.page_size:
+        paged = synth.paginate(batch.k_cache, batch.v_cache, batch.kv_lens, args.page_size, seed=wl.seed,
+                               spare_pages=64, poison=False)
+        kv_len0 = paged.kv_len.clone()
+    mask = batch.tree_mask if tree is not None else None
 
+    if paged is not None:
+        def attention():
+            binding.respec_verify_attention_paged(batch.q, paged.k_pages, paged.v_pages, batch.q_indptr,
+                                                  paged.page_indptr, paged.page_table, kv_len0, out, lse, max_q,
+                                                  batch.max_kv_len, sm_scale, ws, tree_mask=mask)
+
+        def commit():
+            # the lengths are restored first so that every step commits the same verify result
+            paged.kv_len.copy_(kv_len0)
+            binding.respec_commit_accepted_paged(paged.k_pages, paged.v_pages, batch.q_indptr, paged.page_indptr,
+                                                 paged.page_table, paged.kv_len, n_acc, batch.total_q, max_q,
+                                                 path=path if tree is not None else None)
+    else:
+        def commit():
+            pass
+
+        if tree is not None:
+            def attention():
+                binding.respec_verify_attention_tree(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                                                     batch.kv_indptr, batch.tree_mask, out, lse, max_q,
+                                                     batch.max_kv_len, sm_scale, ws)
+        else:
+            def attention():
+                binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                                                batch.kv_indptr, out, lse, max_q, batch.max_kv_len,
+                                                sm_scale, ws)
+
+    if tree is not None:
         def sampler():
             binding.respec_tree_rejection_sample(batch.target_logits, batch.draft_logits, batch.node_tokens,
                                                  batch.parent, batch.q_indptr, batch.u_accept, batch.u_final,
                                                  toks, path, n_acc, flags, max_q, max_out, wl.temperature)
     else:
-        def attention():
-            binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
-                                            batch.kv_indptr, out, lse, max_q, batch.max_kv_len,
-                                            sm_scale, ws)
-
         def sampler():
             binding.respec_rejection_sample(batch.target_logits, batch.draft_logits,
                                             batch.draft_tokens, batch.q_indptr, batch.u_accept,
@@ -253,6 +281,7 @@ def main():
     for _ in range(args.warmup):
         attention()
         sampler()
+        commit()
     torch.cuda.synchronize()
 
     # Timed region: exactly --steps steps.  An event record costs a few microseconds of stream
@@ -272,6 +301,7 @@ def main():
             binding.respec_profile_mark_main(a, b)
         attention()
         sampler()
+        commit()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / args.steps
@@ -280,7 +310,7 @@ def main():
     # The other kernels' times come from a separate, fully instrumented pass after the timed
     # region (five events per step; its steps are slower for it and are not part of `value`).
     n_pass = min(args.steps, 10)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(n_pass)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(n_pass)]
     for e4 in ev:
         e4[1].record()
         e4[4].record()
@@ -292,11 +322,14 @@ def main():
         e4[2].record()
         sampler()
         e4[3].record()
+        commit()
+        e4[5].record()
     torch.cuda.synchronize()
     ms_main_pass = sum(e4[4].elapsed_time(e4[1]) for e4 in ev) / n_pass
     ms_prep = sum(e4[0].elapsed_time(e4[4]) for e4 in ev) / n_pass
     ms_comb = sum(e4[1].elapsed_time(e4[2]) for e4 in ev) / n_pass
     ms_samp = sum(e4[2].elapsed_time(e4[3]) for e4 in ev) / n_pass
+    ms_commit = sum(e4[3].elapsed_time(e4[5]) for e4 in ev) / n_pass if paged is not None else 0.0
 
     # a device copy of 1 GiB, timed live: what this device's memory system gives a trivial kernel
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
@@ -325,7 +358,7 @@ def main():
         samp_bytes = sampler_algorithmic_bytes(batch, n_host)
         samp_all_rows = (batch.total_q + batch.total_q - B) * wl.V * esz
     achieved = attn_bytes / (ms_main * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name) if not changes and tree is None else None
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name) if not changes and tree is None and paged is None else None
 
     line = {
         "metric": "accepted tokens/s of the SD verify step (tokens emitted per step = accepted "
@@ -340,7 +373,10 @@ def main():
         "dtype": wl.dtype,
         "data": "synthetic",
         "config": {
-            "workload": wl.name if tree is None else f"{wl.name}+tree{args.tree}",
+            "workload": (wl.name if tree is None else f"{wl.name}+tree{args.tree}") +
+                        (f"+pages{args.page_size}" if paged is not None else ""),
+            "kv_cache": "contiguous per sequence" if paged is None else
+                        f"paged, {args.page_size} tokens per page, pages handed out in random order",
             "drafts": f"chain of k={wl.k}" if tree is None else
                       f"tree: chain of {depth} nodes, {branch} candidates per position, {len(tree)} rows per sequence",
             "B": B, "k": wl.k, "ragged_k": wl.ragged_k, "Hq": wl.Hq,
@@ -350,7 +386,7 @@ def main():
         },
         "verify_step_us": ms_step * 1e3,
         "kernel_us": {"attention_prep": ms_prep * 1e3, "attention_main": ms_main * 1e3, "attention_combine": ms_comb * 1e3,
-                      "rejection_sample": ms_samp * 1e3},
+                      "rejection_sample": ms_samp * 1e3, "commit_accepted": ms_commit * 1e3},
         "kernel_us_note": "attention_main: HIP events around the launch on every %d-th step of the timed region; "
                           "the others (launch gaps included) and attention_main_instrumented_pass: a separate pass "
                           "of %d fully instrumented steps after it" % (probe, n_pass),
@@ -379,6 +415,9 @@ def main():
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = (run_cpu_baseline_tree(batch, args.cpu_seqs) if tree is not None
                                 else run_cpu_baseline(batch, args.cpu_seqs))
+        if paged is not None:
+            line["cpu_baseline"]["note"] = ("timed on the oracle's contiguous-cache functions: its paged form "
+                                            "gathers a sequence's pages and calls them")
     print(json.dumps(line))
 
 
