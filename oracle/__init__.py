@@ -66,6 +66,10 @@ def _load():
         lib.respec_oracle_commit_accepted_paged.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
             c.c_int32, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int]
+        lib.respec_oracle_kd_rows.restype = c.c_int
+        lib.respec_oracle_kd_rows.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_int, c.c_int]
         lib.respec_oracle_softmax_rows.restype = c.c_int
         lib.respec_oracle_softmax_rows.argtypes = [
             c.c_void_p, c.c_int32, c.c_int32, c.c_int64, c.c_double, c.c_int, c.c_void_p]
@@ -194,6 +198,25 @@ def commit_accepted_paged(k_pages, v_pages, q_indptr, page_indptr, page_table, k
         _ptr(path), stride, _ptr(num_accepted), B, num_pages, page_size, Hkv, D, dtype)
     if rc != 0:
         raise RuntimeError(f"respec_oracle_commit_accepted_paged failed with code {rc}")
+
+
+def kd_rows(target_logits, draft_logits, row_weight, dtype, n_threads=1):
+    """Reward-weighted KD per logits row: returns (grad [rows,V] float64 = w (q - p),
+    row_loss [rows] float64 = w KL(p||q), total float)."""
+    target_logits = _check_elems(target_logits, dtype, "target_logits")
+    draft_logits = _check_elems(draft_logits, dtype, "draft_logits")
+    rows, V = target_logits.shape
+    assert draft_logits.shape == (rows, V)
+    row_weight = np.ascontiguousarray(row_weight, dtype=np.float32)
+    assert row_weight.shape == (rows,)
+    grad = np.empty((rows, V), dtype=np.float64)
+    row_loss = np.empty((rows,), dtype=np.float64)
+    total = np.zeros((1,), dtype=np.float64)
+    rc = _load().respec_oracle_kd_rows(_ptr(target_logits), _ptr(draft_logits), _ptr(row_weight), _ptr(grad),
+                                       _ptr(row_loss), _ptr(total), rows, V, V, V, dtype, n_threads)
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_kd_rows failed with code {rc}")
+    return grad, row_loss, float(total[0])
 
 
 def tree_rejection_sample(target_logits, draft_logits, node_tokens, parent, q_indptr, u_accept,

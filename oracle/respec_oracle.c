@@ -26,6 +26,9 @@
  *                 the page size, poisoned unused slots, a chain commit equals cutting
  *                 the length, a committed tree path attends like a cache built from
  *                 the accepted tokens only.
+ *   KD rows     -- scipy's rel_entr, torch autograd of kl_div over log_softmax in fp64,
+ *                 central differences of an independently written loss, q == p gives
+ *                 zero loss and gradient, gradient rows sum to zero, a two-token closed form.
  *   tree sampler -- a chain-shaped tree reproduces the chain function exactly, a
  *                 hand-worked case (tests/golden/tree_hand_case.json), chi-square of
  *                 the emitted token against p with three sibling candidates, the
@@ -635,6 +638,59 @@ int respec_oracle_tree_rejection_sample(const void *target_logits, const void *d
 #pragma omp critical
             status = rc;
         }
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Reward-weighted knowledge distillation of the drafter, one logits row at a  */
+/* time (Section 5.3, "Reward-Weighted Knowledge Distillation"; Algorithm 1):  */
+/*   loss_row = w * KL(p || q),  p = softmax(target row), q = softmax(draft    */
+/*   row), and its gradient with respect to the drafter's logits, w * (q - p). */
+/* w is the weight w(r) of the row's sample, supplied per row (the paper's     */
+/* default w(r) = r with an unspecified normalisation and clipping is the      */
+/* caller's).  Terms with p(x) = 0 contribute nothing.  total = sum of rows.   */
+/* ------------------------------------------------------------------------- */
+int respec_oracle_kd_rows(const void *target_logits, const void *draft_logits, const float *row_weight,
+                          double *grad, double *row_loss, double *total_loss, int32_t rows, int32_t V,
+                          int64_t ld_t, int64_t ld_d, int dtype, int n_threads)
+{
+    if (!target_logits || !draft_logits || !row_weight || !grad || !row_loss)
+        return ORACLE_ERR_ARG;
+    if (rows <= 0 || V <= 0 || ld_t < V || ld_d < V)
+        return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16)
+        return ORACLE_ERR_ARG;
+    int status = ORACLE_OK;
+    const int nt = pick_threads(n_threads);
+    (void)nt;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nt)
+    for (int32_t r = 0; r < rows; ++r) {
+        double *p = (double *)malloc((size_t)V * sizeof(double));
+        double *q = (double *)malloc((size_t)V * sizeof(double));
+        if (!p || !q) {
+#pragma omp critical
+            status = ORACLE_ERR_ALLOC;
+        } else {
+            softmax_row(target_logits, r, ld_t, V, 1.0, dtype, p);
+            softmax_row(draft_logits, r, ld_d, V, 1.0, dtype, q);
+            const double w = (double)row_weight[r];
+            double kl = 0.0;
+            for (int32_t x = 0; x < V; ++x) {
+                if (p[x] > 0.0)
+                    kl += p[x] * (log(p[x]) - log(q[x]));
+                grad[(int64_t)r * V + x] = w * (q[x] - p[x]);
+            }
+            row_loss[r] = w * kl;
+        }
+        free(p);
+        free(q);
+    }
+    if (status == ORACLE_OK && total_loss) {
+        double t = 0.0;
+        for (int32_t r = 0; r < rows; ++r)
+            t += row_loss[r];
+        *total_loss = t;
     }
     return status;
 }
