@@ -12,8 +12,9 @@
  *                             sequence, grouped-query heads, ragged per-sequence KV cache;
  *   respec_rejection_sample   Eq. 1 / Eq. 2 over the vocabulary with supplied uniforms;
  * their counterparts for a tree of drafts (Section 3.1), respec_verify_attention_tree and
- * respec_tree_rejection_sample, and the paged-cache forms respec_verify_attention_paged and
- * respec_commit_accepted_paged.
+ * respec_tree_rejection_sample, the paged-cache forms respec_verify_attention_paged and
+ * respec_commit_accepted_paged, and respec_kd_rows, the drafter's distillation loss over the
+ * same logits rows (Section 5.3).
  *
  * General rules
  *   - Every data pointer is a DEVICE pointer (HIP global memory) unless it says "host".
@@ -293,6 +294,38 @@ respec_status_t respec_tree_rejection_sample(const void *target_logits, const vo
                                              int32_t max_q_per_seq, int32_t max_depth, int32_t V,
                                              int64_t ld_t, int64_t ld_d, float temperature,
                                              respec_dtype_t logits_dt, void *hip_stream);
+
+/*
+ * Reward-weighted knowledge distillation of the drafter, per logits row (Section 5.3,
+ * "Reward-Weighted Knowledge Distillation"; the update step of Algorithm 1).  For every row r
+ *     p = softmax(target_logits[r, :]),  q = softmax(draft_logits[r, :])
+ *     row_loss[r] = w_r * KL(p || q) = w_r * sum_x p(x) (log p(x) - log q(x))      (p(x) = 0 terms are 0)
+ *     grad_draft_logits[r, x] = w_r * (q(x) - p(x))        (the derivative of row_loss[r] in draft_logits[r, x])
+ *     *total_loss = sum_r row_loss[r]
+ * w_r = row_weight[r] is the weight w(reward) of the sample the row belongs to; the paper's
+ * default w(r) = r, its normalisation and its clipping are the caller's (they are not
+ * specified).  Rows with weight 0 are not read; their gradient is written as zero.
+ * The rows are the [rows, V] logits the sampler reads: both rows are read from memory once and
+ * the gradient is written once.
+ *
+ *   target_logits, draft_logits [rows, V] logits_dt, row strides ld_t, ld_d elements
+ *   row_weight    [rows] f32
+ *   grad_draft_logits [rows, V] logits_dt (written; bf16: rounded to nearest even), stride ld_g
+ *   row_loss      [rows] f32 (written);  total_loss  [1] f64 or NULL (written)
+ *   V * sizeof(element), the strides in bytes and the three base pointers must be multiples of
+ *   16 (RESPEC_ERR_UNSUPPORTED otherwise); V at most 327,680 (bf16) or 163,840 (f32).
+ *   workspace     respec_kd_rows_workspace_bytes(rows, V, logits_dt) bytes, 256-byte aligned,
+ *                 scratch (nothing to prepare, nothing survives).
+ * The kernel is cooperative: work-groups that share a row wait for each other, so it expects to
+ * have the device to itself while it runs; a wait that runs out (a device fault) is reported as
+ * NaN in *total_loss and in row_loss.
+ */
+size_t respec_kd_rows_workspace_bytes(int32_t rows, int32_t V, respec_dtype_t logits_dt);
+respec_status_t respec_kd_rows(const void *target_logits, const void *draft_logits,
+                               const float *row_weight, void *grad_draft_logits, float *row_loss,
+                               double *total_loss, int32_t rows, int32_t V, int64_t ld_t, int64_t ld_d,
+                               int64_t ld_g, respec_dtype_t logits_dt, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

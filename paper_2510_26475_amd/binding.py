@@ -90,6 +90,12 @@ def load():
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
         c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
         c.c_int, c.c_void_p]
+    lib.respec_kd_rows_workspace_bytes.restype = c.c_size_t
+    lib.respec_kd_rows_workspace_bytes.argtypes = [c.c_int32, c.c_int32, c.c_int]
+    lib.respec_kd_rows.restype = c.c_int
+    lib.respec_kd_rows.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
     _lib = lib
     return lib
 
@@ -99,6 +105,7 @@ EXPORTED_SYMBOLS = [
     "respec_verify_attention_workspace_bytes", "respec_verify_attention", "respec_verify_attention_tree",
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample",
     "respec_tree_rejection_sample", "respec_verify_attention_paged", "respec_commit_accepted_paged",
+    "respec_kd_rows_workspace_bytes", "respec_kd_rows",
     "respec_profile_mark_main",
 ]
 
@@ -348,3 +355,33 @@ def respec_commit_accepted_paged(k_pages, v_pages, q_indptr, page_indptr, page_t
         _dev_ptr(page_indptr, "page_indptr"), _dev_ptr(page_table, "page_table"), _dev_ptr(kv_len, "kv_len"),
         _dev_ptr(path, "path"), stride, _dev_ptr(num_accepted, "num_accepted"), B, total_q, max_q_per_seq,
         num_pages, page_table.numel(), page_size, Hkv, D, _dtype_code(k_pages), _stream_ptr(stream)))
+
+
+def respec_kd_rows_workspace_bytes(rows, V, dt) -> int:
+    return int(load().respec_kd_rows_workspace_bytes(rows, V, dt))
+
+
+def respec_kd_rows(target_logits, draft_logits, row_weight, grad, row_loss, total_loss, workspace, stream=None):
+    """target_logits, draft_logits, grad [rows, V]; row_weight, row_loss [rows] f32; total_loss [1] f64 or None."""
+    lib = load()
+    rows, V = target_logits.shape
+    for t, name in ((draft_logits, "draft_logits"), (grad, "grad")):
+        if tuple(t.shape) != (rows, V) or t.dtype != target_logits.dtype or t.stride(1) != 1:
+            raise ValueError(f"{name} must be [rows, V] in the target's dtype with unit-stride rows")
+    if target_logits.stride(1) != 1:
+        raise ValueError("logits rows must be unit-stride")
+    for t, name in ((row_weight, "row_weight"), (row_loss, "row_loss")):
+        if t.dtype != torch.float32 or t.numel() != rows:
+            raise TypeError(f"{name} must be float32 [rows]")
+    if total_loss is not None and (total_loss.dtype != torch.float64 or total_loss.numel() != 1):
+        raise TypeError("total_loss must be float64 [1]")
+    for t, name in ((target_logits, "target_logits"), (draft_logits, "draft_logits"), (grad, "grad")):
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live on the GPU")
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.respec_kd_rows(
+        ctypes.c_void_p(target_logits.data_ptr()), ctypes.c_void_p(draft_logits.data_ptr()),
+        _dev_ptr(row_weight, "row_weight"), ctypes.c_void_p(grad.data_ptr()), _dev_ptr(row_loss, "row_loss"),
+        _dev_ptr(total_loss, "total_loss"), rows, V, target_logits.stride(0), draft_logits.stride(0),
+        grad.stride(0), _dtype_code(target_logits), _dev_ptr(workspace, "workspace"), ws_bytes,
+        _stream_ptr(stream)))

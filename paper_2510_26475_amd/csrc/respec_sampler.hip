@@ -65,14 +65,6 @@ struct Mailbox {
     int part, split, stage;
 };
 
-__device__ inline uint32_t load_dev(const uint32_t *ptr) {
-    return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ inline void store_dev(uint32_t *ptr, uint32_t v) {
-    __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 // One exchange.  Every thread of the block calls it with the same `mine`; afterwards
 // sh.xchg[j] holds what part j published.  Ends with a barrier.  A wait that runs out of its
 // (very large) spin budget marks the block as failed and goes on, so that every block ends.

@@ -374,5 +374,25 @@ __device__ inline void row_stats(const void *rowp, const void *rowq, int nslots,
     if constexpr (TWO) block_combine(tq.ref, tq.total(), sh, parity, 1, p, Mq, Sq);
 }
 
+// Device-scope accesses for the few words that work-groups on different compute units (whose
+// L2 caches are not coherent with each other) exchange.
+__device__ inline uint32_t load_dev(const uint32_t *ptr) {
+    return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline void store_dev(uint32_t *ptr, uint32_t v) {
+    __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ inline double load_dev_f64(const double *ptr) {
+    return __builtin_bit_cast(double, __hip_atomic_load(reinterpret_cast<const unsigned long long *>(ptr),
+                                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+__device__ inline void store_dev_f64(double *ptr, double v) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(ptr), __builtin_bit_cast(unsigned long long, v),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 }  // namespace
 }  // namespace respec
