@@ -25,9 +25,10 @@ namespace respec {
 namespace {
 
 constexpr int kKdMaxSplit = 16;                 // work-groups that can share one row
-constexpr int kKdNS = 5;                        // 16-byte pieces of a row one thread holds
+constexpr int kKdNS = 6;                        // 16-byte pieces of a row one thread holds
+constexpr int kKdDataThreads = kThreads - 64;   // wave 0 holds no data: it is the one that talks to the partners
 constexpr int kKdBoxHeader = 128;               // progress counter of every member
-constexpr int kKdBoxBytes = kKdBoxHeader + kKdMaxSplit * 2 * 4 * 8;  // + [member][parity][4] doubles
+constexpr int kKdBoxBytes = kKdBoxHeader + kKdMaxSplit * 4 * 4 * 8;  // + [member][stage % 4][4] doubles
 constexpr int kKdMaxTeams = 1024;               // sizes the workspace
 constexpr int kKdSpinLimit = 1 << 22;
 
@@ -63,24 +64,33 @@ __global__ void kd_init_kernel(KdParams p) {
     if (i == 0) *p.fail_flag = 0;
 }
 
-// One exchange of four doubles among the members of a team (stage `it`, counted from 0).
-// Member m publishes into payload buffer it % 2 and then raises its progress counter to it + 1;
-// nobody can be two stages ahead of the slowest reader, because a member publishes stage it + 1
-// only after it has read everybody's stage it.  Every thread calls it; ends with a barrier.  A
-// wait that runs out of its (very large) budget marks the launch as failed and goes on.
-__device__ inline void kd_exchange(const KdParams &p, char *box, int member, int it, const double (&mine)[4],
-                                   KdShared &sh) {
-    uint32_t *progress = reinterpret_cast<uint32_t *>(box);
-    double *payload = reinterpret_cast<double *>(box + kKdBoxHeader);
-    const int parity = it & 1;
-    const uint32_t mark = (uint32_t)it + 1u;
+// The exchange of four doubles per row among the members of a team, in two halves so that other
+// work can sit between them.  Stage `it` (the team's it-th row with a weight): member m stores
+// its numbers into payload buffer it % 4 and then raises its progress counter to it + 1
+// (publish); later it waits for every partner's counter to reach it + 1 and reads their numbers
+// (gather).  A member publishes stage it + 1 before it gathers stage it, so a partner can be
+// reading a member's stage it - 1 while that member is already two stages on: four buffers
+// keep the stage being written (it + 1) apart from every stage a partner may still read
+// (it - 1 and later; a partner that has published stage it - 1 has finished with stage it - 3).
+__device__ inline void kd_publish(char *box, int member, int it, const double (&mine)[4]) {
     if (threadIdx.x == 0) {
-        double *dst = payload + (member * 2 + parity) * 4;
+        uint32_t *progress = reinterpret_cast<uint32_t *>(box);
+        double *dst = reinterpret_cast<double *>(box + kKdBoxHeader) + (member * 4 + (it & 3)) * 4;
 #pragma unroll
         for (int i = 0; i < 4; ++i) store_dev_f64(dst + i, mine[i]);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the stores above have completed
-        store_dev(progress + member, mark);
+        store_dev(progress + member, (uint32_t)it + 1u);
     }
+}
+
+// Every thread calls it; afterwards sh.xchg[j] holds what member j published for stage `it`.
+// Ends with a barrier.  A wait that runs out of its (very large) budget marks the launch as
+// failed and goes on, so that every work-group ends.
+__device__ inline void kd_gather(const KdParams &p, char *box, int member, int it, const double (&mine)[4],
+                                 KdShared &sh) {
+    const uint32_t *progress = reinterpret_cast<const uint32_t *>(box);
+    const double *payload = reinterpret_cast<const double *>(box + kKdBoxHeader);
+    const uint32_t mark = (uint32_t)it + 1u;
     if ((int)threadIdx.x < p.split) {
         const int j = threadIdx.x;
         if (j == member) {
@@ -99,7 +109,7 @@ __device__ inline void kd_exchange(const KdParams &p, char *box, int member, int
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            const double *src = payload + (j * 2 + parity) * 4;
+            const double *src = payload + (j * 4 + (it & 3)) * 4;
 #pragma unroll
             for (int i = 0; i < 4; ++i) sh.xchg[j][i] = load_dev_f64(src + i);
         }
@@ -123,10 +133,19 @@ __device__ inline void store_grad(void *dst, const float (&g)[Elem<BF16>::EPV]) 
     }
 }
 
-template <bool BF16>
+// NS: 16-byte pieces of a row one thread holds.  Three rows are in the registers of a team at
+// any time: row k (its partial normalisers published, waiting for the partners'), row k + 1
+// (arriving, then reduced and published) and row k + 2 (requested).  One step of the loop
+// requests row k + 2, reduces and publishes row k + 1, and only then gathers row k's
+// normalisers, which the partners published a whole step ago, and writes its gradient.
+//
+// Wave 0 of a work-group holds no row data and issues no row loads or stores: it does the
+// exchange.  A wave's memory operations complete in order, so a wave with a row's loads in
+// flight could not see a partner's counter (or finish the release before its own) until those
+// loads had returned, and the whole work-group would wait for it at the next barrier.
+template <bool BF16, int NS>
 __global__ __launch_bounds__(kThreads) void kd_rows_kernel(KdParams p) {
     constexpr int EPV = Elem<BF16>::EPV;
-    constexpr int NS = kKdNS;
     __shared__ KdShared sh;
     const int split = p.split;
     const int team = blockIdx.x / split, member = blockIdx.x % split;
@@ -134,7 +153,9 @@ __global__ __launch_bounds__(kThreads) void kd_rows_kernel(KdParams p) {
     const int nslots_row = p.V / EPV;
     const int span = (nslots_row + split - 1) / split;
     const int lo = min(member * span, nslots_row);
-    const int n = min(lo + span, nslots_row) - lo;  // <= NS * kThreads (the host picks split for that)
+    const int n = min(lo + span, nslots_row) - lo;  // <= NS * kKdDataThreads (the host picks split for that)
+    const bool data_wave = wave != 0;
+    const int dt = (int)threadIdx.x - 64;           // index among the data threads
     const size_t esz = BF16 ? 2 : 4;
     char *box = p.boxes + (size_t)team * kKdBoxBytes;
     if (threadIdx.x == 0) sh.failed = 0;
@@ -143,9 +164,10 @@ __global__ __launch_bounds__(kThreads) void kd_rows_kernel(KdParams p) {
     auto load_row = [&](int r, u32x4 (&vp)[NS], u32x4 (&vq)[NS]) __attribute__((always_inline)) {
         const char *rp = static_cast<const char *>(p.target) + (size_t)r * p.ld_t * esz + (size_t)lo * 16;
         const char *rq = static_cast<const char *>(p.draft) + (size_t)r * p.ld_d * esz + (size_t)lo * 16;
+        if (!data_wave) return;  // wave-uniform
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            const int s = i * kThreads + threadIdx.x;
+            const int s = i * kKdDataThreads + dt;
             const bool in = s < n;
             const u32x4 a = *reinterpret_cast<const u32x4 *>(rp + (size_t)(in ? s : 0) * 16);
             const u32x4 b = *reinterpret_cast<const u32x4 *>(rq + (size_t)(in ? s : 0) * 16);
@@ -158,41 +180,26 @@ __global__ __launch_bounds__(kThreads) void kd_rows_kernel(KdParams p) {
     auto next_live = [&](int r) __attribute__((always_inline)) -> int {
         while (r < p.rows && p.weight[r] == 0.f) {
             char *g = static_cast<char *>(p.grad) + (size_t)r * p.ld_g * esz + (size_t)lo * 16;
-            for (int s = threadIdx.x; s < n; s += kThreads)
-                *reinterpret_cast<u32x4 *>(g + (size_t)s * 16) = u32x4{0u, 0u, 0u, 0u};
-            if (threadIdx.x == 0) p.loss_part[(size_t)r * split + member] = 0.0;
+            if (data_wave) {
+                for (int s = dt; s < n; s += kKdDataThreads)
+                    *reinterpret_cast<u32x4 *>(g + (size_t)s * 16) = u32x4{0u, 0u, 0u, 0u};
+                if (dt == 0) p.loss_part[(size_t)r * split + member] = 0.0;
+            }
             r += p.n_teams;
         }
-        return r;
+        return min(r, p.rows);
     };
-
-    u32x4 np_[NS], nq_[NS];
-#pragma unroll
-    for (int i = 0; i < NS; ++i) np_[i] = nq_[i] = neg_inf_slot<BF16>();
-    int r = next_live(team);
-    if (r < p.rows && n > 0) load_row(r, np_, nq_);
-    for (int it = 0; r < p.rows; ++it) {
-        u32x4 vp[NS], vq[NS];
+    // partial normalisers (max, sum) of this member's part of a row pair
+    auto reduce_row = [&](u32x4 (&vp)[NS], u32x4 (&vq)[NS], int parity, double (&mine)[4]) __attribute__((always_inline)) {
+        float refp = kRefInit, refq = kRefInit;
+        float mp = -INFINITY, mq = -INFINITY;
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            vp[i] = np_[i];
-            vq[i] = nq_[i];
+            mp = fmaxf(mp, slot_max<BF16>(vp[i]));
+            mq = fmaxf(mq, slot_max<BF16>(vq[i]));
         }
-        const int rn = next_live(r + p.n_teams);
-        if (rn < p.rows && n > 0) load_row(rn, np_, nq_);  // in flight while this row is worked on
-
-        // partial normalisers of this member's part
-        float refp = kRefInit, refq = kRefInit;
-        if (n > 0) {
-            float mp = -INFINITY, mq = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < NS; ++i) {
-                mp = fmaxf(mp, slot_max<BF16>(vp[i]));
-                mq = fmaxf(mq, slot_max<BF16>(vq[i]));
-            }
-            if (mp > -INFINITY && mp < INFINITY) refp = mp;
-            if (mq > -INFINITY && mq < INFINITY) refq = mq;
-        }
+        if (mp > -INFINITY && mp < INFINITY) refp = mp;
+        if (mq > -INFINITY && mq < INFINITY) refq = mq;
         float accp = 0.f, accq = 0.f;
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
@@ -204,10 +211,9 @@ __global__ __launch_bounds__(kThreads) void kd_rows_kernel(KdParams p) {
                 accp += hw_exp2(exp2_arg(zp[j], refp, p.c_hi, p.c_lo));
                 accq += hw_exp2(exp2_arg(zq[j], refq, p.c_hi, p.c_lo));
             }
-            __builtin_amdgcn_sched_barrier(0);  // one piece at a time: interleaving all of them spills
         }
-        // (the unpacked elements are formed again after the exchange: keeping all of them alive
-        // across it would spill; the pin below stops the compiler from doing so)
+        // (the unpacked elements are formed again when the gradient is written: keeping them
+        // alive until then would spill; the pin stops the compiler from doing so)
 #pragma unroll
         for (int i = 0; i < NS; ++i)
 #pragma unroll
@@ -219,11 +225,34 @@ __global__ __launch_bounds__(kThreads) void kd_rows_kernel(KdParams p) {
             }
         float Mp, Mq;
         double Sp, Sq;
-        block_combine(refp, (double)accp, sh.rows, it & 1, 0, p, Mp, Sp);
-        block_combine(refq, (double)accq, sh.rows, it & 1, 1, p, Mq, Sq);
+        block_combine(refp, (double)accp, sh.rows, parity, 0, p, Mp, Sp);
+        block_combine(refq, (double)accq, sh.rows, parity, 1, p, Mq, Sq);
+        mine[0] = (double)Mp;
+        mine[1] = Sp;
+        mine[2] = (double)Mq;
+        mine[3] = Sq;
+    };
+
+    int it = 0;
+    int r_cur = next_live(team);
+    if (r_cur >= p.rows) return;  // block-uniform
+    int r_next = p.rows;
+    double mine_cur[4];
+
+    // one step; A = row r_cur (published), B = row r_next (requested), C = free
+    auto step = [&](u32x4 (&ap)[NS], u32x4 (&aq)[NS], u32x4 (&bp)[NS], u32x4 (&bq)[NS], u32x4 (&cp)[NS],
+                    u32x4 (&cq)[NS]) __attribute__((always_inline)) {
+        const int r_after = r_next < p.rows ? next_live(r_next + p.n_teams) : p.rows;
+        if (r_after < p.rows) load_row(r_after, cp, cq);
+        double mine_next[4] = {0.0, 0.0, 0.0, 0.0};
+        if (r_next < p.rows) {
+            reduce_row(bp, bq, (it + 1) & 1, mine_next);
+            if (split > 1) kd_publish(box, member, it + 1, mine_next);
+        }
+        float Mp = (float)mine_cur[0], Mq = (float)mine_cur[2];
+        double Sp = mine_cur[1], Sq = mine_cur[3];
         if (split > 1) {
-            const double mine[4] = {(double)Mp, Sp, (double)Mq, Sq};
-            kd_exchange(p, box, member, it, mine, sh);
+            kd_gather(p, box, member, it, mine_cur, sh);
             if (threadIdx.x < 2) {  // thread 0: the target row, thread 1: the drafter row
                 const int w = threadIdx.x;
                 float M = (float)sh.xchg[0][2 * w];
@@ -242,16 +271,16 @@ __global__ __launch_bounds__(kThreads) void kd_rows_kernel(KdParams p) {
         }
         // log2 of the normalisers; p = exp2((z - Mp) c - lsp), q alike
         const float lsp = (float)log2(Sp), lsq = (float)log2(Sq);
-        const float w = p.weight[r];
+        const float w = p.weight[r_cur];
         float kl = 0.f;
-        char *g = static_cast<char *>(p.grad) + (size_t)r * p.ld_g * esz + (size_t)lo * 16;
+        char *g = static_cast<char *>(p.grad) + (size_t)r_cur * p.ld_g * esz + (size_t)lo * 16;
 #pragma unroll
         for (int i = 0; i < NS; ++i) {
-            const int s = i * kThreads + threadIdx.x;
-            if (s < n) {
+            const int s = i * kKdDataThreads + dt;
+            if (data_wave && s < n) {
                 float zp[EPV], zq[EPV], gr[EPV];
-                unpack<BF16>(vp[i], zp);
-                unpack<BF16>(vq[i], zq);
+                unpack<BF16>(ap[i], zp);
+                unpack<BF16>(aq[i], zq);
 #pragma unroll
                 for (int j = 0; j < EPV; ++j) {
                     const float a = exp2_arg(zp[j], Mp, p.c_hi, p.c_lo) - lsp;
@@ -262,19 +291,39 @@ __global__ __launch_bounds__(kThreads) void kd_rows_kernel(KdParams p) {
                 }
                 store_grad<BF16>(g + (size_t)s * 16, gr);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
         // this member's share of KL(p || q) in nats, summed in a fixed order
         const double kw = wave_sum((double)kl);
-        __syncthreads();  // comb_* and the combine buffers have been read by everyone
+        __syncthreads();  // comb_* and the exchange buffer have been read by everyone
         if (lane == 0) sh.loss_wave[wave] = kw;
         __syncthreads();
-        if (threadIdx.x == 0) {
+        if (dt == 0) {  // a data thread: wave 0 keeps its memory queue for the exchange
             double t = 0.0;
             for (int x = 0; x < kWaves; ++x) t += sh.loss_wave[x];
-            p.loss_part[(size_t)r * split + member] = t * 0.69314718055994530942;
+            p.loss_part[(size_t)r_cur * split + member] = t * 0.69314718055994530942;
         }
-        r = rn;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mine_cur[i] = mine_next[i];
+        r_cur = r_next;
+        r_next = r_after;
+        ++it;
+    };
+
+    u32x4 s0p[NS], s0q[NS], s1p[NS], s1q[NS], s2p[NS], s2q[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) s0p[i] = s0q[i] = s1p[i] = s1q[i] = s2p[i] = s2q[i] = neg_inf_slot<BF16>();
+    load_row(r_cur, s0p, s0q);
+    r_next = next_live(r_cur + p.n_teams);
+    if (r_next < p.rows) load_row(r_next, s1p, s1q);
+    reduce_row(s0p, s0q, 0, mine_cur);
+    if (split > 1) kd_publish(box, member, 0, mine_cur);
+    for (;;) {  // r_cur, r_next and it are block-uniform
+        step(s0p, s0q, s1p, s1q, s2p, s2q);
+        if (r_cur >= p.rows) break;
+        step(s1p, s1q, s2p, s2q, s0p, s0q);
+        if (r_cur >= p.rows) break;
+        step(s2p, s2q, s0p, s0q, s1p, s1q);
+        if (r_cur >= p.rows) break;
     }
 }
 
@@ -300,11 +349,34 @@ __global__ __launch_bounds__(1024) void kd_finish_kernel(KdParams p) {
     if (threadIdx.x == 0 && p.total_loss) *p.total_loss = failed ? (double)NAN : sh[0];
 }
 
-int kd_split_for(int32_t V, respec_dtype_t dt) {  // work-groups per row, 0 = too wide
+// Work-groups per row: the fewest (a power of two) whose part of a row fits the registers of
+// the data threads.  0: the row is too wide.
+int kd_split_for(int32_t V, respec_dtype_t dt) {
     const int64_t slots = (int64_t)V * (dt == RESPEC_BF16 ? 2 : 4) / 16;
     int split = 1;
-    while (split <= kKdMaxSplit && (slots + split - 1) / split > (int64_t)kKdNS * kThreads) split *= 2;
+    while (split <= kKdMaxSplit && (slots + split - 1) / split > (int64_t)kKdNS * kKdDataThreads) split *= 2;
     return split <= kKdMaxSplit ? split : 0;
+}
+
+template <bool BF16>
+hipError_t launch_kd(KdParams &p, long forced_teams, hipStream_t stream) {
+    int per_cu = 1, cus = 256, dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kd_rows_kernel<BF16, kKdNS>, kThreads, 0) != hipSuccess ||
+        per_cu < 1)
+        per_cu = 1;
+    // every member of every team has to be resident: no more work-groups than the device holds
+    long teams = (long)per_cu * cus / p.split;
+    if (forced_teams > 0 && forced_teams < teams) teams = forced_teams;
+    if (teams > p.rows) teams = p.rows;
+    if (teams > kKdMaxTeams) teams = kKdMaxTeams;
+    if (teams < 1) teams = 1;
+    p.n_teams = (int32_t)teams;
+    const int init_threads = p.n_teams * (kKdBoxHeader / 4);
+    hipLaunchKernelGGL(kd_init_kernel, dim3((unsigned)((init_threads + 255) / 256)), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((kd_rows_kernel<BF16, kKdNS>), dim3((unsigned)(p.n_teams * p.split)), dim3(kThreads), 0, stream, p);
+    hipLaunchKernelGGL(kd_finish_kernel, dim3(1), dim3(1024), 0, stream, p);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -364,24 +436,10 @@ respec_status_t respec_kd_rows(const void *target_logits, const void *draft_logi
     p.ld_d = ld_d;
     p.ld_g = ld_g;
     p.split = split;
-    int cus = 256, dev = 0;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    long teams = env_long("RESPEC_KD_TEAMS", 0);  // tests and sweeps
-    if (teams <= 0) teams = cus / split;
-    if (teams > rows) teams = rows;
-    if (teams > kKdMaxTeams) teams = kKdMaxTeams;
-    if (teams < 1) teams = 1;
-    p.n_teams = (int32_t)teams;
-
+    const long forced_teams = env_long("RESPEC_KD_TEAMS", 0);  // tests and sweeps
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    const int init_threads = p.n_teams * (kKdBoxHeader / 4);
-    hipLaunchKernelGGL(kd_init_kernel, dim3((unsigned)((init_threads + 255) / 256)), dim3(256), 0, stream, p);
-    if (logits_dt == RESPEC_BF16)
-        hipLaunchKernelGGL(kd_rows_kernel<true>, dim3((unsigned)(p.n_teams * split)), dim3(kThreads), 0, stream, p);
-    else
-        hipLaunchKernelGGL(kd_rows_kernel<false>, dim3((unsigned)(p.n_teams * split)), dim3(kThreads), 0, stream, p);
-    hipLaunchKernelGGL(kd_finish_kernel, dim3(1), dim3(1024), 0, stream, p);
-    const hipError_t err = hipGetLastError();
+    hipError_t err;
+    err = logits_dt == RESPEC_BF16 ? launch_kd<true>(p, forced_teams, stream) : launch_kd<false>(p, forced_teams, stream);
     if (err != hipSuccess)
         return fail(RESPEC_ERR_HIP, "kd_rows: launch failed: %s", hipGetErrorString(err));
     clear_error();
