@@ -7,12 +7,14 @@ are resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sigma S]
                     [--tree DEPTHxBRANCH] [--page-size P] [--no-cpu-baseline]
+    python bench.py --kd-rows N [--workload NAME] [--sigma S]
 
 --tree times the tree-of-drafts variant of the step on the same workload (every sequence
 drafts a main chain of DEPTH nodes with BRANCH candidates per position); the default is the
 chain of k drafts the workload names.  --page-size scatters the KV cache over pages of P tokens
 handed out in random order, runs attention through the page table and adds the commit of the
-accepted tokens to the step.
+accepted tokens to the step.  --kd-rows times the drafter's reward-weighted distillation kernel
+(not part of the verify step) on N row pairs of the workload's vocabulary and logits recipe.
 """
 from __future__ import annotations
 
@@ -161,6 +163,61 @@ def run_cpu_baseline(batch: synth.VerifyBatch, n_seqs: int):
     }
 
 
+def run_kd(args, wl, dev):
+    """respec_kd_rows on args.kd_rows row pairs: HIP-event time of the row kernel's call, oracle beside it."""
+    rows, V = args.kd_rows, wl.V
+    g = torch.Generator(device=dev).manual_seed(wl.seed)
+    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    t32 = 3.0 * torch.randn((rows, V), generator=g, device=dev)
+    target = t32.to(tdt)
+    t32 += wl.sigma * torch.randn((rows, V), generator=g, device=dev)
+    draft = t32.to(tdt)
+    del t32
+    w = 0.1 + 1.9 * torch.rand((rows,), generator=g, device=dev)
+    dt = binding.RESPEC_F32 if wl.dtype == "f32" else binding.RESPEC_BF16
+    ws = torch.empty(binding.respec_kd_rows_workspace_bytes(rows, V, dt), dtype=torch.uint8, device=dev)
+    grad = torch.empty_like(draft)
+    loss = torch.empty((rows,), dtype=torch.float32, device=dev)
+    total = torch.empty((1,), dtype=torch.float64, device=dev)
+    for _ in range(args.warmup):
+        binding.respec_kd_rows(target, draft, w, grad, loss, total, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        binding.respec_kd_rows(target, draft, w, grad, loss, total, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    esz = 4 if wl.dtype == "f32" else 2
+    algo = 3 * rows * V * esz   # both rows read once, the gradient written once
+    line = {
+        "metric": "logit rows/s of the reward-weighted KD row kernel (loss and gradient of the drafter's logits)",
+        "value": rows / (ms * 1e-3), "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"kd_rows on {rows} row pairs of {wl.name}", "rows": rows, "V": V, "sigma": wl.sigma,
+                   "seed": wl.seed},
+        "total_loss": float(total.item()),
+        "roofline": {"kernel": "kd_stream_kernel", "bound": "hbm", "achieved": algo / (ms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None,
+                     "note": "time per call (row kernel + the one-work-group finish kernel) by HIP events"},
+    }
+    if not args.no_cpu_baseline:
+        import oracle  # test infrastructure: allowed here for the cpu_baseline leg only
+        oracle.build()
+        n = min(rows, 64)
+        th, dh, wh = synth.to_host_array(target[:n]), synth.to_host_array(draft[:n]), w[:n].cpu().numpy()
+        odt = oracle.F32 if wl.dtype == "f32" else oracle.BF16
+        t0 = time.perf_counter()
+        oracle.kd_rows(th, dh, wh, odt, n_threads=0)
+        t1 = time.perf_counter()
+        line["cpu_baseline"] = {"value": n / (t1 - t0), "unit": "rows/s", "cores": oracle.max_threads(),
+                                "kind": "oracle", "sample": f"first {n} of {rows} row pairs, OpenMP over rows"}
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -181,6 +238,8 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=256,
                     help="sequences the oracle is timed on (cpu_baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kd-rows", type=int, default=None,
+                    help="time respec_kd_rows on this many row pairs instead of the verify step")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -205,6 +264,9 @@ def main():
 
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.kd_rows:
+        run_kd(args, wl, dev)
+        return
     tree = None
     if args.tree:
         depth, branch = (int(x) for x in args.tree.lower().split("x"))

@@ -305,20 +305,19 @@ respec_status_t respec_tree_rejection_sample(const void *target_logits, const vo
  * w_r = row_weight[r] is the weight w(reward) of the sample the row belongs to; the paper's
  * default w(r) = r, its normalisation and its clipping are the caller's (they are not
  * specified).  Rows with weight 0 are not read; their gradient is written as zero.
- * The rows are the [rows, V] logits the sampler reads: both rows are read from memory once and
- * the gradient is written once.
+ * The rows are the [rows, V] logits the sampler reads.  A row pair is streamed twice (once for
+ * its normalisers, once for the gradient) by one work-group; rows are independent.
  *
  *   target_logits, draft_logits [rows, V] logits_dt, row strides ld_t, ld_d elements
  *   row_weight    [rows] f32
  *   grad_draft_logits [rows, V] logits_dt (written; bf16: rounded to nearest even), stride ld_g
  *   row_loss      [rows] f32 (written);  total_loss  [1] f64 or NULL (written)
  *   V * sizeof(element), the strides in bytes and the three base pointers must be multiples of
- *   16 (RESPEC_ERR_UNSUPPORTED otherwise); V at most 327,680 (bf16) or 163,840 (f32).
+ *   16 (RESPEC_ERR_UNSUPPORTED otherwise).
  *   workspace     respec_kd_rows_workspace_bytes(rows, V, logits_dt) bytes, 256-byte aligned,
  *                 scratch (nothing to prepare, nothing survives).
- * The kernel is cooperative: work-groups that share a row wait for each other, so it expects to
- * have the device to itself while it runs; a wait that runs out (a device fault) is reported as
- * NaN in *total_loss and in row_loss.
+ * Asynchronous on hip_stream like every other call; sums are formed in a fixed order, so a call
+ * repeated on the same inputs gives the same bits.
  */
 size_t respec_kd_rows_workspace_bytes(int32_t rows, int32_t V, respec_dtype_t logits_dt);
 respec_status_t respec_kd_rows(const void *target_logits, const void *draft_logits,
