@@ -8,6 +8,7 @@ are resident in HBM before the timed region.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sigma S]
                     [--tree DEPTHxBRANCH] [--page-size P] [--no-cpu-baseline]
     python bench.py --kd-rows N [--workload NAME] [--sigma S]
+    python bench.py --sweep --workload qwen14b_sweep [--sweep-batches 64,256,...] [--sweep-ks 0,1,2,4,8]
 
 --tree times the tree-of-drafts variant of the step on the same workload (every sequence
 drafts a main chain of DEPTH nodes with BRANCH candidates per position); the default is the
@@ -218,55 +219,8 @@ def run_kd(args, wl, dev):
     print(json.dumps(line))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="qwen7b_b256_k3", choices=sorted(synth.WORKLOADS))
-    ap.add_argument("--sigma", type=float, default=None, help="drafter noise (default: workload's)")
-    ap.add_argument("--batch", type=int, default=None, help="override B (sweeps)")
-    ap.add_argument("--k", type=int, default=None, help="override k (sweeps)")
-    ap.add_argument("--tree", default=None, metavar="DEPTHxBRANCH",
-                    help="time the tree-of-drafts entry points: a chain of DEPTH nodes, BRANCH candidates per position")
-    ap.add_argument("--page-size", type=int, default=None,
-                    help="run on a paged KV cache with pages of this many tokens (adds the commit kernel to the step)")
-    ap.add_argument("--probe-every", type=int, default=4,
-                    help="in the timed region, bracket the main attention kernel with events on every n-th step")
-    ap.add_argument("--layers", type=int, default=None,
-                    help="attention layers of the modelled full-depth figure (default: the model's public card)")
-    ap.add_argument("--cpu-seqs", type=int, default=256,
-                    help="sequences the oracle is timed on (cpu_baseline)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kd-rows", type=int, default=None,
-                    help="time respec_kd_rows on this many row pairs instead of the verify step")
-    args = ap.parse_args()
-
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; the verify step shards over sequences with "
-              "no exchange, so --gpus N > 1 is not measured here", file=sys.stderr)
-        sys.exit(2)
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
-        sys.exit(1)
-
-    import dataclasses
-    wl = synth.WORKLOADS[args.workload]
-    changes = {}
-    if args.sigma is not None:
-        changes["sigma"] = args.sigma
-    if args.batch is not None:
-        changes["B"] = args.batch
-    if args.k is not None:
-        changes["k"] = args.k
-    if changes:
-        wl = dataclasses.replace(wl, **changes)
-
-    torch.cuda.set_device(0)
-    dev = torch.device("cuda:0")
-    if args.kd_rows:
-        run_kd(args, wl, dev)
-        return
+def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
+    """Times the verify step on workload `wl`; returns the JSON line as a dict."""
     tree = None
     if args.tree:
         depth, branch = (int(x) for x in args.tree.lower().split("x"))
@@ -420,7 +374,7 @@ def main():
         samp_bytes = sampler_algorithmic_bytes(batch, n_host)
         samp_all_rows = (batch.total_q + batch.total_q - B) * wl.V * esz
     achieved = attn_bytes / (ms_main * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name) if not changes and tree is None and paged is None else None
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name) if not changed and tree is None and paged is None else None
 
     line = {
         "metric": "accepted tokens/s of the SD verify step (tokens emitted per step = accepted "
@@ -474,12 +428,107 @@ def main():
             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
         },
     }
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         line["cpu_baseline"] = (run_cpu_baseline_tree(batch, args.cpu_seqs) if tree is not None
                                 else run_cpu_baseline(batch, args.cpu_seqs))
         if paged is not None:
             line["cpu_baseline"]["note"] = ("timed on the oracle's contiguous-cache functions: its paged form "
                                             "gathers a sequence's pages and calls them")
+    return line
+
+
+def run_sweep(args, wl, dev):
+    """The B x k sweep of the large-batch workload: one verify step timed per (B, k), k = 0 being
+    plain decoding (one row per sequence, one token per step).  Prints one JSON line whose
+    `sweep` list holds a compact record per point."""
+    import dataclasses
+    import gc
+    Bs = [int(x) for x in args.sweep_batches.split(",")]
+    ks = [int(x) for x in args.sweep_ks.split(",")]
+    rows = []
+    for B in Bs:
+        for k in ks:
+            w2 = dataclasses.replace(wl, B=B, k=k)
+            line = bench_verify(args, w2, dev, True, False)
+            rows.append({
+                "B": B, "k": k, "verify_step_us": line["verify_step_us"], "t_attn_us": line["t_attn_us"],
+                "t_samp_us": line["t_samp_us"], "attention_main_us": line["kernel_us"]["attention_main"],
+                "emitted_per_seq": line["emitted_per_seq"], "tokens_per_s": line["value"],
+                "accepted_drafts_per_s": line["accepted_drafts_per_s"],
+                "attention_frac": line["roofline"]["frac"], "step_hbm_frac": line["step_hbm_frac"],
+                "total_kv": line["config"]["total_kv"],
+                "modelled_full_depth_tokens_per_s": line["modelled_full_depth"]["tokens_per_s"],
+                "layers": line["modelled_full_depth"]["layers"],
+            })
+            print("sweep point", json.dumps(rows[-1]), file=sys.stderr, flush=True)
+            del line
+            gc.collect()
+            torch.cuda.empty_cache()
+    out = {"metric": "accepted tokens/s of the SD verify step over the B x k sweep", "unit": "tokens/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": wl.dtype, "data": "synthetic",
+           "config": {"workload": f"{wl.name} swept over B in {Bs} x k in {ks}", "Hq": wl.Hq, "Hkv": wl.Hkv,
+                      "D": wl.D, "V": wl.V, "sigma": wl.sigma, "kv_len": f"{wl.len_dist}[{wl.len_lo},{wl.len_hi}]"},
+           "sweep": rows}
+    print(json.dumps(out))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen7b_b256_k3", choices=sorted(synth.WORKLOADS))
+    ap.add_argument("--sigma", type=float, default=None, help="drafter noise (default: workload's)")
+    ap.add_argument("--batch", type=int, default=None, help="override B (sweeps)")
+    ap.add_argument("--k", type=int, default=None, help="override k (sweeps)")
+    ap.add_argument("--tree", default=None, metavar="DEPTHxBRANCH",
+                    help="time the tree-of-drafts entry points: a chain of DEPTH nodes, BRANCH candidates per position")
+    ap.add_argument("--page-size", type=int, default=None,
+                    help="run on a paged KV cache with pages of this many tokens (adds the commit kernel to the step)")
+    ap.add_argument("--probe-every", type=int, default=4,
+                    help="in the timed region, bracket the main attention kernel with events on every n-th step")
+    ap.add_argument("--layers", type=int, default=None,
+                    help="attention layers of the modelled full-depth figure (default: the model's public card)")
+    ap.add_argument("--cpu-seqs", type=int, default=256,
+                    help="sequences the oracle is timed on (cpu_baseline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the verify step over --sweep-batches x --sweep-ks of the workload (k = 0: plain decoding)")
+    ap.add_argument("--sweep-batches", default="64,256,512,1024")
+    ap.add_argument("--sweep-ks", default="0,1,2,4,8")
+    ap.add_argument("--kd-rows", type=int, default=None,
+                    help="time respec_kd_rows on this many row pairs instead of the verify step")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the verify step shards over sequences with "
+              "no exchange, so --gpus N > 1 is not measured here", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+
+    import dataclasses
+    wl = synth.WORKLOADS[args.workload]
+    changes = {}
+    if args.sigma is not None:
+        changes["sigma"] = args.sigma
+    if args.batch is not None:
+        changes["B"] = args.batch
+    if args.k is not None:
+        changes["k"] = args.k
+    if changes:
+        wl = dataclasses.replace(wl, **changes)
+
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    if args.kd_rows:
+        run_kd(args, wl, dev)
+        return
+    if args.sweep:
+        run_sweep(args, wl, dev)
+        return
+    line = bench_verify(args, wl, dev, bool(changes), not args.no_cpu_baseline)
     print(json.dumps(line))
 
 

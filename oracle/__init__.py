@@ -48,6 +48,11 @@ def _load():
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
             c.c_void_p, c.c_void_p, c.c_void_p,
             c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_double, c.c_int, c.c_int]
+        lib.respec_oracle_rejection_sample_per_seq.restype = c.c_int
+        lib.respec_oracle_rejection_sample_per_seq.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_void_p, c.c_void_p, c.c_void_p,
+            c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_int, c.c_int]
         lib.respec_oracle_verify_attention_tree.restype = c.c_int
         lib.respec_oracle_verify_attention_tree.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -281,6 +286,42 @@ def rejection_sample(target_logits, draft_logits, draft_tokens, q_indptr, u_acce
         B, max_k, V, V, V, float(np.float32(temperature)), dtype, n_threads)
     if rc != 0:
         raise RuntimeError(f"respec_oracle_rejection_sample failed with code {rc}")
+    return out_tokens, num_accepted, flags
+
+
+def rejection_sample_per_seq(target_logits, draft_logits, draft_tokens, q_indptr, u_accept, u_final,
+                             max_k, temperatures, dtype, n_threads=1):
+    """As ``rejection_sample`` with one binary32 temperature per sequence; 0 selects greedy
+    verification (accept iff the drafted token is the target row's first argmax)."""
+    target_logits = _check_elems(target_logits, dtype, "target_logits")
+    q_indptr = np.ascontiguousarray(q_indptr, dtype=np.int32)
+    B = q_indptr.shape[0] - 1
+    V = target_logits.shape[-1]
+    assert target_logits.ndim == 2 and target_logits.shape[0] == int(q_indptr[-1])
+    n_draft = int(q_indptr[-1]) - B
+    if n_draft > 0:
+        draft_tokens = np.ascontiguousarray(draft_tokens, dtype=np.int32)
+        assert draft_tokens.shape == (n_draft,)
+        if draft_logits is not None:
+            draft_logits = _check_elems(draft_logits, dtype, "draft_logits")
+            assert draft_logits.shape == (n_draft, V)
+        if u_accept is not None:
+            u_accept = np.ascontiguousarray(u_accept, dtype=np.float32)
+            assert u_accept.shape == (n_draft,)
+    else:
+        draft_logits = draft_tokens = u_accept = None
+    u_final = np.ascontiguousarray(u_final, dtype=np.float32)
+    temperatures = np.ascontiguousarray(temperatures, dtype=np.float32)
+    assert u_final.shape == (B,) and temperatures.shape == (B,)
+    out_tokens = np.empty((B, max_k + 1), dtype=np.int32)
+    num_accepted = np.empty((B,), dtype=np.int32)
+    flags = np.empty((B,), dtype=np.int32)
+    rc = _load().respec_oracle_rejection_sample_per_seq(
+        _ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens), _ptr(q_indptr), _ptr(u_accept),
+        _ptr(u_final), _ptr(temperatures), _ptr(out_tokens), _ptr(num_accepted), _ptr(flags),
+        B, max_k, V, V, V, dtype, n_threads)
+    if rc != 0:
+        raise RuntimeError(f"respec_oracle_rejection_sample_per_seq failed with code {rc}")
     return out_tokens, num_accepted, flags
 
 

@@ -29,6 +29,9 @@
  *   KD rows     -- scipy's rel_entr, torch autograd of kl_div over log_softmax in fp64,
  *                 central differences of an independently written loss, q == p gives
  *                 zero loss and gradient, gradient rows sum to zero, a two-token closed form.
+ *   greedy / per-sequence temperature -- numpy's argmax (first maximum) row by row,
+ *                 the T -> 0 limit of the stochastic function on well separated logits,
+ *                 a mixed batch against the one-temperature function sequence by sequence.
  *   tree sampler -- a chain-shaped tree reproduces the chain function exactly, a
  *                 hand-worked case (tests/golden/tree_hand_case.json), chi-square of
  *                 the emitted token against p with three sibling candidates, the
@@ -483,6 +486,107 @@ int respec_oracle_rejection_sample(const void *target_logits, const void *draft_
             target_logits, draft_logits, draft_tokens, row0, row0 - b, k, u_accept, u_final[b],
             out_tokens + (int64_t)b * (max_k + 1), out_num_accepted + b,
             out_flags ? out_flags + b : NULL, max_k, V, ld_t, ld_d, temperature, dtype);
+        if (rc != ORACLE_OK) {
+#pragma omp critical
+            status = rc;
+        }
+    }
+    return status;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Greedy verification and one temperature per sequence.                       */
+/* The paper runs its tasks at different sampling temperatures (Table 2) and   */
+/* a rollout batch can mix them; temperature 0 means greedy decoding.  As T    */
+/* goes to 0, softmax(z/T) tends to a point mass on the largest logit, so      */
+/* Eq. 1 becomes "accept the drafted token iff it is the target's argmax" and  */
+/* Eq. 2 becomes "replace it by the target's argmax"; the bonus token is the   */
+/* argmax of row k_b.  Reading for ties (equal largest logits): the token with */
+/* the lowest id counts as the argmax, and only that one is accepted.  No      */
+/* uniform is read and no flag is raised for a greedy sequence.                */
+/* ------------------------------------------------------------------------- */
+static int32_t argmax_row(const void *logits, int64_t row, int64_t ld, int32_t V, int dtype)
+{
+    int32_t best = 0;
+    double zbest = load_elem(logits, row * ld, dtype);
+    for (int32_t x = 1; x < V; ++x) {
+        const double z = load_elem(logits, row * ld + x, dtype);
+        if (z > zbest) {
+            zbest = z;
+            best = x;
+        }
+    }
+    return best;
+}
+
+static int greedy_one_sequence(const void *target_logits, const int32_t *draft_tokens, int32_t row0,
+                               int32_t drow0, int32_t k, int32_t *out_tokens, int32_t *out_num_accepted,
+                               int32_t *out_flags, int32_t max_k, int32_t V, int64_t ld_t, int dtype)
+{
+    for (int32_t j = 0; j <= max_k; ++j)
+        out_tokens[j] = -1;
+    int32_t n = 0;
+    while (n < k) {
+        const int32_t x = draft_tokens[drow0 + n];
+        if (x < 0 || x >= V)
+            return ORACLE_ERR_DATA;
+        if (x != argmax_row(target_logits, row0 + n, ld_t, V, dtype))
+            break;
+        out_tokens[n] = x;
+        ++n;
+    }
+    /* the replacement of the first rejected draft, or the bonus token: the argmax of row n */
+    out_tokens[n] = argmax_row(target_logits, row0 + n, ld_t, V, dtype);
+    *out_num_accepted = n;
+    if (out_flags)
+        *out_flags = 0;
+    return ORACLE_OK;
+}
+
+/* As respec_oracle_rejection_sample, with temperature[b] per sequence; 0 selects greedy. */
+int respec_oracle_rejection_sample_per_seq(const void *target_logits, const void *draft_logits,
+                                           const int32_t *draft_tokens, const int32_t *q_indptr,
+                                           const float *u_accept, const float *u_final,
+                                           const float *temperature, int32_t *out_tokens,
+                                           int32_t *out_num_accepted, int32_t *out_flags, int32_t B,
+                                           int32_t max_k, int32_t V, int64_t ld_t, int64_t ld_d,
+                                           int dtype, int n_threads)
+{
+    if (!target_logits || !q_indptr || !u_final || !temperature || !out_tokens || !out_num_accepted)
+        return ORACLE_ERR_ARG;
+    if (B <= 0 || V <= 0 || max_k < 0 || ld_t < V)
+        return ORACLE_ERR_ARG;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16)
+        return ORACLE_ERR_ARG;
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t k = q_indptr[b + 1] - q_indptr[b] - 1;
+        if (k < 0 || k > max_k)
+            return ORACLE_ERR_DATA;
+        if (!(temperature[b] >= 0.0f) || isinf(temperature[b]))
+            return ORACLE_ERR_DATA;
+        if (k > 0 && !draft_tokens)
+            return ORACLE_ERR_ARG;
+        if (k > 0 && temperature[b] > 0.0f && (!draft_logits || !u_accept || ld_d < V))
+            return ORACLE_ERR_ARG;
+    }
+    int status = ORACLE_OK;
+    const int nt = pick_threads(n_threads);
+    (void)nt;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nt)
+    for (int32_t b = 0; b < B; ++b) {
+        const int32_t row0 = q_indptr[b];
+        const int32_t k = q_indptr[b + 1] - row0 - 1;
+        int32_t *toks = out_tokens + (int64_t)b * (max_k + 1);
+        int rc;
+        if (temperature[b] == 0.0f)
+            rc = greedy_one_sequence(target_logits, draft_tokens, row0, row0 - b, k, toks,
+                                     out_num_accepted + b, out_flags ? out_flags + b : NULL, max_k, V,
+                                     ld_t, dtype);
+        else
+            rc = sample_one_sequence(target_logits, draft_logits, draft_tokens, row0, row0 - b, k,
+                                     u_accept, u_final[b], toks, out_num_accepted + b,
+                                     out_flags ? out_flags + b : NULL, max_k, V, ld_t, ld_d,
+                                     (double)temperature[b], dtype);
         if (rc != ORACLE_OK) {
 #pragma omp critical
             status = rc;
