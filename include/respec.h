@@ -10,7 +10,8 @@
  *
  *   respec_verify_attention   the attention of that forward: (k_b+1) causal query rows per
  *                             sequence, grouped-query heads, ragged per-sequence KV cache;
- *   respec_rejection_sample   Eq. 1 / Eq. 2 over the vocabulary with supplied uniforms;
+ *   respec_rejection_sample   Eq. 1 / Eq. 2 over the vocabulary with supplied uniforms
+ *                             (respec_rejection_sample_per_seq: one temperature per sequence, 0 = greedy);
  * their counterparts for a tree of drafts (Section 3.1), respec_verify_attention_tree and
  * respec_tree_rejection_sample, the paged-cache forms respec_verify_attention_paged and
  * respec_commit_accepted_paged, and respec_kd_rows, the drafter's distillation loss over the
@@ -250,6 +251,35 @@ respec_status_t respec_rejection_sample(const void *target_logits, const void *d
                                         float temperature, respec_dtype_t logits_dt,
                                         void *workspace, size_t workspace_bytes,
                                         void *hip_stream);
+
+/*
+ * respec_rejection_sample with one temperature per sequence, temperature 0 meaning greedy
+ * verification.  The paper runs its tasks at different sampling temperatures (Table 2); a
+ * rollout batch can mix them, and evaluation decodes greedily.  For temperature[b] > 0 the
+ * sequence is handled exactly as by respec_rejection_sample at that temperature (Section 2.2,
+ * Eq. 1 and Eq. 2).  For temperature[b] == 0, the limit of the same rule: softmax(z/T) tends to
+ * a point mass on the largest logit, so a drafted token is accepted iff it is the argmax of its
+ * target row, the first one that is not is replaced by that argmax, and if all are accepted
+ * the bonus token is the argmax of row k_b.  Among equal largest logits the lowest token id is
+ * the argmax (and the only one accepted).  A greedy sequence reads target rows 0..n_b only, no
+ * drafter logits and no uniforms; its flags are 0.
+ *
+ *   temperature   [B] f32, device; each finite and >= 0
+ *   draft_logits, u_accept   may be NULL when every sequence with drafted tokens is greedy
+ *   other arguments as in respec_rejection_sample; there is no workspace (a sequence is
+ *   handled by one work-group).
+ * Device-side data errors that the host cannot see (a negative or non-finite temperature, a
+ * sampled sequence with drafted tokens but draft_logits or u_accept NULL) give
+ * out_num_accepted[b] = -1 and out_tokens[b, :] = -1 for that sequence.
+ */
+respec_status_t respec_rejection_sample_per_seq(const void *target_logits, const void *draft_logits,
+                                                const int32_t *draft_tokens, const int32_t *q_indptr,
+                                                const float *u_accept, const float *u_final,
+                                                const float *temperature, int32_t *out_tokens,
+                                                int32_t *out_num_accepted, int32_t *out_flags,
+                                                int32_t B, int32_t total_q, int32_t max_k, int32_t V,
+                                                int64_t ld_t, int64_t ld_d, respec_dtype_t logits_dt,
+                                                void *hip_stream);
 
 /*
  * Rejection sampling over a tree of drafts (Section 3.1: candidate branches with branching

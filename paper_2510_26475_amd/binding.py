@@ -73,6 +73,11 @@ def load():
         c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64,
         c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_rejection_sample_per_seq.restype = c.c_int
+    lib.respec_rejection_sample_per_seq.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_int, c.c_void_p]
     lib.respec_tree_rejection_sample.restype = c.c_int
     lib.respec_tree_rejection_sample.argtypes = [
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -103,7 +108,7 @@ def load():
 EXPORTED_SYMBOLS = [
     "respec_status_string", "respec_last_error", "respec_version",
     "respec_verify_attention_workspace_bytes", "respec_verify_attention", "respec_verify_attention_tree",
-    "respec_rejection_sample_workspace_bytes", "respec_rejection_sample",
+    "respec_rejection_sample_workspace_bytes", "respec_rejection_sample", "respec_rejection_sample_per_seq",
     "respec_tree_rejection_sample", "respec_verify_attention_paged", "respec_commit_accepted_paged",
     "respec_kd_rows_workspace_bytes", "respec_kd_rows",
     "respec_profile_mark_main",
@@ -257,6 +262,55 @@ def respec_rejection_sample(target_logits, draft_logits, draft_tokens, q_indptr,
         _dev_ptr(out_tokens, "out_tokens"), _dev_ptr(out_num_accepted, "out_num_accepted"),
         _dev_ptr(out_flags, "out_flags"), B, total_q, max_k, V, target_logits.stride(0), ld_d,
         float(temperature), _dtype_code(target_logits), ws_ptr, ws_bytes, _stream_ptr(stream)))
+
+
+def respec_rejection_sample_per_seq(target_logits, draft_logits, draft_tokens, q_indptr, u_accept, u_final,
+                                    temperatures, out_tokens, out_num_accepted, out_flags, max_k, stream=None):
+    """respec_rejection_sample with temperatures [B] float32 on the device (0 = greedy).
+    draft_logits and u_accept may be None when every sequence that has drafts is greedy."""
+    lib = load()
+    total_q, V = target_logits.shape
+    B = q_indptr.numel() - 1
+    if q_indptr.dtype != torch.int32:
+        raise TypeError("q_indptr must be int32")
+    if out_tokens.dtype != torch.int32 or out_num_accepted.dtype != torch.int32:
+        raise TypeError("out_tokens and out_num_accepted must be int32")
+    if tuple(out_tokens.shape) != (B, max_k + 1) or out_num_accepted.numel() != B:
+        raise ValueError("out_tokens must be [B, max_k+1] and out_num_accepted [B]")
+    if u_final.dtype != torch.float32 or u_final.numel() != B:
+        raise TypeError("u_final must be float32 [B]")
+    if temperatures.dtype != torch.float32 or temperatures.numel() != B:
+        raise TypeError("temperatures must be float32 [B]")
+    n_draft = total_q - B
+    ld_d = V
+    if n_draft > 0:
+        if draft_tokens.dtype != torch.int32 or draft_tokens.numel() != n_draft:
+            raise TypeError("draft_tokens must be int32 [total_q-B]")
+        if draft_logits is not None:
+            if draft_logits.dtype != target_logits.dtype or tuple(draft_logits.shape) != (n_draft, V):
+                raise ValueError("draft_logits must be [total_q-B, V] in the target's dtype")
+            ld_d = draft_logits.stride(0)
+        if u_accept is not None and (u_accept.dtype != torch.float32 or u_accept.numel() != n_draft):
+            raise TypeError("u_accept must be float32 [total_q-B]")
+    else:
+        draft_logits = draft_tokens = u_accept = None
+    if target_logits.stride(1) != 1:
+        raise ValueError("logits rows must be unit-stride")
+
+    def row_ptr(t, name):
+        if t is None:
+            return None
+        if not t.is_cuda:
+            raise ValueError(f"{name} must live on the GPU")
+        return ctypes.c_void_p(t.data_ptr())
+
+    _check(lib.respec_rejection_sample_per_seq(
+        row_ptr(target_logits, "target_logits"), row_ptr(draft_logits, "draft_logits"),
+        _dev_ptr(draft_tokens, "draft_tokens"), _dev_ptr(q_indptr, "q_indptr"),
+        _dev_ptr(u_accept, "u_accept"), _dev_ptr(u_final, "u_final"), _dev_ptr(temperatures, "temperatures"),
+        _dev_ptr(out_tokens, "out_tokens"), _dev_ptr(out_num_accepted, "out_num_accepted"),
+        _dev_ptr(out_flags, "out_flags"), B, total_q, max_k, V, target_logits.stride(0), ld_d,
+        _dtype_code(target_logits), _stream_ptr(stream)))
 
 
 def respec_tree_rejection_sample(target_logits, draft_logits, node_tokens, parent, q_indptr, u_accept,

@@ -43,6 +43,7 @@ struct SamplerParams : RowMath {
     int64_t ld_t, ld_d;
     int split;         // work-groups per sequence (1 when there is no workspace)
     char *boxes;       // [B] mailboxes of kBoxBytes (split > 1)
+    const float *temps;  // [B] one temperature per sequence (0: greedy), or NULL: the RowMath constants hold
 };
 
 
@@ -442,6 +443,123 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     return tok;
 }
 
+// ------------------------------------------------------------------------------------------
+// one temperature per sequence; temperature 0 = greedy verification
+// ------------------------------------------------------------------------------------------
+// The exponent constants of one sequence, formed on the device as set_row_math forms them on
+// the host (IEEE double division and conversions are the same on both).
+__device__ inline void device_row_math(RowMath &m, float temperature) {
+    const double T = (double)temperature;
+    m.c_d = 1.4426950408889634074 / T;
+    float c_hi = (float)m.c_d;
+    if ((double)c_hi >= m.c_d) c_hi = __uint_as_float(__float_as_uint(c_hi) - 1u);  // next binary32 towards 0
+    m.c_hi = c_hi;
+    m.c_lo = (float)(m.c_d - (double)c_hi);
+    m.c_f = (float)m.c_d;
+    m.one_term = 0;
+    m.inv_T = 1.0 / T;
+    m.gap = (float)(40.0 / m.c_d);
+}
+
+// The first argmax of a row: its largest logit, the lowest token id among equal ones (an
+// all -inf row gives token 0).  Every thread returns the same value.  Ends with a barrier.
+template <bool BF16, bool FULL>
+__device__ inline int row_argmax(const void *row, int nslots, int V, bool aligned, SharedState &sh) {
+    constexpr int EPV = Elem<BF16>::EPV;
+    constexpr int kBatch = kThreads * kUnroll;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n_iter = (nslots + kBatch - 1) / kBatch;
+    auto load_batch = [&](int it, u32x4 (&v)[kUnroll]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int slot = it * kBatch + u * kThreads + (int)threadIdx.x;
+            const bool in = slot < nslots;
+            const u32x4 a = load_slot<BF16, FULL>(row, in ? slot : 0, V, aligned);
+            v[u] = in ? a : neg_inf_slot<BF16>();
+        }
+    };
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+    u32x4 v[kUnroll];
+    load_batch(0, v);
+    for (int it = 0; it < n_iter; ++it) {
+        u32x4 nv[kUnroll];
+        const bool more = it + 1 < n_iter;  // block-uniform
+        if (more) load_batch(it + 1, nv);   // in flight while this batch is compared
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            float z[EPV];
+            unpack<BF16>(v[u], z);
+            const int e0 = (it * kBatch + u * kThreads + (int)threadIdx.x) * EPV;
+#pragma unroll
+            for (int j = 0; j < EPV; ++j)  // ascending ids within a thread: strict > keeps the first
+                if (z[j] > best) {
+                    best = z[j];
+                    best_i = e0 + j;
+                }
+        }
+        if (more) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) v[u] = nv[u];
+        }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const float ob = __shfl_xor(best, o);
+        const int oi = __shfl_xor(best_i, o);
+        if (ob > best || (ob == best && oi < best_i)) {
+            best = ob;
+            best_i = oi;
+        }
+    }
+    if (lane == 0) {
+        sh.arg_val[wave] = best;
+        sh.arg_idx[wave] = best_i;
+    }
+    __syncthreads();
+    best = sh.arg_val[0];
+    best_i = sh.arg_idx[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+        const float ob = sh.arg_val[w];
+        const int oi = sh.arg_idx[w];
+        if (ob > best || (ob == best && oi < best_i)) {
+            best = ob;
+            best_i = oi;
+        }
+    }
+    __syncthreads();  // everyone has read the wave results before the next row overwrites them
+    return best_i == 0x7fffffff ? 0 : best_i;
+}
+
+// Greedy verification of one sequence (the T -> 0 limit of Eq. 1 and Eq. 2): a drafted token is
+// accepted iff it is the first argmax of its target row; the first one that is not is replaced
+// by that argmax; if all are accepted the bonus token is the argmax of row k.  Reads target
+// rows 0..n only, no drafter logits and no uniforms.
+template <bool BF16, bool FULL>
+__device__ inline void greedy_sequence(const SamplerParams &p, int b, int row0, int drow0, int k, SharedState &sh) {
+    constexpr int EPV = Elem<BF16>::EPV;
+    const int nslots = (p.V + EPV - 1) / EPV;
+    const size_t esz = BF16 ? 2 : 4;
+    int32_t *out = p.out_tokens + (size_t)b * (p.max_k + 1);
+    int n = 0, a;
+    for (;;) {
+        const char *rowp = static_cast<const char *>(p.target) + (size_t)(row0 + n) * p.ld_t * esz;
+        a = row_argmax<BF16, FULL>(rowp, nslots, p.V, p.aligned != 0, sh);
+        if (n >= k) break;
+        const int x = p.draft_tokens[drow0 + n];
+        if (x != a) break;
+        if (threadIdx.x == 0) out[n] = x;
+        ++n;
+    }
+    if (threadIdx.x == 0) {
+        out[n] = a;
+        for (int j = n + 1; j <= p.max_k; ++j) out[j] = -1;
+        p.out_num_accepted[b] = n;
+        if (p.out_flags) p.out_flags[b] = 0;
+    }
+}
+
 template <bool BF16, bool ONE_TERM, bool FULL, bool SHARED>
 __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParams p) {
     __shared__ SharedState sh;
@@ -466,6 +584,26 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     const char *tbase = static_cast<const char *>(p.target);
     const char *dbase = static_cast<const char *>(p.draft);
     int32_t *out = p.out_tokens + (size_t)b * (p.max_k + 1);
+    if constexpr (!SHARED && !ONE_TERM) {
+        if (p.temps != nullptr) {  // block-uniform
+            const float T = p.temps[b];
+            const bool bad = !(T >= 0.f) || T == INFINITY ||
+                             (T > 0.f && k > 0 && (p.draft == nullptr || p.u_accept == nullptr));
+            if (bad) {  // a caller error: make it impossible to miss
+                if (threadIdx.x == 0) {
+                    for (int j = 0; j <= p.max_k; ++j) out[j] = -1;
+                    p.out_num_accepted[b] = -1;
+                    if (p.out_flags) p.out_flags[b] = 0;
+                }
+                return;
+            }
+            if (T == 0.f) {
+                greedy_sequence<BF16, FULL>(p, b, row0, drow0, k, sh);
+                return;
+            }
+            device_row_math(p, T);
+        }
+    }
     const double u_fin = (double)p.u_final[b];
 
     Mailbox mb{nullptr, nullptr, 0u, part, split, 0};
@@ -571,48 +709,40 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     }
 }
 
-}  // namespace
-}  // namespace respec
-
-extern "C" {
-
-size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t, int32_t, respec_dtype_t) {
-    return B > 0 ? (size_t)B * respec::kBoxBytes : 0;
-}
-
-respec_status_t respec_rejection_sample(const void *target_logits, const void *draft_logits,
-                                        const int32_t *draft_tokens, const int32_t *q_indptr,
-                                        const float *u_accept, const float *u_final,
-                                        int32_t *out_tokens, int32_t *out_num_accepted,
-                                        int32_t *out_flags, int32_t B, int32_t total_q,
-                                        int32_t max_k, int32_t V, int64_t ld_t, int64_t ld_d,
-                                        float temperature, respec_dtype_t logits_dt,
-                                        void *workspace, size_t workspace_bytes,
-                                        void *hip_stream) {
-    using namespace respec;
+// Both entry points: `temps` NULL = one temperature for the batch (`temperature`), else one per
+// sequence on the device (no workspace then: a sequence has one work-group).
+respec_status_t sample_common(const void *target_logits, const void *draft_logits, const int32_t *draft_tokens,
+                              const int32_t *q_indptr, const float *u_accept, const float *u_final,
+                              int32_t *out_tokens, int32_t *out_num_accepted, int32_t *out_flags, int32_t B,
+                              int32_t total_q, int32_t max_k, int32_t V, int64_t ld_t, int64_t ld_d,
+                              float temperature, const float *temps, respec_dtype_t logits_dt, void *workspace,
+                              size_t workspace_bytes, void *hip_stream) {
     if (B <= 0 || total_q < B || max_k < 0 || V <= 0)
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: need B > 0, total_q >= B, max_k >= 0, V > 0 "
                     "(B=%d total_q=%d max_k=%d V=%d)", B, total_q, max_k, V);
-    if (!(temperature > 0.f) || !std::isfinite(temperature))
+    if (!temps && (!(temperature > 0.f) || !std::isfinite(temperature)))
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: temperature must be finite and > 0");
     if (logits_dt != RESPEC_F32 && logits_dt != RESPEC_BF16)
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: unknown logits dtype %d", (int)logits_dt);
     if (!target_logits || !q_indptr || !u_final || !out_tokens || !out_num_accepted)
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: null pointer argument");
     const bool has_drafts = total_q > B;
-    if (has_drafts && (!draft_logits || !draft_tokens || !u_accept))
+    // with one temperature per sequence a batch may be all greedy: then only the drafted tokens are read
+    if (has_drafts && (!draft_tokens || (!temps && (!draft_logits || !u_accept))))
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: drafted tokens present but a draft pointer is null");
+    if (has_drafts && !draft_logits) ld_d = ld_t;
     if (ld_t < V || (has_drafts && ld_d < V))
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: row stride smaller than V");
     if ((int64_t)max_k * B < (int64_t)total_q - B)
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: max_k too small for total_q");
     const size_t esz = logits_dt == RESPEC_BF16 ? 2 : 4;
-    if (!aligned_to(target_logits, esz) || (has_drafts && !aligned_to(draft_logits, esz)))
+    if (!aligned_to(target_logits, esz) || (has_drafts && draft_logits && !aligned_to(draft_logits, esz)))
         return fail(RESPEC_ERR_INVALID_ARG, "rejection_sample: logits pointer not element aligned");
 
     SamplerParams p{};
     p.target = target_logits;
     p.draft = has_drafts ? draft_logits : target_logits;
+    p.temps = temps;
     p.draft_tokens = draft_tokens;
     p.q_indptr = q_indptr;
     p.u_accept = u_accept;
@@ -626,9 +756,10 @@ respec_status_t respec_rejection_sample(const void *target_logits, const void *d
     p.V = V;
     p.ld_t = ld_t;
     p.ld_d = has_drafts ? ld_d : ld_t;
-    set_row_math(p, temperature);
+    set_row_math(p, temps ? 1.0f : temperature);
+    if (temps) p.one_term = 0;  // the per-sequence constants are formed on the device, two-term
     p.aligned = aligned_to(target_logits, 16) && (ld_t * esz) % 16 == 0 &&
-                (!has_drafts || (aligned_to(draft_logits, 16) && (ld_d * esz) % 16 == 0));
+                (!has_drafts || !draft_logits || (aligned_to(draft_logits, 16) && (ld_d * esz) % 16 == 0));
 
     // work-groups per sequence: as many as there are otherwise idle compute units, as long as a
     // part keeps a useful share of the row; one (and no mailbox) without a workspace
@@ -676,6 +807,43 @@ respec_status_t respec_rejection_sample(const void *target_logits, const void *d
         return fail(RESPEC_ERR_HIP, "rejection_sample: launch failed: %s", hipGetErrorString(err));
     clear_error();
     return RESPEC_OK;
+}
+
+}  // namespace
+}  // namespace respec
+
+extern "C" {
+
+size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t, int32_t, respec_dtype_t) {
+    return B > 0 ? (size_t)B * respec::kBoxBytes : 0;
+}
+
+respec_status_t respec_rejection_sample(const void *target_logits, const void *draft_logits,
+                                        const int32_t *draft_tokens, const int32_t *q_indptr,
+                                        const float *u_accept, const float *u_final,
+                                        int32_t *out_tokens, int32_t *out_num_accepted,
+                                        int32_t *out_flags, int32_t B, int32_t total_q,
+                                        int32_t max_k, int32_t V, int64_t ld_t, int64_t ld_d,
+                                        float temperature, respec_dtype_t logits_dt,
+                                        void *workspace, size_t workspace_bytes,
+                                        void *hip_stream) {
+    return respec::sample_common(target_logits, draft_logits, draft_tokens, q_indptr, u_accept, u_final, out_tokens,
+                                 out_num_accepted, out_flags, B, total_q, max_k, V, ld_t, ld_d, temperature, nullptr,
+                                 logits_dt, workspace, workspace_bytes, hip_stream);
+}
+
+respec_status_t respec_rejection_sample_per_seq(const void *target_logits, const void *draft_logits,
+                                                const int32_t *draft_tokens, const int32_t *q_indptr,
+                                                const float *u_accept, const float *u_final,
+                                                const float *temperature, int32_t *out_tokens,
+                                                int32_t *out_num_accepted, int32_t *out_flags, int32_t B,
+                                                int32_t total_q, int32_t max_k, int32_t V, int64_t ld_t,
+                                                int64_t ld_d, respec_dtype_t logits_dt, void *hip_stream) {
+    if (!temperature)
+        return respec::fail(RESPEC_ERR_INVALID_ARG, "rejection_sample_per_seq: null temperature array");
+    return respec::sample_common(target_logits, draft_logits, draft_tokens, q_indptr, u_accept, u_final, out_tokens,
+                                 out_num_accepted, out_flags, B, total_q, max_k, V, ld_t, ld_d, 1.0f, temperature,
+                                 logits_dt, nullptr, 0, hip_stream);
 }
 
 }  // extern "C"

@@ -193,6 +193,8 @@ struct SharedState {
     float comb_m[2];                       // combined (M, S) of the p row and the q row
     double comb_s[2];
     int failed;                            // a bounded wait for a partner ran out
+    float arg_val[kWaves];                 // per-wave (largest logit, its first token) of an argmax pass
+    int arg_idx[kWaves];
     int token;
     int near_edge;
     int last_positive;
