@@ -335,3 +335,46 @@ def softmax_rows(logits, temperature, dtype):
     if rc != 0:
         raise RuntimeError(f"respec_oracle_softmax_rows failed with code {rc}")
     return out
+
+
+def solver_pick(points, active_batch, draft_us_fixed, draft_us_per_seq):
+    """The Solver's choice of the draft length for one active batch size, from a profile table
+    (Section 4.2, "Solver: Offline Profiling Guided Search") under the cost model of Eq. 4.
+
+    ``points``: iterable of (batch, k, step_us, emitted_per_seq) measured offline; k = 0 is plain
+    decoding.  For every k in the table the step time and the emitted tokens per sequence at
+    ``active_batch`` are interpolated linearly between the profiled batch sizes (end values
+    outside their range).  Eq. 4's cost per produced token, with the measured quantities in the
+    place of its symbols: (k * C_q + k * C_p / alpha) / (r * k)  ->
+    (k * draft_us + step_us_k) / emitted_k, draft_us = draft_us_fixed + draft_us_per_seq * batch.
+    Returns (best_k, speedup over k = 0, cost of best_k, {k: cost}); ties go to the smaller k.
+    Plain Python, for small tables.
+    """
+    by_k = {}
+    for (B, k, t, e) in points:
+        by_k.setdefault(int(k), []).append((float(B), float(t), float(e)))
+    if 0 not in by_k:
+        raise ValueError("the profile needs the plain-decoding points (k = 0)")
+    b = float(active_batch)
+    draft = float(draft_us_fixed) + float(draft_us_per_seq) * b
+
+    def interp(rows, col):
+        rows = sorted(rows)
+        if b <= rows[0][0]:
+            return rows[0][col]
+        if b >= rows[-1][0]:
+            return rows[-1][col]
+        for lo, hi in zip(rows[:-1], rows[1:]):
+            if lo[0] <= b <= hi[0]:
+                if hi[0] == lo[0]:
+                    return lo[col]
+                w = (b - lo[0]) / (hi[0] - lo[0])
+                return lo[col] + w * (hi[col] - lo[col])
+        raise AssertionError
+
+    cost = {}
+    for k, rows in by_k.items():
+        t, e = interp(rows, 1), interp(rows, 2)
+        cost[k] = (k * draft + t) / e
+    best = min(sorted(cost), key=lambda k: (cost[k], k))
+    return best, cost[0] / cost[best], cost[best], cost
