@@ -437,6 +437,22 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
     return line
 
 
+def solver_table(rows, ratios=(0.02, 0.05, 0.1, 0.25)):
+    """The Solver's table from a sweep: for every profiled batch size and every drafter cost
+    (one drafter step = ratio x the plain decoding step at that batch), the draft length that
+    respec_solver_pick chooses and the speedup it predicts.  Times are the MODELLED full-depth
+    step, layers x attention + sampler (this path has no GEMMs)."""
+    pts = [(r["B"], r["k"], r["layers"] * r["t_attn_us"] + r["t_samp_us"], r["emitted_per_seq"]) for r in rows]
+    table = []
+    for B in sorted({r["B"] for r in rows}):
+        decode_us = next(t for (b, k, t, e) in pts if b == B and k == 0)
+        for ratio in ratios:
+            best, speedup, cost = binding.respec_solver_pick(pts, B, ratio * decode_us, 0.0)
+            table.append({"B": B, "draft_cost_ratio": ratio, "best_k": best, "predicted_speedup": speedup,
+                          "cost_us_per_token": cost})
+    return table
+
+
 def run_sweep(args, wl, dev):
     """The B x k sweep of the large-batch workload: one verify step timed per (B, k), k = 0 being
     plain decoding (one row per sequence, one token per step).  Prints one JSON line whose
@@ -468,7 +484,10 @@ def run_sweep(args, wl, dev):
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": wl.dtype, "data": "synthetic",
            "config": {"workload": f"{wl.name} swept over B in {Bs} x k in {ks}", "Hq": wl.Hq, "Hkv": wl.Hkv,
                       "D": wl.D, "V": wl.V, "sigma": wl.sigma, "kv_len": f"{wl.len_dist}[{wl.len_lo},{wl.len_hi}]"},
-           "sweep": rows}
+           "sweep": rows,
+           "solver": {"note": "respec_solver_pick on this sweep; step time MODELLED as layers x attention + sampler, "
+                              "one drafter step = draft_cost_ratio x the plain decoding step",
+                      "table": solver_table(rows) if any(r["k"] == 0 for r in rows) else None}}
     print(json.dumps(out))
 
 

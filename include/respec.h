@@ -14,8 +14,8 @@
  *                             (respec_rejection_sample_per_seq: one temperature per sequence, 0 = greedy);
  * their counterparts for a tree of drafts (Section 3.1), respec_verify_attention_tree and
  * respec_tree_rejection_sample, the paged-cache forms respec_verify_attention_paged and
- * respec_commit_accepted_paged, and respec_kd_rows, the drafter's distillation loss over the
- * same logits rows (Section 5.3).
+ * respec_commit_accepted_paged, respec_kd_rows, the drafter's distillation loss over the
+ * same logits rows (Section 5.3), and respec_solver_pick, the Solver's table look-up (host code).
  *
  * General rules
  *   - Every data pointer is a DEVICE pointer (HIP global memory) unless it says "host".
@@ -355,6 +355,41 @@ respec_status_t respec_kd_rows(const void *target_logits, const void *draft_logi
                                double *total_loss, int32_t rows, int32_t V, int64_t ld_t, int64_t ld_d,
                                int64_t ld_g, respec_dtype_t logits_dt, void *workspace,
                                size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The Solver's choice of the draft length for the current active batch size (Section 4.2,
+ * "Solver: Offline Profiling Guided Search": configurations are profiled offline per batch
+ * size, a performance model predicts the speedup, and at run time the configuration with the
+ * best prediction for the observed active batch size is selected).  HOST code: every pointer
+ * is a host pointer, nothing touches the GPU.
+ *
+ * `points` is the offline profile: one entry per (batch size, draft length) that was timed,
+ * k = 0 being plain decoding (required).  The model is piecewise linear: for every k the step
+ * time and the emitted tokens per sequence at `active_batch` are interpolated between the
+ * profiled batch sizes (the end values hold outside their range).  The choice minimises the
+ * cost per produced token of Eq. 4, (k C_q + k C_p / alpha) / (r k), with measured quantities
+ * in the place of its symbols: k C_p / alpha is the verify step's time at (batch, k), r k the
+ * tokens a step emits per sequence, C_q = draft_us_fixed + draft_us_per_seq * active_batch the
+ * time of one drafter step:
+ *     cost(k) = (k * C_q + step_us(batch, k)) / emitted_per_seq(batch, k).
+ * Ties go to the smaller k.
+ *
+ *   best_k    (written) the chosen draft length; 0 = speculation off
+ *   speedup   (written, or NULL) cost(0) / cost(best_k), >= 1
+ *   cost_us   (written, or NULL) cost(best_k)
+ * RESPEC_ERR_INVALID_ARG: empty table, no k = 0 point, a non-positive or non-finite entry.
+ */
+typedef struct {
+    int32_t batch;           /* sequences in the profiled batch */
+    int32_t k;               /* drafted tokens per sequence, 0 = plain decoding */
+    double step_us;          /* time of one target step at (batch, k) */
+    double emitted_per_seq;  /* tokens emitted per sequence and step (1 for k = 0) */
+} respec_profile_point_t;
+
+respec_status_t respec_solver_pick(const respec_profile_point_t *points, int32_t n_points,
+                                   int32_t active_batch, double draft_us_fixed,
+                                   double draft_us_per_seq, int32_t *best_k, double *speedup,
+                                   double *cost_us);
 
 #ifdef __cplusplus
 }

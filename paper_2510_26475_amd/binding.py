@@ -101,8 +101,17 @@ def load():
     lib.respec_kd_rows.argtypes = [
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_solver_pick.restype = c.c_int
+    lib.respec_solver_pick.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_double, c.c_double,
+                                       c.POINTER(c.c_int32), c.POINTER(c.c_double), c.POINTER(c.c_double)]
     _lib = lib
     return lib
+
+
+class ProfilePoint(ctypes.Structure):
+    """respec_profile_point_t"""
+    _fields_ = [("batch", ctypes.c_int32), ("k", ctypes.c_int32), ("step_us", ctypes.c_double),
+                ("emitted_per_seq", ctypes.c_double)]
 
 
 EXPORTED_SYMBOLS = [
@@ -110,7 +119,7 @@ EXPORTED_SYMBOLS = [
     "respec_verify_attention_workspace_bytes", "respec_verify_attention", "respec_verify_attention_tree",
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample", "respec_rejection_sample_per_seq",
     "respec_tree_rejection_sample", "respec_verify_attention_paged", "respec_commit_accepted_paged",
-    "respec_kd_rows_workspace_bytes", "respec_kd_rows",
+    "respec_kd_rows_workspace_bytes", "respec_kd_rows", "respec_solver_pick",
     "respec_profile_mark_main",
 ]
 
@@ -439,3 +448,18 @@ def respec_kd_rows(target_logits, draft_logits, row_weight, grad, row_loss, tota
         _dev_ptr(total_loss, "total_loss"), rows, V, target_logits.stride(0), draft_logits.stride(0),
         grad.stride(0), _dtype_code(target_logits), _dev_ptr(workspace, "workspace"), ws_bytes,
         _stream_ptr(stream)))
+
+
+def respec_solver_pick(points, active_batch, draft_us_fixed, draft_us_per_seq):
+    """points: iterable of (batch, k, step_us, emitted_per_seq), host numbers.
+    Returns (best_k, speedup, cost_us)."""
+    lib = load()
+    pts = list(points)
+    arr = (ProfilePoint * max(len(pts), 1))()
+    for i, (B, k, t, e) in enumerate(pts):
+        arr[i] = ProfilePoint(int(B), int(k), float(t), float(e))
+    best, speedup, cost = ctypes.c_int32(-1), ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib.respec_solver_pick(ctypes.cast(arr, ctypes.c_void_p) if pts else None, len(pts), int(active_batch),
+                                  float(draft_us_fixed), float(draft_us_per_seq), ctypes.byref(best),
+                                  ctypes.byref(speedup), ctypes.byref(cost)))
+    return best.value, speedup.value, cost.value
