@@ -214,19 +214,14 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
 
     // phase A: region totals (the next batch of slots is in flight while one is summed)
     double lane_sum = 0.0;
-    auto load_batch = [&](int s0, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) {
+    // (no select behind a load: it would make the loads of a batch wait for one another; slots
+    // past the region are replaced by -inf when the batch is summed)
+    auto load_batch = [&](int s0, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < kUnroll; ++c) {
             const int slot = s0 + c * 64 + lane;
-            const bool in = slot < end;
-            const u32x4 a = load_slot<BF16, FULL>(rowp, in ? slot : beg, Vrow, aligned);
-            vp[c] = in ? a : neg_inf_slot<BF16>();
-            if constexpr (RESID) {
-                const u32x4 b = load_slot<BF16, FULL>(rowq, in ? slot : beg, Vrow, aligned);
-                vq[c] = in ? b : neg_inf_slot<BF16>();
-            } else {
-                vq[c] = vp[c];
-            }
+            vp[c] = load_slot<BF16, FULL>(rowp, slot < end ? slot : beg, Vrow, aligned);
+            if constexpr (RESID) vq[c] = load_slot<BF16, FULL>(rowq, slot < end ? slot : beg, Vrow, aligned);
         }
     };
     if (beg < end) {  // wave-uniform
@@ -238,8 +233,11 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
             if (more) load_batch(s0 + 64 * kUnroll, np, nq);
 #pragma unroll
             for (int c = 0; c < kUnroll; ++c) {
+                const bool in = s0 + c * 64 + lane < end;
+                const u32x4 a = in ? vp[c] : neg_inf_slot<BF16>();
+                const u32x4 b = RESID ? (in ? vq[c] : neg_inf_slot<BF16>()) : a;
                 double w[EPV];
-                slot_weights<BF16, RESID>(vp[c], vq[c], Mp, Cp, Mq, Cq, p, w);
+                slot_weights<BF16, RESID>(a, b, Mp, Cp, Mq, Cq, p, w);
 #pragma unroll
                 for (int j = 0; j < EPV; ++j) lane_sum += w[j];
             }
@@ -247,7 +245,7 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
 #pragma unroll
                 for (int c = 0; c < kUnroll; ++c) {
                     vp[c] = np[c];
-                    vq[c] = nq[c];
+                    if constexpr (RESID) vq[c] = nq[c];
                 }
             }
         }
@@ -319,19 +317,22 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     // (a 151,936-wide bf16 row needs one chunk)
     double my_total = 0.0;
     int my_last = -1;
-    auto load_chunk = [&](int c0, u32x4 (&vp)[kChunk], u32x4 (&vq)[kChunk]) {
+    // (the loads carry no select, which would make them wait for one another; mask_chunk puts
+    // -inf into the slots past the run once all of them are on their way)
+    auto load_chunk = [&](int c0, u32x4 (&vp)[kChunk], u32x4 (&vq)[kChunk]) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < kChunk; ++j) {
-            const int slot = c0 + j;
-            const bool in = slot < my1;
-            const u32x4 a = load_slot<BF16, FULL>(rowp, in ? slot : rb, Vrow, aligned);
-            vp[j] = in ? a : neg_inf_slot<BF16>();
-            if constexpr (RESID) {
-                const u32x4 b = load_slot<BF16, FULL>(rowq, in ? slot : rb, Vrow, aligned);
-                vq[j] = in ? b : neg_inf_slot<BF16>();
-            } else {
-                vq[j] = vp[j];
-            }
+            const int slot = c0 + j < my1 ? c0 + j : rb;
+            vp[j] = load_slot<BF16, FULL>(rowp, slot, Vrow, aligned);
+            if constexpr (RESID) vq[j] = load_slot<BF16, FULL>(rowq, slot, Vrow, aligned);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+            const bool in = c0 + j < my1;
+            vp[j] = in ? vp[j] : neg_inf_slot<BF16>();
+            if constexpr (RESID) vq[j] = in ? vq[j] : neg_inf_slot<BF16>();
+            else vq[j] = vp[j];
         }
     };
     // the totals of the slots of the first chunk are kept for the walk, and (when the registers
@@ -469,13 +470,13 @@ __device__ inline int row_argmax(const void *row, int nslots, int V, bool aligne
     constexpr int kBatch = kThreads * kUnroll;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n_iter = (nslots + kBatch - 1) / kBatch;
+    // loads are clamped to the row and carry no select (a select right behind a load makes the
+    // loads of a batch wait for one another); slots past the row are skipped when compared
     auto load_batch = [&](int it, u32x4 (&v)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int slot = it * kBatch + u * kThreads + (int)threadIdx.x;
-            const bool in = slot < nslots;
-            const u32x4 a = load_slot<BF16, FULL>(row, in ? slot : 0, V, aligned);
-            v[u] = in ? a : neg_inf_slot<BF16>();
+            v[u] = load_slot<BF16, FULL>(row, it + 1 < n_iter ? slot : max(0, min(slot, nslots - 1)), V, aligned);
         }
     };
     float best = -INFINITY;
@@ -490,10 +491,11 @@ __device__ inline int row_argmax(const void *row, int nslots, int V, bool aligne
         for (int u = 0; u < kUnroll; ++u) {
             float z[EPV];
             unpack<BF16>(v[u], z);
-            const int e0 = (it * kBatch + u * kThreads + (int)threadIdx.x) * EPV;
+            const int slot = it * kBatch + u * kThreads + (int)threadIdx.x;
+            const int e0 = slot * EPV;
 #pragma unroll
             for (int j = 0; j < EPV; ++j)  // ascending ids within a thread: strict > keeps the first
-                if (z[j] > best) {
+                if (slot < nslots && z[j] > best) {
                     best = z[j];
                     best_i = e0 + j;
                 }

@@ -269,8 +269,10 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
     float refp = 0.f, refq = 0.f, Kp = 0.f, Kq = 0.f;
     const int n_iter = (nslots + kBatch - 1) / kBatch;  // block-uniform, >= 1
     // batch `it` of this thread: slots it*kBatch + tid + u*kThreads; only the last batch can
-    // run past the row (those slots read as -inf)
-    auto load_batch = [&](int it, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) {
+    // run past the row.  Its loads are clamped to the row and all issued together; the slots
+    // past the row are replaced by -inf when the batch is consumed (mask_last), not here: a
+    // select right behind each load makes the loads wait for one another.
+    auto load_batch = [&](int it, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) __attribute__((always_inline)) {
         const int s0 = it * kBatch + threadIdx.x;
         if (it + 1 < n_iter) {
 #pragma unroll
@@ -281,20 +283,24 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
         } else {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
-                const int slot = s0 + u * kThreads;
-                const bool in = slot < nslots;
-                const int safe = in ? slot : 0;
-                const u32x4 a = load_slot<BF16, true>(rowp, safe, Vrow, true);
-                vp[u] = in ? a : neg_inf_slot<BF16>();
-                if constexpr (TWO) {
-                    const u32x4 b = load_slot<BF16, true>(rowq, safe, Vrow, true);
-                    vq[u] = in ? b : neg_inf_slot<BF16>();
-                }
+                const int safe = max(0, min(s0 + u * kThreads, nslots - 1));
+                vp[u] = load_slot<BF16, true>(rowp, safe, Vrow, true);
+                if constexpr (TWO) vq[u] = load_slot<BF16, true>(rowq, safe, Vrow, true);
             }
+        }
+    };
+    auto mask_last = [&](u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) __attribute__((always_inline)) {
+        const int s0 = (n_iter - 1) * kBatch + threadIdx.x;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const bool in = s0 + u * kThreads < nslots;
+            vp[u] = in ? vp[u] : neg_inf_slot<BF16>();
+            if constexpr (TWO) vq[u] = in ? vq[u] : neg_inf_slot<BF16>();
         }
     };
     u32x4 vp[kUnroll], vq[kUnroll];
     load_batch(0, vp, vq);
+    if (n_iter == 1) mask_last(vp, vq);  // block-uniform
     {   // references from the first batch
         float mp = slot_max<BF16>(vp[0]), mq = -INFINITY;
 #pragma unroll
@@ -310,6 +316,7 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
             Kq = -refq * p.c_f;
         }
     }
+    // (a third register set with two batches in flight measured slower, not faster)
     for (int it = 0; it < n_iter; ++it) {
         u32x4 np[kUnroll], nq[kUnroll];
         const bool more = it + 1 < n_iter;  // block-uniform
@@ -325,6 +332,7 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
                 vp[u] = np[u];
                 if constexpr (TWO) vq[u] = nq[u];
             }
+            if (it + 2 == n_iter) mask_last(vp, vq);  // block-uniform: the batch consumed next is the last
         }
     }
     double sp = 0.0, sq = 0.0;

@@ -99,17 +99,10 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
     double lane_sum = 0.0;
     auto load_batch = [&](int s0, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int c = 0; c < kUnroll; ++c) {
+        for (int c = 0; c < kUnroll; ++c) {  // no select behind a load: the loads of a batch go out together
             const int slot = s0 + c * 64 + lane;
-            const bool in = slot < end;
-            const u32x4 a = load_slot<BF16, FULL>(rowp, in ? slot : beg, V, aligned);
-            vp[c] = in ? a : neg_inf_slot<BF16>();
-            if (two) {
-                const u32x4 b = load_slot<BF16, FULL>(rowq, in ? slot : beg, V, aligned);
-                vq[c] = in ? b : neg_inf_slot<BF16>();
-            } else {
-                vq[c] = vp[c];
-            }
+            vp[c] = load_slot<BF16, FULL>(rowp, slot < end ? slot : beg, V, aligned);
+            vq[c] = two ? load_slot<BF16, FULL>(rowq, slot < end ? slot : beg, V, aligned) : vp[c];
         }
     };
     if (beg < end) {  // wave-uniform
@@ -121,8 +114,10 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
             if (more) load_batch(s0 + 64 * kUnroll, np, nq);
 #pragma unroll
             for (int c = 0; c < kUnroll; ++c) {
+                const bool in = s0 + c * 64 + lane < end;  // slots past the region count as -inf
+                const u32x4 a = in ? vp[c] : neg_inf_slot<BF16>(), b = in ? vq[c] : neg_inf_slot<BF16>();
                 double w[EPV];
-                tree_slot_weights<BF16>(vp[c], vq[c], Mp, Cp, Mq, Cq, d, p, w);
+                tree_slot_weights<BF16>(a, b, Mp, Cp, Mq, Cq, d, p, w);
 #pragma unroll
                 for (int j = 0; j < EPV; ++j) lane_sum += w[j];
             }
@@ -192,17 +187,17 @@ __device__ inline int tree_draw(const void *rowp, const void *rowq, int nslots, 
     int my_last = -1;
     auto load_chunk = [&](int c0, u32x4 (&vp)[kChunk], u32x4 (&vq)[kChunk]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < kChunk; ++j) {
-            const int slot = c0 + j;
-            const bool in = slot < my1;
-            const u32x4 a = load_slot<BF16, FULL>(rowp, in ? slot : rb, V, aligned);
-            vp[j] = in ? a : neg_inf_slot<BF16>();
-            if (two) {
-                const u32x4 b = load_slot<BF16, FULL>(rowq, in ? slot : rb, V, aligned);
-                vq[j] = in ? b : neg_inf_slot<BF16>();
-            } else {
-                vq[j] = vp[j];
-            }
+        for (int j = 0; j < kChunk; ++j) {  // no select behind a load: the loads go out together
+            const int slot = c0 + j < my1 ? c0 + j : rb;
+            vp[j] = load_slot<BF16, FULL>(rowp, slot, V, aligned);
+            if (two) vq[j] = load_slot<BF16, FULL>(rowq, slot, V, aligned);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {  // slots past the run count as -inf
+            const bool in = c0 + j < my1;
+            vp[j] = in ? vp[j] : neg_inf_slot<BF16>();
+            vq[j] = two ? (in ? vq[j] : neg_inf_slot<BF16>()) : vp[j];
         }
     };
     double slot_total[kChunk];
