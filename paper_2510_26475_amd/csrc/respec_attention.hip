@@ -220,21 +220,27 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     for (int b0 = 0; b0 < p.B; b0 += 1024) {
         const int b = b0 + tid;
         const int nt = b < p.B ? seq_info(p, b).tiles : 0;
-        sh_scan[tid] = nt;
-        __syncthreads();
-        for (int o = 1; o < 1024; o <<= 1) {
-            const int add = tid >= o ? sh_scan[tid - o] : 0;
-            __syncthreads();
-            sh_scan[tid] += add;
-            __syncthreads();
+        // inclusive scan of the block: lane shuffles inside a wave, wave totals through LDS
+        int incl = nt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(incl, o);
+            if ((tid & 63) >= o) incl += y;
         }
+        if ((tid & 63) == 63) sh_scan[tid >> 6] = incl;
+        __syncthreads();
+        int before = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w)
+            if (w < (tid >> 6)) before += sh_scan[w];
+        incl += before;
         const int base = sh_base;
         if (b < p.B) {
-            p.tile_prefix[b + 1] = base + sh_scan[tid];
-            if (in_lds) sh_prefix[b + 1] = base + sh_scan[tid];
+            p.tile_prefix[b + 1] = base + incl;
+            if (in_lds) sh_prefix[b + 1] = base + incl;
         }
         __syncthreads();
-        if (tid == 1023) sh_base = base + sh_scan[1023];
+        if (tid == 1023) sh_base = base + incl;
         __syncthreads();
     }
     auto prefix = [&](int i) { return in_lds ? sh_prefix[i] : p.tile_prefix[i]; };
