@@ -188,6 +188,52 @@ __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, 
     }
 }
 
+// The same weights in fp32, for calls whose exponent constant rounds well (RowMath::one_term):
+// p(x) = exp2(z c_f + K) (1 + e) with K + log2(1 + e) = -M c_f - log2(S) split so that the
+// rounding of K is put back to first order; the weights of a slot are summed in fp32 in a
+// fixed pairwise order, and everything above a slot is carried in fp64.  A weight is within a
+// few 1e-7 (relative) of its fp64 value, far inside the boundary band of 1e-6; the scan is
+// bound by instruction issue, and this form needs about half of the instructions.
+struct FastNorm {
+    float Kp, ep, Kq, eq;
+};
+
+__device__ inline FastNorm make_fast_norm(float Mp, double Sp, float Mq, double Sq, const RowMath &p) {
+    FastNorm f;
+    const double kp = -(double)Mp * (double)p.c_f - log2(Sp);
+    const double kq = -(double)Mq * (double)p.c_f - log2(Sq);
+    f.Kp = (float)kp;
+    f.Kq = (float)kq;
+    f.ep = (float)((kp - (double)f.Kp) * 0.69314718055994530942);
+    f.eq = (float)((kq - (double)f.Kq) * 0.69314718055994530942);
+    return f;
+}
+
+// Returns the slot's total (fp32, pairwise); w[] are its elements' weights.
+template <bool BF16, bool RESID>
+__device__ inline float slot_weights_f32(const u32x4 &vp, const u32x4 &vq, const FastNorm &f, const RowMath &p,
+                                         float (&w)[Elem<BF16>::EPV]) {
+    constexpr int EPV = Elem<BF16>::EPV;
+    float zp[EPV], zq[EPV];
+    unpack<BF16>(vp, zp);
+    if constexpr (RESID) unpack<BF16>(vq, zq);
+#pragma unroll
+    for (int j = 0; j < EPV; ++j) {
+        const float pe = hw_exp2(fmaf(zp[j], p.c_f, f.Kp));
+        const float P = fmaf(pe, f.ep, pe);
+        if constexpr (RESID) {
+            const float qe = hw_exp2(fmaf(zq[j], p.c_f, f.Kq));
+            w[j] = fmaxf(P - fmaf(qe, f.eq, qe), 0.f);
+        } else {
+            w[j] = P;
+        }
+    }
+    if constexpr (EPV == 8)
+        return ((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]));
+    else
+        return (w[0] + w[1]) + (w[2] + w[3]);
+}
+
 // The single final draw of a sequence: first token, in ascending id, whose running sum of
 // weights exceeds u*Z (all sums in fp64).
 //   phase A  each wave owns a contiguous eighth of the row and streams it with coalesced loads;
@@ -200,7 +246,7 @@ __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, 
 // Phase B adds the same numbers in another order than phase A, so at the last bit a crossing
 // can fall off the end of the region; that draw then takes the last token with mass and is
 // flagged as a boundary draw (it is within rounding of a CDF edge).
-template <bool BF16, bool RESID, bool FULL, bool SHARED>
+template <bool BF16, bool RESID, bool FULL, bool SHARED, bool FAST = false>
 __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int nslots, int Vrow, int tok_off,
                                        float Mp, double Sp, float Mq, double Sq, double u, SharedState &sh,
                                        Mailbox &mb, const SamplerParams &p, int &near_edge, double &Z_out,
@@ -209,10 +255,12 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool aligned = p.aligned != 0;
     const double Cp = 1.0 / Sp, Cq = RESID ? 1.0 / Sq : 0.0;
+    const FastNorm fn = make_fast_norm(Mp, Sp, Mq, RESID ? Sq : Sp, p);
     const int span = ((nslots + kWaves - 1) / kWaves + 63) / 64 * 64;
     const int beg = min(wave * span, nslots), end = min(beg + span, nslots);
 
-    // phase A: region totals (the next batch of slots is in flight while one is summed)
+    // phase A: region totals (the next batch of slots is in flight while one is summed; batches
+    // twice as long measured the same)
     double lane_sum = 0.0;
     // (no select behind a load: it would make the loads of a batch wait for one another; slots
     // past the region are replaced by -inf when the batch is summed)
@@ -236,10 +284,15 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
                 const bool in = s0 + c * 64 + lane < end;
                 const u32x4 a = in ? vp[c] : neg_inf_slot<BF16>();
                 const u32x4 b = RESID ? (in ? vq[c] : neg_inf_slot<BF16>()) : a;
-                double w[EPV];
-                slot_weights<BF16, RESID>(a, b, Mp, Cp, Mq, Cq, p, w);
+                if constexpr (FAST) {
+                    float w[EPV];
+                    lane_sum += (double)slot_weights_f32<BF16, RESID>(a, b, fn, p, w);
+                } else {
+                    double w[EPV];
+                    slot_weights<BF16, RESID>(a, b, Mp, Cp, Mq, Cq, p, w);
 #pragma unroll
-                for (int j = 0; j < EPV; ++j) lane_sum += w[j];
+                    for (int j = 0; j < EPV; ++j) lane_sum += w[j];
+                }
             }
             if (more) {
 #pragma unroll
@@ -347,13 +400,21 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         load_chunk(c0, vp, vq);
 #pragma unroll
         for (int j = 0; j < kChunk; ++j) {
-            double w[EPV];
-            slot_weights<BF16, RESID>(vp[j], vq[j], Mp, Cp, Mq, Cq, p, w);
             double st = 0.0;
+            if constexpr (FAST) {
+                float w[EPV];
+                st = (double)slot_weights_f32<BF16, RESID>(vp[j], vq[j], fn, p, w);
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) {
-                st += w[e];
-                if (w[e] > 0.0) my_last = tok_off + (c0 + j) * EPV + e;
+                for (int e = 0; e < EPV; ++e)
+                    if (w[e] > 0.f) my_last = tok_off + (c0 + j) * EPV + e;
+            } else {
+                double w[EPV];
+                slot_weights<BF16, RESID>(vp[j], vq[j], Mp, Cp, Mq, Cq, p, w);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    st += w[e];
+                    if (w[e] > 0.0) my_last = tok_off + (c0 + j) * EPV + e;
+                }
             }
             my_total += st;
             if (c0 == my0) {
@@ -383,7 +444,14 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         double before = c, after = c;
         auto walk_slot = [&](int slot, const u32x4 &vp, const u32x4 &vq) {
             double w[EPV];
-            slot_weights<BF16, RESID>(vp, vq, Mp, Cp, Mq, Cq, p, w);
+            if constexpr (FAST) {
+                float wf[EPV];
+                (void)slot_weights_f32<BF16, RESID>(vp, vq, fn, p, wf);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) w[e] = (double)wf[e];
+            } else {
+                slot_weights<BF16, RESID>(vp, vq, Mp, Cp, Mq, Cq, p, w);
+            }
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
                 if (tok < 0) {
@@ -567,6 +635,9 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     __shared__ SharedState sh;
     __shared__ uint32_t sh_epoch;
     constexpr int EPV = Elem<BF16>::EPV;
+    // the fp32 form of the final draw's weights: calls whose exponent constant rounds well, one
+    // work-group per sequence
+    constexpr bool kFastScan = ONE_TERM && !SHARED;
     const int split = SHARED ? p.split : 1;
     const int b = blockIdx.x / split, part = blockIdx.x % split;
     // bounds come from device data: clamp them by the host-side totals so that no value of
@@ -660,7 +731,7 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         // first rejection: one draw from the residual distribution (Eq. 2)
         double Z;
         int edge = 0;
-        final_token = inverse_cdf_pass<BF16, true, FULL, SHARED>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16, nslots, Vrow,
+        final_token = inverse_cdf_pass<BF16, true, FULL, SHARED, kFastScan>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16, nslots, Vrow,
                                                          tok_off, Mp, Sp, Mq, Sq, u_fin, sh, mb, p, edge, Z, mine);
         flag_cdf = edge;
         rejected = true;
@@ -685,7 +756,7 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     if (scan_target) {
         double Z;
         int edge = 0;
-        final_token = inverse_cdf_pass<BF16, false, FULL, SHARED>(scan_row + (size_t)lo * 16, scan_row + (size_t)lo * 16, nslots,
+        final_token = inverse_cdf_pass<BF16, false, FULL, SHARED, kFastScan>(scan_row + (size_t)lo * 16, scan_row + (size_t)lo * 16, nslots,
                                                           Vrow, tok_off, scan_M, scan_S, scan_M, scan_S, u_fin, sh,
                                                           mb, p, edge, Z, mine);
         flag_cdf = rejected ? 1 : edge;
