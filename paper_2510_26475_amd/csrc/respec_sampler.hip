@@ -44,6 +44,7 @@ struct SamplerParams : RowMath {
     int split;         // work-groups per sequence (1 when there is no workspace)
     char *boxes;       // [B] mailboxes of kBoxBytes (split > 1)
     const float *temps;  // [B] one temperature per sequence (0: greedy), or NULL: the RowMath constants hold
+    int tab_slots;       // > 0: the launch carries dynamic LDS for one float per slot of a row
 };
 
 
@@ -250,10 +251,13 @@ template <bool BF16, bool RESID, bool FULL, bool SHARED, bool FAST = false>
 __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int nslots, int Vrow, int tok_off,
                                        float Mp, double Sp, float Mq, double Sq, double u, SharedState &sh,
                                        Mailbox &mb, const SamplerParams &p, int &near_edge, double &Z_out,
-                                       bool &mine) {
+                                       bool &mine, float *tab = nullptr) {
     constexpr int EPV = Elem<BF16>::EPV;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool aligned = p.aligned != 0;
+    // FAST with a table: LDS room for one float per slot of the row.  Phase A leaves every slot's
+    // total there, and phase B works from the table instead of reading the region again.
+    const bool use_tab = FAST && tab != nullptr;  // block-uniform
     const double Cp = 1.0 / Sp, Cq = RESID ? 1.0 / Sq : 0.0;
     const FastNorm fn = make_fast_norm(Mp, Sp, Mq, RESID ? Sq : Sp, p);
     const int span = ((nslots + kWaves - 1) / kWaves + 63) / 64 * 64;
@@ -286,7 +290,9 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
                 const u32x4 b = RESID ? (in ? vq[c] : neg_inf_slot<BF16>()) : a;
                 if constexpr (FAST) {
                     float w[EPV];
-                    lane_sum += (double)slot_weights_f32<BF16, RESID>(a, b, fn, p, w);
+                    const float ts = slot_weights_f32<BF16, RESID>(a, b, fn, p, w);
+                    lane_sum += (double)ts;
+                    if (use_tab && in) tab[s0 + c * 64 + lane] = ts;
                 } else {
                     double w[EPV];
                     slot_weights<BF16, RESID>(a, b, Mp, Cp, Mq, Cq, p, w);
@@ -366,6 +372,82 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     const int rb = min(wstar * span, nslots), re = min(rb + span, nslots);
     const int per = (re - rb + kThreads - 1) / kThreads;  // <= 5 for a 151,936-wide bf16 row
     const int my0 = rb + threadIdx.x * per, my1 = min(my0 + per, re);
+    if constexpr (FAST) {
+        if (use_tab) {
+            // thread totals from the table; my_last_slot: the last slot of the run with mass
+            double my_total = 0.0;
+            int my_last_slot = -1;
+            for (int sidx = my0; sidx < my1; ++sidx) {
+                const float ts = tab[sidx];
+                my_total += (double)ts;
+                if (ts > 0.f) my_last_slot = sidx;
+            }
+            const double incl_wave = wave_inclusive_scan(my_total, lane);
+            if (lane == 63) sh.scan_total[wave] = incl_wave;
+            __syncthreads();
+            double before_wave = 0.0;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w)
+                if (w < wave) before_wave += sh.scan_total[w];
+            const double run_incl = base + (before_wave + incl_wave);
+            const double run_excl = base + (before_wave + (incl_wave - my_total));
+            if (!forced && run_incl > t && my_total > 0.0) atomicMin(&sh.first_thread, (int)threadIdx.x);
+            if (my_last_slot >= 0) atomicMax(&sh.last_positive, my_last_slot);
+            __syncthreads();
+            // one slot's elements, formed again from memory: the last of them with mass, and (if
+            // walk) the first whose running sum passes t
+            auto open_slot = [&](int sidx, bool walk, double &c, int &tok, double &before, double &after) -> int {
+                const u32x4 vp = load_slot<BF16, FULL>(rowp, sidx, Vrow, aligned);
+                u32x4 vq = vp;
+                if constexpr (RESID) vq = load_slot<BF16, FULL>(rowq, sidx, Vrow, aligned);
+                float wf[EPV];
+                (void)slot_weights_f32<BF16, RESID>(vp, vq, fn, p, wf);
+                int last = -1;
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    if (wf[e] > 0.f) last = tok_off + sidx * EPV + e;
+                    if (walk && tok < 0) {
+                        const double cn = c + (double)wf[e];
+                        if (cn > t) {
+                            tok = tok_off + sidx * EPV + e;
+                            before = c;
+                            after = cn;
+                        }
+                        c = cn;
+                    }
+                }
+                return last;
+            };
+            const bool walker = (int)threadIdx.x == sh.first_thread;  // at most one thread
+            const bool nobody = sh.first_thread == kThreads;          // forced, or lost to rounding
+            if (walker || (nobody && threadIdx.x == 0)) {
+                double c = run_excl, before = c, after = c;
+                int tok = -1, edge = 0;
+                if (walker) {
+                    for (int sidx = my0; sidx < my1 && tok < 0; ++sidx) {
+                        const double cn = c + (double)tab[sidx];
+                        if (cn > t) (void)open_slot(sidx, true, c, tok, before, after);  // (a crossing lost to
+                        else c = cn;                                                    // rounding carries on)
+                    }
+                }
+                if (tok < 0) {  // take the last token with mass (of the run, or of the region)
+                    const int sidx = walker ? my_last_slot : sh.last_positive;
+                    if (sidx >= 0) tok = open_slot(sidx, false, c, tok, before, after);
+                    edge = 1;
+                } else {
+                    const double lo = fabs(t - before), hi = fabs(after - t);
+                    if (fmin(lo, hi) <= kBoundaryEps * Z) edge = 1;
+                }
+                sh.token = tok;
+                sh.near_edge = edge;
+            }
+            __syncthreads();
+            const int tok = sh.token;
+            near_edge = sh.near_edge;
+            __syncthreads();
+            return tok;
+        }
+    }
     // a thread's run is read kChunk slots at a time, all loads of a chunk in flight together
     // (a 151,936-wide bf16 row needs one chunk)
     double my_total = 0.0;
@@ -638,6 +720,8 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     // the fp32 form of the final draw's weights: calls whose exponent constant rounds well, one
     // work-group per sequence
     constexpr bool kFastScan = ONE_TERM && !SHARED;
+    extern __shared__ __align__(16) char sampler_smem[];
+    float *tab = kFastScan && p.tab_slots > 0 ? reinterpret_cast<float *>(sampler_smem) : nullptr;
     const int split = SHARED ? p.split : 1;
     const int b = blockIdx.x / split, part = blockIdx.x % split;
     // bounds come from device data: clamp them by the host-side totals so that no value of
@@ -732,7 +816,7 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         double Z;
         int edge = 0;
         final_token = inverse_cdf_pass<BF16, true, FULL, SHARED, kFastScan>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16, nslots, Vrow,
-                                                         tok_off, Mp, Sp, Mq, Sq, u_fin, sh, mb, p, edge, Z, mine);
+                                                         tok_off, Mp, Sp, Mq, Sq, u_fin, sh, mb, p, edge, Z, mine, tab);
         flag_cdf = edge;
         rejected = true;
         scan_row = rowp;
@@ -758,7 +842,7 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         int edge = 0;
         final_token = inverse_cdf_pass<BF16, false, FULL, SHARED, kFastScan>(scan_row + (size_t)lo * 16, scan_row + (size_t)lo * 16, nslots,
                                                           Vrow, tok_off, scan_M, scan_S, scan_M, scan_S, u_fin, sh,
-                                                          mb, p, edge, Z, mine);
+                                                          mb, p, edge, Z, mine, tab);
         flag_cdf = rejected ? 1 : edge;
         if (!(Z > 0.0)) {  // row without any finite logit: part 0 reports the last token
             mine = part == 0;
@@ -858,14 +942,32 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
     const int epv = logits_dt == RESPEC_BF16 ? 8 : 4;
     const bool full = p.aligned && V % epv == 0 && env_long("RESPEC_SAMPLER_GUARDED", 0) == 0;
     const bool bf = logits_dt == RESPEC_BF16, one = p.one_term != 0;
+    // the final draw's table of slot totals (fp32 form, one work-group per sequence): one float
+    // per 16-byte slot of a row in dynamic LDS, when that fits beside the static part
+    size_t smem = 0;
+    {
+        const size_t slots_row = ((size_t)V + epv - 1) / epv;
+        if (full && one && split == 1 && slots_row * sizeof(float) <= kTableMaxBytes &&
+            env_long("RESPEC_SAMPLER_NO_TABLE", 0) == 0) {
+            smem = round_up(slots_row * sizeof(float), 16);
+            p.tab_slots = (int)slots_row;
+        }
+    }
 #define RESPEC_LAUNCH_SAMPLER(BF, ONE, FULL)                                                                        \
     do {                                                                                                           \
-        if (split > 1)                                                                                             \
+        if (split > 1) {                                                                                           \
             hipLaunchKernelGGL((rejection_sample_kernel<BF, ONE, FULL, true>), dim3((unsigned)(B * split)),        \
                                dim3(kThreads), 0, stream, p);                                                      \
-        else                                                                                                       \
+        } else {                                                                                                   \
+            if (smem > 0 &&                                                                                        \
+                hipFuncSetAttribute(reinterpret_cast<const void *>(&rejection_sample_kernel<BF, ONE, FULL, false>), \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) {        \
+                smem = 0;                                                                                          \
+                p.tab_slots = 0;                                                                                   \
+            }                                                                                                      \
             hipLaunchKernelGGL((rejection_sample_kernel<BF, ONE, FULL, false>), dim3((unsigned)B), dim3(kThreads), \
-                               0, stream, p);                                                                      \
+                               smem, stream, p);                                                                   \
+        }                                                                                                          \
     } while (0)
     if (!full) {
         if (bf) RESPEC_LAUNCH_SAMPLER(true, false, false); else RESPEC_LAUNCH_SAMPLER(false, false, false);

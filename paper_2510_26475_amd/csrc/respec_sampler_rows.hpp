@@ -22,6 +22,7 @@ constexpr int kBoxHeaderBytes = 128;                      // epoch at word 0, pr
 constexpr int kBoxPayload = kMaxSplit * 2 * 8;            // [part][stage parity][8 doubles]
 constexpr size_t kBoxBytes = kBoxHeaderBytes + (size_t)kBoxPayload * 8;
 constexpr int kSpinLimit = 1 << 22;
+constexpr size_t kTableMaxBytes = 96 * 1024;  // LDS a launch may add for the final draw's slot totals
 
 // The exponent constants of one call: exp((z - ref)/T) is taken as exp2((z - ref) * log2(e)/T).
 struct RowMath {

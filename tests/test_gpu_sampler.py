@@ -82,13 +82,25 @@ def test_identical_drafter_accepts_everything(oracle):
     assert gpu[1].tolist() == ks
 
 
-@pytest.mark.parametrize("env", ["RESPEC_SAMPLER_GUARDED", "RESPEC_SAMPLER_TWO_TERM"])
+@pytest.mark.parametrize("env", ["RESPEC_SAMPLER_GUARDED", "RESPEC_SAMPLER_TWO_TERM", "RESPEC_SAMPLER_NO_TABLE"])
 def test_alternative_normaliser_passes_agree(oracle, env, monkeypatch):
     # the guarded pass (running per-thread references) and the two-term exponent are the paths
-    # taken for unaligned rows / temperatures whose log2(e)/T rounds badly; force them here
+    # taken for unaligned rows / temperatures whose log2(e)/T rounds badly; without the table of
+    # slot totals the final draw reads its region again (rows too wide for LDS); force them here
     monkeypatch.setenv(env, "1")
     wl = _wl("alt", 151936, "bf16", sigma=1.0)
-    _parity(oracle, _batch(wl, [3] * 16, seed=21))
+    _parity(oracle, _batch(wl, [3] * 16 + [0, 1, 2, 4], seed=21))
+
+
+def test_f32_logits_full_vocab_are_too_wide_for_the_slot_table(oracle):
+    # 151,936 f32 logits are 37,984 slots (148 KB of totals): the draw falls back to re-reading
+    _parity(oracle, _batch(_wl("wide_f32", 151936, "f32", sigma=1.0), [3] * 12 + [0, 2], seed=22))
+
+
+@pytest.mark.parametrize("V", [24576 * 8, 24576 * 8 + 8])
+def test_rows_at_the_edge_of_the_slot_table(oracle, V):
+    # 24,576 slots are exactly the 96 KB the table may take; one more slot goes without it
+    _parity(oracle, _batch(_wl("edge", V, "bf16", sigma=1.0), [2] * 10 + [0, 3], seed=23))
 
 
 def test_huge_outlier_logit_takes_the_guarded_pass(oracle):
