@@ -244,3 +244,35 @@ def test_bad_arguments_are_rejected_before_any_launch():
         binding.respec_rejection_sample(batch.target_logits, batch.draft_logits,
                                         batch.draft_tokens, batch.q_indptr, batch.u_accept,
                                         batch.u_final, toks[:, :2].contiguous(), n, None, 1, 1.0)
+
+
+@pytest.mark.parametrize("no_table", [0, 1])
+def test_extreme_final_uniforms_pick_tokens_with_mass(oracle, no_table, monkeypatch):
+    """u_final = 0 and the largest binary32 below 1 sit on a CDF edge by construction (always
+    flagged, so parity says nothing): the token drawn must still carry mass, the first such
+    token for u = 0 and one at the far end of the support for u -> 1."""
+    if no_table:
+        monkeypatch.setenv("RESPEC_SAMPLER_NO_TABLE", "1")
+    wl = _wl("extreme", 151936, "bf16", sigma=1.0)
+    ks = [2] * 16 + [0] * 4
+    batch = _batch(wl, ks, seed=31)
+    B = len(ks)
+    u = np.zeros(B, dtype=np.float32)
+    u[1::2] = np.float32(1.0) - np.float32(2.0 ** -24)
+    batch.u_final.copy_(torch.from_numpy(u))
+    toks, n, _ = gpu_sample(batch, workspace=None)
+    ref_t, ref_n, ref_f = oracle_sample(oracle, batch)
+    assert np.array_equal(n, ref_n)                      # the acceptance tests do not involve u_final
+    P = oracle.softmax_rows(synth.to_host_array(batch.target_logits), 1.0, oracle.BF16)
+    Q = oracle.softmax_rows(synth.to_host_array(batch.draft_logits), 1.0, oracle.BF16)
+    qi = batch.q_indptr.cpu().numpy()
+    for b in range(B):
+        row = qi[b] + n[b]
+        w = P[row] if n[b] == ks[b] else np.maximum(P[row] - Q[qi[b] - b + n[b]], 0.0)
+        tok = toks[b, n[b]]
+        assert w[tok] > 0.0, (b, tok)
+        cdf = np.cumsum(w) / w.sum()
+        if u[b] == 0:
+            assert cdf[tok] - w[tok] / w.sum() <= 2e-6      # nothing but rounding noise before it
+        else:
+            assert cdf[tok] >= 1.0 - 2e-6                   # at the far end of the support
