@@ -362,6 +362,40 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
     main_sorted = sorted(a.elapsed_time(b) for a, b in probes)
     layers = args.layers or {"qwen3b": 36, "qwen7b": 28, "qwen14b": 48}.get(wl.name.split("_")[0], 1)
 
+    # Optional: the full-depth step measured instead of modelled.  Every layer gets a KV cache of
+    # its own (same lengths, fresh random values, so no layer finds its cache in a cache), one
+    # attention call per layer, then the sampler.  GEMMs, norms and the LM head stay outside.
+    measured_depth = None
+    if args.measure_depth and tree is None and paged is None:
+        g2 = torch.Generator(device=dev).manual_seed(wl.seed + 1000)
+        caches = [(batch.k_cache, batch.v_cache)]
+        for _ in range(layers - 1):
+            kc = torch.empty_like(batch.k_cache).normal_(generator=g2)
+            vc = torch.empty_like(batch.v_cache).normal_(generator=g2)
+            caches.append((kc, vc))
+
+        def deep_step():
+            for i, (kc, vc) in enumerate(caches):  # layers after the first reuse the first one's set-up
+                call = binding.respec_verify_attention if i == 0 else binding.respec_verify_attention_next_layer
+                call(batch.q, kc, vc, batch.q_indptr, batch.kv_indptr, out, lse, max_q, batch.max_kv_len,
+                     sm_scale, ws)
+            sampler()
+
+        for _ in range(2):
+            deep_step()
+        torch.cuda.synchronize()
+        n_deep = max(3, min(args.steps, 10))
+        d0 = time.perf_counter()
+        for _ in range(n_deep):
+            deep_step()
+        torch.cuda.synchronize()
+        us_deep = (time.perf_counter() - d0) * 1e6 / n_deep
+        measured_depth = {"layers": layers, "steps": n_deep, "us_per_step": us_deep,
+                          "note": "MEASURED: one attention call per layer on a KV cache of its own (the first call sets up, the "
+                                  "others reuse it: respec_verify_attention_next_layer), then the sampler; "
+                                  "the forward's GEMMs are outside this path"}
+        del caches
+
     n_host = n_acc.cpu().tolist()
     accepted = int(sum(n_host))
     emitted = accepted + B
@@ -419,6 +453,8 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
         "tokens_per_s_kernels": emitted / ((ms_prep + ms_main_pass + ms_comb + ms_samp) * 1e-3),
         "modelled_full_depth": {"layers": layers, "note": "MODELLED, not measured: emitted / (layers * t_attn + t_samp)",
                                 "tokens_per_s": emitted / ((layers * (ms_prep + ms_main_pass + ms_comb) + ms_samp) * 1e-3)},
+        "measured_full_depth": (dict(measured_depth, tokens_per_s=emitted / (measured_depth["us_per_step"] * 1e-6))
+                                if measured_depth else None),
         "attention_main_us_median_min": [main_sorted[len(main_sorted) // 2] * 1e3, main_sorted[0] * 1e3],
         "measured_copy_gbs": copy_gbs,
         "attention_frac_of_measured_copy": achieved / copy_gbs,
@@ -508,6 +544,8 @@ def main():
                     help="in the timed region, bracket the main attention kernel with events on every n-th step")
     ap.add_argument("--layers", type=int, default=None,
                     help="attention layers of the modelled full-depth figure (default: the model's public card)")
+    ap.add_argument("--measure-depth", action="store_true",
+                    help="also time the step with one attention call per layer (each layer its own KV cache)")
     ap.add_argument("--cpu-seqs", type=int, default=256,
                     help="sequences the oracle is timed on (cpu_baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

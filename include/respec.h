@@ -108,6 +108,30 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
                                         size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The attention of ANOTHER LAYER of the same forward pass.  The target's single forward over the
+ * drafted block (Figure 2) runs this attention once per layer with the same sequences: the
+ * index arrays, the lengths and every size are those of the previous call, only q, the caches
+ * and out (and sm_scale) belong to another layer.  The set-up that a call derives from the
+ * index arrays (tile counts, where every wave starts) is then reused instead of being computed
+ * again.
+ *
+ * Contract: `workspace` is the workspace of an earlier respec_verify_attention or
+ * respec_verify_attention_tree call (or of a call of this function) on the same stream with the
+ * same q_indptr and kv_indptr CONTENTS, B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv,
+ * D and dt, and nothing else has written to it since.  tree_mask: NULL for chains, else as in
+ * respec_verify_attention_tree.  Everything else as in respec_verify_attention; the result is
+ * bit-equal to what a full call on the same arguments gives.  If the contract is broken the
+ * output is wrong, but no access leaves the buffers (every index is clamped as in a full call).
+ */
+respec_status_t respec_verify_attention_next_layer(const void *q, const void *k_cache, const void *v_cache,
+                                                   const int32_t *q_indptr, const int64_t *kv_indptr,
+                                                   const uint64_t *tree_mask, void *out, float *lse,
+                                                   int32_t B, int32_t total_q, int64_t total_kv,
+                                                   int32_t max_q_per_seq, int32_t max_kv_len, int32_t Hq,
+                                                   int32_t Hkv, int32_t D, float sm_scale, respec_dtype_t dt,
+                                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Verify attention over a tree of drafts (Section 3.1: candidate branches, branching factor
  * t, validated in parallel).  As respec_verify_attention, except for which of a sequence's
  * own new tokens a row sees: row i of sequence b (rows in an order in which parents come

@@ -63,6 +63,8 @@ def load():
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
         c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_verify_attention_next_layer.restype = c.c_int
+    lib.respec_verify_attention_next_layer.argtypes = lib.respec_verify_attention_tree.argtypes
     lib.respec_profile_mark_main.restype = None
     lib.respec_profile_mark_main.argtypes = [c.c_void_p, c.c_void_p]
     lib.respec_rejection_sample_workspace_bytes.restype = c.c_size_t
@@ -117,6 +119,7 @@ class ProfilePoint(ctypes.Structure):
 EXPORTED_SYMBOLS = [
     "respec_status_string", "respec_last_error", "respec_version",
     "respec_verify_attention_workspace_bytes", "respec_verify_attention", "respec_verify_attention_tree",
+    "respec_verify_attention_next_layer",
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample", "respec_rejection_sample_per_seq",
     "respec_tree_rejection_sample", "respec_verify_attention_paged", "respec_commit_accepted_paged",
     "respec_kd_rows_workspace_bytes", "respec_kd_rows", "respec_solver_pick",
@@ -183,6 +186,31 @@ def respec_verify_attention(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, 
         _dev_ptr(q, "q"), _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
         _dev_ptr(q_indptr, "q_indptr"), _dev_ptr(kv_indptr, "kv_indptr"), _dev_ptr(out, "out"),
         _dev_ptr(lse, "lse"), B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D,
+        float(sm_scale), _dtype_code(q), ws_ptr, ws_bytes, _stream_ptr(stream)))
+
+
+def respec_verify_attention_next_layer(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, max_q_per_seq,
+                                       max_kv_len, sm_scale, workspace, tree_mask=None, stream=None):
+    """Another layer of the same forward: same index arrays and sizes as the previous call on this
+    workspace, other q / caches / out.  Reuses the set-up the workspace holds."""
+    lib = load()
+    total_q, Hq, D = q.shape
+    total_kv, Hkv, _ = k_cache.shape
+    B = q_indptr.numel() - 1
+    if q_indptr.dtype != torch.int32 or kv_indptr.dtype != torch.int64:
+        raise TypeError("q_indptr must be int32 and kv_indptr int64")
+    if tree_mask is not None and (tree_mask.element_size() != 8 or tree_mask.numel() != total_q):
+        raise TypeError("tree_mask must hold one 64-bit word per query row")
+    if lse is not None and lse.dtype != torch.float32:
+        raise TypeError("lse must be float32")
+    if out.dtype != q.dtype or k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise TypeError("q, k_cache, v_cache and out must share one dtype")
+    ws_ptr = _dev_ptr(workspace, "workspace") if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.respec_verify_attention_next_layer(
+        _dev_ptr(q, "q"), _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
+        _dev_ptr(q_indptr, "q_indptr"), _dev_ptr(kv_indptr, "kv_indptr"), _dev_ptr(tree_mask, "tree_mask"),
+        _dev_ptr(out, "out"), _dev_ptr(lse, "lse"), B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D,
         float(sm_scale), _dtype_code(q), ws_ptr, ws_bytes, _stream_ptr(stream)))
 
 

@@ -1251,7 +1251,7 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
                                      int32_t total_q, int64_t total_kv, int32_t max_q_per_seq,
                                      int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D, float sm_scale,
                                      respec_dtype_t dt, void *workspace, size_t workspace_bytes,
-                                     void *hip_stream) {
+                                     void *hip_stream, bool reuse_plan = false) {
     const bool paged = pg.page_table != nullptr;
     if (tree_mask && max_q_per_seq > 64)
         return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention_tree: at most 64 rows per sequence, got %d",
@@ -1383,10 +1383,14 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     if (W % hi != 0 || env_long("RESPEC_ATTN_HEAD_MAJOR", 0) != 0) hi = 1;
     p.HI = hi;
 
-    hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
-    err = hipGetLastError();
-    if (err != hipSuccess)
-        return fail(RESPEC_ERR_HIP, "verify_attention: prep launch failed: %s", hipGetErrorString(err));
+    // the set-up depends on the index arrays and the sizes only: the layers of one forward share
+    // it (reuse_plan: the workspace still holds what the set-up of an earlier call left there)
+    if (!reuse_plan) {
+        hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
+        err = hipGetLastError();
+        if (err != hipSuccess)
+            return fail(RESPEC_ERR_HIP, "verify_attention: prep launch failed: %s", hipGetErrorString(err));
+    }
     if (g_mark_before_main) {
         (void)hipEventRecord(g_mark_before_main, stream);
         g_mark_before_main = nullptr;
@@ -1429,6 +1433,18 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
     return respec::verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, respec::Pages{}, nullptr, out, lse,
                                         B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt,
                                         workspace, workspace_bytes, hip_stream);
+}
+
+respec_status_t respec_verify_attention_next_layer(const void *q, const void *k_cache, const void *v_cache,
+                                                   const int32_t *q_indptr, const int64_t *kv_indptr,
+                                                   const uint64_t *tree_mask, void *out, float *lse, int32_t B,
+                                                   int32_t total_q, int64_t total_kv, int32_t max_q_per_seq,
+                                                   int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                                   float sm_scale, respec_dtype_t dt, void *workspace,
+                                                   size_t workspace_bytes, void *hip_stream) {
+    return respec::verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, respec::Pages{}, tree_mask, out,
+                                        lse, B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale,
+                                        dt, workspace, workspace_bytes, hip_stream, true);
 }
 
 respec_status_t respec_verify_attention_tree(const void *q, const void *k_cache, const void *v_cache,

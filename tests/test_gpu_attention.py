@@ -4,6 +4,7 @@ Tolerances are the contract's: max abs error 2e-2 for bf16, 1e-5 for fp32.  bf16
 check a tighter rms bound (the bf16 rounding of the probabilities and of the output keeps
 the rms error near 1e-3 for N(0,1) data), so that a systematic slip cannot hide under 2e-2.
 """
+import dataclasses
 import math
 
 import numpy as np
@@ -217,6 +218,47 @@ def test_qwen7b_headline_workload_sampled_sequences(oracle):
     qi = batch.q_indptr.tolist()
     rows = torch.tensor([r for b in seqs for r in range(qi[b], qi[b + 1])], device="cuda")
     _check(out[rows], lse[rows], ref, ref_lse, "bf16")
+
+
+def test_next_layer_reuses_the_set_up_and_is_bit_equal_to_a_full_call(oracle):
+    """The layers of one forward share the index arrays: respec_verify_attention_next_layer skips
+    the set-up kernel and must give the bits of a full call on the same arguments."""
+    wl = synth.Workload("layers", B=37, k=3, Hq=28, Hkv=4, D=128, V=1024, dtype="bf16",
+                        len_dist="uniform", len_lo=40, len_hi=3000, seed=33)
+    batch = synth.make_batch(wl, device="cuda", with_logits=False)
+    max_q = batch.max_k + 1
+    ws = torch.empty(binding.respec_verify_attention_workspace_bytes(
+        wl.B, batch.total_q, batch.total_kv, max_q, batch.max_kv_len, wl.Hq, wl.Hkv, wl.D, binding.RESPEC_BF16),
+        dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda").manual_seed(5)
+    layers = [(batch.q, batch.k_cache, batch.v_cache)]
+    for _ in range(2):
+        layers.append(tuple(torch.empty_like(t).normal_(generator=g) for t in layers[0]))
+    scale = 1.0 / np.sqrt(wl.D)
+    full = []
+    for q, k, v in layers:
+        out = torch.empty_like(q)
+        lse = torch.empty((batch.total_q, wl.Hq), dtype=torch.float32, device="cuda")
+        binding.respec_verify_attention(q, k, v, batch.q_indptr, batch.kv_indptr, out, lse, max_q,
+                                        batch.max_kv_len, scale, ws)
+        full.append((out, lse))
+    torch.cuda.synchronize()
+    # one full call, then the other layers on the same workspace
+    ws.zero_()
+    outs = []
+    for i, (q, k, v) in enumerate(layers):
+        out = torch.empty_like(q)
+        lse = torch.empty((batch.total_q, wl.Hq), dtype=torch.float32, device="cuda")
+        call = binding.respec_verify_attention if i == 0 else binding.respec_verify_attention_next_layer
+        call(q, k, v, batch.q_indptr, batch.kv_indptr, out, lse, max_q, batch.max_kv_len, scale, ws)
+        outs.append((out, lse))
+    torch.cuda.synchronize()
+    for (a, la), (b, lb) in zip(full, outs):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
+    # and the last layer against the oracle
+    sb = dataclasses.replace(batch, q=layers[2][0], k_cache=layers[2][1], v_cache=layers[2][2])
+    ref, _ = oracle_attention(oracle, sb)
+    assert np.abs(outs[2][0].double().cpu().numpy() - ref).max() <= 2e-2
 
 
 def test_bad_arguments_are_rejected_before_any_launch():
