@@ -381,6 +381,30 @@ respec_status_t respec_kd_rows(const void *target_logits, const void *draft_logi
                                size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Debug check of the device-side data that the other entry points cannot report: they clamp
+ * every index they derive from q_indptr / kv_indptr (so bad data never causes an access outside
+ * the buffers) but then compute something meaningless.  This call checks the arrays of one
+ * verify batch (Section 2.2: B sequences, k_b drafted tokens each) and, unlike every other call,
+ * WAITS for the result (it synchronises hip_stream).
+ *
+ * Checked: both index arrays start at 0; every sequence has 1 <= k_b + 1 <= max_q_per_seq rows
+ * and k_b + 1 <= L_b <= max_kv_len cached tokens; the last entries equal total_q / total_kv;
+ * every drafted token lies in [0, V).
+ *
+ *   kv_indptr     may be NULL (paged caches: only the rows and the tokens are checked)
+ *   draft_tokens  [total_q - B] or NULL (not checked)
+ *   workspace     respec_validate_batch_workspace_bytes(B) bytes of device memory, scratch
+ * Returns RESPEC_OK, or RESPEC_ERR_INVALID_ARG with respec_last_error() naming the lowest
+ * sequence that has a defect and the defect.
+ */
+size_t respec_validate_batch_workspace_bytes(int32_t B);
+respec_status_t respec_validate_batch(const int32_t *q_indptr, const int64_t *kv_indptr,
+                                      const int32_t *draft_tokens, int32_t B, int32_t total_q,
+                                      int64_t total_kv, int32_t max_q_per_seq, int32_t max_kv_len,
+                                      int32_t V, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream);
+
+/*
  * The Solver's choice of the draft length for the current active batch size (Section 4.2,
  * "Solver: Offline Profiling Guided Search": configurations are profiled offline per batch
  * size, a performance model predicts the speedup, and at run time the configuration with the

@@ -103,6 +103,11 @@ def load():
     lib.respec_kd_rows.argtypes = [
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int64, c.c_int64, c.c_int64, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_validate_batch_workspace_bytes.restype = c.c_size_t
+    lib.respec_validate_batch_workspace_bytes.argtypes = [c.c_int32]
+    lib.respec_validate_batch.restype = c.c_int
+    lib.respec_validate_batch.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int64,
+                                          c.c_int32, c.c_int32, c.c_int32, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.respec_solver_pick.restype = c.c_int
     lib.respec_solver_pick.argtypes = [c.c_void_p, c.c_int32, c.c_int32, c.c_double, c.c_double,
                                        c.POINTER(c.c_int32), c.POINTER(c.c_double), c.POINTER(c.c_double)]
@@ -123,6 +128,7 @@ EXPORTED_SYMBOLS = [
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample", "respec_rejection_sample_per_seq",
     "respec_tree_rejection_sample", "respec_verify_attention_paged", "respec_commit_accepted_paged",
     "respec_kd_rows_workspace_bytes", "respec_kd_rows", "respec_solver_pick",
+    "respec_validate_batch_workspace_bytes", "respec_validate_batch",
     "respec_profile_mark_main",
 ]
 
@@ -491,3 +497,20 @@ def respec_solver_pick(points, active_batch, draft_us_fixed, draft_us_per_seq):
                                   float(draft_us_fixed), float(draft_us_per_seq), ctypes.byref(best),
                                   ctypes.byref(speedup), ctypes.byref(cost)))
     return best.value, speedup.value, cost.value
+
+
+def respec_validate_batch(q_indptr, kv_indptr, draft_tokens, total_q, total_kv, max_q_per_seq, max_kv_len, V,
+                          stream=None):
+    """Debug check of a batch's index arrays and drafted tokens; raises RespecError naming the
+    first bad sequence.  Synchronises the stream."""
+    lib = load()
+    B = q_indptr.numel() - 1
+    if q_indptr.dtype != torch.int32 or (kv_indptr is not None and kv_indptr.dtype != torch.int64):
+        raise TypeError("q_indptr must be int32 and kv_indptr int64")
+    if draft_tokens is not None and draft_tokens.dtype != torch.int32:
+        raise TypeError("draft_tokens must be int32")
+    ws = torch.empty(int(lib.respec_validate_batch_workspace_bytes(B)), dtype=torch.uint8, device=q_indptr.device)
+    _check(lib.respec_validate_batch(_dev_ptr(q_indptr, "q_indptr"), _dev_ptr(kv_indptr, "kv_indptr"),
+                                     _dev_ptr(draft_tokens, "draft_tokens"), B, int(total_q), int(total_kv),
+                                     int(max_q_per_seq), int(max_kv_len), int(V), _dev_ptr(ws, "workspace"),
+                                     ws.numel(), _stream_ptr(stream)))

@@ -15,7 +15,7 @@ CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "librespec.so")
 
-SOURCES = ["respec_common.hip", "respec_solver.hip", "respec_sampler.hip", "respec_tree_sampler.hip", "respec_kd.hip",
+SOURCES = ["respec_common.hip", "respec_solver.hip", "respec_validate.hip", "respec_sampler.hip", "respec_tree_sampler.hip", "respec_kd.hip",
            "respec_attention.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
