@@ -195,21 +195,6 @@ __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, 
 // fixed pairwise order, and everything above a slot is carried in fp64.  A weight is within a
 // few 1e-7 (relative) of its fp64 value, far inside the boundary band of 1e-6; the scan is
 // bound by instruction issue, and this form needs about half of the instructions.
-struct FastNorm {
-    float Kp, ep, Kq, eq;
-};
-
-__device__ inline FastNorm make_fast_norm(float Mp, double Sp, float Mq, double Sq, const RowMath &p) {
-    FastNorm f;
-    const double kp = -(double)Mp * (double)p.c_f - log2(Sp);
-    const double kq = -(double)Mq * (double)p.c_f - log2(Sq);
-    f.Kp = (float)kp;
-    f.Kq = (float)kq;
-    f.ep = (float)((kp - (double)f.Kp) * 0.69314718055994530942);
-    f.eq = (float)((kq - (double)f.Kq) * 0.69314718055994530942);
-    return f;
-}
-
 // Returns the slot's total (fp32, pairwise); w[] are its elements' weights.
 template <bool BF16, bool RESID>
 __device__ inline float slot_weights_f32(const u32x4 &vp, const u32x4 &vq, const FastNorm &f, const RowMath &p,

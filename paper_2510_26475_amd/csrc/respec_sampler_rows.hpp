@@ -385,6 +385,24 @@ __device__ inline void row_stats(const void *rowp, const void *rowq, int nslots,
     if constexpr (TWO) block_combine(tq.ref, tq.total(), sh, parity, 1, p, Mq, Sq);
 }
 
+// fp32 form of a normalised probability, for calls whose exponent constant rounds well
+// (RowMath::one_term): p(x) = exp2(z c_f + K) (1 + e), where K + log2(1 + e) = -M c_f - log2(S)
+// is split so that the rounding of K is put back to first order through e.
+struct FastNorm {
+    float Kp, ep, Kq, eq;
+};
+
+__device__ inline FastNorm make_fast_norm(float Mp, double Sp, float Mq, double Sq, const RowMath &p) {
+    FastNorm f;
+    const double kp = -(double)Mp * (double)p.c_f - log2(Sp);
+    const double kq = -(double)Mq * (double)p.c_f - log2(Sq);
+    f.Kp = (float)kp;
+    f.Kq = (float)kq;
+    f.ep = (float)((kp - (double)f.Kp) * 0.69314718055994530942);
+    f.eq = (float)((kq - (double)f.Kq) * 0.69314718055994530942);
+    return f;
+}
+
 // Device-scope accesses for the few words that work-groups on different compute units (whose
 // L2 caches are not coherent with each other) exchange.
 __device__ inline uint32_t load_dev(const uint32_t *ptr) {

@@ -80,11 +80,72 @@ __device__ inline void tree_slot_weights(const u32x4 &vp, const u32x4 &vq, float
     }
 }
 
+// The same weights in fp32 (calls whose exponent constant rounds well): probabilities as in
+// FastNorm, every factor 1/Z_j as a two-term binary32 constant so that no systematic error
+// enters, the weights of a slot summed in fp32 in a fixed pairwise order (returned); everything
+// above a slot is carried in fp64.  About half of the instructions of the fp64 form, which is
+// what bounds these passes.
+struct FastDepth {
+    int depth;
+    float z1h, z1l, z2h, z2l;   // 1/Z_1 and 1/Z_2 as hi + lo
+    const double *inv_z;
+};
+
+__device__ inline FastDepth make_fast_depth(const Depth &d) {
+    FastDepth f;
+    f.depth = d.depth;
+    f.z1h = (float)d.z1;
+    f.z1l = (float)(d.z1 - (double)f.z1h);
+    f.z2h = (float)d.z2;
+    f.z2l = (float)(d.z2 - (double)f.z2h);
+    f.inv_z = d.inv_z;
+    return f;
+}
+
+__device__ inline float running_weight_f32(float pe, float qe, const FastDepth &d) {
+    float a = pe;
+    if (d.depth >= 1) a = fmaxf(a - qe, 0.f);
+    if (d.depth >= 2) a = fmaxf(fmaf(a, d.z1h, a * d.z1l) - qe, 0.f);
+    if (d.depth >= 3) a = fmaxf(fmaf(a, d.z2h, a * d.z2l) - qe, 0.f);
+    for (int j = kRegDepth; j < d.depth; ++j) {
+        const float zh = (float)d.inv_z[j], zl = (float)(d.inv_z[j] - (double)zh);
+        a = fmaxf(fmaf(a, zh, a * zl) - qe, 0.f);
+    }
+    return a;
+}
+
+template <bool BF16>
+__device__ inline float tree_slot_weights_f32(const u32x4 &vp, const u32x4 &vq, const FastNorm &f,
+                                              const FastDepth &d, const RowMath &p,
+                                              float (&w)[Elem<BF16>::EPV]) {
+    constexpr int EPV = Elem<BF16>::EPV;
+    float zp[EPV], zq[EPV];
+    unpack<BF16>(vp, zp);
+    unpack<BF16>(vq, zq);
+    if (d.depth == 0) {  // block-uniform
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) {
+            const float pe = hw_exp2(fmaf(zp[j], p.c_f, f.Kp));
+            w[j] = fmaf(pe, f.ep, pe);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < EPV; ++j) {
+            const float pe = hw_exp2(fmaf(zp[j], p.c_f, f.Kp)), qe = hw_exp2(fmaf(zq[j], p.c_f, f.Kq));
+            w[j] = running_weight_f32(fmaf(pe, f.ep, pe), fmaf(qe, f.eq, qe), d);
+        }
+    }
+    if constexpr (EPV == 8)
+        return ((w[0] + w[1]) + (w[2] + w[3])) + ((w[4] + w[5]) + (w[6] + w[7]));
+    else
+        return (w[0] + w[1]) + (w[2] + w[3]);
+}
+
 // Region totals of the running distribution: each wave owns a contiguous eighth of the row
 // and streams it with coalesced loads; lanes keep their own fp64 sums, one reduction per wave
 // gives the region total (left in sh.wave_total).  Returns Z = the ordered sum of the region
 // totals, the same bits in every thread.  At depth 0 only the target row is read.
-template <bool BF16, bool FULL>
+template <bool BF16, bool FULL, bool FAST>
 __device__ inline double tree_region_totals(const void *rowp, const void *rowq, int nslots, int V, float Mp,
                                             double Sp, float Mq, double Sq, const Depth &d, SharedState &sh,
                                             const RowMath &p) {
@@ -93,6 +154,8 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
     const bool aligned = p.aligned != 0;
     const bool two = d.depth > 0;
     const double Cp = 1.0 / Sp, Cq = two ? 1.0 / Sq : 0.0;
+    const FastNorm fn = make_fast_norm(Mp, Sp, Mq, two ? Sq : Sp, p);
+    const FastDepth fd = make_fast_depth(d);
     const int span = ((nslots + kWaves - 1) / kWaves + 63) / 64 * 64;
     const int beg = min(wave * span, nslots), end = min(beg + span, nslots);
     __syncthreads();  // the totals of an earlier pass have been read by everyone
@@ -116,10 +179,15 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
             for (int c = 0; c < kUnroll; ++c) {
                 const bool in = s0 + c * 64 + lane < end;  // slots past the region count as -inf
                 const u32x4 a = in ? vp[c] : neg_inf_slot<BF16>(), b = in ? vq[c] : neg_inf_slot<BF16>();
-                double w[EPV];
-                tree_slot_weights<BF16>(a, b, Mp, Cp, Mq, Cq, d, p, w);
+                if constexpr (FAST) {
+                    float w[EPV];
+                    lane_sum += (double)tree_slot_weights_f32<BF16>(a, b, fn, fd, p, w);
+                } else {
+                    double w[EPV];
+                    tree_slot_weights<BF16>(a, b, Mp, Cp, Mq, Cq, d, p, w);
 #pragma unroll
-                for (int j = 0; j < EPV; ++j) lane_sum += w[j];
+                    for (int j = 0; j < EPV; ++j) lane_sum += w[j];
+                }
             }
             if (more) {
 #pragma unroll
@@ -145,7 +213,7 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
 // thread whose running sum passes u*Z walks its run element by element.  The re-read adds
 // the same numbers in another order than the region pass, so at the last bit a crossing can
 // fall off the end of the region; that draw takes the last token with mass and is flagged.
-template <bool BF16, bool FULL>
+template <bool BF16, bool FULL, bool FAST>
 __device__ inline int tree_draw(const void *rowp, const void *rowq, int nslots, int V, float Mp, double Sp,
                                 float Mq, double Sq, const Depth &d, double u, SharedState &sh,
                                 const RowMath &p, int &near_edge) {
@@ -154,6 +222,8 @@ __device__ inline int tree_draw(const void *rowp, const void *rowq, int nslots, 
     const bool aligned = p.aligned != 0;
     const bool two = d.depth > 0;
     const double Cp = 1.0 / Sp, Cq = two ? 1.0 / Sq : 0.0;
+    const FastNorm fn = make_fast_norm(Mp, Sp, Mq, two ? Sq : Sp, p);
+    const FastDepth fd = make_fast_depth(d);
     const int span = ((nslots + kWaves - 1) / kWaves + 63) / 64 * 64;
     if (threadIdx.x == 0) {
         sh.token = -1;
@@ -208,13 +278,21 @@ __device__ inline int tree_draw(const void *rowp, const void *rowq, int nslots, 
         load_chunk(c0, vp, vq);
 #pragma unroll
         for (int j = 0; j < kChunk; ++j) {
-            double w[EPV];
-            tree_slot_weights<BF16>(vp[j], vq[j], Mp, Cp, Mq, Cq, d, p, w);
             double st = 0.0;
+            if constexpr (FAST) {
+                float w[EPV];
+                st = (double)tree_slot_weights_f32<BF16>(vp[j], vq[j], fn, fd, p, w);
 #pragma unroll
-            for (int e = 0; e < EPV; ++e) {
-                st += w[e];
-                if (w[e] > 0.0) my_last = (c0 + j) * EPV + e;
+                for (int e = 0; e < EPV; ++e)
+                    if (w[e] > 0.f) my_last = (c0 + j) * EPV + e;
+            } else {
+                double w[EPV];
+                tree_slot_weights<BF16>(vp[j], vq[j], Mp, Cp, Mq, Cq, d, p, w);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    st += w[e];
+                    if (w[e] > 0.0) my_last = (c0 + j) * EPV + e;
+                }
             }
             my_total += st;
             if (c0 == my0) slot_total[j] = st;
@@ -238,7 +316,14 @@ __device__ inline int tree_draw(const void *rowp, const void *rowq, int nslots, 
         double before = c, after = c;
         auto walk_slot = [&](int slot, const u32x4 &vp, const u32x4 &vq) __attribute__((always_inline)) {
             double w[EPV];
-            tree_slot_weights<BF16>(vp, vq, Mp, Cp, Mq, Cq, d, p, w);
+            if constexpr (FAST) {
+                float wf[EPV];
+                (void)tree_slot_weights_f32<BF16>(vp, vq, fn, fd, p, wf);
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) w[e] = (double)wf[e];
+            } else {
+                tree_slot_weights<BF16>(vp, vq, Mp, Cp, Mq, Cq, d, p, w);
+            }
 #pragma unroll
             for (int e = 0; e < EPV; ++e) {
                 if (tok < 0) {
@@ -345,10 +430,10 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
                 row_stats<BF16, false>(rowp, rowp, nslots, p.V, sh, parity, p, M, S, Mq, Sq);
             }
             const Depth d0{0, 1.0, 1.0, sh_inv_z};
-            const double Z = tree_region_totals<BF16, FULL>(rowp, rowp, nslots, p.V, M, S, M, S, d0, sh, p);
+            const double Z = tree_region_totals<BF16, FULL, ONE_TERM>(rowp, rowp, nslots, p.V, M, S, M, S, d0, sh, p);
             if (Z > 0.0) {
                 int edge = 0;
-                final_token = tree_draw<BF16, FULL>(rowp, rowp, nslots, p.V, M, S, M, S, d0, u_fin, sh, p, edge);
+                final_token = tree_draw<BF16, FULL, ONE_TERM>(rowp, rowp, nslots, p.V, M, S, M, S, d0, u_fin, sh, p, edge);
                 flag_cdf |= edge;
             } else {  // row without any finite logit: report the last token
                 final_token = p.V - 1;
@@ -408,7 +493,7 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
             depth += 1;
             {
                 const Depth d{depth, sh_inv_z[1], sh_inv_z[2], sh_inv_z};
-                Zd = tree_region_totals<BF16, FULL>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, sh, p);
+                Zd = tree_region_totals<BF16, FULL, ONE_TERM>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, sh, p);
             }
             if (Zd > 0.0) {
                 have_totals = true;
@@ -427,10 +512,10 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
         // every child was rejected: one draw from the running distribution
         const Depth d{depth, sh_inv_z[1], sh_inv_z[2], sh_inv_z};
         if (!have_totals)
-            Zd = tree_region_totals<BF16, FULL>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, sh, p);
+            Zd = tree_region_totals<BF16, FULL, ONE_TERM>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, sh, p);
         if (Zd > 0.0) {
             int edge = 0;
-            final_token = tree_draw<BF16, FULL>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, u_fin, sh, p, edge);
+            final_token = tree_draw<BF16, FULL, ONE_TERM>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, u_fin, sh, p, edge);
             flag_cdf |= edge;
         } else {
             final_token = p.V - 1;
