@@ -6,7 +6,7 @@ A "step" is one pass of the whole hot path over one synthetic batch: verify atte
 are resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sigma S]
-                    [--tree DEPTHxBRANCH] [--page-size P] [--no-cpu-baseline]
+                    [--tree DEPTHxBRANCH] [--page-size P] [--no-cpu-baseline] [--no-measure-depth]
     python bench.py --kd-rows N [--workload NAME] [--sigma S]
     python bench.py --sweep --workload qwen14b_sweep [--sweep-batches 64,256,...] [--sweep-ks 0,1,2,4,8]
 
@@ -366,7 +366,10 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
     # its own (same lengths, fresh random values, so no layer finds its cache in a cache), one
     # attention call per layer, then the sampler.  GEMMs, norms and the LM head stay outside.
     measured_depth = None
-    if args.measure_depth and tree is None and paged is None:
+    kv_bytes_all_layers = layers * 2 * batch.k_cache.numel() * batch.k_cache.element_size()
+    want_depth = args.measure_depth if args.measure_depth is not None else (
+        kv_bytes_all_layers < 64e9 and not args.sweep)
+    if want_depth and tree is None and paged is None:
         g2 = torch.Generator(device=dev).manual_seed(wl.seed + 1000)
         caches = [(batch.k_cache, batch.v_cache)]
         for _ in range(layers - 1):
@@ -544,8 +547,9 @@ def main():
                     help="in the timed region, bracket the main attention kernel with events on every n-th step")
     ap.add_argument("--layers", type=int, default=None,
                     help="attention layers of the modelled full-depth figure (default: the model's public card)")
-    ap.add_argument("--measure-depth", action="store_true",
-                    help="also time the step with one attention call per layer (each layer its own KV cache)")
+    ap.add_argument("--measure-depth", action=argparse.BooleanOptionalAction, default=None,
+                    help="also time the step with one attention call per layer, each layer on a KV cache of its "
+                         "own (default: on when those caches take less than 64 GB; never in --sweep)")
     ap.add_argument("--cpu-seqs", type=int, default=256,
                     help="sequences the oracle is timed on (cpu_baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
