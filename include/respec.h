@@ -184,6 +184,21 @@ respec_status_t respec_verify_attention_paged(const void *q, const void *k_pages
                                               size_t workspace_bytes, void *hip_stream);
 
 /*
+ * respec_verify_attention_next_layer for a paged cache: another layer of the same forward,
+ * whose K and V pools (k_pages, v_pages) are laid out by the same page table.  Same contract:
+ * the workspace is the one of an earlier respec_verify_attention_paged call (or of a call of
+ * this function) with the same q_indptr, page_indptr, page_table and kv_len contents and the
+ * same sizes, untouched since; the set-up it holds is reused.  Bit-equal to a full call.
+ */
+respec_status_t respec_verify_attention_paged_next_layer(
+    const void *q, const void *k_pages, const void *v_pages, const int32_t *q_indptr,
+    const int32_t *page_indptr, const int32_t *page_table, const int32_t *kv_len,
+    const uint64_t *tree_mask, void *out, float *lse, int32_t B, int32_t total_q, int32_t num_pages,
+    int32_t page_table_len, int32_t page_size, int32_t max_q_per_seq, int32_t max_kv_len, int32_t Hq,
+    int32_t Hkv, int32_t D, float sm_scale, respec_dtype_t dt, void *workspace, size_t workspace_bytes,
+    void *hip_stream);
+
+/*
  * Commit of a verify step in a paged cache (Section 2.2, "Validation": accepted drafts are
  * kept, the rest of the speculative tokens are dropped; Section 4.3: sequences move between
  * speculative and plain decoding with their cache in place).  Before the call sequence b holds

@@ -92,6 +92,8 @@ def load():
         c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
         c.c_int32, c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
+    lib.respec_verify_attention_paged_next_layer.restype = c.c_int
+    lib.respec_verify_attention_paged_next_layer.argtypes = lib.respec_verify_attention_paged.argtypes
     lib.respec_commit_accepted_paged.restype = c.c_int
     lib.respec_commit_accepted_paged.argtypes = [
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
@@ -124,7 +126,7 @@ class ProfilePoint(ctypes.Structure):
 EXPORTED_SYMBOLS = [
     "respec_status_string", "respec_last_error", "respec_version",
     "respec_verify_attention_workspace_bytes", "respec_verify_attention", "respec_verify_attention_tree",
-    "respec_verify_attention_next_layer",
+    "respec_verify_attention_next_layer", "respec_verify_attention_paged_next_layer",
     "respec_rejection_sample_workspace_bytes", "respec_rejection_sample", "respec_rejection_sample_per_seq",
     "respec_tree_rejection_sample", "respec_verify_attention_paged", "respec_commit_accepted_paged",
     "respec_kd_rows_workspace_bytes", "respec_kd_rows", "respec_solver_pick",
@@ -396,8 +398,18 @@ def respec_tree_rejection_sample(target_logits, draft_logits, node_tokens, paren
         _stream_ptr(stream)))
 
 
+def respec_verify_attention_paged_next_layer(q, k_pages, v_pages, q_indptr, page_indptr, page_table, kv_len, out,
+                                             lse, max_q_per_seq, max_kv_len, sm_scale, workspace, tree_mask=None,
+                                             stream=None):
+    """Another layer's pools behind the same page table: reuses the set-up in the workspace."""
+    respec_verify_attention_paged(q, k_pages, v_pages, q_indptr, page_indptr, page_table, kv_len, out, lse,
+                                  max_q_per_seq, max_kv_len, sm_scale, workspace, tree_mask=tree_mask, stream=stream,
+                                  _entry="respec_verify_attention_paged_next_layer")
+
+
 def respec_verify_attention_paged(q, k_pages, v_pages, q_indptr, page_indptr, page_table, kv_len, out, lse,
-                                  max_q_per_seq, max_kv_len, sm_scale, workspace, tree_mask=None, stream=None):
+                                  max_q_per_seq, max_kv_len, sm_scale, workspace, tree_mask=None, stream=None,
+                                  _entry="respec_verify_attention_paged"):
     """k_pages, v_pages [num_pages, page_size, Hkv, D]; out is written in place."""
     lib = load()
     total_q, Hq, D = q.shape
@@ -419,7 +431,7 @@ def respec_verify_attention_paged(q, k_pages, v_pages, q_indptr, page_indptr, pa
     if lse is not None and (lse.dtype != torch.float32 or tuple(lse.shape) != (total_q, Hq)):
         raise TypeError("lse must be float32 [total_q, Hq]")
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib.respec_verify_attention_paged(
+    _check(getattr(lib, _entry)(
         _dev_ptr(q, "q"), _dev_ptr(k_pages, "k_pages"), _dev_ptr(v_pages, "v_pages"), _dev_ptr(q_indptr, "q_indptr"),
         _dev_ptr(page_indptr, "page_indptr"), _dev_ptr(page_table, "page_table"), _dev_ptr(kv_len, "kv_len"),
         _dev_ptr(tree_mask, "tree_mask"), _dev_ptr(out, "out"), _dev_ptr(lse, "lse"), B, total_q, num_pages,

@@ -1478,6 +1478,24 @@ respec_status_t respec_verify_attention_paged(const void *q, const void *k_pages
                                         workspace_bytes, hip_stream);
 }
 
+respec_status_t respec_verify_attention_paged_next_layer(const void *q, const void *k_pages, const void *v_pages,
+                                                         const int32_t *q_indptr, const int32_t *page_indptr,
+                                                         const int32_t *page_table, const int32_t *kv_len,
+                                                         const uint64_t *tree_mask, void *out, float *lse,
+                                                         int32_t B, int32_t total_q, int32_t num_pages,
+                                                         int32_t page_table_len, int32_t page_size,
+                                                         int32_t max_q_per_seq, int32_t max_kv_len, int32_t Hq,
+                                                         int32_t Hkv, int32_t D, float sm_scale, respec_dtype_t dt,
+                                                         void *workspace, size_t workspace_bytes,
+                                                         void *hip_stream) {
+    if (!page_table)
+        return respec::fail(RESPEC_ERR_INVALID_ARG, "verify_attention_paged: null page_table");
+    const respec::Pages pg{page_indptr, page_table, kv_len, num_pages, page_table_len, page_size};
+    return respec::verify_attention_any(q, k_pages, v_pages, q_indptr, nullptr, pg, tree_mask, out, lse, B, total_q,
+                                        0, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt, workspace,
+                                        workspace_bytes, hip_stream, true);
+}
+
 respec_status_t respec_commit_accepted_paged(void *k_pages, void *v_pages, const int32_t *q_indptr,
                                              const int32_t *page_indptr, const int32_t *page_table,
                                              int32_t *kv_len, const int32_t *path, int32_t path_stride,

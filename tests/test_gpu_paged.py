@@ -195,6 +195,40 @@ def test_verify_commit_then_plain_decode(oracle):
     _check(out, lse, ref, ref_lse, "bf16")
 
 
+def test_next_layer_on_a_paged_cache_is_bit_equal_to_a_full_call(oracle):
+    """Another layer's K/V pools behind the same page table: the set-up in the workspace is reused."""
+    wl = _wl("paged_layers", 28, 4, 128, "bf16")
+    batch = synth.make_batch(wl, device="cuda", kv_lens=LENS, k_per_seq=KS, seed=41, with_logits=False)
+    pk = synth.paginate(batch.k_cache, batch.v_cache, batch.kv_lens, 16, seed=42, extra_pages_per_seq=1)
+    g = torch.Generator(device="cuda").manual_seed(43)
+    k2 = torch.empty_like(pk.k_pages).normal_(generator=g)      # layer 2: other values in the same slots
+    v2 = torch.empty_like(pk.v_pages).normal_(generator=g)
+    q2 = torch.empty_like(batch.q).normal_(generator=g)
+    B, max_rows, max_kv = pk.kv_len.numel(), max(KS) + 1, int(pk.kv_len.max())
+    ws = torch.empty(binding.respec_verify_attention_workspace_bytes(
+        B, batch.total_q, pk.num_pages * pk.page_size, max_rows, max_kv, wl.Hq, wl.Hkv, wl.D, binding.RESPEC_BF16),
+        dtype=torch.uint8, device="cuda")
+
+    def run(entry, q, kp, vp):
+        out = torch.full_like(q, float("nan"))
+        lse = torch.full((batch.total_q, wl.Hq), float("nan"), dtype=torch.float32, device="cuda")
+        entry(q, kp, vp, batch.q_indptr, pk.page_indptr, pk.page_table, pk.kv_len, out, lse, max_rows, max_kv,
+              1.0 / math.sqrt(wl.D), ws)
+        torch.cuda.synchronize()
+        return out, lse
+
+    full2 = run(binding.respec_verify_attention_paged, q2, k2, v2)
+    ws.zero_()
+    run(binding.respec_verify_attention_paged, batch.q, pk.k_pages, pk.v_pages)              # layer 1 sets up
+    next2 = run(binding.respec_verify_attention_paged_next_layer, q2, k2, v2)               # layer 2 reuses
+    assert torch.equal(full2[0].view(torch.int16), next2[0].view(torch.int16)) and torch.equal(full2[1], next2[1])
+    ref, ref_lse = oracle.verify_attention_paged(
+        synth.to_host_array(q2), synth.to_host_array(k2), synth.to_host_array(v2), batch.q_indptr.cpu().numpy(),
+        pk.page_indptr.cpu().numpy(), pk.page_table.cpu().numpy(), pk.kv_len.cpu().numpy(), wl.Hq, wl.Hkv, wl.D,
+        float(np.float32(1.0 / math.sqrt(wl.D))), oracle.BF16, tree_mask=None, want_lse=True, n_threads=0)
+    _check(next2[0], next2[1], ref, ref_lse, "bf16")
+
+
 def test_bad_arguments_are_rejected_before_any_launch():
     wl = _wl("paged_err", 4, 2, 64, "f32")
     batch = synth.make_batch(wl, device="cuda", kv_lens=[40, 20], k_per_seq=[1, 1], seed=1, with_logits=False)
