@@ -268,8 +268,16 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
                                                  paged.page_table, paged.kv_len, n_acc, batch.total_q, max_q,
                                                  path=path if tree is not None else None)
     else:
+        # --rotate N: N copies of the large inputs (KV cache, logits) used in turn, so that no step
+        # finds its data in the last-level cache from the step before (chain drafts only)
+        n_sets = max(1, args.rotate) if tree is None else 1
+        sets = [(batch.k_cache, batch.v_cache, batch.target_logits, batch.draft_logits)]
+        for _ in range(n_sets - 1):
+            sets.append(tuple(t.clone() for t in sets[0]))
+        turn = {"i": 0}
+
         def commit():
-            pass
+            turn["i"] += 1
 
         if tree is not None:
             def attention():
@@ -278,7 +286,8 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
                                                      batch.max_kv_len, sm_scale, ws)
         else:
             def attention():
-                binding.respec_verify_attention(batch.q, batch.k_cache, batch.v_cache, batch.q_indptr,
+                kc, vc = sets[turn["i"] % n_sets][:2]
+                binding.respec_verify_attention(batch.q, kc, vc, batch.q_indptr,
                                                 batch.kv_indptr, out, lse, max_q, batch.max_kv_len,
                                                 sm_scale, ws)
 
@@ -289,7 +298,8 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
                                                  toks, path, n_acc, flags, max_q, max_out, wl.temperature)
     else:
         def sampler():
-            binding.respec_rejection_sample(batch.target_logits, batch.draft_logits,
+            tl, dl = sets[turn["i"] % n_sets][2:] if paged is None else (batch.target_logits, batch.draft_logits)
+            binding.respec_rejection_sample(tl, dl,
                                             batch.draft_tokens, batch.q_indptr, batch.u_accept,
                                             batch.u_final, toks, n_acc, flags, batch.max_k,
                                             wl.temperature, workspace=samp_ws)
@@ -440,7 +450,7 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
             "B": B, "k": wl.k, "ragged_k": wl.ragged_k, "Hq": wl.Hq,
             "Hkv": wl.Hkv, "D": wl.D, "V": wl.V, "sigma": wl.sigma, "temperature": wl.temperature,
             "kv_len": f"{wl.len_dist}[{wl.len_lo},{wl.len_hi}]", "total_kv": batch.total_kv,
-            "seed": wl.seed,
+            "seed": wl.seed, "rotating_input_sets": args.rotate if (tree is None and paged is None) else 1,
         },
         "verify_step_us": ms_step * 1e3,
         "kernel_us": {"attention_prep": ms_prep * 1e3, "attention_main": ms_main * 1e3, "attention_combine": ms_comb * 1e3,
@@ -555,6 +565,8 @@ def main():
     ap.add_argument("--measure-depth", action=argparse.BooleanOptionalAction, default=None,
                     help="also time the step with one attention call per layer, each layer on a KV cache of its "
                          "own (default: on when those caches take less than 64 GB; never in --sweep)")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="copies of the KV cache and the logits used in turn (cold-cache timing of small workloads)")
     ap.add_argument("--cpu-seqs", type=int, default=256,
                     help="sequences the oracle is timed on (cpu_baseline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
