@@ -12,7 +12,7 @@
  *                             sequence, grouped-query heads, ragged per-sequence KV cache;
  *   respec_rejection_sample   Eq. 1 / Eq. 2 over the vocabulary with supplied uniforms
  *                             (respec_rejection_sample_per_seq: one temperature per sequence, 0 = greedy);
- * their counterparts for a tree of drafts (Section 3.1), respec_verify_attention_tree and
+ * their counterparts for a tree of drafts (Section 4.1), respec_verify_attention_tree and
  * respec_tree_rejection_sample, the paged-cache forms respec_verify_attention_paged and
  * respec_commit_accepted_paged, respec_kd_rows, the drafter's distillation loss over the
  * same logits rows (Section 5.3), and respec_solver_pick, the Solver's table look-up (host code).
@@ -132,7 +132,7 @@ respec_status_t respec_verify_attention_next_layer(const void *q, const void *k_
                                                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Verify attention over a tree of drafts (Section 3.1: candidate branches, branching factor
+ * Verify attention over a tree of drafts (Section 4.1: candidate branches, branching factor
  * t, validated in parallel).  As respec_verify_attention, except for which of a sequence's
  * own new tokens a row sees: row i of sequence b (rows in an order in which parents come
  * first, row 0 the root = the last committed token; the R_b new tokens are the last R_b
@@ -154,7 +154,7 @@ respec_status_t respec_verify_attention_tree(const void *q, const void *k_cache,
 
 /*
  * Verify attention over a paged KV cache (the cache the serving side manages while it moves
- * sequences between speculative and plain decoding, Sections 4.2 and 4.3; the paper fixes no
+ * sequences between speculative and plain decoding, Sections 5.1 and 5.2; the paper fixes no
  * layout, this one is the library's).  The result is that of respec_verify_attention (or, with
  * a tree_mask, of respec_verify_attention_tree) on the sequence's tokens taken in order:
  * token j of sequence b lives in slot j % page_size of page
@@ -200,7 +200,7 @@ respec_status_t respec_verify_attention_paged_next_layer(
 
 /*
  * Commit of a verify step in a paged cache (Section 2.2, "Validation": accepted drafts are
- * kept, the rest of the speculative tokens are dropped; Section 4.3: sequences move between
+ * kept, the rest of the speculative tokens are dropped; Section 5.2: sequences move between
  * speculative and plain decoding with their cache in place).  Before the call sequence b holds
  * kv_len[b] tokens of which the last R_b are the new ones, row r at position
  * first_new + r (first_new = kv_len[b] - R_b; row 0 is the last committed token).  With
@@ -321,7 +321,7 @@ respec_status_t respec_rejection_sample_per_seq(const void *target_logits, const
                                                 void *hip_stream);
 
 /*
- * Rejection sampling over a tree of drafts (Section 3.1: candidate branches with branching
+ * Rejection sampling over a tree of drafts (Section 4.1: candidate branches with branching
  * factor t validated in parallel; Section 2.2, Eq. 1 and Eq. 2 applied to sibling candidates
  * one after the other).  The paper states the rule for a chain only; this is the reading
  * that keeps the result distributed as the target model when the children of a node are
@@ -420,7 +420,7 @@ respec_status_t respec_validate_batch(const int32_t *q_indptr, const int64_t *kv
                                       void *hip_stream);
 
 /*
- * The Solver's choice of the draft length for the current active batch size (Section 4.2,
+ * The Solver's choice of the draft length for the current active batch size (Section 5.2,
  * "Solver: Offline Profiling Guided Search": configurations are profiled offline per batch
  * size, a performance model predicts the speedup, and at run time the configuration with the
  * best prediction for the observed active batch size is selected).  HOST code: every pointer

@@ -339,7 +339,7 @@ def softmax_rows(logits, temperature, dtype):
 
 def solver_pick(points, active_batch, draft_us_fixed, draft_us_per_seq):
     """The Solver's choice of the draft length for one active batch size, from a profile table
-    (Section 4.2, "Solver: Offline Profiling Guided Search") under the cost model of Eq. 4.
+    (Section 5.2, "Solver: Offline Profiling Guided Search") under the cost model of Eq. 4.
 
     ``points``: iterable of (batch, k, step_us, emitted_per_seq) measured offline; k = 0 is plain
     decoding.  For every k in the table the step time and the emitted tokens per sequence at

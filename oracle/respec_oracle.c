@@ -207,7 +207,7 @@ int respec_oracle_verify_attention(const void *q, const void *k_cache, const voi
                                 sm_scale, dtype, n_threads, NULL);
 }
 
-/* Verify attention over a tree of drafts (Section 3.1: candidate branches validated in
+/* Verify attention over a tree of drafts (Section 4.1: candidate branches validated in
  * parallel); tree_mask [total_q] as described above, at most 64 rows per sequence. */
 int respec_oracle_verify_attention_tree(const void *q, const void *k_cache, const void *v_cache,
                                         const int32_t *q_indptr, const int64_t *kv_indptr,
@@ -222,7 +222,7 @@ int respec_oracle_verify_attention_tree(const void *q, const void *k_cache, cons
 }
 
 /* ------------------------------------------------------------------------- */
-/* Paged KV cache (the cache the serving side manages, Sections 4.2 and 4.3;   */
+/* Paged KV cache (the cache the serving side manages, Sections 5.1 and 5.2;   */
 /* the paper fixes no layout).  K and V live in pages of page_size tokens,     */
 /* [num_pages, page_size, Hkv, D]; sequence b owns the page ids                */
 /* page_table[page_indptr[b] .. page_indptr[b+1]) in token order and holds     */
@@ -597,7 +597,7 @@ int respec_oracle_rejection_sample_per_seq(const void *target_logits, const void
 
 /* ------------------------------------------------------------------------- */
 /* Rejection sampling over a tree of drafts.                                   */
-/* The paper names the tree (branching factor t, Section 3.1) and refers to    */
+/* The paper names the tree (branching factor t, Section 4.1) and refers to    */
 /* its drafting method for the rest; this build's reading is the multi-round   */
 /* form of Eq. 1 / Eq. 2 for sibling candidates drawn independently from the   */
 /* same drafter distribution q:                                                */

@@ -1,4 +1,4 @@
-// The Solver's choice of the draft length for an active batch size (Section 4.2, "Solver:
+// The Solver's choice of the draft length for an active batch size (Section 5.2, "Solver:
 // Offline Profiling Guided Search"), host code only.  The profile table is what an offline
 // sweep of the verify step measures (batch size, draft length, step time, tokens emitted per
 // sequence); the choice minimises Eq. 4's cost per produced token with the measured

@@ -1,4 +1,4 @@
-// Rejection sampling over a tree of drafts for gfx950 (Section 3.1: several candidate
+// Rejection sampling over a tree of drafts for gfx950 (Section 4.1: several candidate
 // branches per position, branching factor t, validated in one target forward).
 //
 // The paper gives the chain rule (Section 2.2, Eq. 1 and Eq. 2) and leaves the rule for
