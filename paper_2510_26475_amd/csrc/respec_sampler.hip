@@ -702,11 +702,12 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     __shared__ SharedState sh;
     __shared__ uint32_t sh_epoch;
     constexpr int EPV = Elem<BF16>::EPV;
-    // the fp32 form of the final draw's weights: calls whose exponent constant rounds well, one
-    // work-group per sequence
-    constexpr bool kFastScan = ONE_TERM && !SHARED;
+    // the fp32 form of the final draw's weights: calls whose exponent constant rounds well (the
+    // parts of a shared sequence form identical constants from the identical normalisers they
+    // hold after the exchange); the table of slot totals only with one work-group per sequence
+    constexpr bool kFastScan = ONE_TERM;
     extern __shared__ __align__(16) char sampler_smem[];
-    float *tab = kFastScan && p.tab_slots > 0 ? reinterpret_cast<float *>(sampler_smem) : nullptr;
+    float *tab = kFastScan && !SHARED && p.tab_slots > 0 ? reinterpret_cast<float *>(sampler_smem) : nullptr;
     const int split = SHARED ? p.split : 1;
     const int b = blockIdx.x / split, part = blockIdx.x % split;
     // bounds come from device data: clamp them by the host-side totals so that no value of
