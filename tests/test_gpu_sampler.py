@@ -276,3 +276,13 @@ def test_extreme_final_uniforms_pick_tokens_with_mass(oracle, no_table, monkeypa
             assert cdf[tok] - w[tok] / w.sum() <= 2e-6      # nothing but rounding noise before it
         else:
             assert cdf[tok] >= 1.0 - 2e-6                   # at the far end of the support
+
+
+@pytest.mark.parametrize("T", [0.25, 0.5, 0.6, 0.7, 1.3, 2.0])
+def test_temperatures_on_both_sides_of_the_one_term_criterion(oracle, T):
+    """log2(e)/T rounds well for some temperatures (powers of two times 1, a few others) and
+    badly for the rest: the former take the one-fma exponent and the fp32 weights of the final
+    draw, the latter the two-term exponent and fp64 weights.  Both must agree with the oracle."""
+    wl = _wl("temps", 151936, "bf16", sigma=1.0, T=T)
+    _, ref, _ = _parity(oracle, _batch(wl, [3] * 20 + [0, 1, 2, 4], seed=int(100 * T)))
+    assert len(set(ref[1].tolist())) >= 2
