@@ -443,11 +443,14 @@ __device__ inline void wait_at_least(LdsCounter flag, uint32_t need, bool &alive
 // each with half of the columns, and the two producers of the range move its tiles in turn
 // (producer w the tiles j = w mod 2, each into its own ring).  A work-group then walks two
 // ranges instead of four.  Each consumer keeps its own `consumed`; a producer reuses a slot once
-// both have passed it.
+// both have passed it.  CW = 4 is the same with all four consumers on one range (up to 128
+// columns: the trees of a drafter that proposes ten to eighteen nodes per sequence at a group of
+// seven heads): the four producers take the range's tiles in turn and the work-group walks one
+// range.
 template <int D, int NT, typename OutT, int CW>
 __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnParams p) {
     using C = Bf16Cfg<D>;
-    static_assert(CW == 1 || CW == 2, "one or two consumers per range");
+    static_assert(CW == 1 || CW == 2 || CW == 4, "one, two or four consumers per range");
     constexpr int kStreams = kConsumers / CW;     // ranges per work-group
     extern __shared__ __align__(16) char smem[];  // [kConsumers][kSlots][kWaveBytes] | counters
     const LdsCounter counters = (LdsCounter)(smem + kConsumers * kSlots * C::kWaveBytes);
@@ -459,7 +462,9 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     const int stream = role / CW, way = role % CW;
     const int c16 = lane & 15, g4 = lane >> 4;
     const int u = blockIdx.x * kStreams + stream;  // index of this range in the split
-    const int col0 = blockIdx.y * kMaxColsPerBlock + (producer ? 0 : way * NT * kColTile);
+    // columns of a column block: 64 with one consumer per range, else what the consumers hold
+    constexpr int kBlockCols = CW == 1 ? kMaxColsPerBlock : CW * NT * kColTile;
+    const int col0 = blockIdx.y * kBlockCols + (producer ? 0 : way * NT * kColTile);
 
     if (threadIdx.x < 3 * kConsumers) counters[threadIdx.x] = 0;
     __syncthreads();  // the only barrier, before any wave can leave
@@ -512,10 +517,10 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
         // buffer leaves exactly the younger ones in flight.  An idle request re-reads one
         // 256-byte piece of the last tile, which the caches hold.
         bool next_known = false;  // cp.nb / cp.nh / cp.nsi have been looked up
-        if (CW > 1 && way > 0 && way < n_tiles) {  // the second producer starts one tile in
+        if (CW > 1 && way > 0 && way < n_tiles) {  // producer `way` starts `way` tiles in
             cursor_find_next(p, cp);
             next_known = true;
-            cursor_advance(p, cp);
+            for (int c = 0; c < way; ++c) cursor_advance(p, cp);
         }
         const bool paged = p.page_table != nullptr;
         TileOffsets next_off{0, 0};
@@ -791,50 +796,56 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             asm volatile("" ::: "memory");
             if constexpr (CW > 1) {
                 read_done[role] = (uint32_t)(idx + 1);
-                wait_at_least(read_done + (role ^ 1), (uint32_t)(idx + 1), alive, p.error_flag);
+#pragma unroll
+                for (int c = 1; c < CW; ++c)  // every consumer of the range has read the tile
+                    wait_at_least(read_done + stream * CW + (way + c) % CW, (uint32_t)(idx + 1), alive, p.error_flag);
                 asm volatile("" ::: "memory");
             }
-            constexpr int kTilesPerPass = 2 / CW;             // column tiles staged together
-            constexpr int kStageCols = kTilesPerPass * kColTile;
-            float *stage = reinterpret_cast<float *>(k_lds + (CW > 1 ? way * C::kTileBytes : 0));  // [kStageCols][kMergeStride]
+            // columns staged together: what fits this consumer's share of the slot
+            constexpr int kStageCols = 2 * kColTile / CW;     // 32, 16 or 8
+            constexpr int kPasses = (NT * kColTile + kStageCols - 1) / kStageCols;
+            float *stage = reinterpret_cast<float *>(k_lds + way * (C::kWaveBytes / CW));  // [kStageCols][kMergeStride]
             float *stat = stage + kStageCols * C::kMergeStride;  // [kStageCols]: max, sum, output row, largest magnitude
             static_assert((kStageCols * C::kMergeStride + kStageCols * 4) * 4 <= C::kWaveBytes / CW, "staging fits its share of a slot");
+            static_assert((C::kWaveBytes / CW) % 16 == 0, "shares of a slot stay 16-byte aligned");
             constexpr int kLanesPerOutRow = D / 4;            // lanes that cover a row, 4 floats each
             constexpr int kRowsPerPass = 64 / kLanesPerOutRow;
 #pragma unroll
-            for (int pp = 0; pp < (NT + kTilesPerPass - 1) / kTilesPerPass; ++pp) {
+            for (int pp = 0; pp < kPasses; ++pp) {
 #pragma unroll
-                for (int h = 0; h < kTilesPerPass; ++h) {
-                    const int nt = kTilesPerPass * pp + h;
-                    if (nt < NT) {
-                        const float lt = sum_across_rows(l_run[nt < NT ? nt : 0]);
-                        float *row = stage + (h * kColTile + c16) * C::kMergeStride;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-#pragma unroll
-                            for (int t = 0; t < C::kEpl; t += 4)
-                                *reinterpret_cast<floatx4 *>(row + C::kEpl * (4 * g4 + r) + t) =
-                                    floatx4{acc_o[nt < NT ? nt : 0][t][r], acc_o[nt < NT ? nt : 0][t + 1][r],
-                                            acc_o[nt < NT ? nt : 0][t + 2][r], acc_o[nt < NT ? nt : 0][t + 3][r]};
+                for (int nt = 0; nt < NT; ++nt) {
+                    // column tile nt has columns nt*16 .. nt*16+15 of this consumer; pass pp
+                    // stages columns pp*kStageCols .. +kStageCols-1 of them
+                    if ((nt * kColTile) / kStageCols <= pp && pp <= (nt * kColTile + kColTile - 1) / kStageCols) {
+                        const int local = nt * kColTile + c16 - pp * kStageCols;   // row of the stage, if in this pass
+                        const bool mine = local >= 0 && local < kStageCols;       // (lane-dependent only for 8-column passes)
+                        const float lt = sum_across_rows(l_run[nt]);
                         float amax = 0.f;  // largest magnitude of the column (scale of a partial)
                         if (!whole) {
 #pragma unroll
                             for (int t = 0; t < C::kDTiles; ++t)
 #pragma unroll
-                                for (int r = 0; r < 4; ++r) amax = fmaxf(amax, fabsf(acc_o[nt < NT ? nt : 0][t][r]));
+                                for (int r = 0; r < 4; ++r) amax = fmaxf(amax, fabsf(acc_o[nt][t][r]));
                             amax = max_across_rows(amax);
                         }
-                        if (g4 == 0) {
-                            const int ci = col_i[nt < NT ? nt : 0];
-                            const int orow = ci < cp.si.R
-                                                 ? (cp.si.q0 + ci) * p.Hq + kvh * p.G + col_gh[nt < NT ? nt : 0]
-                                                 : -1;
-                            *reinterpret_cast<floatx4 *>(stat + (h * kColTile + c16) * 4) =
-                                floatx4{m_run[nt < NT ? nt : 0], lt, __int_as_float(orow), amax};
+                        if (mine) {
+                            float *row = stage + local * C::kMergeStride;
+#pragma unroll
+                            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                                for (int t = 0; t < C::kEpl; t += 4)
+                                    *reinterpret_cast<floatx4 *>(row + C::kEpl * (4 * g4 + r) + t) =
+                                        floatx4{acc_o[nt][t][r], acc_o[nt][t + 1][r], acc_o[nt][t + 2][r], acc_o[nt][t + 3][r]};
+                            if (g4 == 0) {
+                                const int ci = col_i[nt];
+                                const int orow = ci < cp.si.R ? (cp.si.q0 + ci) * p.Hq + kvh * p.G + col_gh[nt] : -1;
+                                *reinterpret_cast<floatx4 *>(stat + local * 4) =
+                                    floatx4{m_run[nt], lt, __int_as_float(orow), amax};
+                            }
                         }
                     }
                 }
-                const int n_cols = (NT - kTilesPerPass * pp) >= kTilesPerPass ? kStageCols : kColTile;  // columns staged in this pass
+                const int n_cols = min(kStageCols, NT * kColTile - pp * kStageCols);  // columns staged in this pass
 #pragma unroll
                 for (int it = 0; it < kStageCols / kRowsPerPass; ++it) {
                     if (it * kRowsPerPass >= n_cols) break;
@@ -1197,6 +1208,7 @@ hipError_t launch_bf16(const AttnParams &p, dim3 grid, hipStream_t stream) {
 // nt: column tiles of a column block; cw: consumers that share a range
 template <int D>
 hipError_t launch_bf16_nt(int nt, int cw, const AttnParams &p, dim3 grid, hipStream_t stream) {
+    if (cw == 4) return launch_bf16<D, 2, 4>(p, grid, stream);
     if (cw == 2) return launch_bf16<D, 2, 2>(p, grid, stream);
     switch (nt) {
         case 1: return launch_bf16<D, 1, 1>(p, grid, stream);
@@ -1360,16 +1372,20 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
         return RESPEC_OK;
     }
 
-    const int col_blocks = (M + kMaxColsPerBlock - 1) / kMaxColsPerBlock;
+    // more than 64 columns (draft trees): blocks of 128 columns, four consumers per range, so
+    // that K and V are read once per 128 columns (RESPEC_ATTN_QUAD = 0: blocks of 64 as below)
+    const bool quad = M > kMaxColsPerBlock && env_long("RESPEC_ATTN_QUAD", 1) != 0;
+    const int block_cols = quad ? 2 * kMaxColsPerBlock : kMaxColsPerBlock;
+    const int col_blocks = (M + block_cols - 1) / block_cols;
     const int cols = col_blocks == 1 ? M : kMaxColsPerBlock;
-    const int nt = (cols + kColTile - 1) / kColTile;
+    const int nt = quad ? 2 : (cols + kColTile - 1) / kColTile;
     // a column block of four column tiles at D = 128 is more than one wave's registers hold
     // (400 bytes of spills per lane, measured 1.5x slower): two consumers share each range then.
     // Three tiles still run faster with one consumer per range and a few spills.
     // RESPEC_ATTN_WIDE = 0 / 1 overrides the choice for any block of more than two tiles (tests,
     // comparisons).
     const long wide = env_long("RESPEC_ATTN_WIDE", -1);
-    const int cw = nt > 2 && (wide < 0 ? (D == 128 && nt == 4) : wide != 0) ? 2 : 1;
+    const int cw = quad ? 4 : (nt > 2 && (wide < 0 ? (D == 128 && nt == 4) : wide != 0) ? 2 : 1);
     const int streams = kConsumers / cw;  // ranges per work-group
     // the split width: one range per consumer (or pair of consumers) of the device
     // (RESPEC_ATTN_WGS overrides it, for tests and sweeps)

@@ -86,9 +86,19 @@ def test_bf16_draft_lengths_14b_heads(oracle, k):
     _run(oracle, wl, [1500, 64 + k, 333], [k, k, k], seed=20 + k, wgs=37)
 
 
-def test_more_than_64_columns_uses_two_column_blocks(oracle):
-    wl = _wl("bf16_wide", 16, 2, 128, "bf16")            # G = 8, k = 8 -> 72 columns
-    _run(oracle, wl, [400, 90, 1025], [8, 8, 5], seed=31, wgs=11)
+@pytest.mark.parametrize("quad", [1, 0])
+@pytest.mark.parametrize("wgs", [None, 1, 3, 11, 64])
+@pytest.mark.parametrize("shape", [(16, 2, 128, 8), (28, 4, 128, 12), (16, 2, 128, 15), (16, 2, 128, 17),
+                                   (8, 1, 64, 10), (40, 8, 128, 20), (32, 2, 128, 15)])
+def test_more_than_64_columns(oracle, shape, wgs, quad):
+    """65 .. 256 MFMA columns (72, 91, 128, 144, 88, 105, 256).  quad = 1: column blocks of 128 with the
+    four consumers of a work-group on one range; quad = 0: column blocks of 64."""
+    Hq, Hkv, D, k = shape
+    wl = _wl("bf16_wide", Hq, Hkv, D, "bf16")
+    lens = [400, 90, 1025, 33, 2049, 64 + k, k + 1]
+    ks = [k, k, k - 3, k, k, k, k]
+    with env_setting("RESPEC_ATTN_QUAD", quad):
+        _run(oracle, wl, lens, ks, seed=31 + Hq + k + (wgs or 0), wgs=wgs)
 
 
 @pytest.mark.parametrize("wgs", [None, 1, 2, 3, 7, 64, 500])

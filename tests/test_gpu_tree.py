@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import attn_wgs, gpu_attention, gpu_tree_attention, oracle_tree_attention, sub_tree_batch
+from helpers import attn_wgs, env_setting, gpu_attention, gpu_tree_attention, oracle_tree_attention, sub_tree_batch
 from paper_2510_26475_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -85,12 +85,16 @@ def test_chain_mask_equals_the_chain_entry_point_bit_for_bit():
     assert torch.equal(out_t, out_c) and torch.equal(lse_t, lse_c)
 
 
-def test_wide_trees_use_two_column_blocks(oracle):
-    # 13 rows x 7 heads per group = 91 columns
+@pytest.mark.parametrize("quad", [1, 0])
+@pytest.mark.parametrize("wgs", [None, 2, 7])
+def test_wide_trees(oracle, wgs, quad):
+    # 13 rows x 7 heads per group = 91 columns: one block of 128 columns (quad) or two of 64
     wl = _wl("tree_wide", 28, 4, 128, "bf16")
-    pars = [synth.caterpillar_parents(4, 3), synth.caterpillar_parents(3, 4), synth.caterpillar_parents(2, 2)]
-    tb = synth.make_tree_batch(wl, pars, device="cuda", kv_lens=[600, 200, 90], seed=4, with_logits=False)
-    out, lse = gpu_tree_attention(tb)
+    pars = [synth.caterpillar_parents(4, 3), synth.caterpillar_parents(3, 4), synth.caterpillar_parents(2, 2),
+            synth.caterpillar_parents(6, 2), [-1]]
+    tb = synth.make_tree_batch(wl, pars, device="cuda", kv_lens=[600, 200, 90, 1300, 5], seed=4, with_logits=False)
+    with env_setting("RESPEC_ATTN_QUAD", quad), attn_wgs(wgs):
+        out, lse = gpu_tree_attention(tb)
     ref, ref_lse = oracle_tree_attention(oracle, tb)
     _check(out, lse, ref, ref_lse, "bf16")
 
