@@ -671,17 +671,31 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
         floatx4 s_acc[NT][2];
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) s_acc[nt][0] = s_acc[nt][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+        {
+            // The K fragments are read a few steps ahead of the products that use them: with one
+            // consumer wave per SIMD nothing else hides the latency of a read, and left to
+            // itself the compiler waits for each read right behind its issue.  The scheduling
+            // barriers keep the order written here.
+            constexpr int kFrags = 2 * C::kKSteps;  // (js, t) pairs, js-major
+            constexpr int kAhead = 3;
+            u32x4 kf[kFrags];
+            auto read_k = [&](const int i) __attribute__((always_inline)) {
+                const int js = i / C::kKSteps, t = i % C::kKSteps;
+                kf[i] = *reinterpret_cast<const u32x4 *>(k_lds + (js * 16 + c16) * C::kRowBytes + (t * 32 + g4 * 8) * 2);
+            };
 #pragma unroll
-        for (int js = 0; js < 2; ++js) {
+            for (int i = 0; i < kAhead; ++i) read_k(i);
 #pragma unroll
-            for (int t = 0; t < C::kKSteps; ++t) {
-                const u32x4 raw = *reinterpret_cast<const u32x4 *>(
-                    k_lds + (js * 16 + c16) * C::kRowBytes + (t * 32 + g4 * 8) * 2);
-                const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
+            for (int i = 0; i < kFrags; ++i) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (i + kAhead < kFrags) read_k(i + kAhead);
+                const bf16x8 a = __builtin_bit_cast(bf16x8, kf[i]);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    s_acc[nt][js] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[nt][t], s_acc[nt][js], 0, 0, 0);
+                    s_acc[nt][i / C::kKSteps] =
+                        __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qreg[nt][i % C::kKSteps], s_acc[nt][i / C::kKSteps], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         // online softmax per column; accumulator element (js, i) is key key0 + 16 js + 4 g4 + i
