@@ -43,10 +43,13 @@ __device__ inline void store_grad(void *dst, const float (&g)[Elem<BF16>::EPV]) 
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             w[j] = __builtin_bit_cast(uint32_t, __builtin_convertvector(floatx2{g[2 * j], g[2 * j + 1]}, bf16x2));
-        *reinterpret_cast<u32x4 *>(dst) = u32x4{w[0], w[1], w[2], w[3]};
+        // (written once and not read here: the non-temporal hint keeps the stores from
+        // displacing the rows that pass 2 is about to read again; 605 -> 570 us on 2048 rows)
+        __builtin_nontemporal_store(u32x4{w[0], w[1], w[2], w[3]}, reinterpret_cast<u32x4 *>(dst));
     } else {
-        *reinterpret_cast<u32x4 *>(dst) =
-            u32x4{__float_as_uint(g[0]), __float_as_uint(g[1]), __float_as_uint(g[2]), __float_as_uint(g[3])};
+        __builtin_nontemporal_store(
+            u32x4{__float_as_uint(g[0]), __float_as_uint(g[1]), __float_as_uint(g[2]), __float_as_uint(g[3])},
+            reinterpret_cast<u32x4 *>(dst));
     }
 }
 
@@ -90,8 +93,9 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
             for (int u = 0; u < kUnroll; ++u) {
                 const int s = it * kBatch + u * kThreads + (int)threadIdx.x;
                 const int safe = s < nslots ? s : 0;
-                vp[u] = *reinterpret_cast<const u32x4 *>(rp + (size_t)safe * 16);
-                vq[u] = *reinterpret_cast<const u32x4 *>(rq + (size_t)safe * 16);
+                // (the rows' last read: non-temporal, 568 -> 532 us on 2048 rows)
+                vp[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(rp + (size_t)safe * 16));
+                vq[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(rq + (size_t)safe * 16));
             }
         };
         double kl = 0.0;

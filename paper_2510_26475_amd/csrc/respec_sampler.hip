@@ -257,8 +257,8 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
 #pragma unroll
         for (int c = 0; c < kUnroll; ++c) {
             const int slot = s0 + c * 64 + lane;
-            vp[c] = load_slot<BF16, FULL>(rowp, slot < end ? slot : beg, Vrow, aligned);
-            if constexpr (RESID) vq[c] = load_slot<BF16, FULL>(rowq, slot < end ? slot : beg, Vrow, aligned);
+            vp[c] = load_slot<BF16, FULL, true>(rowp, slot < end ? slot : beg, Vrow, aligned);
+            if constexpr (RESID) vq[c] = load_slot<BF16, FULL, true>(rowq, slot < end ? slot : beg, Vrow, aligned);
         }
     };
     if (beg < end) {  // wave-uniform
