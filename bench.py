@@ -38,7 +38,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the attention main kernel from rocprofv3 --pmc (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by the same counters on a copy kernel of known size); the
 # summaries are under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"qwen7b_b256_k3": 1.2364e9}
+MEASURED_TRAFFIC_BYTES = {"qwen7b_b256_k3": 1.2337e9}
 
 
 def attention_algorithmic_bytes(batch: synth.VerifyBatch) -> int:
@@ -202,7 +202,7 @@ def run_kd(args, wl, dev):
         "total_loss": float(total.item()),
         "roofline": {"kernel": "kd_stream_kernel", "bound": "hbm", "achieved": algo / (ms * 1e-3) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": 3.004e9 if (rows == 2048 and V == 151936 and wl.dtype == "bf16") else None,
+                     "traffic": 2.880e9 if (rows == 2048 and V == 151936 and wl.dtype == "bf16") else None,
                      "note": "time per call (row kernel + the one-work-group finish kernel) by HIP events"},
     }
     if not args.no_cpu_baseline:
