@@ -1237,7 +1237,7 @@ hipError_t launch_bf16(const AttnParams &p, dim3 grid, hipStream_t stream) {
 template <int D>
 hipError_t launch_bf16_nt(int nt, int cw, const AttnParams &p, dim3 grid, hipStream_t stream) {
     if (cw == 4) return launch_bf16<D, 2, 4>(p, grid, stream);
-    if (cw == 2) return launch_bf16<D, 2, 2>(p, grid, stream);
+    if (cw == 2) return nt <= 2 ? launch_bf16<D, 1, 2>(p, grid, stream) : launch_bf16<D, 2, 2>(p, grid, stream);
     switch (nt) {
         case 1: return launch_bf16<D, 1, 1>(p, grid, stream);
         case 2: return launch_bf16<D, 2, 1>(p, grid, stream);
@@ -1410,10 +1410,11 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     // a column block of four column tiles at D = 128 is more than one wave's registers hold
     // (400 bytes of spills per lane, measured 1.5x slower): two consumers share each range then.
     // Three tiles still run faster with one consumer per range and a few spills.
-    // RESPEC_ATTN_WIDE = 0 / 1 overrides the choice for any block of more than two tiles (tests,
-    // comparisons).
+    // RESPEC_ATTN_WIDE = 0 / 1 overrides the choice for any block of two or more tiles (tests,
+    // comparisons; at two tiles the shared form halves the partials and the combine's work but
+    // measured 4 us slower in the main kernel, 211 vs 206 us at B = 256 and the 7B shape).
     const long wide = env_long("RESPEC_ATTN_WIDE", -1);
-    const int cw = quad ? 4 : (nt > 2 && (wide < 0 ? (D == 128 && nt == 4) : wide != 0) ? 2 : 1);
+    const int cw = quad ? 4 : (nt >= 2 && (wide < 0 ? (D == 128 && nt == 4) : wide != 0) ? 2 : 1);
     const int streams = kConsumers / cw;  // ranges per work-group
     // the split width: one range per consumer (or pair of consumers) of the device
     // (RESPEC_ATTN_WGS overrides it, for tests and sweeps)
