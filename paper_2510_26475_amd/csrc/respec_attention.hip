@@ -635,6 +635,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     constexpr bool kPrefetchQ = !(D == 128 && NT >= 3);
     bf16x8 qnext[kPrefetchQ ? NT : 1][C::kKSteps];
     bool qnext_valid = false;
+    bool q_in_place = false;  // qreg already holds the rows of the segment that begins
 
     // per-segment state
     int seg_t_first = 0;
@@ -664,7 +665,9 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
 #pragma unroll
                 for (int t = 0; t < C::kDTiles; ++t) acc_o[nt][t] = floatx4{0.f, 0.f, 0.f, 0.f};
             }
-            if (kPrefetchQ && qnext_valid) {
+            if (q_in_place) {
+                // (moved over at the end of the previous segment)
+            } else if (kPrefetchQ && qnext_valid) {
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -672,6 +675,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             } else if (idx > 0) {
                 load_q(qreg, cp.si, cp.h);
             }
+            q_in_place = false;
             if constexpr (kPrefetchQ) {
                 qnext_valid = cp.nh < p.Hkv;  // the segment after this one, if the list goes on
                 if (qnext_valid) load_q(qnext, cp.nsi, cp.nh);
@@ -818,6 +822,20 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
             // time, once both have read the tile.
             const bool whole = seg_t_first == 0 && cp.t == cp.si.tiles - 1;
             const int64_t slot = 2 * (int64_t)u + (seg_t_first > 0 ? 0 : 1);
+            // The next segment's query rows (requested when this segment began) move into place
+            // now, ahead of the stores below: vector memory operations complete in issue order,
+            // so taking them over after the stores would wait for every store's acknowledgement
+            // while the ring fills up behind this wave.
+            if constexpr (kPrefetchQ) {
+                if (qnext_valid && idx + 1 < n_tiles) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                        for (int t = 0; t < C::kKSteps; ++t) qreg[nt][t] = qnext[nt][t];
+                    q_in_place = true;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
             // (the staging reuses memory that other code reads and writes as 32-bit integer
             // vectors: keep the compiler from moving either across the borders of this block;
             // the hardware runs a wave's LDS operations in order)
@@ -894,7 +912,13 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                             if (p.lse && d4 == 0)
                                 p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
                         } else {
-                            const int64_t prow = slot * p.Mpad + col0 + pp * kStageCols + cl;
+                            // (row = wave-uniform part + this lane's row of the pass: written so
+                            // that the address is a scalar base plus one 32-bit lane offset that
+                            // all passes share; as one 64-bit per-lane expression the compiler
+                            // kept a register pair per pass alive through the whole kernel and
+                            // spilled some of them)
+                            const int64_t prow_u = slot * p.Mpad + col0 + pp * kStageCols + it * kRowsPerPass;
+                            const uint32_t lane_row = (uint32_t)(lane / kLanesPerOutRow);
                             // A partial is written as 16-bit fixed point relative to the row's
                             // largest magnitude (error below 2^-16 of it, far under the bf16
                             // rounding of the output): stores into a stream of reads cost several
@@ -904,11 +928,11 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
                             const float qs = (amax > 0.f && amax < INFINITY) ? 32767.f / amax : 0.f;
                             const int q0 = (int)__builtin_rintf(x[0] * qs), q1 = (int)__builtin_rintf(x[1] * qs);
                             const int q2 = (int)__builtin_rintf(x[2] * qs), q3 = (int)__builtin_rintf(x[3] * qs);
-                            stream_store(reinterpret_cast<u32x2 *>(p.ws_o + prow * D + d4),
+                            stream_store(reinterpret_cast<u32x2 *>(p.ws_o + prow_u * D + (lane_row * (uint32_t)D + (uint32_t)d4)),
                                       (u32x2{((uint32_t)q0 & 0xffffu) | ((uint32_t)q1 << 16),
                                              ((uint32_t)q2 & 0xffffu) | ((uint32_t)q3 << 16)}));
                             if (d4 == 0)
-                                *reinterpret_cast<floatx4 *>(p.ws_ml + prow * 4) = floatx4{mt, lt, amax, 0.f};
+                                *reinterpret_cast<floatx4 *>(p.ws_ml + prow_u * 4 + lane_row * 4u) = floatx4{mt, lt, amax, 0.f};
                         }
                     }
                 }
