@@ -1260,7 +1260,7 @@ hipError_t launch_bf16(const AttnParams &p, dim3 grid, hipStream_t stream) {
 // nt: column tiles of a column block; cw: consumers that share a range
 template <int D>
 hipError_t launch_bf16_nt(int nt, int cw, const AttnParams &p, dim3 grid, hipStream_t stream) {
-    if (cw == 4) return launch_bf16<D, 2, 4>(p, grid, stream);
+    if (cw == 4) return nt <= 4 ? launch_bf16<D, 1, 4>(p, grid, stream) : launch_bf16<D, 2, 4>(p, grid, stream);
     if (cw == 2) return nt <= 2 ? launch_bf16<D, 1, 2>(p, grid, stream) : launch_bf16<D, 2, 2>(p, grid, stream);
     switch (nt) {
         case 1: return launch_bf16<D, 1, 1>(p, grid, stream);
@@ -1426,11 +1426,23 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
 
     // more than 64 columns (draft trees): blocks of 128 columns, four consumers per range, so
     // that K and V are read once per 128 columns (RESPEC_ATTN_QUAD = 0: blocks of 64 as below)
-    const bool quad = M > kMaxColsPerBlock && env_long("RESPEC_ATTN_QUAD", 1) != 0;
+    const long quad_env = env_long("RESPEC_ATTN_QUAD", 1);
+    const bool quad = M > kMaxColsPerBlock && quad_env != 0;
+    // Four consumers per range also serve 17 to 64 columns, 16 each, when the batch is so small
+    // that a consumer's own range would hold only a few tiles: a quarter of the ranges means a
+    // quarter of the partials and of the combine kernel's work (B = 64 at the 3B shape: combine
+    // 18 -> 10 us, main kernel unchanged; on large batches this form is bound by the consumers
+    // and 40 % slower).  RESPEC_ATTN_QUAD = 2 forces it, 0 switches it off.
+    // (cached tokens: the host-side total, for a paged cache what its page-table entries can hold)
+    const int64_t kv_tokens = paged ? (int64_t)pg.table_len * pg.page_size : total_kv;
+    const int64_t tiles_per_narrow_range =
+        (kv_tokens / kTileKeys + B) * (int64_t)Hkv / ((int64_t)kConsumers * compute_units());
+    const bool quad_narrow = M > kColTile && M <= kMaxColsPerBlock &&
+                             (quad_env == 2 || (quad_env == 1 && tiles_per_narrow_range < 16));
     const int block_cols = quad ? 2 * kMaxColsPerBlock : kMaxColsPerBlock;
     const int col_blocks = (M + block_cols - 1) / block_cols;
     const int cols = col_blocks == 1 ? M : kMaxColsPerBlock;
-    const int nt = quad ? 2 : (cols + kColTile - 1) / kColTile;
+    const int nt = quad ? 8 : (cols + kColTile - 1) / kColTile;  // column tiles of a block
     // a column block of four column tiles at D = 128 is more than one wave's registers hold
     // (400 bytes of spills per lane, measured 1.5x slower): two consumers share each range then.
     // Three tiles still run faster with one consumer per range and a few spills.
@@ -1438,7 +1450,7 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     // comparisons; at two tiles the shared form halves the partials and the combine's work but
     // measured 4 us slower in the main kernel, 211 vs 206 us at B = 256 and the 7B shape).
     const long wide = env_long("RESPEC_ATTN_WIDE", -1);
-    const int cw = quad ? 4 : (nt >= 2 && (wide < 0 ? (D == 128 && nt == 4) : wide != 0) ? 2 : 1);
+    const int cw = quad || quad_narrow ? 4 : (nt >= 2 && (wide < 0 ? (D == 128 && nt == 4) : wide != 0) ? 2 : 1);
     const int streams = kConsumers / cw;  // ranges per work-group
     // the split width: one range per consumer (or pair of consumers) of the device
     // (RESPEC_ATTN_WGS overrides it, for tests and sweeps)

@@ -112,6 +112,18 @@ def test_wide_column_blocks_share_a_range_between_two_consumers(oracle, heads, w
     _run(oracle, wl, lens, ks, seed=Hq + k + (wgs or 0), wgs=wgs)
 
 
+@pytest.mark.parametrize("wgs", [None, 1, 3, 64])
+@pytest.mark.parametrize("shape", [(28, 4, 128, 3), (16, 2, 128, 4), (40, 8, 128, 8), (8, 2, 64, 7), (7, 1, 128, 2)])
+def test_four_consumers_on_a_block_of_up_to_64_columns(oracle, shape, wgs):
+    # 17..64 MFMA columns with the four consumers of a work-group on one range, 16 columns each
+    Hq, Hkv, D, k = shape
+    wl = _wl("bf16_quad_narrow", Hq, Hkv, D, "bf16")
+    lens = [33, 130, 257, 1000, 9, 10, 128, 129, 2049, 64, 65]
+    ks = [k, k, 0, k, k, k - 1, 1, 2, k, k, min(3, k)]
+    with env_setting("RESPEC_ATTN_QUAD", 2):
+        _run(oracle, wl, lens, ks, seed=77 + Hq + k + (wgs or 0), wgs=wgs)
+
+
 @pytest.mark.parametrize("wide", [0, 1])
 @pytest.mark.parametrize("D", [64, 128])
 def test_both_forms_of_a_wide_column_block_agree_with_the_oracle(oracle, D, wide):
