@@ -99,19 +99,15 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
             }
         };
         double kl = 0.0;
-        u32x4 vp[kUnroll], vq[kUnroll];
-        load_batch(n_iter - 1, vp, vq);
-        for (int it = n_iter - 1; it >= 0; --it) {
-            u32x4 np_[kUnroll], nq_[kUnroll];
-            if (it > 0) load_batch(it - 1, np_, nq_);  // in flight while this batch is worked on
+        auto work_batch = [&](int it, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll]) __attribute__((always_inline)) {
             float klb = 0.f;
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int s = it * kBatch + u * kThreads + (int)threadIdx.x;
                 if (s < nslots) {
                     float zp[EPV], zq[EPV], gr[EPV];
-                    unpack<BF16>(vp[u], zp);
-                    unpack<BF16>(vq[u], zq);
+                    unpack<BF16>(xp[u], zp);
+                    unpack<BF16>(xq[u], zq);
 #pragma unroll
                     for (int j = 0; j < EPV; ++j) {
                         const float a = exp2_arg(zp[j], Mp, p.c_hi, p.c_lo) - lsp;
@@ -125,12 +121,17 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
                 __builtin_amdgcn_sched_barrier(0);  // one slot at a time: interleaving all of them spills
             }
             kl += (double)klb;
-            if (it > 0) {
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    vp[u] = np_[u];
-                    vq[u] = nq_[u];
-                }
+        };
+        // two register sets take turns: one batch is worked on while the next one's loads are in flight
+        u32x4 vp[kUnroll], vq[kUnroll], wp[kUnroll], wq[kUnroll];
+        load_batch(n_iter - 1, vp, vq);
+        for (int it = n_iter - 1; it >= 0; it -= 2) {
+            const bool second = it > 0;
+            if (second) load_batch(it - 1, wp, wq);
+            work_batch(it, vp, vq);
+            if (second) {
+                if (it > 1) load_batch(it - 2, vp, vq);
+                work_batch(it - 1, wp, wq);
             }
         }
         // KL(p || q) of the row in nats, summed in a fixed order

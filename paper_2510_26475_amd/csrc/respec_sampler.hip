@@ -262,17 +262,14 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         }
     };
     if (beg < end) {  // wave-uniform
-        u32x4 vp[kUnroll], vq[kUnroll];
-        load_batch(beg, vp, vq);
-        for (int s0 = beg; s0 < end; s0 += 64 * kUnroll) {
-            u32x4 np[kUnroll], nq[kUnroll];
-            const bool more = s0 + 64 * kUnroll < end;
-            if (more) load_batch(s0 + 64 * kUnroll, np, nq);
+        // two register sets take turns: one is summed while the other's loads are in flight
+        u32x4 vp[kUnroll], vq[kUnroll], wp[kUnroll], wq[kUnroll];
+        auto sum_batch = [&](int s0, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < kUnroll; ++c) {
                 const bool in = s0 + c * 64 + lane < end;
-                const u32x4 a = in ? vp[c] : neg_inf_slot<BF16>();
-                const u32x4 b = RESID ? (in ? vq[c] : neg_inf_slot<BF16>()) : a;
+                const u32x4 a = in ? xp[c] : neg_inf_slot<BF16>();
+                const u32x4 b = RESID ? (in ? xq[c] : neg_inf_slot<BF16>()) : a;
                 if constexpr (FAST) {
                     float w[EPV];
                     const float ts = slot_weights_f32<BF16, RESID>(a, b, fn, p, w);
@@ -285,12 +282,16 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
                     for (int j = 0; j < EPV; ++j) lane_sum += w[j];
                 }
             }
-            if (more) {
-#pragma unroll
-                for (int c = 0; c < kUnroll; ++c) {
-                    vp[c] = np[c];
-                    if constexpr (RESID) vq[c] = nq[c];
-                }
+        };
+        constexpr int kStep = 64 * kUnroll;
+        load_batch(beg, vp, vq);
+        for (int s0 = beg; s0 < end; s0 += 2 * kStep) {
+            const bool second = s0 + kStep < end;
+            if (second) load_batch(s0 + kStep, wp, wq);
+            sum_batch(s0, vp, vq);
+            if (second) {
+                if (s0 + 2 * kStep < end) load_batch(s0 + 2 * kStep, vp, vq);
+                sum_batch(s0 + kStep, wp, wq);
             }
         }
     }
