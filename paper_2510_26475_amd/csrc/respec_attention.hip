@@ -460,7 +460,8 @@ __device__ inline void wait_at_least(LdsCounter flag, uint32_t need, bool &alive
 // both have passed it.  CW = 4 is the same with all four consumers on one range (up to 128
 // columns: the trees of a drafter that proposes ten to eighteen nodes per sequence at a group of
 // seven heads): the four producers take the range's tiles in turn and the work-group walks one
-// range.
+// range.  With 16 columns per consumer the same form serves narrow blocks on small batches, where
+a quarter of the ranges means a quarter of the partials.
 template <int D, int NT, typename OutT, int CW>
 __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnParams p) {
     using C = Bf16Cfg<D>;
@@ -483,7 +484,7 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     if (threadIdx.x < 3 * kConsumers) counters[threadIdx.x] = 0;
     __syncthreads();  // the only barrier, before any wave can leave
     // filled[r]: tiles producer r has written to its ring; consumed[r]: tiles of the range that
-    // consumer r has finished with; read_done[r]: tiles whose K and V consumer r has read (CW = 2)
+    // consumer r has finished with; read_done[r]: tiles whose K and V consumer r has read (CW > 1)
     const LdsCounter filled = counters;
     const LdsCounter consumed = counters + kConsumers;
     const LdsCounter read_done = counters + 2 * kConsumers;
