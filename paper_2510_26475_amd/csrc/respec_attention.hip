@@ -461,7 +461,7 @@ __device__ inline void wait_at_least(LdsCounter flag, uint32_t need, bool &alive
 // columns: the trees of a drafter that proposes ten to eighteen nodes per sequence at a group of
 // seven heads): the four producers take the range's tiles in turn and the work-group walks one
 // range.  With 16 columns per consumer the same form serves narrow blocks on small batches, where
-a quarter of the ranges means a quarter of the partials.
+// a quarter of the ranges means a quarter of the partials.
 template <int D, int NT, typename OutT, int CW>
 __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnParams p) {
     using C = Bf16Cfg<D>;
