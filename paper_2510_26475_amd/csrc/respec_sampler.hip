@@ -51,18 +51,24 @@ struct SamplerParams : RowMath {
 // ------------------------------------------------------------------------------------------
 // mailbox: the few numbers the parts of one sequence exchange after a streaming pass
 // ------------------------------------------------------------------------------------------
-// Layout of one box (kBoxBytes): word 0 the epoch (calls that have used the box), words
-// 16.. the progress counter of every part, then [part][stage parity][8] doubles of payload.
-// A part publishes stage s by storing its payload and then progress = epoch*1024 + s + 1; a
-// part that has seen every partner's stage s may publish stage s+1 into the other payload
-// buffer, and nobody can be two stages ahead of the slowest reader.  Part 0 bumps the epoch
-// when it leaves (every partner has read it by then: they publish their first stage after
-// reading it, and part 0 waits for that), so the counters never need resetting and the box
-// only has to be zero before its first use.  All accesses are device-scope atomics: the
-// parts run on compute units whose L2 caches are not coherent with each other.
+// Layout of one box (kBoxBytes): word 0 the epoch (calls that have used the box), then
+// [part][stage parity][16] tagged words of payload: the eight doubles a part publishes per
+// stage, each as two 64-bit words that carry 32 bits of the value below a 32-bit mark,
+// mark = epoch*1024 + stage + 1.  A word is written and read with one 8-byte device-scope
+// access, so a reader that finds the mark it waits for has the value that belongs to it: no
+// separate flag and no fence; a reader fetches a partner's sixteen words together and is done
+// after one memory round trip once the partner has published (a flag behind the payload costs
+// three: the writer's wait for its stores, the reader's poll, the reader's dependent read).
+// A part that has read every partner's stage s may publish stage s+1 into the other parity
+// buffer, and nobody can be two stages ahead of the slowest reader, so a word is never
+// overwritten while somebody still waits for it.  Part 0 bumps the epoch when it leaves (every
+// partner has read it by then: they publish their first stage after reading it, and part 0 has
+// read that stage), so nothing needs resetting and the box only has to be zero before its
+// first use (a mark is never 0).  All accesses are device-scope atomics: the parts run on
+// compute units whose L2 caches are not coherent with each other.
 struct Mailbox {
     uint32_t *words;
-    double *payload;
+    unsigned long long *payload;
     uint32_t base;
     int part, split, stage;
 };
@@ -73,15 +79,15 @@ struct Mailbox {
 __device__ inline void exchange(Mailbox &mb, const double (&mine)[8], SharedState &sh) {
     const int parity = mb.stage & 1;
     const uint32_t mark = mb.base + (uint32_t)mb.stage + 1u;
-    if (threadIdx.x == 0) {
-        double *dst = mb.payload + (mb.part * 2 + parity) * 8;
+    const unsigned long long tag = (unsigned long long)mark << 32;
+    if (threadIdx.x == 64) {  // (a thread of the second wave publishes, the first wave collects)
+        unsigned long long *dst = mb.payload + (mb.part * 2 + parity) * 16;
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            __hip_atomic_store(reinterpret_cast<unsigned long long *>(dst + i),
-                               __builtin_bit_cast(unsigned long long, mine[i]), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the stores above have completed
-        store_dev(mb.words + 16 + mb.part, mark);
+        for (int i = 0; i < 8; ++i) {
+            const unsigned long long bits = __builtin_bit_cast(unsigned long long, mine[i]);
+            __hip_atomic_store(dst + 2 * i, tag | (bits & 0xffffffffull), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(dst + 2 * i + 1, tag | (bits >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     if ((int)threadIdx.x < mb.split) {
         const int j = threadIdx.x;
@@ -89,23 +95,32 @@ __device__ inline void exchange(Mailbox &mb, const double (&mine)[8], SharedStat
 #pragma unroll
             for (int i = 0; i < 8; ++i) sh.xchg[j][i] = mine[i];
         } else {
+            const unsigned long long *src = mb.payload + (j * 2 + parity) * 16;
+            unsigned long long w[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) w[i] = 0;
             if (!sh.failed) {
                 int spin = 0;
-                while ((int32_t)(load_dev(mb.words + 16 + j) - mark) < 0) {
+                for (;;) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        w[i] = __hip_atomic_load(src + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    bool all = true;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) all = all && (uint32_t)(w[i] >> 32) == mark;
+                    if (all) break;
                     if (++spin > kSpinLimit) {
                         sh.failed = 1;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) w[i] = 0;
                         break;
                     }
                     __builtin_amdgcn_s_sleep(2);
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-            const double *src = mb.payload + (j * 2 + parity) * 8;
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                sh.xchg[j][i] = __builtin_bit_cast(
-                    double, __hip_atomic_load(reinterpret_cast<const unsigned long long *>(src + i),
-                                              __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                sh.xchg[j][i] = __builtin_bit_cast(double, (w[2 * i] & 0xffffffffull) | (w[2 * i + 1] << 32));
         }
     }
     ++mb.stage;
@@ -754,7 +769,7 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     if (threadIdx.x == 0) sh.failed = 0;
     if constexpr (SHARED) {
         mb.words = reinterpret_cast<uint32_t *>(p.boxes + (size_t)b * kBoxBytes);
-        mb.payload = reinterpret_cast<double *>(p.boxes + (size_t)b * kBoxBytes + kBoxHeaderBytes);
+        mb.payload = reinterpret_cast<unsigned long long *>(p.boxes + (size_t)b * kBoxBytes + kBoxHeaderBytes);
         if (threadIdx.x == 0) sh_epoch = load_dev(mb.words);
     }
     __syncthreads();

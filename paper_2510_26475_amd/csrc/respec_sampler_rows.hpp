@@ -18,8 +18,8 @@ constexpr int kChunk = 5;   // slots of a thread's run in the inverse-CDF walk t
 constexpr float kRefInit = -1.0e30f;
 constexpr double kBoundaryEps = 1e-6;
 constexpr int kMaxSplit = 8;          // work-groups that can share one sequence
-constexpr int kBoxHeaderBytes = 128;                      // epoch at word 0, progress counters at words 16..
-constexpr int kBoxPayload = kMaxSplit * 2 * 8;            // [part][stage parity][8 doubles]
+constexpr int kBoxHeaderBytes = 128;                      // epoch at word 0
+constexpr int kBoxPayload = kMaxSplit * 2 * 16;           // [part][stage parity][8 doubles as 16 tagged words]
 constexpr size_t kBoxBytes = kBoxHeaderBytes + (size_t)kBoxPayload * 8;
 constexpr int kSpinLimit = 1 << 22;
 constexpr size_t kTableMaxBytes = 96 * 1024;  // LDS a launch may add for the final draw's slot totals
