@@ -1172,8 +1172,13 @@ __global__ __launch_bounds__(256) void commit_accepted_kernel(CommitParams p) {
     e0 = max(0, min(e0, p.table_len));
     pages = max(0, min(pages, p.table_len - e0));
     const int64_t cap = (int64_t)pages << p.page_shift;
-    const int64_t L = max((int64_t)0, min((int64_t)p.kv_len[b], cap));
-    if (R < 1 || L < R) return;  // nothing that could be committed: the length stays
+    // The length is read once, by the thread that overwrites it at the end, and handed to the
+    // others through LDS: a wave that starts late must not see the new length in its place.
+    __shared__ int sh_len;
+    if (threadIdx.x == 0) sh_len = p.kv_len[b];
+    __syncthreads();
+    const int64_t L = max((int64_t)0, min((int64_t)sh_len, cap));
+    if (R < 1 || L < R) return;  // nothing that could be committed: the length stays (block-uniform)
     const int first_new = (int)(L - R);
     int n = max(0, min(p.num_accepted[b], R - 1));
     if (p.path) n = min(n, p.path_stride);

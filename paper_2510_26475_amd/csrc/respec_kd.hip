@@ -124,15 +124,22 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
         };
         // two register sets take turns: one batch is worked on while the next one's loads are in flight
         u32x4 vp[kUnroll], vq[kUnroll], wp[kUnroll], wq[kUnroll];
+        // (the loads of the steady state are unconditional: behind a condition the wait for the
+        // batch in front of a load becomes a wait for everything in flight)
         load_batch(n_iter - 1, vp, vq);
-        for (int it = n_iter - 1; it >= 0; it -= 2) {
-            const bool second = it > 0;
-            if (second) load_batch(it - 1, wp, wq);
+        int it = n_iter - 1;  // vp holds batch `it`
+        for (; it >= 2; it -= 2) {
+            load_batch(it - 1, wp, wq);
             work_batch(it, vp, vq);
-            if (second) {
-                if (it > 1) load_batch(it - 2, vp, vq);
-                work_batch(it - 1, wp, wq);
-            }
+            load_batch(it - 2, vp, vq);
+            work_batch(it - 1, wp, wq);
+        }
+        if (it == 1) {
+            load_batch(0, wp, wq);
+            work_batch(1, vp, vq);
+            work_batch(0, wp, wq);
+        } else {
+            work_batch(0, vp, vq);
         }
         // KL(p || q) of the row in nats, summed in a fixed order
         const double kw = wave_sum(kl);

@@ -300,14 +300,21 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         };
         constexpr int kStep = 64 * kUnroll;
         load_batch(beg, vp, vq);
-        for (int s0 = beg; s0 < end; s0 += 2 * kStep) {
-            const bool second = s0 + kStep < end;
-            if (second) load_batch(s0 + kStep, wp, wq);
+        // (both loads of a round are unconditional: behind a condition, the wait for the batch
+        // in front of a load becomes a wait for everything in flight)
+        int s0 = beg;
+        for (; s0 + 2 * kStep < end; s0 += 2 * kStep) {
+            load_batch(s0 + kStep, wp, wq);
             sum_batch(s0, vp, vq);
-            if (second) {
-                if (s0 + 2 * kStep < end) load_batch(s0 + 2 * kStep, vp, vq);
-                sum_batch(s0 + kStep, wp, wq);
-            }
+            load_batch(s0 + 2 * kStep, vp, vq);
+            sum_batch(s0 + kStep, wp, wq);
+        }
+        if (s0 + kStep < end) {
+            load_batch(s0 + kStep, wp, wq);
+            sum_batch(s0, vp, vq);
+            sum_batch(s0 + kStep, wp, wq);
+        } else {
+            sum_batch(s0, vp, vq);
         }
     }
     const double region_total = wave_sum(lane_sum);
@@ -632,16 +639,11 @@ __device__ inline int row_argmax(const void *row, int nslots, int V, bool aligne
     };
     float best = -INFINITY;
     int best_i = 0x7fffffff;
-    u32x4 v[kUnroll];
-    load_batch(0, v);
-    for (int it = 0; it < n_iter; ++it) {
-        u32x4 nv[kUnroll];
-        const bool more = it + 1 < n_iter;  // block-uniform
-        if (more) load_batch(it + 1, nv);   // in flight while this batch is compared
+    auto compare_batch = [&](int it, const u32x4 (&x)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             float z[EPV];
-            unpack<BF16>(v[u], z);
+            unpack<BF16>(x[u], z);
             const int slot = it * kBatch + u * kThreads + (int)threadIdx.x;
             const int e0 = slot * EPV;
 #pragma unroll
@@ -651,10 +653,24 @@ __device__ inline int row_argmax(const void *row, int nslots, int V, bool aligne
                     best_i = e0 + j;
                 }
         }
-        if (more) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) v[u] = nv[u];
-        }
+    };
+    // two register sets take turns; the loads of the steady state are unconditional (behind a
+    // condition the wait for the batch in front of a load becomes a wait for everything in flight)
+    u32x4 v[kUnroll], nv[kUnroll];
+    load_batch(0, v);
+    int it = 0;  // v holds batch `it`; conditions are block-uniform
+    for (; it + 2 < n_iter; it += 2) {
+        load_batch(it + 1, nv);  // in flight while batch `it` is compared
+        compare_batch(it, v);
+        load_batch(it + 2, v);
+        compare_batch(it + 1, nv);
+    }
+    if (it + 1 < n_iter) {
+        load_batch(it + 1, nv);
+        compare_batch(it, v);
+        compare_batch(it + 1, nv);
+    } else {
+        compare_batch(it, v);
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {

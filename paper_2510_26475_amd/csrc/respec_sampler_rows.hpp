@@ -330,16 +330,25 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
             if constexpr (TWO) fast_absorb<BF16, ONE_TERM>(xq[u], accq, refq, Kq, p);
         }
     };
-    for (int it = 0; it < n_iter; it += 2) {  // every condition below is block-uniform
-        const bool second = it + 1 < n_iter;
-        if (second) load_batch(it + 1, wp, wq);  // in flight while batch `it` is summed
-        if (it > 0 && it + 1 == n_iter) mask_last(vp, vq);
+    // Steady state: every round issues both of its batches unconditionally.  A load behind a
+    // condition makes the compiler's wait for the batch in front of it a wait for everything in
+    // flight (it must assume the branch was not taken), and then no load overlaps any sum.  The
+    // last one or two batches are taken outside the loop.
+    int it = 0;  // vp holds batch `it`; every condition below is block-uniform
+    for (; it + 2 < n_iter; it += 2) {
+        load_batch(it + 1, wp, wq);  // in flight while batch `it` is summed
         absorb_batch(vp, vq);
-        if (second) {
-            if (it + 2 < n_iter) load_batch(it + 2, vp, vq);
-            if (it + 2 == n_iter) mask_last(wp, wq);
-            absorb_batch(wp, wq);
-        }
+        load_batch(it + 2, vp, vq);
+        absorb_batch(wp, wq);
+    }
+    if (it + 1 < n_iter) {
+        load_batch(it + 1, wp, wq);
+        absorb_batch(vp, vq);
+        mask_last(wp, wq);
+        absorb_batch(wp, wq);
+    } else {
+        mask_last(vp, vq);  // (a second time when the row has one batch: harmless)
+        absorb_batch(vp, vq);
     }
     double sp = 0.0, sq = 0.0;
 #pragma unroll

@@ -169,16 +169,13 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
         }
     };
     if (beg < end) {  // wave-uniform
-        u32x4 vp[kUnroll], vq[kUnroll];
-        load_batch(beg, vp, vq);
-        for (int s0 = beg; s0 < end; s0 += 64 * kUnroll) {
-            u32x4 np[kUnroll], nq[kUnroll];
-            const bool more = s0 + 64 * kUnroll < end;
-            if (more) load_batch(s0 + 64 * kUnroll, np, nq);
+        // two register sets take turns: one is summed while the other's loads are in flight
+        u32x4 vp[kUnroll], vq[kUnroll], np[kUnroll], nq[kUnroll];
+        auto sum_batch = [&](int s0, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < kUnroll; ++c) {
                 const bool in = s0 + c * 64 + lane < end;  // slots past the region count as -inf
-                const u32x4 a = in ? vp[c] : neg_inf_slot<BF16>(), b = in ? vq[c] : neg_inf_slot<BF16>();
+                const u32x4 a = in ? xp[c] : neg_inf_slot<BF16>(), b = in ? xq[c] : neg_inf_slot<BF16>();
                 if constexpr (FAST) {
                     float w[EPV];
                     lane_sum += (double)tree_slot_weights_f32<BF16>(a, b, fn, fd, p, w);
@@ -189,13 +186,24 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
                     for (int j = 0; j < EPV; ++j) lane_sum += w[j];
                 }
             }
-            if (more) {
-#pragma unroll
-                for (int c = 0; c < kUnroll; ++c) {
-                    vp[c] = np[c];
-                    vq[c] = nq[c];
-                }
-            }
+        };
+        constexpr int kStep = 64 * kUnroll;
+        load_batch(beg, vp, vq);
+        // (the loads of the steady state are unconditional: behind a condition the wait for the
+        // batch in front of a load becomes a wait for everything in flight)
+        int s0 = beg;
+        for (; s0 + 2 * kStep < end; s0 += 2 * kStep) {
+            load_batch(s0 + kStep, np, nq);
+            sum_batch(s0, vp, vq);
+            load_batch(s0 + 2 * kStep, vp, vq);
+            sum_batch(s0 + kStep, np, nq);
+        }
+        if (s0 + kStep < end) {
+            load_batch(s0 + kStep, np, nq);
+            sum_batch(s0, vp, vq);
+            sum_batch(s0 + kStep, np, nq);
+        } else {
+            sum_batch(s0, vp, vq);
         }
     }
     const double region_total = wave_sum(lane_sum);
