@@ -277,8 +277,9 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         }
     };
     if (beg < end) {  // wave-uniform
-        // two register sets take turns: one is summed while the other's loads are in flight
-        u32x4 vp[kUnroll], vq[kUnroll], wp[kUnroll], wq[kUnroll];
+        // a ring of register sets: all but one are in flight while one is summed
+        constexpr int NSETS = FULL ? kSetsDraw : 2;  // (the guarded loads of the general form need the registers)
+        u32x4 rp[NSETS][kUnroll], rq[NSETS][kUnroll];
         auto sum_batch = [&](int s0, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < kUnroll; ++c) {
@@ -299,23 +300,26 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
             }
         };
         constexpr int kStep = 64 * kUnroll;
-        load_batch(beg, vp, vq);
-        // (both loads of a round are unconditional: behind a condition, the wait for the batch
-        // in front of a load becomes a wait for everything in flight)
-        int s0 = beg;
-        for (; s0 + 2 * kStep < end; s0 += 2 * kStep) {
-            load_batch(s0 + kStep, wp, wq);
-            sum_batch(s0, vp, vq);
-            load_batch(s0 + 2 * kStep, vp, vq);
-            sum_batch(s0 + kStep, wp, wq);
+        const int n_b = (end - beg + kStep - 1) / kStep;  // wave-uniform, >= 1
+        // (the loads of the steady state are unconditional: behind a condition, the wait for the
+        // batch in front of a load becomes a wait for everything in flight; batches past the
+        // region read its first slot again and are never summed)
+#pragma unroll
+        for (int s = 0; s + 1 < NSETS; ++s) load_batch(beg + s * kStep, rp[s], rq[s]);
+        int ib = 0;  // set s holds batch ib + s for s < NSETS - 1
+        for (; ib + NSETS < n_b; ib += NSETS) {
+#pragma unroll
+            for (int s = 0; s < NSETS; ++s) {
+                constexpr int kAhead = NSETS - 1;
+                load_batch(beg + (ib + s + kAhead) * kStep, rp[(s + kAhead) % NSETS], rq[(s + kAhead) % NSETS]);
+                sum_batch(beg + (ib + s) * kStep, rp[s], rq[s]);
+            }
         }
-        if (s0 + kStep < end) {
-            load_batch(s0 + kStep, wp, wq);
-            sum_batch(s0, vp, vq);
-            sum_batch(s0 + kStep, wp, wq);
-        } else {
-            sum_batch(s0, vp, vq);
-        }
+        const int rem = n_b - ib;  // 1..NSETS
+        if (rem == NSETS) load_batch(beg + (ib + NSETS - 1) * kStep, rp[NSETS - 1], rq[NSETS - 1]);
+#pragma unroll
+        for (int s = 0; s < NSETS; ++s)
+            if (s < rem) sum_batch(beg + (ib + s) * kStep, rp[s], rq[s]);
     }
     const double region_total = wave_sum(lane_sum);
     if (lane == 0) sh.wave_total[wave] = region_total;

@@ -14,6 +14,13 @@ namespace {
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kUnroll = 4;
+// Register sets of the streaming loops (one is summed while the others' loads are in flight).
+// Two is the measured optimum: a compute unit does not take more requests than one batch of a
+// 512-thread work-group at a time, so a third set only makes waves block at the issue of their
+// loads (headline workload: 103 us with two sets, 109 us with three, 135 us with four).
+constexpr int kSetsTwoRows = 2;  // fast normaliser pass over a row pair
+constexpr int kSetsOneRow = 2;   // ... over one row
+constexpr int kSetsDraw = 2;     // the final draw's pass over the row pair
 constexpr int kChunk = 5;   // slots of a thread's run in the inverse-CDF walk that are loaded together
 constexpr float kRefInit = -1.0e30f;
 constexpr double kBoundaryEps = 1e-6;
@@ -93,7 +100,10 @@ __device__ inline u32x4 neg_inf_slot() {
 template <bool BF16, bool FULL = false, bool LAST_USE = false>
 __device__ inline u32x4 load_slot(const void *row, int slot, int V, bool aligned) {
     constexpr int EPV = Elem<BF16>::EPV;
-    const u32x4 *whole = reinterpret_cast<const u32x4 *>(static_cast<const char *>(row) + (size_t)slot * 16);
+    // (a 32-bit unsigned byte offset from the row's uniform base: the load then takes a scalar
+    // base and one offset register instead of a 64-bit address pair formed per load; rows are
+    // shorter than 4 GiB, checked on the host)
+    const u32x4 *whole = reinterpret_cast<const u32x4 *>(static_cast<const char *>(row) + ((uint32_t)slot * 16u));
     if constexpr (FULL) return LAST_USE ? __builtin_nontemporal_load(whole) : *whole;
     const int e0 = slot * EPV;
     if (aligned && e0 + EPV <= V) return LAST_USE ? __builtin_nontemporal_load(whole) : *whole;
@@ -302,27 +312,31 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
             if constexpr (TWO) vq[u] = in ? vq[u] : neg_inf_slot<BF16>();
         }
     };
-    u32x4 vp[kUnroll], vq[kUnroll];
-    load_batch(0, vp, vq);
-    if (n_iter == 1) mask_last(vp, vq);  // block-uniform
-    {   // references from the first batch
-        float mp = slot_max<BF16>(vp[0]), mq = -INFINITY;
+    // A ring of NSETS register sets: NSETS - 1 batches are in flight while one is summed.  The
+    // loads of the steady state are unconditional: a load behind a condition makes
+    // the compiler's wait for the batch in front of it a wait for everything in flight (it must
+    // assume the branch was not taken), and then no load overlaps any sum.  Batches past the
+    // row's end read its last slot again and are never summed.
+    constexpr int NSETS = TWO ? kSetsTwoRows : kSetsOneRow;
+    u32x4 rp[NSETS][kUnroll], rq[NSETS][kUnroll];
 #pragma unroll
-        for (int u = 1; u < kUnroll; ++u) mp = fmaxf(mp, slot_max<BF16>(vp[u]));
+    for (int s = 0; s + 1 < NSETS; ++s) load_batch(s, rp[s], rq[s]);
+    if (n_iter == 1) mask_last(rp[0], rq[0]);  // block-uniform
+    {   // references from the first batch
+        float mp = slot_max<BF16>(rp[0][0]), mq = -INFINITY;
+#pragma unroll
+        for (int u = 1; u < kUnroll; ++u) mp = fmaxf(mp, slot_max<BF16>(rp[0][u]));
         mp = wave_max(mp);
         refp = (mp > -INFINITY && mp < INFINITY) ? mp : 0.f;
         Kp = -refp * p.c_f;
         if constexpr (TWO) {
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) mq = fmaxf(mq, slot_max<BF16>(vq[u]));
+            for (int u = 0; u < kUnroll; ++u) mq = fmaxf(mq, slot_max<BF16>(rq[0][u]));
             mq = wave_max(mq);
             refq = (mq > -INFINITY && mq < INFINITY) ? mq : 0.f;
             Kq = -refq * p.c_f;
         }
     }
-    // Two register sets take turns (no copy from one to the other: the copies were 6 % of the
-    // loop's instructions).  A third set with two batches in flight measured slower, not faster.
-    u32x4 wp[kUnroll], wq[kUnroll];
     auto absorb_batch = [&](const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
@@ -330,25 +344,24 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
             if constexpr (TWO) fast_absorb<BF16, ONE_TERM>(xq[u], accq, refq, Kq, p);
         }
     };
-    // Steady state: every round issues both of its batches unconditionally.  A load behind a
-    // condition makes the compiler's wait for the batch in front of it a wait for everything in
-    // flight (it must assume the branch was not taken), and then no load overlaps any sum.  The
-    // last one or two batches are taken outside the loop.
-    int it = 0;  // vp holds batch `it`; every condition below is block-uniform
-    for (; it + 2 < n_iter; it += 2) {
-        load_batch(it + 1, wp, wq);  // in flight while batch `it` is summed
-        absorb_batch(vp, vq);
-        load_batch(it + 2, vp, vq);
-        absorb_batch(wp, wq);
+    int it = 0;  // set s holds batch it + s for s < NSETS - 1; every condition below is block-uniform
+    for (; it + NSETS < n_iter; it += NSETS) {
+#pragma unroll
+        for (int s = 0; s < NSETS; ++s) {
+            constexpr int kAhead = NSETS - 1;
+            load_batch(it + s + kAhead, rp[(s + kAhead) % NSETS], rq[(s + kAhead) % NSETS]);
+            absorb_batch(rp[s], rq[s]);
+        }
     }
-    if (it + 1 < n_iter) {
-        load_batch(it + 1, wp, wq);
-        absorb_batch(vp, vq);
-        mask_last(wp, wq);
-        absorb_batch(wp, wq);
-    } else {
-        mask_last(vp, vq);  // (a second time when the row has one batch: harmless)
-        absorb_batch(vp, vq);
+    // the last 1..NSETS batches
+    const int rem = n_iter - it;
+    if (rem == NSETS) load_batch(it + NSETS - 1, rp[NSETS - 1], rq[NSETS - 1]);
+#pragma unroll
+    for (int s = 0; s < NSETS; ++s) {
+        if (s < rem) {
+            if (s == rem - 1) mask_last(rp[s], rq[s]);  // (a second time when the row has one batch: harmless)
+            absorb_batch(rp[s], rq[s]);
+        }
     }
     double sp = 0.0, sq = 0.0;
 #pragma unroll
