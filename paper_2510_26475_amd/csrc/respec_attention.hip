@@ -90,6 +90,7 @@ struct AttnParams {
                            // head), first query row, query rows; error_flag[1]: every part owns tiles
     int32_t Mpad;          // G*max_q rounded up to kColTile
     float scale2;          // sm_scale * log2(e)
+    int32_t inline_setup;  // the main kernel builds the split itself (no set-up kernel in front of it)
 };
 
 struct SeqInfo {
@@ -199,10 +200,56 @@ __device__ inline bool part_owns_tiles(const Split &s, int r) {
     return range_begin(s, r + 1) > range_begin(s, r);
 }
 
-// Builds the tile prefix over sequences, every wave's starting point and, for every
-// (sequence, KV head), the first and the last part that hold its tiles (the 64-bit divisions
-// behind them are done once here, not by every thread of the combine kernel).
+// Where wave w of the split starts: `prefix(i)` is the tile prefix over sequences (LDS or global).
+template <typename Prefix>
+__device__ inline WaveStart make_wave_start(const AttnParams &p, const Split &sp, int w, Prefix prefix) {
+    WaveStart st{0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    const int64_t T = sp.T;
+    if (T > 0) {
+        const int r = w / p.HI, sub = w % p.HI;
+        const int64_t a0 = range_begin(sp, r), a1 = range_begin(sp, r + 1);
+        st.n = (int32_t)(a1 - a0);
+        st.h = sub * sp.hps + (int32_t)(a0 / T);
+        const int32_t rem = (int32_t)(a0 % T);
+        int lo = 0, hi = p.B - 1;          // last b with prefix[b] <= rem
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (prefix(mid) <= rem) lo = mid; else hi = mid - 1;
+        }
+        st.b = lo;
+        st.t = rem - prefix(lo);
+        const SeqInfo si = seq_info(p, lo);
+        st.q0 = si.q0;
+        st.R = si.R;
+        st.L = si.L;
+        st.tiles = si.tiles;
+        st.kv0 = si.kv0;
+    }
+    return st;
+}
+
+// For (sequence, KV head) idx: the first and the last part that hold its tiles, its first query
+// row and its query rows (what the combine kernel needs; the 64-bit divisions behind the parts
+// are done once here, not by every thread of that kernel).
+template <typename Prefix>
+__device__ inline void write_cut(const AttnParams &p, const Split &sp, int idx, Prefix prefix) {
+    const int b = idx / p.Hkv, kvh = idx % p.Hkv;
+    const int tiles = prefix(b + 1) - prefix(b);
+    int r_first = 0, r_last = 0;
+    if (tiles > 0) {
+        const int64_t first_tile = (int64_t)(kvh % sp.hps) * sp.T + prefix(b);
+        r_first = part_of_tile(sp, first_tile);
+        r_last = part_of_tile(sp, first_tile + tiles - 1);
+    }
+    const SeqInfo si = seq_info(p, b);
+    *reinterpret_cast<int4 *>(p.cuts + 4 * (int64_t)idx) = int4{r_first, r_last, si.q0, si.R};
+}
+
+// Set-up kernel (one work-group): builds the tile prefix over sequences, every wave's starting
+// point and the cut table.  Only batches too large for the main kernel to do this itself in its
+// prologue (kInlineSeqs) take this extra launch.
 constexpr int kPrepLdsSeqs = 8192;  // batches up to this size keep the prefix in LDS for the searches
+constexpr int kInlineSeqs = 2048;   // batches up to this size: the main kernel's work-groups build the split themselves
 
 __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     __shared__ int sh_scan[1024];
@@ -245,43 +292,8 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     }
     auto prefix = [&](int i) { return in_lds ? sh_prefix[i] : p.tile_prefix[i]; };
     const Split sp = make_split(p, sh_base);
-    const int64_t T = sp.T;
-    for (int w = tid; w < p.W; w += 1024) {
-        WaveStart st{0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        if (T > 0) {
-            const int r = w / p.HI, sub = w % p.HI;
-            const int64_t a0 = range_begin(sp, r), a1 = range_begin(sp, r + 1);
-            st.n = (int32_t)(a1 - a0);
-            st.h = sub * sp.hps + (int32_t)(a0 / T);
-            const int32_t rem = (int32_t)(a0 % T);
-            int lo = 0, hi = p.B - 1;          // last b with prefix[b] <= rem
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (prefix(mid) <= rem) lo = mid; else hi = mid - 1;
-            }
-            st.b = lo;
-            st.t = rem - prefix(lo);
-            const SeqInfo si = seq_info(p, lo);
-            st.q0 = si.q0;
-            st.R = si.R;
-            st.L = si.L;
-            st.tiles = si.tiles;
-            st.kv0 = si.kv0;
-        }
-        p.wave_start[w] = st;
-    }
-    for (int idx = tid; idx < p.B * p.Hkv; idx += 1024) {
-        const int b = idx / p.Hkv, kvh = idx % p.Hkv;
-        const int tiles = prefix(b + 1) - prefix(b);
-        int r_first = 0, r_last = 0;
-        if (tiles > 0) {
-            const int64_t first_tile = (int64_t)(kvh % sp.hps) * T + prefix(b);
-            r_first = part_of_tile(sp, first_tile);
-            r_last = part_of_tile(sp, first_tile + tiles - 1);
-        }
-        const SeqInfo si = seq_info(p, b);
-        *reinterpret_cast<int4 *>(p.cuts + 4 * (int64_t)idx) = int4{r_first, r_last, si.q0, si.R};
-    }
+    for (int w = tid; w < p.W; w += 1024) p.wave_start[w] = make_wave_start(p, sp, w, prefix);
+    for (int idx = tid; idx < p.B * p.Hkv; idx += 1024) write_cut(p, sp, idx, prefix);
     if (tid == 0) p.error_flag[1] = sp.sub_total >= sp.parts ? 1 : 0;
 }
 
@@ -482,7 +494,67 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     const int col0 = blockIdx.y * kBlockCols + (producer ? 0 : way * NT * kColTile);
 
     if (threadIdx.x < 3 * kConsumers) counters[threadIdx.x] = 0;
-    __syncthreads();  // the only barrier, before any wave can leave
+    // The split, built by every work-group for itself when the batch is small enough for its
+    // tile prefix to sit in LDS beside the rings (one kernel launch and its gap less in front
+    // of every call: 11-12 us; a work-group needs 3-4 us for it).  Each work-group also leaves
+    // its own starting points and its share of the cut table in the workspace: the combine
+    // kernel reads the table, and a later layer of the same forward reads the starting points.
+    __shared__ int32_t sh_prefix[kInlineSeqs + 1];
+    __shared__ int32_t sh_wave_sum[2 * kConsumers];
+    __shared__ WaveStart sh_start[kConsumers];
+    if (p.inline_setup) {  // uniform over the launch
+        constexpr int kBlock = 2 * kConsumers * 64;
+        int base = 0;
+        for (int b0 = 0; b0 < p.B; b0 += kBlock) {
+            const int b = b0 + (int)threadIdx.x;
+            int incl = b < p.B ? seq_info(p, b).tiles : 0;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int y = __shfl_up(incl, o);
+                if (lane >= o) incl += y;
+            }
+            if (lane == 63) sh_wave_sum[threadIdx.x >> 6] = incl;
+            __syncthreads();
+            int before = 0, all = 0;
+#pragma unroll
+            for (int w = 0; w < 2 * kConsumers; ++w) {
+                const int x = sh_wave_sum[w];
+                if (w < (int)(threadIdx.x >> 6)) before += x;
+                all += x;
+            }
+            if (b < p.B) sh_prefix[b + 1] = base + before + incl;
+            base += all;
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) sh_prefix[0] = 0;
+        __syncthreads();
+        auto prefix = [&](int i) { return sh_prefix[i]; };
+        const Split sp = make_split(p, base);
+        if ((int)threadIdx.x < kStreams) {
+            const int w = blockIdx.x * kStreams + (int)threadIdx.x;
+            WaveStart st{0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            if (w < p.W) {
+                st = make_wave_start(p, sp, w, prefix);
+                if (blockIdx.y == 0) p.wave_start[w] = st;
+            }
+            sh_start[threadIdx.x] = st;
+        }
+        if (blockIdx.y == 0) {
+            const int n_cuts = p.B * p.Hkv, per = (n_cuts + (int)gridDim.x - 1) / (int)gridDim.x;
+            for (int j = threadIdx.x; j < per; j += kBlock) {
+                const int idx = blockIdx.x * per + j;
+                if (idx < n_cuts) write_cut(p, sp, idx, prefix);
+            }
+            if (blockIdx.x == 0) {
+                for (int b = threadIdx.x; b <= p.B; b += kBlock) p.tile_prefix[b] = sh_prefix[b];
+                if (threadIdx.x == 0) {
+                    p.error_flag[0] = 0;
+                    p.error_flag[1] = sp.sub_total >= sp.parts ? 1 : 0;
+                }
+            }
+        }
+    }
+    __syncthreads();  // the last barrier, before any wave can leave
     // filled[r]: tiles producer r has written to its ring; consumed[r]: tiles of the range that
     // consumer r has finished with; read_done[r]: tiles whose K and V consumer r has read (CW > 1)
     const LdsCounter filled = counters;
@@ -490,7 +562,16 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     const LdsCounter read_done = counters + 2 * kConsumers;
 
     if (u >= p.W) return;  // wave-uniform, and the same for all waves of a range
-    const ConstPtr<int32_t> start = as_constant(reinterpret_cast<const int32_t *>(p.wave_start + u));
+    int32_t start[10];  // the fields of this range's WaveStart, wave-uniform
+    if (p.inline_setup) {
+        const int32_t *src = reinterpret_cast<const int32_t *>(&sh_start[stream]);
+#pragma unroll
+        for (int j = 0; j < 10; ++j) start[j] = __builtin_amdgcn_readfirstlane(src[j]);
+    } else {
+        const ConstPtr<int32_t> src = as_constant(reinterpret_cast<const int32_t *>(p.wave_start + u));
+#pragma unroll
+        for (int j = 0; j < 10; ++j) start[j] = src[j];
+    }
     const int n_tiles = start[3];
     if (n_tiles <= 0 || start[0] >= p.Hkv) return;
 
@@ -1472,7 +1553,10 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
 
     // the set-up depends on the index arrays and the sizes only: the layers of one forward share
     // it (reuse_plan: the workspace still holds what the set-up of an earlier call left there)
-    if (!reuse_plan) {
+    // (small batches: the main kernel's work-groups build it in their prologue and leave it in
+    // the workspace; large ones take a set-up kernel in front)
+    p.inline_setup = !reuse_plan && B <= kInlineSeqs ? 1 : 0;
+    if (!reuse_plan && !p.inline_setup) {
         hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
         err = hipGetLastError();
         if (err != hipSuccess)
