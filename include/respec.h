@@ -108,6 +108,34 @@ respec_status_t respec_verify_attention(const void *q, const void *k_cache, cons
                                         size_t workspace_bytes, void *hip_stream);
 
 /*
+ * respec_verify_attention for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, layouts and results as respec_verify_attention (contiguous
+ * cache, chain of drafts) without the workspace pair: the scratch of the launch (partial
+ * results of cut sequences, the tile prefix, the starting points of the split) lives in a
+ * buffer of respec_static_scratch_bytes() bytes (40 MiB) that is part of the library's device
+ * image.  Every GPU the library runs on holds its own copy until the process ends.
+ *
+ *   - A batch whose scratch does not fit (sized for a split of at most 1024 ranges: roughly
+ *     G * max_q_per_seq <= 64 at D = 128, B <= about 500,000) is refused with
+ *     RESPEC_ERR_WORKSPACE before anything is launched; use respec_verify_attention then.
+ *   - The call allocates nothing and frees nothing.  Its first use on a device looks the
+ *     buffer's address up (hipGetSymbolAddress); call respec_static_scratch_init() once per
+ *     device beforehand where that must not happen inside the call (graph capture).
+ *   - All calls on one GPU share the one buffer: calls that overlap on a GPU (two streams,
+ *     two host threads) race and give wrong results.  Calls in stream order are fine; nothing
+ *     in the buffer has to survive from one call to the next and nothing has to be cleared.
+ */
+size_t respec_static_scratch_bytes(void);
+respec_status_t respec_static_scratch_init(void);
+respec_status_t respec_verify_attention_static(const void *q, const void *k_cache, const void *v_cache,
+                                               const int32_t *q_indptr, const int64_t *kv_indptr,
+                                               void *out, float *lse, int32_t B, int32_t total_q,
+                                               int64_t total_kv, int32_t max_q_per_seq,
+                                               int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D,
+                                               float sm_scale, respec_dtype_t dt, void *hip_stream);
+
+/*
  * The attention of ANOTHER LAYER of the same forward pass.  The target's single forward over the
  * drafted block (Figure 2) runs this attention once per layer with the same sequences: the
  * index arrays, the lengths and every size are those of the previous call, only q, the caches

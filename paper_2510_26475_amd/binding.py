@@ -65,6 +65,15 @@ def load():
         c.c_float, c.c_int, c.c_void_p, c.c_size_t, c.c_void_p]
     lib.respec_verify_attention_next_layer.restype = c.c_int
     lib.respec_verify_attention_next_layer.argtypes = lib.respec_verify_attention_tree.argtypes
+    lib.respec_static_scratch_bytes.restype = c.c_size_t
+    lib.respec_static_scratch_bytes.argtypes = []
+    lib.respec_static_scratch_init.restype = c.c_int
+    lib.respec_static_scratch_init.argtypes = []
+    lib.respec_verify_attention_static.restype = c.c_int
+    lib.respec_verify_attention_static.argtypes = [
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+        c.c_int32, c.c_int32, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
+        c.c_float, c.c_int, c.c_void_p]
     lib.respec_profile_mark_main.restype = None
     lib.respec_profile_mark_main.argtypes = [c.c_void_p, c.c_void_p]
     lib.respec_rejection_sample_workspace_bytes.restype = c.c_size_t
@@ -132,6 +141,7 @@ EXPORTED_SYMBOLS = [
     "respec_kd_rows_workspace_bytes", "respec_kd_rows", "respec_solver_pick",
     "respec_validate_batch_workspace_bytes", "respec_validate_batch",
     "respec_profile_mark_main",
+    "respec_static_scratch_bytes", "respec_static_scratch_init", "respec_verify_attention_static",
 ]
 
 
@@ -195,6 +205,34 @@ def respec_verify_attention(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, 
         _dev_ptr(q_indptr, "q_indptr"), _dev_ptr(kv_indptr, "kv_indptr"), _dev_ptr(out, "out"),
         _dev_ptr(lse, "lse"), B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D,
         float(sm_scale), _dtype_code(q), ws_ptr, ws_bytes, _stream_ptr(stream)))
+
+
+def respec_static_scratch_bytes() -> int:
+    return int(load().respec_static_scratch_bytes())
+
+
+def respec_static_scratch_init():
+    _check(load().respec_static_scratch_init())
+
+
+def respec_verify_attention_static(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, max_q_per_seq,
+                                   max_kv_len, sm_scale, stream=None):
+    """respec_verify_attention without a workspace: the scratch is the library's built-in buffer."""
+    lib = load()
+    total_q, Hq, D = q.shape
+    total_kv, Hkv, _ = k_cache.shape
+    B = q_indptr.numel() - 1
+    if q_indptr.dtype != torch.int32 or kv_indptr.dtype != torch.int64:
+        raise TypeError("q_indptr must be int32 and kv_indptr int64")
+    if lse is not None and lse.dtype != torch.float32:
+        raise TypeError("lse must be float32")
+    if out.dtype != q.dtype or k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise TypeError("q, k_cache, v_cache and out must share one dtype")
+    _check(lib.respec_verify_attention_static(
+        _dev_ptr(q, "q"), _dev_ptr(k_cache, "k_cache"), _dev_ptr(v_cache, "v_cache"),
+        _dev_ptr(q_indptr, "q_indptr"), _dev_ptr(kv_indptr, "kv_indptr"), _dev_ptr(out, "out"),
+        _dev_ptr(lse, "lse"), B, total_q, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D,
+        float(sm_scale), _dtype_code(q), _stream_ptr(stream)))
 
 
 def respec_verify_attention_next_layer(q, k_cache, v_cache, q_indptr, kv_indptr, out, lse, max_q_per_seq,

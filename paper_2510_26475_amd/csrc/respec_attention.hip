@@ -25,6 +25,13 @@
 #include "respec_common.hpp"
 
 #include <cmath>
+#include <mutex>
+
+// Scratch of respec_verify_attention_static (the entry point for callers that cannot allocate):
+// one copy per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; the kernels get the device address that call returns.
+constexpr size_t kStaticScratchBytes = (size_t)40 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace respec {
 namespace {
@@ -1297,7 +1304,7 @@ struct Plan {
 };
 
 bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, int32_t Hq,
-               int32_t Hkv, int32_t D, respec_dtype_t dt, Plan &pl) {
+               int32_t Hkv, int32_t D, respec_dtype_t dt, Plan &pl, int max_waves = kMaxWaves) {
     if (B <= 0 || total_kv <= 0 || max_q <= 0 || max_kv_len <= 0 || Hq <= 0 || Hkv <= 0) return false;
     if (Hq % Hkv != 0 || (D != 64 && D != 128)) return false;
     if (dt != RESPEC_F32 && dt != RESPEC_BF16) return false;
@@ -1305,10 +1312,10 @@ bool make_plan(int32_t B, int64_t total_kv, int32_t max_q, int32_t max_kv_len, i
     if ((int64_t)G * max_q > 256) return false;
     pl.Mpad = (G * max_q + kColTile - 1) / kColTile * kColTile;
     // sized for the widest split so that the query needs no device
-    pl.ws_o_bytes = round_up((size_t)2 * kMaxWaves * pl.Mpad * D * sizeof(int16_t), 256);
-    pl.ws_ml_bytes = round_up((size_t)2 * kMaxWaves * pl.Mpad * 4 * sizeof(float), 256);
+    pl.ws_o_bytes = round_up((size_t)2 * max_waves * pl.Mpad * D * sizeof(int16_t), 256);
+    pl.ws_ml_bytes = round_up((size_t)2 * max_waves * pl.Mpad * 4 * sizeof(float), 256);
     pl.prefix_bytes = round_up((size_t)(B + 1) * sizeof(int32_t), 256);
-    pl.start_bytes = round_up((size_t)kMaxWaves * sizeof(WaveStart), 256);
+    pl.start_bytes = round_up((size_t)max_waves * sizeof(WaveStart), 256);
     pl.flag_bytes = 256;
     pl.cut_bytes = round_up((size_t)B * Hkv * 4 * sizeof(int32_t), 256);
     pl.ws_bytes = pl.ws_o_bytes + pl.ws_ml_bytes + pl.prefix_bytes + pl.start_bytes + pl.flag_bytes + pl.cut_bytes;
@@ -1333,12 +1340,14 @@ template <int D, int NT, int CW>
 hipError_t launch_bf16(const AttnParams &p, dim3 grid, hipStream_t stream) {
     using C = Bf16Cfg<D>;
     const size_t smem = (size_t)kConsumers * kSlots * C::kWaveBytes + 3 * kConsumers * sizeof(uint32_t);
-    static bool configured = false;  // benign race: the attribute is idempotent
-    if (!configured) {
+    static bool configured[64] = {false};  // per device; benign race: the attribute is idempotent
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+    if (dev < 0 || !configured[dev]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, NT, uint16_t, CW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
-        configured = true;
+        if (dev >= 0) configured[dev] = true;
     }
     hipLaunchKernelGGL((attn_bf16_kernel<D, NT, uint16_t, CW>), grid, dim3(2 * kConsumers * 64), smem, stream, p);
     return hipGetLastError();
@@ -1402,7 +1411,7 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
                                      int32_t total_q, int64_t total_kv, int32_t max_q_per_seq,
                                      int32_t max_kv_len, int32_t Hq, int32_t Hkv, int32_t D, float sm_scale,
                                      respec_dtype_t dt, void *workspace, size_t workspace_bytes,
-                                     void *hip_stream, bool reuse_plan = false) {
+                                     void *hip_stream, bool reuse_plan = false, int max_waves = kMaxWaves) {
     const bool paged = pg.page_table != nullptr;
     if (tree_mask && max_q_per_seq > 64)
         return fail(RESPEC_ERR_UNSUPPORTED, "verify_attention_tree: at most 64 rows per sequence, got %d",
@@ -1441,7 +1450,7 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     if (!aligned_to(q, 16) || !aligned_to(k_cache, 16) || !aligned_to(v_cache, 16) || !aligned_to(out, 16))
         return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: q, k_cache, v_cache and out must be 16-byte aligned");
     Plan pl;
-    if (!make_plan(B, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, dt, pl))
+    if (!make_plan(B, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, dt, pl, max_waves))
         return fail(RESPEC_ERR_INVALID_ARG, "verify_attention: could not plan the launch");
     if (!workspace || workspace_bytes < pl.ws_bytes || !aligned_to(workspace, 256))
         return fail(RESPEC_ERR_WORKSPACE, "verify_attention: workspace of %zu bytes (256-byte aligned) needed, got %zu",
@@ -1544,7 +1553,7 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     long W = env_long("RESPEC_ATTN_WGS", 0);
     if (W <= 0) W = (long)streams * compute_units() / col_blocks;
     if (W < 1) W = 1;
-    if (W > kMaxWaves) W = kMaxWaves;
+    if (W > max_waves) W = max_waves;
     p.W = (int32_t)W;
     int hi = Hkv % 4 == 0 ? 4 : (Hkv % 2 == 0 ? 2 : 1);
     if (hi > streams) hi = streams;
@@ -1665,6 +1674,73 @@ respec_status_t respec_verify_attention_paged_next_layer(const void *q, const vo
     return respec::verify_attention_any(q, k_pages, v_pages, q_indptr, nullptr, pg, tree_mask, out, lse, B, total_q,
                                         0, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt, workspace,
                                         workspace_bytes, hip_stream, true);
+}
+
+}  // extern "C"
+
+namespace respec {
+namespace {
+
+constexpr int kStaticMaxWaves = 1024;  // split width the static scratch is sized for
+constexpr int kMaxDevices = 64;
+
+// Device address of `scratch` on the current device, looked up once per device (each GPU holds
+// its own copy of the array at its own address).  Returns NULL and sets the error text on failure.
+void *static_scratch_address() {
+    static std::mutex mu;
+    static void *addr[kMaxDevices] = {nullptr};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        fail(RESPEC_ERR_HIP, "static scratch: no usable current device (%s)", hipGetErrorString(e));
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            fail(RESPEC_ERR_HIP, "static scratch: hipGetSymbolAddress failed on device %d: %s", dev,
+                 hipGetErrorString(e));
+            return nullptr;
+        }
+        addr[dev] = ptr;
+    }
+    return addr[dev];
+}
+
+}  // namespace
+}  // namespace respec
+
+extern "C" {
+
+size_t respec_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+respec_status_t respec_static_scratch_init(void) {
+    if (!respec::static_scratch_address()) return RESPEC_ERR_HIP;
+    respec::clear_error();
+    return RESPEC_OK;
+}
+
+respec_status_t respec_verify_attention_static(const void *q, const void *k_cache, const void *v_cache,
+                                               const int32_t *q_indptr, const int64_t *kv_indptr, void *out,
+                                               float *lse, int32_t B, int32_t total_q, int64_t total_kv,
+                                               int32_t max_q_per_seq, int32_t max_kv_len, int32_t Hq,
+                                               int32_t Hkv, int32_t D, float sm_scale, respec_dtype_t dt,
+                                               void *hip_stream) {
+    using namespace respec;
+    Plan pl;
+    if (!make_plan(B, total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, dt, pl, kStaticMaxWaves))
+        return fail(RESPEC_ERR_INVALID_ARG, "verify_attention_static: sizes out of range (see respec_verify_attention)");
+    if (pl.ws_bytes > kStaticScratchBytes)
+        return fail(RESPEC_ERR_WORKSPACE,
+                    "verify_attention_static: this batch needs %zu bytes of scratch, the built-in buffer holds %zu; "
+                    "use respec_verify_attention with a workspace", pl.ws_bytes, kStaticScratchBytes);
+    void *ws = static_scratch_address();
+    if (!ws) return RESPEC_ERR_HIP;
+    return verify_attention_any(q, k_cache, v_cache, q_indptr, kv_indptr, Pages{}, nullptr, out, lse, B, total_q,
+                                total_kv, max_q_per_seq, max_kv_len, Hq, Hkv, D, sm_scale, dt, ws,
+                                kStaticScratchBytes, hip_stream, false, kStaticMaxWaves);
 }
 
 respec_status_t respec_commit_accepted_paged(void *k_pages, void *v_pages, const int32_t *q_indptr,
