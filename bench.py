@@ -9,6 +9,7 @@ are resident in HBM before the timed region.  Prints ONE JSON line.
                     [--tree DEPTHxBRANCH] [--page-size P] [--no-cpu-baseline] [--no-measure-depth]
     python bench.py --kd-rows N [--workload NAME] [--sigma S]
     python bench.py --sweep --workload qwen14b_sweep [--sweep-batches 64,256,...] [--sweep-ks 0,1,2,4,8]
+    python bench.py --copy-probe 1024      # a copy of known size, to calibrate rocprofv3's byte counters
 
 --tree times the tree-of-drafts variant of the step on the same workload (every sequence
 drafts a main chain of DEPTH nodes with BRANCH candidates per position); the default is the
@@ -39,6 +40,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 # WRITE_SIZE runs, scaled by the same counters on a copy kernel of known size); the
 # summaries are under profiles/.  None = not measured for that workload.
 MEASURED_TRAFFIC_BYTES = {"qwen7b_b256_k3": 1.2285e9}
+TRAFFIC_SOURCE = {"qwen7b_b256_k3": "profiles/verify_step_qwen7b_b256_k3.md (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE "
+                                    "runs of this command, scaled by the same counters of `bench.py --copy-probe`; "
+                                    "a constant copied from that summary, not a counter read in this run)"}
 
 
 def attention_algorithmic_bytes(batch: synth.VerifyBatch) -> int:
@@ -130,11 +134,12 @@ def run_cpu_baseline(batch: synth.VerifyBatch, n_seqs: int):
         ua=sb.u_accept.cpu().numpy(), uf=sb.u_final.cpu().numpy())
     threads = oracle.max_threads()
     t0 = time.perf_counter()
-    oracle.verify_attention(host["q"], host["k"], host["v"], host["qi"], host["ki"], wl.Hq, wl.Hkv,
-                            wl.D, float(np.float32(1.0 / math.sqrt(wl.D))), dt, n_threads=0)
+    attn_out, attn_lse = oracle.verify_attention(host["q"], host["k"], host["v"], host["qi"], host["ki"], wl.Hq,
+                                                 wl.Hkv, wl.D, float(np.float32(1.0 / math.sqrt(wl.D))), dt,
+                                                 want_lse=True, n_threads=0)
     t1 = time.perf_counter()
     n_draft = sb.total_q - n_seqs
-    toks, n, _ = oracle.rejection_sample(
+    toks, n, oflags = oracle.rejection_sample(
         host["t"], host["d"] if n_draft else None, host["tok"] if n_draft else None, host["qi"],
         host["ua"] if n_draft else None, host["uf"], sb.max_k, wl.temperature, dt, n_threads=0)
     t2 = time.perf_counter()
@@ -154,13 +159,37 @@ def run_cpu_baseline(batch: synth.VerifyBatch, n_seqs: int):
         h1["t"], h1["d"] if nd1 else None, h1["tok"] if nd1 else None, h1["qi"],
         h1["ua"] if nd1 else None, h1["uf"], s1.max_k, wl.temperature, dt, n_threads=1)
     t4 = time.perf_counter()
-    return {
+    line = {
         "one_thread": {"value": int((n_1 + 1).sum()) / (t4 - t3), "unit": "tokens/s",
                        "sample": f"first {n1} sequences"},
         "value": emitted / (t2 - t0), "unit": "tokens/s", "cores": threads, "kind": "oracle",
         "sample": f"first {n_seqs} of {len(batch.k_per_seq)} sequences of the same workload, "
                   f"one attention layer + sampler, OpenMP over sequences",
         "attention_s": t1 - t0, "sampler_s": t2 - t1, "emitted_tokens": emitted,
+    }
+    return line, dict(n_seqs=n_seqs, rows=sb.total_q, out=attn_out, lse=attn_lse, tokens=toks, n=n, flags=oflags)
+
+
+def parity_tally(ref, gpu_out, gpu_lse, gpu_toks, gpu_n, gpu_flags, bf16: bool):
+    """The HIP path's results of the benchmarked launch against the oracle's, on the sequences the
+    cpu_baseline leg walked (outside the timed region).  Tokens and counts must agree exactly on
+    every sequence that neither side flags as a boundary draw; flagged ones are counted."""
+    import numpy as np
+    ns, rows = ref["n_seqs"], ref["rows"]
+    gt, gn, gf = gpu_toks[:ns].cpu().numpy(), gpu_n[:ns].cpu().numpy(), gpu_flags[:ns].cpu().numpy()
+    same = (gt == ref["tokens"]).all(axis=1) & (gn == ref["n"])
+    flagged = (ref["flags"] != 0) | (gf != 0)
+    err = np.abs(gpu_out[:rows].double().cpu().numpy() - ref["out"])
+    row_ref = np.abs(ref["out"]).max(axis=-1, keepdims=True)
+    lse_err = np.abs(gpu_lse[:rows].double().cpu().numpy() - ref["lse"])
+    return {
+        "sequences": int(ns), "oracle_flagged": int((ref["flags"] != 0).sum()), "gpu_flagged": int((gf != 0).sum()),
+        "unflagged_mismatch": int((~same & ~flagged).sum()), "flagged_mismatch": int((~same & flagged).sum()),
+        "attention_rows": int(rows), "attention_max_abs_err": float(err.max()),
+        "attention_max_err_over_row_max": float((err / np.maximum(row_ref, 1e-30)).max()),
+        "attention_tolerance": 2e-2 if bf16 else 1e-5, "lse_max_abs_err": float(lse_err.max()),
+        "note": "oracle vs the HIP path on the same bytes; a boundary draw lies within 1e-6 of an accept "
+                "threshold or of an edge of the chosen token's CDF cell",
     }
 
 
@@ -248,6 +277,7 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
     samp_ws = torch.zeros(binding.respec_rejection_sample_workspace_bytes(B, batch.total_q, wl.V, dt),
                           dtype=torch.uint8, device=dev)
 
+    turn = {"i": 0}
     paged = None
     if args.page_size:
         paged = synth.paginate(batch.k_cache, batch.v_cache, batch.kv_lens, args.page_size, seed=wl.seed,
@@ -274,7 +304,6 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
         sets = [(batch.k_cache, batch.v_cache, batch.target_logits, batch.draft_logits)]
         for _ in range(n_sets - 1):
             sets.append(tuple(t.clone() for t in sets[0]))
-        turn = {"i": 0}
 
         def commit():
             turn["i"] += 1
@@ -480,11 +509,20 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
             "kernel": "attn_bf16_kernel" if wl.dtype == "bf16" else "attn_f32_kernel",
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "traffic_source": TRAFFIC_SOURCE.get(wl.name) if traffic is not None else None,
         },
     }
     if cpu_baseline:
-        line["cpu_baseline"] = (run_cpu_baseline_tree(batch, args.cpu_seqs) if tree is not None
-                                else run_cpu_baseline(batch, args.cpu_seqs))
+        if tree is not None:
+            line["cpu_baseline"] = run_cpu_baseline_tree(batch, args.cpu_seqs)
+        else:
+            line["cpu_baseline"], ref = run_cpu_baseline(batch, args.cpu_seqs)
+            # the benchmarked launch's own outputs against the oracle's (first input set)
+            turn["i"] = 0
+            attention()
+            sampler()
+            torch.cuda.synchronize()
+            line["parity"] = parity_tally(ref, out, lse, toks, n_acc, flags, wl.dtype == "bf16")
         if paged is not None:
             line["cpu_baseline"]["note"] = ("timed on the oracle's contiguous-cache functions: its paged form "
                                             "gathers a sequence's pages and calls them")
@@ -545,6 +583,20 @@ def run_sweep(args, wl, dev):
     print(json.dumps(out))
 
 
+def run_copy_probe(mib: int, iters: int):
+    """A plain device-to-device copy of known size, for calibrating rocprofv3's byte counters: what
+    FETCH_SIZE / WRITE_SIZE report for its kernel, divided by the bytes copied, is the factor applied
+    to the same counters of the verify kernels."""
+    n = mib << 20
+    src = torch.arange(n // 4, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(iters):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe_bytes": n, "iters": iters}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -576,6 +628,8 @@ def main():
     ap.add_argument("--sweep-ks", default="0,1,2,4,8")
     ap.add_argument("--kd-rows", type=int, default=None,
                     help="time respec_kd_rows on this many row pairs instead of the verify step")
+    ap.add_argument("--copy-probe", type=int, default=None, metavar="MIB",
+                    help="only copy this many MiB device to device three times (calibrates rocprofv3's byte counters)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -600,6 +654,9 @@ def main():
 
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    if args.copy_probe:
+        run_copy_probe(args.copy_probe, 3)
+        return
     if args.kd_rows:
         run_kd(args, wl, dev)
         return

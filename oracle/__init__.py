@@ -17,6 +17,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "respec_oracle.c")
 _LIB = os.path.join(_HERE, "librespec_oracle.so")
+# A test may point the loader at another build of the same source (the sanitizer build of
+# tests/test_oracle_sanitizers.py); that build is then used as it is.
+_OVERRIDE = os.environ.get("RESPEC_ORACLE_LIBRARY")
 
 F32 = 0
 BF16 = 1
@@ -26,6 +29,10 @@ _lib = None
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (no HIP, no third-party code)."""
+    global _LIB
+    if _OVERRIDE:
+        _LIB = _OVERRIDE
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
                "-o", _LIB, _SRC, "-lm"]

@@ -179,15 +179,18 @@ __device__ inline float sum_across_rows(float x) {
 // The split.  The KV heads form HI sub-lists of Hkv/HI heads; a sub-list is the flat tile list
 // (head, sequence, tile) of its heads, `sub_total` tiles long, cut evenly into W/HI parts.
 // Wave u takes part u / HI of sub-list u % HI.  Part r owns flat tiles
-// [range_begin(r), range_begin(r+1)) of its sub-list.  (Unequal parts were tried, to make up
-// for the odd-numbered dies being served about 5 % slower under saturation; the kernel did not
-// get faster: the dies share one memory system and the early finishers' share is not taken up.)
+// [range_begin(r), range_begin(r+1)) of its sub-list.
 struct Split {
     int64_t T;           // tiles of one KV head
     int64_t sub_total;   // tiles of one sub-list
     int32_t parts, hps;  // parts per sub-list, heads per sub-list
 };
 
+// (Unequal parts were tried twice, to make up for dies that are served less bandwidth under
+// saturation: with equal parts the work-groups of two to four of the eight dies end 10-15 us
+// after the others', and the launch lasts as long as they do.  Which dies are the slow ones
+// changes from launch to launch, so no fixed weighting helps: 200-204 us with the odd-numbered
+// dies' parts 2-7 % smaller, 203-204 us with equal parts.)
 __device__ inline Split make_split(const AttnParams &p, int64_t T) {
     Split s;
     s.T = T;
@@ -197,27 +200,41 @@ __device__ inline Split make_split(const AttnParams &p, int64_t T) {
     return s;
 }
 
-__device__ inline int64_t range_begin(const Split &s, int r) { return (int64_t)r * s.sub_total / s.parts; }
+// Quotient of two non-negative 64-bit numbers.  A 64-bit division is a long instruction sequence
+// on this hardware; the operands here nearly always fit 32 bits, where it is a short one.  Both
+// branches give the same integer.
+__device__ inline int64_t div_nonneg(int64_t num, int64_t den) {
+    if (((uint64_t)num | (uint64_t)den) <= 0xffffffffull) return (int64_t)((uint32_t)num / (uint32_t)den);
+    return num / den;
+}
+
+__device__ inline int64_t range_begin(const Split &s, int r) {
+    const int64_t num = (int64_t)r * s.sub_total;
+    if ((s.parts & (s.parts - 1)) == 0) return num >> (31 - __builtin_clz(s.parts));  // the usual case
+    return div_nonneg(num, s.parts);
+}
 
 __device__ inline int part_of_tile(const Split &s, int64_t x) {  // x: flat index in the sub-list
-    return (int)(((x + 1) * s.parts - 1) / s.sub_total);
+    return (int)div_nonneg((x + 1) * s.parts - 1, s.sub_total);
 }
 
 __device__ inline bool part_owns_tiles(const Split &s, int r) {
     return range_begin(s, r + 1) > range_begin(s, r);
 }
 
-// Where wave w of the split starts: `prefix(i)` is the tile prefix over sequences (LDS or global).
-template <typename Prefix>
-__device__ inline WaveStart make_wave_start(const AttnParams &p, const Split &sp, int w, Prefix prefix) {
+// Where wave w of the split starts: `prefix(i)` is the tile prefix over sequences and `info(b)`
+// the bounds of sequence b (from LDS, or from the index arrays in global memory).
+template <typename Prefix, typename Info>
+__device__ inline WaveStart make_wave_start(const AttnParams &p, const Split &sp, int w, Prefix prefix, Info info) {
     WaveStart st{0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     const int64_t T = sp.T;
     if (T > 0) {
         const int r = w / p.HI, sub = w % p.HI;
         const int64_t a0 = range_begin(sp, r), a1 = range_begin(sp, r + 1);
         st.n = (int32_t)(a1 - a0);
-        st.h = sub * sp.hps + (int32_t)(a0 / T);
-        const int32_t rem = (int32_t)(a0 % T);
+        const int64_t head = a0 < T ? 0 : div_nonneg(a0, T);  // (one head per sub-list: always 0)
+        st.h = sub * sp.hps + (int32_t)head;
+        const int32_t rem = (int32_t)(a0 - head * T);
         int lo = 0, hi = p.B - 1;          // last b with prefix[b] <= rem
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
@@ -225,7 +242,7 @@ __device__ inline WaveStart make_wave_start(const AttnParams &p, const Split &sp
         }
         st.b = lo;
         st.t = rem - prefix(lo);
-        const SeqInfo si = seq_info(p, lo);
+        const SeqInfo si = info(lo);
         st.q0 = si.q0;
         st.R = si.R;
         st.L = si.L;
@@ -238,8 +255,8 @@ __device__ inline WaveStart make_wave_start(const AttnParams &p, const Split &sp
 // For (sequence, KV head) idx: the first and the last part that hold its tiles, its first query
 // row and its query rows (what the combine kernel needs; the 64-bit divisions behind the parts
 // are done once here, not by every thread of that kernel).
-template <typename Prefix>
-__device__ inline void write_cut(const AttnParams &p, const Split &sp, int idx, Prefix prefix) {
+template <typename Prefix, typename Info>
+__device__ inline void write_cut(const AttnParams &p, const Split &sp, int idx, Prefix prefix, Info info) {
     const int b = idx / p.Hkv, kvh = idx % p.Hkv;
     const int tiles = prefix(b + 1) - prefix(b);
     int r_first = 0, r_last = 0;
@@ -248,7 +265,7 @@ __device__ inline void write_cut(const AttnParams &p, const Split &sp, int idx, 
         r_first = part_of_tile(sp, first_tile);
         r_last = part_of_tile(sp, first_tile + tiles - 1);
     }
-    const SeqInfo si = seq_info(p, b);
+    const SeqInfo si = info(b);
     *reinterpret_cast<int4 *>(p.cuts + 4 * (int64_t)idx) = int4{r_first, r_last, si.q0, si.R};
 }
 
@@ -299,8 +316,9 @@ __global__ __launch_bounds__(1024) void attn_prep_kernel(AttnParams p) {
     }
     auto prefix = [&](int i) { return in_lds ? sh_prefix[i] : p.tile_prefix[i]; };
     const Split sp = make_split(p, sh_base);
-    for (int w = tid; w < p.W; w += 1024) p.wave_start[w] = make_wave_start(p, sp, w, prefix);
-    for (int idx = tid; idx < p.B * p.Hkv; idx += 1024) write_cut(p, sp, idx, prefix);
+    auto info = [&](int b) { return seq_info(p, b); };
+    for (int w = tid; w < p.W; w += 1024) p.wave_start[w] = make_wave_start(p, sp, w, prefix, info);
+    for (int idx = tid; idx < p.B * p.Hkv; idx += 1024) write_cut(p, sp, idx, prefix, info);
     if (tid == 0) p.error_flag[1] = sp.sub_total >= sp.parts ? 1 : 0;
 }
 
@@ -501,20 +519,29 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
     const int col0 = blockIdx.y * kBlockCols + (producer ? 0 : way * NT * kColTile);
 
     if (threadIdx.x < 3 * kConsumers) counters[threadIdx.x] = 0;
-    // The split, built by every work-group for itself when the batch is small enough for its
-    // tile prefix to sit in LDS beside the rings (one kernel launch and its gap less in front
-    // of every call: 11-12 us; a work-group needs 3-4 us for it).  Each work-group also leaves
-    // its own starting points and its share of the cut table in the workspace: the combine
-    // kernel reads the table, and a later layer of the same forward reads the starting points.
-    __shared__ int32_t sh_prefix[kInlineSeqs + 1];
+    // The split, built by every work-group for itself when the batch is small enough (one kernel
+    // launch and its gap less in front of every call).  The bounds of all sequences and their
+    // tile prefix are staged in the LDS that the rings will use afterwards, so the searches below
+    // read no global memory.  Each work-group also leaves its own starting points and its share
+    // of the cut table in the workspace: the combine kernel reads the table, and a later layer
+    // of the same forward reads the starting points.
     __shared__ int32_t sh_wave_sum[2 * kConsumers];
     __shared__ WaveStart sh_start[kConsumers];
     if (p.inline_setup) {  // uniform over the launch
         constexpr int kBlock = 2 * kConsumers * 64;
+        static_assert((size_t)kInlineSeqs * sizeof(SeqInfo) + (kInlineSeqs + 1) * sizeof(int32_t) <=
+                          (size_t)kConsumers * kSlots * C::kWaveBytes, "the staging fits where the rings will be");
+        SeqInfo *sh_seq = reinterpret_cast<SeqInfo *>(smem);
+        int32_t *sh_prefix = reinterpret_cast<int32_t *>(smem + (size_t)kInlineSeqs * sizeof(SeqInfo));
         int base = 0;
         for (int b0 = 0; b0 < p.B; b0 += kBlock) {
             const int b = b0 + (int)threadIdx.x;
-            int incl = b < p.B ? seq_info(p, b).tiles : 0;
+            int incl = 0;
+            if (b < p.B) {
+                const SeqInfo si = seq_info(p, b);
+                sh_seq[b] = si;
+                incl = si.tiles;
+            }
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 const int y = __shfl_up(incl, o);
@@ -536,25 +563,26 @@ __global__ __launch_bounds__(2 * kConsumers * 64, 1) void attn_bf16_kernel(AttnP
         if (threadIdx.x == 0) sh_prefix[0] = 0;
         __syncthreads();
         auto prefix = [&](int i) { return sh_prefix[i]; };
+        auto info = [&](int b) { return sh_seq[b]; };
         const Split sp = make_split(p, base);
-        if ((int)threadIdx.x < kStreams) {
+        if ((int)threadIdx.x < kStreams) {  // (first wave: the starting points; the others: the cut table)
             const int w = blockIdx.x * kStreams + (int)threadIdx.x;
             WaveStart st{0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
             if (w < p.W) {
-                st = make_wave_start(p, sp, w, prefix);
+                st = make_wave_start(p, sp, w, prefix, info);
                 if (blockIdx.y == 0) p.wave_start[w] = st;
             }
             sh_start[threadIdx.x] = st;
         }
-        if (blockIdx.y == 0) {
+        if (blockIdx.y == 0 && threadIdx.x >= 64) {
             const int n_cuts = p.B * p.Hkv, per = (n_cuts + (int)gridDim.x - 1) / (int)gridDim.x;
-            for (int j = threadIdx.x; j < per; j += kBlock) {
+            for (int j = (int)threadIdx.x - 64; j < per; j += kBlock - 64) {
                 const int idx = blockIdx.x * per + j;
-                if (idx < n_cuts) write_cut(p, sp, idx, prefix);
+                if (idx < n_cuts) write_cut(p, sp, idx, prefix, info);
             }
             if (blockIdx.x == 0) {
-                for (int b = threadIdx.x; b <= p.B; b += kBlock) p.tile_prefix[b] = sh_prefix[b];
-                if (threadIdx.x == 0) {
+                for (int b = (int)threadIdx.x - 64; b <= p.B; b += kBlock - 64) p.tile_prefix[b] = sh_prefix[b];
+                if (threadIdx.x == 64) {
                     p.error_flag[0] = 0;
                     p.error_flag[1] = sp.sub_total >= sp.parts ? 1 : 0;
                 }
@@ -1564,7 +1592,7 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     // it (reuse_plan: the workspace still holds what the set-up of an earlier call left there)
     // (small batches: the main kernel's work-groups build it in their prologue and leave it in
     // the workspace; large ones take a set-up kernel in front)
-    p.inline_setup = !reuse_plan && B <= kInlineSeqs ? 1 : 0;
+    p.inline_setup = !reuse_plan && B <= kInlineSeqs && env_long("RESPEC_ATTN_INLINE", 1) != 0 ? 1 : 0;
     if (!reuse_plan && !p.inline_setup) {
         hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
         err = hipGetLastError();

@@ -146,6 +146,50 @@ def oracle_sample(oracle, batch: synth.VerifyBatch, temperature=None, max_k=None
         dt, n_threads=n_threads)
 
 
+def check_bf16_attention_rows(got: np.ndarray, ref: np.ndarray, rms_bound: float = 2.5e-3):
+    """Element-wise bounds of a bf16 attention output [rows, heads, D] against the fp64 oracle.
+
+    * absolute, the stated tolerance: 2e-2;
+    * relative to the row: |err| <= 2^-7 * max|ref row| + 1e-3.  The output is rounded to bf16
+      (half an ulp: at most 2^-8 of the element's magnitude) and so are the probabilities before
+      the second product (2^-9 each, averaging over the keys); the largest absolute errors
+      therefore sit in rows whose outputs are large, i.e. rows that see few keys or one dominant
+      key (outputs of magnitude 2-4 round by up to 0.008-0.016), not in the long contexts;
+    * rms over everything: 2.5e-3.
+    """
+    err = np.abs(got - ref)
+    assert err.max() <= 2e-2, f"max abs err {err.max():.3e} > 2e-2"
+    row_max = np.abs(ref).max(axis=-1, keepdims=True)
+    excess = err - (2.0 ** -7 * row_max + 1e-3)
+    assert excess.max() <= 0.0, (f"row-relative bound exceeded by {excess.max():.3e} at "
+                                 f"{np.unravel_index(np.argmax(excess), excess.shape)}")
+    rms = math.sqrt(float((err ** 2).mean()))
+    assert rms <= rms_bound, f"rms err {rms:.3e}"
+    return float(err.max())
+
+
+def expected_flag_rate(V: int, logit_sigma: float = 3.0, eps: float = 1e-6) -> float:
+    """Expected share of boundary draws for rows of V iid N(0, logit_sigma^2) logits.
+
+    A draw is flagged when u*Z lies within eps*Z of an edge of the chosen token's CDF cell: for a
+    token of mass w that happens with probability min(w, 2 eps), so the rate is
+    sum_x min(w_x, 2 eps).  With w = e^z / (V e^{sigma^2/2}) the tokens above the threshold
+    z* = ln(2 eps V) + sigma^2/2 contribute 2 eps each and the others their (lognormal) mass.
+    (The accept tests add 2 eps per test, which is nothing.)  V = 151,936 and sigma = 3 give 0.07.
+    """
+    from scipy.stats import norm
+    zs = math.log(2 * eps * V) + logit_sigma ** 2 / 2
+    above = V * norm.sf(zs / logit_sigma)
+    below_mass = norm.cdf((zs - logit_sigma ** 2) / logit_sigma)
+    return min(1.0, 2 * eps * above + below_mass)
+
+
+def flag_bound(B: int, V: int, logit_sigma: float = 3.0) -> float:
+    """Mean plus four standard deviations (and one) of the number of boundary draws among B."""
+    r = expected_flag_rate(V, logit_sigma)
+    return B * r + 4.0 * math.sqrt(B * r * (1 - r)) + 1.0
+
+
 def compare_sampler(gpu, ref):
     """Exact equality of tokens and counts on unflagged sequences; returns the boundary tally."""
     g_t, g_n, g_f = gpu

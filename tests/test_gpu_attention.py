@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import attn_wgs, env_setting, gpu_attention, oracle_attention, sub_batch
+from helpers import attn_wgs, check_bf16_attention_rows, env_setting, gpu_attention, oracle_attention, sub_batch
 from paper_2510_26475_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -31,8 +31,7 @@ def _check(out, lse, ref, ref_lse, dtype, rms_bound=2.5e-3):
     tol = F32_TOL if dtype == "f32" else BF16_TOL
     assert err.max() <= tol, f"max abs err {err.max():.3e} > {tol}"
     if dtype == "bf16":
-        rms = math.sqrt(float((err ** 2).mean()))
-        assert rms <= rms_bound, f"rms err {rms:.3e}"
+        check_bf16_attention_rows(got, ref, rms_bound)
     if lse is not None:
         lerr = np.abs(lse.double().cpu().numpy() - ref_lse)
         assert lerr.max() <= (1e-4 if dtype == "f32" else 2e-2), f"lse err {lerr.max():.3e}"
@@ -226,20 +225,15 @@ def test_qwen3b_workload_full_batch(oracle):
     _check(out[rows], lse[rows], ref, ref_lse, "bf16")
 
 
-def test_qwen7b_headline_workload_sampled_sequences(oracle):
-    """Full-size B=256, k=3, 28/4 heads in the launch configuration the benchmark times;
-    the oracle checks a sample of sequences (longest, shortest and a spread)."""
+def test_qwen7b_headline_workload_whole_batch(oracle):
+    """Full-size B=256, k=3, 28/4 heads in the launch configuration the benchmark times: every
+    row of every sequence against the oracle (which walks the batch in about a second)."""
     wl = synth.WORKLOADS["qwen7b_b256_k3"]
     batch = synth.make_batch(wl, device="cuda", with_logits=False)
     out, lse = gpu_attention(batch)
-    assert torch.isfinite(out.float()).all()
-    seqs = sorted(set([int(np.argmax(batch.kv_lens)), int(np.argmin(batch.kv_lens)),
-                       0, 50, 101, 199, 255]))
-    sb = sub_batch(batch, seqs)
-    ref, ref_lse = oracle_attention(oracle, sb)
-    qi = batch.q_indptr.tolist()
-    rows = torch.tensor([r for b in seqs for r in range(qi[b], qi[b + 1])], device="cuda")
-    _check(out[rows], lse[rows], ref, ref_lse, "bf16")
+    ref, ref_lse = oracle_attention(oracle, batch)
+    worst = _check(out, lse, ref, ref_lse, "bf16")
+    print(f"headline attention: max abs err {worst:.3e} over {batch.total_q} rows")
 
 
 def test_next_layer_reuses_the_set_up_and_is_bit_equal_to_a_full_call(oracle):

@@ -9,7 +9,8 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import compare_sampler, gpu_attention, gpu_sample, oracle_attention, oracle_sample
+from helpers import (check_bf16_attention_rows, compare_sampler, flag_bound, gpu_attention, gpu_sample,
+                     oracle_attention, oracle_sample)
 from paper_2510_26475_amd import synth
 from paper_2510_26475_amd.synth import sub_batch
 
@@ -23,8 +24,7 @@ def _attention_sample(oracle, batch, seqs):
     ref, ref_lse = oracle_attention(oracle, sb)
     qi = batch.q_indptr.tolist()
     rows = torch.tensor([r for b in seqs for r in range(qi[b], qi[b + 1])], device="cuda")
-    err = np.abs(out[rows].double().cpu().numpy() - ref)
-    assert err.max() <= 2e-2 and np.sqrt((err ** 2).mean()) <= 2.5e-3, (err.max(), np.sqrt((err ** 2).mean()))
+    check_bf16_attention_rows(out[rows].double().cpu().numpy(), ref)
     assert np.abs(lse[rows].double().cpu().numpy() - ref_lse).max() <= 2e-2
 
 
@@ -42,14 +42,15 @@ def _sampler_sample(oracle, batch, seqs):
     sb = sub_batch(batch, seqs)
     ref = oracle_sample(oracle, sb, max_k=batch.max_k)
     tally = compare_sampler((toks[seqs], n[seqs], flags[seqs]), ref)
-    assert tally["flagged"] <= max(3, 0.2 * len(seqs)), tally
+    assert tally["flagged"] <= flag_bound(len(seqs), batch.wl.V), tally
     return n
 
 
 def test_sweep_corner_b1024_k8(oracle):
     wl = dataclasses.replace(synth.WORKLOADS["qwen14b_sweep"], B=1024, k=8)
     batch = synth.make_batch(wl, device="cuda", with_logits=False)
-    seqs = sorted(set([int(np.argmax(batch.kv_lens)), int(np.argmin(batch.kv_lens)), 0, 333, 1023]))
+    # longest, shortest, and every 32nd sequence
+    seqs = sorted(set([int(np.argmax(batch.kv_lens)), int(np.argmin(batch.kv_lens)), 1023] + list(range(0, 1024, 32))))
     _attention_sample(oracle, batch, seqs)
     del batch
     torch.cuda.empty_cache()
@@ -65,7 +66,7 @@ def test_ragged_dynamic_batch_b1024(oracle):
     assert ks.min() == 0 and ks.max() == 8
     pick = [int(np.argmax(batch.kv_lens)), int(np.argmin(batch.kv_lens)), int(np.flatnonzero(ks == 0)[0]),
             int(np.flatnonzero(ks == 8)[0]), int(np.flatnonzero(ks == 3)[0])]
-    _attention_sample(oracle, batch, sorted(set(pick)))
+    _attention_sample(oracle, batch, sorted(set(pick + list(range(5, 1024, 32)))))
     del batch
     torch.cuda.empty_cache()
     batch = synth.make_batch(wl, device="cuda", with_attention=False)

@@ -9,7 +9,7 @@ import pytest
 import torch
 from scipy import stats
 
-from helpers import compare_sampler, gpu_sample, oracle_sample, sampler_split
+from helpers import compare_sampler, flag_bound, gpu_sample, oracle_sample, sampler_split
 from paper_2510_26475_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -29,7 +29,10 @@ def _parity(oracle, batch, **kw):
     gpu = gpu_sample(batch, **kw)
     ref = oracle_sample(oracle, batch, **kw)
     tally = compare_sampler(gpu, ref)
-    assert tally["flagged"] <= max(3, 0.2 * tally["B"]), tally
+    # boundary draws: no more than the recipe's logits make likely (mean + 4 sd, see flag_bound)
+    assert tally["flagged"] <= flag_bound(tally["B"], batch.wl.V), tally
+    print(f"{batch.wl.name}: B={tally['B']} flagged by the oracle {tally['flagged']}, by the GPU "
+          f"{tally['gpu_flagged']}, flagged sequences that differ {tally['flagged_mismatch']}")
     return gpu, ref, tally
 
 
@@ -54,7 +57,9 @@ def test_small_vocab_sizes_and_ragged_tails(oracle, dtype, V):
 def test_full_vocab_bf16(oracle, sigma):
     wl = _wl("full_bf16", 151936, "bf16", sigma=sigma)
     gpu, ref, tally = _parity(oracle, _batch(wl, [3] * 24 + [4] * 8, seed=int(10 * sigma)))
-    assert tally["flagged_mismatch"] <= tally["flagged"]
+    # a flagged draw sits within 1e-6 (relative) of a decision boundary and the HIP path's sums
+    # carry a few 1e-7: at most about half of the flagged draws may come out on the other side
+    assert tally["flagged_mismatch"] <= max(1, (tally["flagged"] + 1) // 2), tally
 
 
 def test_full_vocab_f32_with_temperature(oracle):
