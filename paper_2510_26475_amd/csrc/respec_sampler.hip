@@ -186,7 +186,7 @@ __device__ inline void row_stats_any(const void *rowp, const void *rowq, int nsl
 // fp64 weights of one slot: p(x) (RESID = false) or max(0, p(x) - q(x)) (Eq. 2).
 template <bool BF16, bool RESID>
 __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, double Cp, float Mq,
-                                    double Cq, const SamplerParams &p,
+                                    double Cq, const RowMath &p,
                                     double (&w)[Elem<BF16>::EPV]) {
     constexpr int EPV = Elem<BF16>::EPV;
     float zp[EPV], zq[EPV];
@@ -237,26 +237,49 @@ __device__ inline float slot_weights_f32(const u32x4 &vp, const u32x4 &vq, const
 
 // The single final draw of a sequence: first token, in ascending id, whose running sum of
 // weights exceeds u*Z (all sums in fp64).
-//   phase A  each wave owns a contiguous eighth of the row and streams it with coalesced loads;
-//            lanes keep their own fp64 sums, one reduction per wave gives the region total;
-//   choice   every thread takes the ordered prefix over the region totals and finds the
-//            region that holds the crossing;
+//   phase A  (draw_region_totals) each wave owns a contiguous eighth of the part at hand and
+//            streams it with coalesced loads; lanes keep their own fp64 sums, one reduction per
+//            wave gives the region total;
+//   choice   every thread takes the ordered prefix over the region totals of the whole row and
+//            finds the region that holds the crossing;
 //   phase B  the whole block re-reads that one region, each thread a short contiguous run of
 //            slots: thread totals -> one block scan -> the first thread whose running sum
 //            passes u*Z walks its run element by element.
 // Phase B adds the same numbers in another order than phase A, so at the last bit a crossing
 // can fall off the end of the region; that draw then takes the last token with mass and is
 // flagged as a boundary draw (it is within rounding of a CDF edge).
-template <bool BF16, bool RESID, bool FULL, bool SHARED, bool FAST = false>
-__device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int nslots, int Vrow, int tok_off,
-                                       float Mp, double Sp, float Mq, double Sq, double u, SharedState &sh,
-                                       Mailbox &mb, const SamplerParams &p, int &near_edge, double &Z_out,
-                                       bool &mine, float *tab = nullptr) {
+
+// One contiguous part of a row (pair) as a block sees it: pointers at the part's first slot.
+struct RowPart {
+    const void *rowp;
+    const void *rowq;
+    int nslots;   // slots of the part
+    int Vrow;     // elements from the part's first slot to the end of the row
+    int tok_off;  // token id of the part's first element
+    float *tab;   // LDS room for one float per slot of the part (fp32 form of the weights), or NULL
+};
+
+// The exponent constants of the weights of one row pair.
+struct DrawNorm {
+    float Mp, Mq;
+    double Sp, Sq;
+};
+
+// Phase A over one part: leaves the eight region totals in sh.wave_total (no barrier), and with
+// a table every slot's total in part.tab.
+template <bool BF16, bool RESID, bool FULL, bool FAST>
+__device__ inline void draw_region_totals(const RowPart &part, const DrawNorm &nm, SharedState &sh,
+                                          const RowMath &p) {
     constexpr int EPV = Elem<BF16>::EPV;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool aligned = p.aligned != 0;
-    // FAST with a table: LDS room for one float per slot of the row.  Phase A leaves every slot's
-    // total there, and phase B works from the table instead of reading the region again.
+    const void *rowp = part.rowp, *rowq = part.rowq;
+    const int nslots = part.nslots, Vrow = part.Vrow;
+    float *tab = part.tab;
+    const float Mp = nm.Mp, Mq = nm.Mq;
+    const double Sp = nm.Sp, Sq = nm.Sq;
+    // FAST with a table: phase A leaves every slot's total there, and phase B works from the
+    // table instead of reading the region again.
     const bool use_tab = FAST && tab != nullptr;  // block-uniform
     const double Cp = 1.0 / Sp, Cq = RESID ? 1.0 / Sq : 0.0;
     const FastNorm fn = make_fast_norm(Mp, Sp, Mq, RESID ? Sq : Sp, p);
@@ -323,29 +346,30 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     }
     const double region_total = wave_sum(lane_sum);
     if (lane == 0) sh.wave_total[wave] = region_total;
+}
+
+// Choice and phase B.  `totals` are the n_reg region totals of the whole row in vocabulary order
+// (LDS); the regions [my_reg0, my_reg0 + n_parts * kWaves) are this block's, eight per part of
+// `parts`.  Returns the token, or -1 with mine = false when another block holds the crossing, or
+// -1 with Z_out <= 0 when the row carries no mass.  Ends with a barrier.
+template <bool BF16, bool RESID, bool FULL, bool FAST, bool KEEP_SLOTS>
+__device__ inline int draw_finish(const double *totals, int n_reg, int my_reg0, const RowPart (&parts)[2], int n_parts,
+                                  const DrawNorm &nm, double u, SharedState &sh, const RowMath &p, int &near_edge,
+                                  double &Z_out, bool &mine) {
+    constexpr int EPV = Elem<BF16>::EPV;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool aligned = p.aligned != 0;
+    const float Mp = nm.Mp, Mq = nm.Mq;
+    const double Sp = nm.Sp, Sq = nm.Sq;
+    const double Cp = 1.0 / Sp, Cq = RESID ? 1.0 / Sq : 0.0;
+    const FastNorm fn = make_fast_norm(Mp, Sp, Mq, RESID ? Sq : Sp, p);
     if (threadIdx.x == 0) {
         sh.token = -1;
         sh.near_edge = 0;
         sh.first_thread = kThreads;
         sh.last_positive = -1;
     }
-    __syncthreads();
-
-    // the region totals of all parts, in vocabulary order
-    const int n_reg = SHARED ? mb.split * kWaves : kWaves;
-    if constexpr (!SHARED) {
-        // (one part: the wave totals are the region totals)
-    } else {
-        double pub[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) pub[w] = sh.wave_total[w];
-        exchange(mb, pub, sh);
-        if ((int)threadIdx.x < n_reg) sh.all_total[threadIdx.x] = sh.xchg[threadIdx.x / kWaves][threadIdx.x % kWaves];
-        __syncthreads();
-    }
-
     // every thread: ordered prefix over the regions, find the region holding the crossing
-    const double *totals = SHARED ? sh.all_total : sh.wave_total;
     double Z = 0.0;
     for (int w = 0; w < n_reg; ++w) Z += totals[w];
     Z_out = Z;
@@ -370,14 +394,18 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     }
     const bool forced = rstar < 0;  // u*Z rounded up to Z: take the last token with mass
     if (forced) rstar = rlast;
-    if constexpr (SHARED) {
-        __syncthreads();  // all_total and xchg may be rewritten from here on
-        if (rstar / kWaves != mb.part) {  // another part holds the crossing and finishes the draw
-            near_edge = 0;
-            return -1;
-        }
+    __syncthreads();  // the totals may be rewritten from here on; sh.token and friends are set
+    if (rstar < my_reg0 || rstar >= my_reg0 + n_parts * kWaves) {  // another block finishes the draw
+        near_edge = 0;
+        return -1;
     }
     mine = true;
+    const RowPart &part = parts[(rstar - my_reg0) / kWaves];  // block-uniform
+    const void *rowp = part.rowp, *rowq = part.rowq;
+    const int nslots = part.nslots, Vrow = part.Vrow, tok_off = part.tok_off;
+    float *tab = part.tab;
+    const bool use_tab = FAST && tab != nullptr;  // block-uniform
+    const int span = ((nslots + kWaves - 1) / kWaves + 63) / 64 * 64;
     const int wstar = rstar % kWaves;
 
     // phase B: the block walks region wstar; thread i owns slots [rb + i*per, rb + (i+1)*per)
@@ -483,8 +511,8 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         }
     };
     // the totals of the slots of the first chunk are kept for the walk, and (when the registers
-    // allow: one work-group per sequence) so are the slots themselves
-    constexpr bool kKeepSlots = !SHARED;
+    // allow: not in the form that several work-groups share) so are the slots themselves
+    constexpr bool kKeepSlots = KEEP_SLOTS;
     double slot_total[kChunk];
     u32x4 keep_p[kKeepSlots ? kChunk : 1], keep_q[kKeepSlots ? kChunk : 1];
 #pragma unroll
@@ -604,6 +632,33 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
     }
     __syncthreads();
     return tok;
+}
+
+// The draw of a block that sees one part of the row: its own share of a sequence that several
+// work-groups walk together (SHARED: the region totals are exchanged, and the block that holds
+// the crossing finishes), or the whole row.
+template <bool BF16, bool RESID, bool FULL, bool SHARED, bool FAST = false>
+__device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int nslots, int Vrow, int tok_off,
+                                       float Mp, double Sp, float Mq, double Sq, double u, SharedState &sh,
+                                       Mailbox &mb, const SamplerParams &p, int &near_edge, double &Z_out,
+                                       bool &mine, float *tab = nullptr) {
+    const RowPart parts[2] = {{rowp, rowq, nslots, Vrow, tok_off, tab}, {rowp, rowq, 0, Vrow, tok_off, nullptr}};
+    const DrawNorm nm{Mp, Mq, Sp, Sq};
+    draw_region_totals<BF16, RESID, FULL, FAST>(parts[0], nm, sh, p);
+    __syncthreads();
+    // the region totals of all parts, in vocabulary order
+    const int n_reg = SHARED ? mb.split * kWaves : kWaves;
+    if constexpr (SHARED) {
+        double pub[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) pub[w] = sh.wave_total[w];
+        exchange(mb, pub, sh);
+        if ((int)threadIdx.x < n_reg) sh.all_total[threadIdx.x] = sh.xchg[threadIdx.x / kWaves][threadIdx.x % kWaves];
+        __syncthreads();
+    }
+    const double *totals = SHARED ? sh.all_total : sh.wave_total;
+    return draw_finish<BF16, RESID, FULL, FAST, !SHARED>(totals, n_reg, SHARED ? mb.part * kWaves : 0, parts, 1, nm, u,
+                                                         sh, p, near_edge, Z_out, mine);
 }
 
 // ------------------------------------------------------------------------------------------
