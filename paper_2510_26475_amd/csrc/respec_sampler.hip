@@ -431,8 +431,7 @@ __device__ inline int draw_finish(const double *totals, int n_reg, int my_reg0, 
                 if (w < wave) before_wave += sh.scan_total[w];
             const double run_incl = base + (before_wave + incl_wave);
             const double run_excl = base + (before_wave + (incl_wave - my_total));
-            if (!forced && run_incl > t && my_total > 0.0) atomicMin(&sh.first_thread, (int)threadIdx.x);
-            if (my_last_slot >= 0) atomicMax(&sh.last_positive, my_last_slot);
+            note_first_and_last(!forced && run_incl > t && my_total > 0.0, my_last_slot, &sh.first_thread, &sh.last_positive);
             __syncthreads();
             // one slot's elements, formed again from memory: the last of them with mass, and (if
             // walk) the first whose running sum passes t
@@ -557,8 +556,7 @@ __device__ inline int draw_finish(const double *totals, int n_reg, int my_reg0, 
         if (w < wave) before_wave += sh.scan_total[w];
     const double run_incl = base + (before_wave + incl_wave);
     const double run_excl = base + (before_wave + (incl_wave - my_total));
-    if (!forced && run_incl > t && my_total > 0.0) atomicMin(&sh.first_thread, (int)threadIdx.x);
-    if (my_last >= 0) atomicMax(&sh.last_positive, my_last);
+    note_first_and_last(!forced && run_incl > t && my_total > 0.0, my_last, &sh.first_thread, &sh.last_positive);
     __syncthreads();
     if ((int)threadIdx.x == sh.first_thread) {  // at most one thread
         double c = run_excl;

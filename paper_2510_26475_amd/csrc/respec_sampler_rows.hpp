@@ -197,6 +197,21 @@ __device__ inline double wave_inclusive_scan(double x, int lane) {
     return x;
 }
 
+// The block-wide "first thread for which `hit` holds" and "largest `last` (a value that grows
+// with the thread index, -1 = none)" of the draw's walk, left in sh_first / sh_last (preset to
+// kThreads / -1): one ballot per wave and one LDS atomic per wave.  (An atomic from every thread
+// on one LDS word is served one lane at a time: 512 of them took 4 us of every draw.)
+__device__ inline void note_first_and_last(bool hit, int last, int *sh_first, int *sh_last) {
+    const int lane = threadIdx.x & 63;
+    const unsigned long long hits = __ballot(hit), have = __ballot(last >= 0);
+    if (hits != 0ull && lane == 0) atomicMin(sh_first, (int)(threadIdx.x & ~63u) + __builtin_ctzll(hits));
+    if (have != 0ull) {
+        const int top = 63 - __builtin_clzll(have);  // wave-uniform: the values grow with the lane
+        const int v = __builtin_amdgcn_readlane(last, top);
+        if (lane == 0) atomicMax(sh_last, v);
+    }
+}
+
 struct SharedState {
     float m[2][2][kWaves];   // [parity][row p/q][wave]
     double s[2][2][kWaves];

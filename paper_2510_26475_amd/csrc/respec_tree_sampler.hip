@@ -315,8 +315,7 @@ __device__ inline int tree_draw(const void *rowp, const void *rowq, int nslots, 
         if (w < wave) before_wave += sh.scan_total[w];
     const double run_incl = base + (before_wave + incl_wave);
     const double run_excl = base + (before_wave + (incl_wave - my_total));
-    if (!forced && run_incl > t && my_total > 0.0) atomicMin(&sh.first_thread, (int)threadIdx.x);
-    if (my_last >= 0) atomicMax(&sh.last_positive, my_last);
+    note_first_and_last(!forced && run_incl > t && my_total > 0.0, my_last, &sh.first_thread, &sh.last_positive);
     __syncthreads();
     if ((int)threadIdx.x == sh.first_thread) {  // at most one thread
         double c = run_excl;
