@@ -271,7 +271,7 @@ template <bool BF16, bool RESID, bool FULL, bool FAST>
 __device__ inline void draw_region_totals(const RowPart &part, const DrawNorm &nm, SharedState &sh,
                                           const RowMath &p) {
     constexpr int EPV = Elem<BF16>::EPV;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = opaque_thread_index() & 63, wave = threadIdx.x >> 6;
     const bool aligned = p.aligned != 0;
     const void *rowp = part.rowp, *rowq = part.rowq;
     const int nslots = part.nslots, Vrow = part.Vrow;
@@ -349,15 +349,15 @@ __device__ inline void draw_region_totals(const RowPart &part, const DrawNorm &n
 }
 
 // Choice and phase B.  `totals` are the n_reg region totals of the whole row in vocabulary order
-// (LDS); the regions [my_reg0, my_reg0 + n_parts * kWaves) are this block's, eight per part of
-// `parts`.  Returns the token, or -1 with mine = false when another block holds the crossing, or
+// (LDS); the regions [my_reg0, my_reg0 + kWaves) are those of `part`, this block's part of the
+// row.  Returns the token, or -1 with mine = false when another block holds the crossing, or
 // -1 with Z_out <= 0 when the row carries no mass.  Ends with a barrier.
 template <bool BF16, bool RESID, bool FULL, bool FAST, bool KEEP_SLOTS>
-__device__ inline int draw_finish(const double *totals, int n_reg, int my_reg0, const RowPart (&parts)[2], int n_parts,
+__device__ inline int draw_finish(const double *totals, int n_reg, int my_reg0, const RowPart &part,
                                   const DrawNorm &nm, double u, SharedState &sh, const RowMath &p, int &near_edge,
                                   double &Z_out, bool &mine) {
     constexpr int EPV = Elem<BF16>::EPV;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = opaque_thread_index() & 63, wave = threadIdx.x >> 6;
     const bool aligned = p.aligned != 0;
     const float Mp = nm.Mp, Mq = nm.Mq;
     const double Sp = nm.Sp, Sq = nm.Sq;
@@ -395,12 +395,11 @@ __device__ inline int draw_finish(const double *totals, int n_reg, int my_reg0, 
     const bool forced = rstar < 0;  // u*Z rounded up to Z: take the last token with mass
     if (forced) rstar = rlast;
     __syncthreads();  // the totals may be rewritten from here on; sh.token and friends are set
-    if (rstar < my_reg0 || rstar >= my_reg0 + n_parts * kWaves) {  // another block finishes the draw
+    if (rstar < my_reg0 || rstar >= my_reg0 + kWaves) {  // another block finishes the draw
         near_edge = 0;
         return -1;
     }
     mine = true;
-    const RowPart &part = parts[(rstar - my_reg0) / kWaves];  // block-uniform
     const void *rowp = part.rowp, *rowq = part.rowq;
     const int nslots = part.nslots, Vrow = part.Vrow, tok_off = part.tok_off;
     float *tab = part.tab;
@@ -640,9 +639,9 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
                                        float Mp, double Sp, float Mq, double Sq, double u, SharedState &sh,
                                        Mailbox &mb, const SamplerParams &p, int &near_edge, double &Z_out,
                                        bool &mine, float *tab = nullptr) {
-    const RowPart parts[2] = {{rowp, rowq, nslots, Vrow, tok_off, tab}, {rowp, rowq, 0, Vrow, tok_off, nullptr}};
+    const RowPart part{rowp, rowq, nslots, Vrow, tok_off, tab};
     const DrawNorm nm{Mp, Mq, Sp, Sq};
-    draw_region_totals<BF16, RESID, FULL, FAST>(parts[0], nm, sh, p);
+    draw_region_totals<BF16, RESID, FULL, FAST>(part, nm, sh, p);
     __syncthreads();
     // the region totals of all parts, in vocabulary order
     const int n_reg = SHARED ? mb.split * kWaves : kWaves;
@@ -655,8 +654,8 @@ __device__ inline int inverse_cdf_pass(const void *rowp, const void *rowq, int n
         __syncthreads();
     }
     const double *totals = SHARED ? sh.all_total : sh.wave_total;
-    return draw_finish<BF16, RESID, FULL, FAST, !SHARED>(totals, n_reg, SHARED ? mb.part * kWaves : 0, parts, 1, nm, u,
-                                                         sh, p, near_edge, Z_out, mine);
+    return draw_finish<BF16, RESID, FULL, FAST, !SHARED>(totals, n_reg, SHARED ? mb.part * kWaves : 0, part, nm, u, sh,
+                                                         p, near_edge, Z_out, mine);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -683,7 +682,7 @@ template <bool BF16, bool FULL>
 __device__ inline int row_argmax(const void *row, int nslots, int V, bool aligned, SharedState &sh) {
     constexpr int EPV = Elem<BF16>::EPV;
     constexpr int kBatch = kThreads * kUnroll;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = opaque_thread_index() & 63, wave = threadIdx.x >> 6;
     const int n_iter = (nslots + kBatch - 1) / kBatch;
     // loads are clamped to the row and carry no select (a select right behind a load makes the
     // loads of a batch wait for one another); slots past the row are skipped when compared

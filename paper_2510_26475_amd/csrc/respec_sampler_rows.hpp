@@ -212,6 +212,16 @@ __device__ inline void note_first_and_last(bool hit, int last, int *sh_first, in
     }
 }
 
+// The thread's index (or lane) as a value the compiler cannot trace back to threadIdx: per-lane
+// offsets formed from it are formed in the pass that uses them instead of being kept in
+// registers across every pass of a long kernel (which cost the tree sampler and the general
+// forms of the chain sampler up to 60 spilled registers).
+__device__ inline int opaque_thread_index() {
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
 struct SharedState {
     float m[2][2][kWaves];   // [parity][row p/q][wave]
     double s[2][2][kWaves];
@@ -292,6 +302,7 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
                                       double &Sp, float &Mq, double &Sq) {
     constexpr int EPV = Elem<BF16>::EPV;
     constexpr int kBatch = kThreads * kUnroll;  // slots per block iteration
+    const int tid = opaque_thread_index();
     float accp[EPV], accq[EPV];
 #pragma unroll
     for (int j = 0; j < EPV; ++j) accp[j] = accq[j] = 0.f;
@@ -302,7 +313,7 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
     // past the row are replaced by -inf when the batch is consumed (mask_last), not here: a
     // select right behind each load makes the loads wait for one another.
     auto load_batch = [&](int it, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) __attribute__((always_inline)) {
-        const int s0 = it * kBatch + threadIdx.x;
+        const int s0 = it * kBatch + tid;
         if (it + 1 < n_iter) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -319,7 +330,7 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
         }
     };
     auto mask_last = [&](u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) __attribute__((always_inline)) {
-        const int s0 = (n_iter - 1) * kBatch + threadIdx.x;
+        const int s0 = (n_iter - 1) * kBatch + tid;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const bool in = s0 + u * kThreads < nslots;
@@ -407,7 +418,7 @@ __device__ inline void row_stats(const void *rowp, const void *rowq, int nslots,
     tp.init();
     tq.init();
     const bool aligned = p.aligned != 0;
-    for (int s0 = threadIdx.x; s0 < nslots; s0 += kThreads * kUnroll) {
+    for (int s0 = opaque_thread_index(); s0 < nslots; s0 += kThreads * kUnroll) {
         u32x4 vp[kUnroll], vq[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {

@@ -150,7 +150,7 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
                                             double Sp, float Mq, double Sq, const Depth &d, SharedState &sh,
                                             const RowMath &p) {
     constexpr int EPV = Elem<BF16>::EPV;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = opaque_thread_index() & 63, wave = threadIdx.x >> 6;
     const bool aligned = p.aligned != 0;
     const bool two = d.depth > 0;
     const double Cp = 1.0 / Sp, Cq = two ? 1.0 / Sq : 0.0;
@@ -226,7 +226,7 @@ __device__ inline int tree_draw(const void *rowp, const void *rowq, int nslots, 
                                 float Mq, double Sq, const Depth &d, double u, SharedState &sh,
                                 const RowMath &p, int &near_edge) {
     constexpr int EPV = Elem<BF16>::EPV;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = opaque_thread_index() & 63, wave = threadIdx.x >> 6;
     const bool aligned = p.aligned != 0;
     const bool two = d.depth > 0;
     const double Cp = 1.0 / Sp, Cq = two ? 1.0 / Sq : 0.0;
@@ -410,9 +410,10 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
     const size_t esz = BF16 ? 2 : 4;
     const char *tbase = static_cast<const char *>(p.target);
     const char *dbase = static_cast<const char *>(p.draft);
-    int32_t *out = p.out_tokens + (size_t)b * (p.max_depth + 1);
-    int32_t *path = p.out_path + (size_t)b * max(p.max_depth, 1);
-    const double u_fin = (double)p.u_final[b];
+    // (the output rows are addressed where they are written and the final uniform is loaded where
+    // it is used: values that live across the streaming passes cost registers there)
+    auto out_row = [&]() { return p.out_tokens + (size_t)b * (p.max_depth + 1); };
+    auto path_row = [&]() { return p.out_path + (size_t)b * max(p.max_depth, 1); };
     if (threadIdx.x < kMaxTreeRows) {
         sh_parent[threadIdx.x] = (int)threadIdx.x < R ? p.parent[row0 + threadIdx.x] : -2;
         sh_inv_z[threadIdx.x] = 1.0;
@@ -440,7 +441,7 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
             const double Z = tree_region_totals<BF16, FULL, ONE_TERM>(rowp, rowp, nslots, p.V, M, S, M, S, d0, sh, p);
             if (Z > 0.0) {
                 int edge = 0;
-                final_token = tree_draw<BF16, FULL, ONE_TERM>(rowp, rowp, nslots, p.V, M, S, M, S, d0, u_fin, sh, p, edge);
+                final_token = tree_draw<BF16, FULL, ONE_TERM>(rowp, rowp, nslots, p.V, M, S, M, S, d0, (double)p.u_final[b], sh, p, edge);
                 flag_cdf |= edge;
             } else {  // row without any finite logit: report the last token
                 final_token = p.V - 1;
@@ -488,8 +489,8 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
             if (fabs(u - thr) <= kBoundaryEps) flag_accept = 1;
             if (u < thr) {  // accepted: the child becomes the node
                 if (threadIdx.x == 0) {
-                    out[n] = x;
-                    path[n] = c;
+                    out_row()[n] = x;
+                    path_row()[n] = c;
                 }
                 n += 1;
                 cur = c;
@@ -522,7 +523,7 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
             Zd = tree_region_totals<BF16, FULL, ONE_TERM>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, sh, p);
         if (Zd > 0.0) {
             int edge = 0;
-            final_token = tree_draw<BF16, FULL, ONE_TERM>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, u_fin, sh, p, edge);
+            final_token = tree_draw<BF16, FULL, ONE_TERM>(rowp, rowq, nslots, p.V, Mp, Sp, Mq, Sq, d, (double)p.u_final[b], sh, p, edge);
             flag_cdf |= edge;
         } else {
             final_token = p.V - 1;
@@ -531,6 +532,7 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
         break;
     }
     if (threadIdx.x == 0) {
+        int32_t *out = out_row(), *path = path_row();
         out[n] = final_token;
         for (int j = n + 1; j <= p.max_depth; ++j) out[j] = -1;
         for (int j = n; j < p.max_depth; ++j) path[j] = -1;

@@ -1,10 +1,10 @@
 """Register budget of the kernels the headline workload runs (host-side check, no GPU).
 
-The attention main kernel and the chain sampler are tuned to fit the 256 vector registers a wave
-gets at one 512-thread work-group per compute unit.  A spill in them costs more than its
+The attention main kernel, the samplers and the distillation row kernel are tuned to fit the 256
+vector registers a wave gets at one 512-thread work-group per compute unit.  A spill in them costs more than its
 instructions: a scratch reload is a vector memory operation and waits for every store issued
 before it.  hipcc reports registers and scratch per kernel (-Rpass-analysis=kernel-resource-usage);
-this test compiles the two sources for the device only and reads that report.
+this test compiles the sources for the device only and reads that report.
 """
 import os
 import re
@@ -24,6 +24,9 @@ NO_SCRATCH = [
     ("respec_attention.hip", "attn_bf16_kernelILi128ELi2EtLi4E", "attention, D=128, four consumers per range"),
     ("respec_attention.hip", "attn_bf16_kernelILi128ELi1EtLi4E", "attention, D=128, four consumers, narrow block"),
     ("respec_sampler.hip", "rejection_sample_kernelILb1ELb1ELb1ELb0E", "chain sampler, bf16, one work-group per sequence"),
+    ("respec_sampler.hip", "rejection_sample_kernelILb1ELb1ELb1ELb1E", "chain sampler, bf16, sequences shared by several work-groups"),
+    ("respec_tree_sampler.hip", "tree_rejection_sample_kernelILb1ELb1ELb1E", "tree sampler, bf16, temperature 1"),
+    ("respec_kd.hip", "kd_stream_kernelILb1E", "distillation rows, bf16"),
 ]
 
 
