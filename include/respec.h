@@ -254,13 +254,24 @@ respec_status_t respec_commit_accepted_paged(void *k_pages, void *v_pages, const
                                              int32_t D, respec_dtype_t dt, void *hip_stream);
 
 /*
- * Profiling hook (benchmarks only).  The calling thread's next respec_verify_attention
- * records `before_main` (if non-NULL) on the call's stream right before its main kernel
- * (after the small set-up kernel) and `after_main` (if non-NULL) right after it, before
- * the combine kernel; then it forgets both.  Both are hipEvent_t passed as void*.  This
- * is the only state the library keeps, and it is thread-local.
+ * Profiling hook (benchmarks only; not for production callers).  One-shot: the calling
+ * thread's NEXT attention call (any of the respec_verify_attention* entry points) records
+ * `before_main` (if non-NULL) on that call's stream right before its main kernel and
+ * `after_main` (if non-NULL) right after it, before the combine kernel; then both are
+ * forgotten.  Both are hipEvent_t passed as void*.  Pass NULL, NULL to disarm a hook that was
+ * set and not used.  Do not arm it in front of a call that is being captured into a HIP graph.
+ * Apart from the knobs below this is the only state the library keeps between calls; it is
+ * thread-local.
  */
 void respec_profile_mark_main(void *before_main, void *after_main);
+
+/*
+ * Test and tuning hook.  The library reads its RESPEC_* environment knobs (forced split
+ * widths and kernel forms, used by the tests and by sweeps; none is needed in production)
+ * once, at its first call.  A process that changes those variables afterwards calls this to
+ * have them read again.  Not thread-safe against calls in flight on other threads.
+ */
+void respec_reload_knobs(void);
 
 /*
  * Bytes of the optional workspace of respec_rejection_sample.  With a workspace a sequence
@@ -271,6 +282,16 @@ void respec_profile_mark_main(void *before_main, void *after_main);
  * (any B up to the one it was sized for), so it is allocated and cleared once.  Calls that
  * share a workspace must not overlap.  NULL may be passed: one work-group then walks each
  * sequence and nothing else changes.
+ *
+ * The work-groups that share a sequence wait for one another, so they must all be on the
+ * device at the same time: the library never launches more of them than the device has
+ * compute units, and the call should have the device to itself (a kernel of another stream
+ * that occupies compute units for long can make a wait run out).  A wait that runs out is
+ * bounded and reported (out_num_accepted[b] = -1, see respec_rejection_sample); the mailbox
+ * of that sequence is then marked unusable and every later call reports -1 for the sequence
+ * in that slot until the caller has set the workspace to zero again.  The marks that tell one
+ * call's words from another's are 32 bits wide with ten bits for the stage within a call:
+ * zero the workspace again before 2^22 (about four million) calls have used it.
  */
 size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t total_q, int32_t V,
                                                respec_dtype_t logits_dt);
@@ -306,8 +327,10 @@ size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t total_q, int32
  *   temperature   T > 0, applied to target and drafter logits alike
  *   workspace     NULL, or respec_rejection_sample_workspace_bytes bytes (see there)
  * Errors: RESPEC_ERR_INVALID_ARG / RESPEC_ERR_WORKSPACE before any launch.  If work-groups
- * that share a sequence ever lose each other (a bounded wait runs out: a device fault or a
- * workspace that was not zero at first use), out_num_accepted[b] of that sequence is -1.
+ * that share a sequence ever lose each other (a bounded wait runs out: a device fault, a
+ * workspace that was not zero at first use, or compute units held by another stream's kernel),
+ * out_num_accepted[b] of that sequence is -1 and the workspace has to be zeroed again before
+ * its next use (see respec_rejection_sample_workspace_bytes).
  */
 respec_status_t respec_rejection_sample(const void *target_logits, const void *draft_logits,
                                         const int32_t *draft_tokens, const int32_t *q_indptr,

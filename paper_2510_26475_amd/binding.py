@@ -74,6 +74,8 @@ def load():
         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
         c.c_int32, c.c_int32, c.c_int64, c.c_int32, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
         c.c_float, c.c_int, c.c_void_p]
+    lib.respec_reload_knobs.restype = None
+    lib.respec_reload_knobs.argtypes = []
     lib.respec_profile_mark_main.restype = None
     lib.respec_profile_mark_main.argtypes = [c.c_void_p, c.c_void_p]
     lib.respec_rejection_sample_workspace_bytes.restype = c.c_size_t
@@ -142,6 +144,7 @@ EXPORTED_SYMBOLS = [
     "respec_validate_batch_workspace_bytes", "respec_validate_batch",
     "respec_profile_mark_main",
     "respec_static_scratch_bytes", "respec_static_scratch_init", "respec_verify_attention_static",
+    "respec_reload_knobs",
 ]
 
 
@@ -173,6 +176,11 @@ def _dev_ptr(t: Optional[torch.Tensor], name: str):
 def _stream_ptr(stream: Optional[torch.cuda.Stream]):
     s = torch.cuda.current_stream() if stream is None else stream
     return ctypes.c_void_p(s.cuda_stream)
+
+
+def respec_reload_knobs():
+    """Have the library read its RESPEC_* environment knobs again (tests and sweeps)."""
+    load().respec_reload_knobs()
 
 
 def respec_version() -> int:

@@ -1550,7 +1550,8 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
 
     // more than 64 columns (draft trees): blocks of 128 columns, four consumers per range, so
     // that K and V are read once per 128 columns (RESPEC_ATTN_QUAD = 0: blocks of 64 as below)
-    const long quad_env = env_long("RESPEC_ATTN_QUAD", 1);
+    const Knobs kn = knobs();
+    const long quad_env = kn.get(&Knobs::attn_quad, 1);
     const bool quad = M > kMaxColsPerBlock && quad_env != 0;
     // Four consumers per range also serve 17 to 64 columns, 16 each, when the batch is so small
     // that a consumer's own range would hold only a few tiles: a quarter of the ranges means a
@@ -1573,26 +1574,26 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
     // RESPEC_ATTN_WIDE = 0 / 1 overrides the choice for any block of two or more tiles (tests,
     // comparisons; at two tiles the shared form halves the partials and the combine's work but
     // measured 4 us slower in the main kernel, 211 vs 206 us at B = 256 and the 7B shape).
-    const long wide = env_long("RESPEC_ATTN_WIDE", -1);
+    const long wide = kn.get(&Knobs::attn_wide, -1);
     const int cw = quad || quad_narrow ? 4 : (nt >= 2 && (wide < 0 ? (D == 128 && nt == 4) : wide != 0) ? 2 : 1);
     const int streams = kConsumers / cw;  // ranges per work-group
     // the split width: one range per consumer (or pair of consumers) of the device
     // (RESPEC_ATTN_WGS overrides it, for tests and sweeps)
-    long W = env_long("RESPEC_ATTN_WGS", 0);
+    long W = kn.get(&Knobs::attn_wgs, 0);
     if (W <= 0) W = (long)streams * compute_units() / col_blocks;
     if (W < 1) W = 1;
     if (W > max_waves) W = max_waves;
     p.W = (int32_t)W;
     int hi = Hkv % 4 == 0 ? 4 : (Hkv % 2 == 0 ? 2 : 1);
     if (hi > streams) hi = streams;
-    if (W % hi != 0 || env_long("RESPEC_ATTN_HEAD_MAJOR", 0) != 0) hi = 1;
+    if (W % hi != 0 || kn.get(&Knobs::attn_head_major, 0) != 0) hi = 1;
     p.HI = hi;
 
     // the set-up depends on the index arrays and the sizes only: the layers of one forward share
     // it (reuse_plan: the workspace still holds what the set-up of an earlier call left there)
     // (small batches: the main kernel's work-groups build it in their prologue and leave it in
     // the workspace; large ones take a set-up kernel in front)
-    p.inline_setup = !reuse_plan && B <= kInlineSeqs && env_long("RESPEC_ATTN_INLINE", 1) != 0 ? 1 : 0;
+    p.inline_setup = !reuse_plan && B <= kInlineSeqs && kn.get(&Knobs::attn_inline, 1) != 0 ? 1 : 0;
     if (!reuse_plan && !p.inline_setup) {
         hipLaunchKernelGGL(attn_prep_kernel, dim3(1), dim3(1024), 0, stream, p);
         err = hipGetLastError();

@@ -3,6 +3,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 namespace respec {
 
@@ -20,12 +21,45 @@ respec_status_t fail(respec_status_t status, const char *fmt, ...) {
 
 void clear_error() { g_last_error[0] = '\0'; }
 
-long env_long(const char *name, long fallback) {
+namespace {
+
+long env_long(const char *name) {
     const char *s = std::getenv(name);
-    if (!s || !*s) return fallback;
+    if (!s || !*s) return Knobs::kUnset;
     char *end = nullptr;
     const long v = std::strtol(s, &end, 10);
-    return (end && *end == '\0') ? v : fallback;
+    return (end && *end == '\0') ? v : Knobs::kUnset;
+}
+
+std::mutex g_knob_mutex;
+bool g_knobs_read = false;
+Knobs g_knobs;
+
+void read_knobs_locked() {
+    g_knobs.attn_wgs = env_long("RESPEC_ATTN_WGS");
+    g_knobs.attn_head_major = env_long("RESPEC_ATTN_HEAD_MAJOR");
+    g_knobs.attn_wide = env_long("RESPEC_ATTN_WIDE");
+    g_knobs.attn_quad = env_long("RESPEC_ATTN_QUAD");
+    g_knobs.attn_inline = env_long("RESPEC_ATTN_INLINE");
+    g_knobs.sampler_split = env_long("RESPEC_SAMPLER_SPLIT");
+    g_knobs.sampler_two_term = env_long("RESPEC_SAMPLER_TWO_TERM");
+    g_knobs.sampler_guarded = env_long("RESPEC_SAMPLER_GUARDED");
+    g_knobs.sampler_no_table = env_long("RESPEC_SAMPLER_NO_TABLE");
+    g_knobs.kd_wgs = env_long("RESPEC_KD_WGS");
+    g_knobs_read = true;
+}
+
+}  // namespace
+
+Knobs knobs() {
+    std::lock_guard<std::mutex> lock(g_knob_mutex);
+    if (!g_knobs_read) read_knobs_locked();
+    return g_knobs;
+}
+
+void reload_knobs() {
+    std::lock_guard<std::mutex> lock(g_knob_mutex);
+    read_knobs_locked();
 }
 
 }  // namespace respec
@@ -45,6 +79,8 @@ const char *respec_status_string(respec_status_t status) {
 
 const char *respec_last_error(void) { return respec::g_last_error; }
 
-int respec_version(void) { return 100; /* 0.1.0 */ }
+int respec_version(void) { return 200; /* 0.2.0 */ }
+
+void respec_reload_knobs(void) { respec::reload_knobs(); }
 
 }  // extern "C"

@@ -176,7 +176,7 @@ template <bool BF16>
 hipError_t launch_kd(KdParams &p, hipStream_t stream) {
     int cus = 256, dev = 0;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    long wgs = env_long("RESPEC_KD_WGS", (long)cus);  // tests and sweeps
+    long wgs = knobs().get(&Knobs::kd_wgs, (long)cus);  // tests and sweeps
     if (wgs > p.rows) wgs = p.rows;
     if (wgs < 1) wgs = 1;
     hipLaunchKernelGGL((kd_stream_kernel<BF16>), dim3((unsigned)wgs), dim3(kThreads), 0, stream, p);

@@ -842,7 +842,12 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     if constexpr (SHARED) {
         mb.words = reinterpret_cast<uint32_t *>(p.boxes + (size_t)b * kBoxBytes);
         mb.payload = reinterpret_cast<unsigned long long *>(p.boxes + (size_t)b * kBoxBytes + kBoxHeaderBytes);
-        if (threadIdx.x == 0) sh_epoch = load_dev(mb.words);
+        if (threadIdx.x == 0) {
+            sh_epoch = load_dev(mb.words);
+            // a box that an earlier call left poisoned (one of its waits ran out) cannot be trusted
+            // until the caller has zeroed it again: every part reports failure without waiting
+            if (sh_epoch == kBoxPoison) sh.failed = 1;
+        }
     }
     __syncthreads();
     if constexpr (SHARED) mb.base = sh_epoch * 1024u;
@@ -935,7 +940,15 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
             p.out_num_accepted[b] = -1;  // a wait for a partner ran out: make it impossible to miss
         }
         if constexpr (SHARED) {
-            if (part == 0) store_dev(mb.words, sh_epoch + 1u);
+            // Part 0 advances the epoch; a part whose wait ran out poisons the box instead (a
+            // partner that turns up later must not find an epoch it could publish under, and the
+            // next call must not trust what this one left).  Both are atomic maxima, so the
+            // poison wins whatever the order.
+            if (failed) {
+                __hip_atomic_fetch_max(mb.words, kBoxPoison, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            } else if (part == 0) {
+                __hip_atomic_fetch_max(mb.words, sh_epoch + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }
@@ -987,7 +1000,8 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
     p.V = V;
     p.ld_t = ld_t;
     p.ld_d = has_drafts ? ld_d : ld_t;
-    set_row_math(p, temps ? 1.0f : temperature);
+    const Knobs kn = knobs();
+    set_row_math(p, temps ? 1.0f : temperature, kn.get(&Knobs::sampler_two_term, 0) != 0);
     if (temps) p.one_term = 0;  // the per-sequence constants are formed on the device, two-term
     p.aligned = aligned_to(target_logits, 16) && (ld_t * esz) % 16 == 0 &&
                 (!has_drafts || !draft_logits || (aligned_to(draft_logits, 16) && (ld_d * esz) % 16 == 0));
@@ -1004,8 +1018,13 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
         const int epv0 = logits_dt == RESPEC_BF16 ? 8 : 4;
         const long slots_row = ((long)V + epv0 - 1) / epv0;
         while (split < kMaxSplit && (long)B * split * 2 <= cus && slots_row / (split * 2) >= 2048) split *= 2;
-        const long forced = env_long("RESPEC_SAMPLER_SPLIT", 0);
+        const long forced = kn.get(&Knobs::sampler_split, 0);
         if (forced == 1 || forced == 2 || forced == 4 || forced == 8) split = (int)forced;
+        // The parts of a sequence wait for one another, so all of them have to be on the device at
+        // once: never more work-groups than compute units, whatever the knob asks for.  And a
+        // pass's mark has ten bits for the stage: very long draft chains take one work-group.
+        while (split > 1 && (long)B * split > cus) split /= 2;
+        if (2 * ((long)max_k + 1) + 4 >= 1024) split = 1;
     }
     if ((int64_t)B * split > 0x7fffffffLL)
         return fail(RESPEC_ERR_UNSUPPORTED, "rejection_sample: too many work-groups");
@@ -1014,7 +1033,7 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int epv = logits_dt == RESPEC_BF16 ? 8 : 4;
-    const bool full = p.aligned && V % epv == 0 && env_long("RESPEC_SAMPLER_GUARDED", 0) == 0;
+    const bool full = p.aligned && V % epv == 0 && kn.get(&Knobs::sampler_guarded, 0) == 0;
     const bool bf = logits_dt == RESPEC_BF16, one = p.one_term != 0;
     // the final draw's table of slot totals (fp32 form, one work-group per sequence): one float
     // per 16-byte slot of a row in dynamic LDS, when that fits beside the static part
@@ -1022,7 +1041,7 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
     {
         const size_t slots_row = ((size_t)V + epv - 1) / epv;
         if (full && one && split == 1 && slots_row * sizeof(float) <= kTableMaxBytes &&
-            env_long("RESPEC_SAMPLER_NO_TABLE", 0) == 0) {
+            kn.get(&Knobs::sampler_no_table, 0) == 0) {
             smem = round_up(slots_row * sizeof(float), 16);
             p.tab_slots = (int)slots_row;
         }

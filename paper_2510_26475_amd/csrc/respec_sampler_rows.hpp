@@ -29,6 +29,7 @@ constexpr int kBoxHeaderBytes = 128;                      // epoch at word 0
 constexpr int kBoxPayload = kMaxSplit * 2 * 16;           // [part][stage parity][8 doubles as 16 tagged words]
 constexpr size_t kBoxBytes = kBoxHeaderBytes + (size_t)kBoxPayload * 8;
 constexpr int kSpinLimit = 1 << 22;
+constexpr uint32_t kBoxPoison = 0xffffffffu;             // epoch word of a box whose call failed
 constexpr size_t kTableMaxBytes = 96 * 1024;  // LDS a launch may add for the final draw's slot totals
 
 // The exponent constants of one call: exp((z - ref)/T) is taken as exp2((z - ref) * log2(e)/T).
@@ -42,7 +43,7 @@ struct RowMath {
     int aligned;       // every row starts 16-byte aligned
 };
 
-inline void set_row_math(RowMath &m, float temperature) {
+inline void set_row_math(RowMath &m, float temperature, bool force_two_term = false) {
     const double T = (double)temperature;
     m.c_d = 1.4426950408889634074 / T;
     float c_hi = (float)m.c_d;
@@ -51,7 +52,7 @@ inline void set_row_math(RowMath &m, float temperature) {
     m.c_lo = (float)(m.c_d - (double)c_hi);
     m.c_f = (float)m.c_d;
     m.one_term = std::fabs((double)m.c_f / m.c_d - 1.0) <= 2.0e-8 ? 1 : 0;
-    if (env_long("RESPEC_SAMPLER_TWO_TERM", 0) != 0) m.one_term = 0;
+    if (force_two_term) m.one_term = 0;
     m.inv_T = 1.0 / T;
     m.gap = (float)(40.0 / m.c_d);
 }

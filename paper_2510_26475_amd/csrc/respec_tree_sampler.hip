@@ -596,7 +596,7 @@ extern "C" respec_status_t respec_tree_rejection_sample(
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int epv = logits_dt == RESPEC_BF16 ? 8 : 4;
-    const bool full = p.aligned && V % epv == 0 && env_long("RESPEC_SAMPLER_GUARDED", 0) == 0;
+    const bool full = p.aligned && V % epv == 0 && knobs().get(&Knobs::sampler_guarded, 0) == 0;
     const bool bf = logits_dt == RESPEC_BF16, one = p.one_term != 0;
 #define RESPEC_LAUNCH_TREE(BF, ONE, FULL)                                                                       \
     hipLaunchKernelGGL((tree_rejection_sample_kernel<BF, ONE, FULL>), dim3((unsigned)B), dim3(kThreads), 0,    \

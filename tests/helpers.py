@@ -19,6 +19,7 @@ def env_setting(name, value):
         os.environ.pop(name, None)
     else:
         os.environ[name] = str(value)
+    binding.respec_reload_knobs()   # the library reads its environment once; tell it to look again
     try:
         yield
     finally:
@@ -26,25 +27,14 @@ def env_setting(name, value):
             os.environ.pop(name, None)
         else:
             os.environ[name] = old
+        binding.respec_reload_knobs()
 
 
-@contextmanager
 def attn_wgs(wgs):
     """Force the number of ranges the key tiles are split over (None = the default, four per
     compute unit).  Small counts put many sequences in one range, large counts cut every
     sequence into many partials."""
-    old = os.environ.get("RESPEC_ATTN_WGS")
-    if wgs is None:
-        os.environ.pop("RESPEC_ATTN_WGS", None)
-    else:
-        os.environ["RESPEC_ATTN_WGS"] = str(wgs)
-    try:
-        yield
-    finally:
-        if old is None:
-            os.environ.pop("RESPEC_ATTN_WGS", None)
-        else:
-            os.environ["RESPEC_ATTN_WGS"] = old
+    return env_setting("RESPEC_ATTN_WGS", wgs)
 
 
 def gpu_attention(batch: synth.VerifyBatch, sm_scale=None, want_lse=True, stream=None):
@@ -96,21 +86,9 @@ def sampler_workspace(B, V, dtype_code, device):
     return ws
 
 
-@contextmanager
 def sampler_split(split):
     """Force the number of work-groups that share a sequence (None: the library's choice)."""
-    old = os.environ.get("RESPEC_SAMPLER_SPLIT")
-    if split is None:
-        os.environ.pop("RESPEC_SAMPLER_SPLIT", None)
-    else:
-        os.environ["RESPEC_SAMPLER_SPLIT"] = str(split)
-    try:
-        yield
-    finally:
-        if old is None:
-            os.environ.pop("RESPEC_SAMPLER_SPLIT", None)
-        else:
-            os.environ["RESPEC_SAMPLER_SPLIT"] = old
+    return env_setting("RESPEC_SAMPLER_SPLIT", split)
 
 
 def gpu_sample(batch: synth.VerifyBatch, temperature=None, max_k=None, stream=None, workspace="shared"):

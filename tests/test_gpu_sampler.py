@@ -149,6 +149,43 @@ def test_shared_sequences_with_small_and_ragged_vocabularies(oracle, V):
             compare_sampler(gpu_sample(batch), ref)
 
 
+def test_a_mailbox_marked_unusable_reports_failure_until_it_is_zeroed(oracle):
+    """What a call whose wait ran out leaves behind, forced from the host: the epoch word of one
+    sequence's mailbox holds the poison value.  Every work-group of that sequence then reports
+    failure at once (no waiting), the other sequences are untouched, and a zeroed workspace works
+    again."""
+    wl = _wl("poisoned_box", 151936, "bf16")
+    ks = [3, 1, 0, 2, 3, 3]
+    batch = _batch(wl, ks, seed=41)
+    ref = oracle_sample(oracle, batch)
+    B, V = len(ks), 151936
+    ws = torch.zeros(binding.respec_rejection_sample_workspace_bytes(B, B, V, binding.RESPEC_BF16),
+                     dtype=torch.uint8, device="cuda")
+    box = ws.numel() // B
+    with sampler_split(4):
+        compare_sampler(gpu_sample(batch, workspace=ws), ref)            # a healthy call first
+        ws.view(torch.int32)[2 * box // 4] = -1                            # sequence 2's epoch word = 0xffffffff
+        toks, n, flags = gpu_sample(batch, workspace=ws)
+        assert n[2] == -1
+        keep = [b for b in range(B) if b != 2]
+        compare_sampler((toks[keep], n[keep], flags[keep]), tuple(r[keep] for r in ref))
+        toks, n, flags = gpu_sample(batch, workspace=ws)                   # it stays that way
+        assert n[2] == -1
+        ws.zero_()
+        compare_sampler(gpu_sample(batch, workspace=ws), ref)
+
+
+def test_a_forced_split_never_outgrows_the_device(oracle):
+    """All parts of a sequence wait for one another, so the library launches no more work-groups
+    than the device has compute units: a forced split of 8 on 96 sequences is cut down and the
+    results are what they always are."""
+    wl = _wl("clamped_split", 32768, "bf16")
+    batch = _batch(wl, [2, 3, 1, 0] * 24, seed=43)
+    ref = oracle_sample(oracle, batch)
+    with sampler_split(8):
+        compare_sampler(gpu_sample(batch), ref)
+
+
 def test_without_a_workspace_one_work_group_walks_a_sequence(oracle):
     wl = _wl("nows", 151936, "bf16")
     batch = _batch(wl, [3, 1, 0, 2], seed=33)
