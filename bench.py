@@ -482,9 +482,12 @@ def bench_verify(args, wl, dev, changed: bool, cpu_baseline: bool):
             "seed": wl.seed, "rotating_input_sets": args.rotate if (tree is None and paged is None) else 1,
         },
         "verify_step_us": ms_step * 1e3,
-        "kernel_us": {"attention_prep": ms_prep * 1e3, "attention_main": ms_main * 1e3, "attention_combine": ms_comb * 1e3,
+        "kernel_us": {"attention_before_main": ms_prep * 1e3, "attention_main": ms_main * 1e3, "attention_combine": ms_comb * 1e3,
                       "rejection_sample": ms_samp * 1e3, "commit_accepted": ms_commit * 1e3},
-        "kernel_us_note": "attention_main: HIP events around the launch on every %d-th step of the timed region; "
+        "kernel_us_note": "attention_before_main: from an event ahead of the call to the start of the main kernel "
+                          "(a launch gap; plus the set-up kernel for batches of more than 2048 sequences, whose "
+                          "split is not built in the main kernel's prologue); "
+                          "attention_main: HIP events around the launch on every %d-th step of the timed region; "
                           "the others (launch gaps included) and attention_main_instrumented_pass: a separate pass "
                           "of %d fully instrumented steps after it" % (probe, n_pass),
         "attention_main_instrumented_pass_us": ms_main_pass * 1e3,
