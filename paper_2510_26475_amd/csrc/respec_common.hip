@@ -45,6 +45,7 @@ void read_knobs_locked() {
     g_knobs.sampler_two_term = env_long("RESPEC_SAMPLER_TWO_TERM");
     g_knobs.sampler_guarded = env_long("RESPEC_SAMPLER_GUARDED");
     g_knobs.sampler_no_table = env_long("RESPEC_SAMPLER_NO_TABLE");
+    g_knobs.sampler_two_items = env_long("RESPEC_SAMPLER_TWO_ITEMS");
     g_knobs.kd_wgs = env_long("RESPEC_KD_WGS");
     g_knobs_read = true;
 }

@@ -37,6 +37,7 @@ struct Knobs {
     long sampler_two_term;  // RESPEC_SAMPLER_TWO_TERM: never the one-fma exponent
     long sampler_guarded;   // RESPEC_SAMPLER_GUARDED: the guarded normaliser pass everywhere
     long sampler_no_table;  // RESPEC_SAMPLER_NO_TABLE: the final draw without its table of slot totals
+    long sampler_two_items; // RESPEC_SAMPLER_TWO_ITEMS: 0/1 shared sequences walk one or two chain items per stage
     long kd_wgs;            // RESPEC_KD_WGS: work-groups of the distillation kernel
     long get(long Knobs::*field, long fallback) const { return this->*field == kUnset ? fallback : this->*field; }
 };

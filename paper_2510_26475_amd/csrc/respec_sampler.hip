@@ -45,6 +45,7 @@ struct SamplerParams : RowMath {
     char *boxes;       // [B] mailboxes of kBoxBytes (split > 1)
     const float *temps;  // [B] one temperature per sequence (0: greedy), or NULL: the RowMath constants hold
     int tab_slots;       // > 0: the launch carries dynamic LDS for one float per slot of a row
+    int two_items;       // shared sequences: two chain items per stage (row_stats_two_items)
 };
 
 
@@ -150,7 +151,7 @@ __device__ inline void row_stats_any(const void *rowp, const void *rowq, int nsl
         Sp = Sq = 0.0;
         ok = FULL;
     } else if constexpr (FULL) {
-        ok = row_stats_fast<BF16, TWO, ONE_TERM>(rowp, rowq, nslots, Vrow, sh, parity, p, Mp, Sp, Mq, Sq);
+        ok = row_stats_fast<BF16, TWO, ONE_TERM, true>(rowp, rowq, nslots, Vrow, sh, parity, p, Mp, Sp, Mq, Sq);
     }
     if constexpr (FULL) {
         const double mine[8] = {(double)Mp, Sp, (double)Mq, Sq, ok ? 1.0 : 0.0, 0.0, 0.0, 0.0};
@@ -165,15 +166,20 @@ __device__ inline void row_stats_any(const void *rowp, const void *rowq, int nsl
         const double mine[8] = {(double)Mp, Sp, (double)Mq, Sq, 1.0, 0.0, 0.0, 0.0};
         exchange(mb, mine, sh);
     }
-    if (threadIdx.x < 2) {  // thread 0: the p row, thread 1: the q row
-        const int r = threadIdx.x;
-        float M = (float)sh.xchg[0][2 * r];
-        for (int j = 1; j < mb.split; ++j) M = fmaxf(M, (float)sh.xchg[j][2 * r]);
-        double S = 0.0;
-        for (int j = 0; j < mb.split; ++j)
-            S += sh.xchg[j][2 * r + 1] * exp2_f64(((double)(float)sh.xchg[j][2 * r] - (double)M) * p.c_d);
-        sh.comb_m[r] = M;
-        sh.comb_s[r] = S;
+    if (threadIdx.x < 2 * kMaxSplit) {  // lane 8 r + j: row r (p, q) of part j; one exp2 per lane
+        const int r = threadIdx.x / kMaxSplit, j = threadIdx.x % kMaxSplit;
+        const bool have = j < mb.split;
+        const float m_j = have ? (float)sh.xchg[j][2 * r] : -INFINITY;
+        float M = m_j;
+#pragma unroll
+        for (int o = kMaxSplit / 2; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+        double S = have ? sh.xchg[j][2 * r + 1] * exp2_f64(((double)m_j - (double)M) * p.c_d) : 0.0;
+#pragma unroll
+        for (int o = kMaxSplit / 2; o >= 1; o >>= 1) S += __shfl_xor(S, o);
+        if (j == 0) {
+            sh.comb_m[r] = M;
+            sh.comb_s[r] = S;
+        }
     }
     __syncthreads();
     Mp = sh.comb_m[0];
@@ -181,6 +187,77 @@ __device__ inline void row_stats_any(const void *rowp, const void *rowq, int nsl
     Mq = sh.comb_m[1];
     Sq = sh.comb_s[1];
     __syncthreads();  // comb_* and xchg may be rewritten by the next stage
+}
+
+// The normalisers of one row pair: references and sums of the p row and the q row.
+struct DrawNorm {
+    float Mp, Mq;
+    double Sp, Sq;
+};
+
+// Shared sequences, fast pass only: the normalisers of two consecutive items of a chain in one
+// stage.  Item A is the row pair of position i, item B the row pair of position i + 1 or, when
+// i + 1 is past the last draft, the target row of the bonus token alone (b_pair false).  B is
+// streamed before A's acceptance test is known: when A rejects, B's bytes were read for nothing,
+// but a shared sequence runs on compute units that would otherwise idle, an exchange costs more
+// than a part's pass over a row pair, and this halves the exchanges of a chain.  Returns bit 0 if
+// A's numbers are valid and bit 1 if B's are (every part returns the same); an item whose fast
+// pass overflowed or came out empty in some part is repeated by the caller the ordinary way.
+template <bool BF16, bool ONE_TERM>
+__device__ inline int row_stats_two_items(const void *pa, const void *qa, const void *pb, const void *qb,
+                                          bool b_pair, int nslots, int Vrow, SharedState &sh, Mailbox &mb,
+                                          const SamplerParams &p, DrawNorm &A, DrawNorm &Bn) {
+    bool ok_a = true, ok_b = true;
+    A.Mp = A.Mq = Bn.Mp = Bn.Mq = kRefInit;
+    A.Sp = A.Sq = Bn.Sp = Bn.Sq = 0.0;
+    if (nslots > 0) {  // (a part without slots has nothing to read and no mass)
+        ok_a = row_stats_fast<BF16, true, ONE_TERM, true>(pa, qa, nslots, Vrow, sh, 0, p, A.Mp, A.Sp, A.Mq, A.Sq);
+        if (b_pair)  // block-uniform
+            ok_b = row_stats_fast<BF16, true, ONE_TERM, true>(pb, qb, nslots, Vrow, sh, 1, p, Bn.Mp, Bn.Sp, Bn.Mq, Bn.Sq);
+        else
+            ok_b = row_stats_fast<BF16, false, ONE_TERM, true>(pb, pb, nslots, Vrow, sh, 1, p, Bn.Mp, Bn.Sp, Bn.Mq, Bn.Sq);
+    }
+    // two binary32 references travel as the halves of one 8-byte word (moved, never computed with)
+    auto pack = [](float lo, float hi) {
+        return __builtin_bit_cast(double, (unsigned long long)__float_as_uint(lo) |
+                                              ((unsigned long long)__float_as_uint(hi) << 32));
+    };
+    const double mine[8] = {pack(A.Mp, A.Mq), A.Sp, A.Sq, pack(Bn.Mp, Bn.Mq), Bn.Sp, Bn.Sq,
+                            (double)((ok_a ? 1 : 0) | (ok_b ? 2 : 0)), 0.0};
+    exchange(mb, mine, sh);
+    int ok = 3;
+    for (int j = 0; j < mb.split; ++j) ok &= (int)sh.xchg[j][6];
+    if (threadIdx.x < 4 * kMaxSplit) {  // lane 8 (2 item + row) + j: part j; one exp2 per lane
+        const int g = threadIdx.x / kMaxSplit, j = threadIdx.x % kMaxSplit;
+        const int item = g >> 1, r = g & 1;
+        const bool have = j < mb.split;
+        float m_j = -INFINITY;
+        if (have) {
+            const unsigned long long w = __builtin_bit_cast(unsigned long long, sh.xchg[j][3 * item]);
+            m_j = __uint_as_float((uint32_t)(r ? w >> 32 : w & 0xffffffffull));
+        }
+        float M = m_j;
+#pragma unroll
+        for (int o = kMaxSplit / 2; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o));
+        double S = have ? sh.xchg[j][3 * item + 1 + r] * exp2_f64(((double)m_j - (double)M) * p.c_d) : 0.0;
+#pragma unroll
+        for (int o = kMaxSplit / 2; o >= 1; o >>= 1) S += __shfl_xor(S, o);
+        if (j == 0) {
+            sh.comb2_m[item][r] = M;
+            sh.comb2_s[item][r] = S;
+        }
+    }
+    __syncthreads();
+    A.Mp = sh.comb2_m[0][0];
+    A.Sp = sh.comb2_s[0][0];
+    A.Mq = sh.comb2_m[0][1];
+    A.Sq = sh.comb2_s[0][1];
+    Bn.Mp = sh.comb2_m[1][0];
+    Bn.Sp = sh.comb2_s[1][0];
+    Bn.Mq = sh.comb2_m[1][1];
+    Bn.Sq = sh.comb2_s[1][1];
+    __syncthreads();  // comb2_* and xchg may be rewritten by the next stage
+    return ok;
 }
 
 // fp64 weights of one slot: p(x) (RESID = false) or max(0, p(x) - q(x)) (Eq. 2).
@@ -257,12 +334,6 @@ struct RowPart {
     int Vrow;     // elements from the part's first slot to the end of the row
     int tok_off;  // token id of the part's first element
     float *tab;   // LDS room for one float per slot of the part (fp32 form of the weights), or NULL
-};
-
-// The exponent constants of the weights of one row pair.
-struct DrawNorm {
-    float Mp, Mq;
-    double Sp, Sq;
 };
 
 // Phase A over one part: leaves the eight region totals in sh.wave_total (no barrier), and with
@@ -792,10 +863,10 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     constexpr int EPV = Elem<BF16>::EPV;
     // the fp32 form of the final draw's weights: calls whose exponent constant rounds well (the
     // parts of a shared sequence form identical constants from the identical normalisers they
-    // hold after the exchange); the table of slot totals only with one work-group per sequence
+    // hold after the exchange); the table holds the totals of the slots of this block's part
     constexpr bool kFastScan = ONE_TERM;
     extern __shared__ __align__(16) char sampler_smem[];
-    float *tab = kFastScan && !SHARED && p.tab_slots > 0 ? reinterpret_cast<float *>(sampler_smem) : nullptr;
+    float *tab = kFastScan && p.tab_slots > 0 ? reinterpret_cast<float *>(sampler_smem) : nullptr;
     const int split = SHARED ? p.split : 1;
     const int b = blockIdx.x / split, part = blockIdx.x % split;
     // bounds come from device data: clamp them by the host-side totals so that no value of
@@ -854,6 +925,11 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
 
     int n = 0, flag_accept = 0, flag_cdf = 0, final_token = -1;
     bool rejected = false, mine = false;
+    // shared sequences walk their chain two items per stage (see row_stats_two_items); `ahead`
+    // holds the normalisers of item `ahead_of` (a position, or k for the bonus token's row)
+    constexpr bool kTwoItems = SHARED && FULL;
+    DrawNorm ahead{};
+    int ahead_of = -1;
     const char *scan_row = tbase;  // row, reference and sum of the final inverse-CDF walk over p
     float scan_M = 0.f;
     double scan_S = 1.0;
@@ -875,8 +951,31 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         const double u = (double)p.u_accept[drow0 + i];
         float Mp, Mq;
         double Sp, Sq;
-        row_stats_any<BF16, true, ONE_TERM, FULL, SHARED>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16, nslots, Vrow, sh,
-                                                  i & 1, mb, p, Mp, Sp, Mq, Sq);
+        bool have = false;
+        if constexpr (kTwoItems) {
+            if (ahead_of == i) {  // this position's normalisers came with the previous stage (block-uniform)
+                Mp = ahead.Mp, Sp = ahead.Sp, Mq = ahead.Mq, Sq = ahead.Sq;
+                have = true;
+            } else if (p.two_items) {
+                // one stage for this position and the next item of the chain: position i + 1, or
+                // the bonus token's row when this is the last draft
+                const bool b_pair = i + 1 < k;
+                const char *rowpb = tbase + (size_t)(row0 + i + 1) * p.ld_t * esz;
+                const char *rowqb = b_pair ? dbase + (size_t)(drow0 + i + 1) * p.ld_d * esz : rowpb;
+                DrawNorm a;
+                const int ok = row_stats_two_items<BF16, ONE_TERM>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16,
+                                                                   rowpb + (size_t)lo * 16, rowqb + (size_t)lo * 16, b_pair,
+                                                                   nslots, Vrow, sh, mb, p, a, ahead);
+                ahead_of = (ok & 2) ? i + 1 : -1;
+                if (ok & 1) {
+                    Mp = a.Mp, Sp = a.Sp, Mq = a.Mq, Sq = a.Sq;
+                    have = true;
+                }
+            }
+        }
+        if (!have)
+            row_stats_any<BF16, true, ONE_TERM, FULL, SHARED>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16, nslots, Vrow, sh,
+                                                      i & 1, mb, p, Mp, Sp, Mq, Sq);
         // Eq. 1 in fp64: rho = p(x)/q(x) = exp(((zp-Mp) - (zq-Mq))/T) * Sq/Sp
         double rho;
         if (zqx == -INFINITY)
@@ -910,8 +1009,13 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         scan_row = tbase + (size_t)(row0 + k) * p.ld_t * esz;
         float Mq;
         double Sq;
-        row_stats_any<BF16, false, ONE_TERM, FULL, SHARED>(scan_row + (size_t)lo * 16, scan_row + (size_t)lo * 16, nslots, Vrow,
-                                                   sh, k & 1, mb, p, scan_M, scan_S, Mq, Sq);
+        if (kTwoItems && ahead_of == k) {
+            scan_M = ahead.Mp;
+            scan_S = ahead.Sp;
+        } else {
+            row_stats_any<BF16, false, ONE_TERM, FULL, SHARED>(scan_row + (size_t)lo * 16, scan_row + (size_t)lo * 16, nslots,
+                                                       Vrow, sh, k & 1, mb, p, scan_M, scan_S, Mq, Sq);
+        }
         scan_target = true;
     } else if (final_token == -2) {
         scan_target = true;
@@ -1008,12 +1112,12 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
 
     // work-groups per sequence: as many as there are otherwise idle compute units, as long as a
     // part keeps a useful share of the row; one (and no mailbox) without a workspace
-    int split = 1;
+    int split = 1, cus = 256;
     if (workspace) {
         if (workspace_bytes < (size_t)B * kBoxBytes || !aligned_to(workspace, 16))
             return fail(RESPEC_ERR_WORKSPACE, "rejection_sample: workspace of %zu bytes (16-byte aligned) needed, got %zu",
                         (size_t)B * kBoxBytes, workspace_bytes);
-        int cus = 256, dev = 0;
+        int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         const int epv0 = logits_dt == RESPEC_BF16 ? 8 : 4;
         const long slots_row = ((long)V + epv0 - 1) / epv0;
@@ -1030,6 +1134,9 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
         return fail(RESPEC_ERR_UNSUPPORTED, "rejection_sample: too many work-groups");
     p.split = split;
     p.boxes = static_cast<char *>(workspace);
+    // Two chain items per stage read a row pair that the chain may not need.  That pays while
+    // the stage is bound by what one compute unit can stream, not by HBM: few sequences.
+    p.two_items = split > 1 && kn.get(&Knobs::sampler_two_items, (long)B * 8 <= cus ? 1 : 0) != 0;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int epv = logits_dt == RESPEC_BF16 ? 8 : 4;
@@ -1040,17 +1147,23 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
     size_t smem = 0;
     {
         const size_t slots_row = ((size_t)V + epv - 1) / epv;
-        if (full && one && split == 1 && slots_row * sizeof(float) <= kTableMaxBytes &&
+        // (a part of a shared sequence: the kernel's own rounding of the split)
+        const size_t slots_part = split > 1 ? ((slots_row + split - 1) / split + 63) / 64 * 64 : slots_row;
+        if (full && one && slots_part * sizeof(float) <= kTableMaxBytes &&
             kn.get(&Knobs::sampler_no_table, 0) == 0) {
-            smem = round_up(slots_row * sizeof(float), 16);
-            p.tab_slots = (int)slots_row;
+            smem = round_up(slots_part * sizeof(float), 16);
+            p.tab_slots = (int)slots_part;
         }
     }
 #define RESPEC_LAUNCH_SAMPLER(BF, ONE, FULL)                                                                        \
     do {                                                                                                           \
         if (split > 1) {                                                                                           \
+            if (smem > 48 * 1024) { /* (only whole rows need more than the default limit) */                      \
+                smem = 0;                                                                                          \
+                p.tab_slots = 0;                                                                                   \
+            }                                                                                                      \
             hipLaunchKernelGGL((rejection_sample_kernel<BF, ONE, FULL, true>), dim3((unsigned)(B * split)),        \
-                               dim3(kThreads), 0, stream, p);                                                      \
+                               dim3(kThreads), smem, stream, p);                                                   \
         } else {                                                                                                   \
             if (smem > 0 &&                                                                                        \
                 hipFuncSetAttribute(reinterpret_cast<const void *>(&rejection_sample_kernel<BF, ONE, FULL, false>), \

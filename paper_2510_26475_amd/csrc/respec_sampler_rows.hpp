@@ -232,6 +232,8 @@ struct SharedState {
     double xchg[kMaxSplit][8];             // what the parts published in the current stage
     float comb_m[2];                       // combined (M, S) of the p row and the q row
     double comb_s[2];
+    float comb2_m[2][2];                   // the same for the two items of a double stage: [item][p/q]
+    double comb2_s[2][2];
     int failed;                            // a bounded wait for a partner ran out
     float arg_val[kWaves];                 // per-wave (largest logit, its first token) of an argmax pass
     int arg_idx[kWaves];
@@ -263,6 +265,44 @@ __device__ inline void block_combine(float ref, double sum, SharedState &sh, int
     for (int o = kWaves / 2; o >= 1; o >>= 1) part += __shfl_xor(part, o);
     M = mm;
     S = part;
+}
+
+// The same for the fast pass, both rows at once.  The threads of a wave share one reference
+// there (the pass sets it per wave), so a wave's sums add up as they are; sixteen lanes then
+// reconcile the eight (reference, sum) pairs of each row behind a single barrier, with one fp64
+// exp2 each.  ONE_TERM: the sums were taken as exp2(z c_f + K) with K = -ref c_f rounded; the
+// residue K + ref c_f is undone in the same exp2.  Every thread returns the same bits.
+template <bool TWO, bool ONE_TERM>
+__device__ inline void block_combine_fast(float refp, double sp, float refq, double sq, SharedState &sh, int parity,
+                                          const RowMath &p, float &Mp, double &Sp, float &Mq, double &Sq) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const double swp = wave_sum(sp);
+    const double swq = TWO ? wave_sum(sq) : 0.0;
+    if (lane == 0) {
+        sh.m[parity][0][wave] = refp;
+        sh.s[parity][0][wave] = swp;
+        if constexpr (TWO) {
+            sh.m[parity][1][wave] = refq;
+            sh.s[parity][1][wave] = swq;
+        }
+    }
+    __syncthreads();
+    const int w = lane & (kWaves - 1), r = TWO ? (lane >> 3) & 1 : 0;  // lanes 8..15 (mod 16): the q row
+    const float my_m = sh.m[parity][r][w];
+    float mm = my_m;
+#pragma unroll
+    for (int o = kWaves / 2; o >= 1; o >>= 1) mm = fmaxf(mm, __shfl_xor(mm, o));
+    double e = (double)(my_m - mm) * p.c_d;
+    if constexpr (ONE_TERM) e -= (double)(-my_m * p.c_f) + (double)my_m * (double)p.c_f;
+    double part = sh.s[parity][r][w] * exp2_f64(e);
+#pragma unroll
+    for (int o = kWaves / 2; o >= 1; o >>= 1) part += __shfl_xor(part, o);
+    Mp = __shfl(mm, 0);
+    Sp = __shfl(part, 0);
+    if constexpr (TWO) {
+        Mq = __shfl(mm, 8);
+        Sq = __shfl(part, 8);
+    }
 }
 
 // One thread's share of the fast pass: 8 (bf16) or 4 (f32) running sums of
@@ -297,7 +337,10 @@ __device__ inline float slot_max(const u32x4 &v) {
 // exp2 keeps full relative precision for any offset, only a logit more than ~88/c above the
 // reference would overflow.  Returns false (every thread alike) when a sum came out
 // non-finite or empty, and the caller then repeats the row with the guarded pass below.
-template <bool BF16, bool TWO, bool ONE_TERM>
+// DEEP: a ring of three register sets.  For the short parts of a shared sequence (two or three
+// batches per thread) the whole part is then in flight before the first sum, one memory latency
+// instead of one per batch; on whole rows the third set measured slower (see kSetsTwoRows).
+template <bool BF16, bool TWO, bool ONE_TERM, bool DEEP = false>
 __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int nslots, int Vrow,
                                       SharedState &sh, int parity, const RowMath &p, float &Mp,
                                       double &Sp, float &Mq, double &Sq) {
@@ -344,10 +387,14 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
     // the compiler's wait for the batch in front of it a wait for everything in flight (it must
     // assume the branch was not taken), and then no load overlaps any sum.  Batches past the
     // row's end read its last slot again and are never summed.
-    constexpr int NSETS = TWO ? kSetsTwoRows : kSetsOneRow;
+    constexpr int NSETS = DEEP ? 3 : (TWO ? kSetsTwoRows : kSetsOneRow);
     u32x4 rp[NSETS][kUnroll], rq[NSETS][kUnroll];
 #pragma unroll
     for (int s = 0; s + 1 < NSETS; ++s) load_batch(s, rp[s], rq[s]);
+    // a row of exactly NSETS batches never enters the loop below: its last batch is requested
+    // here, ahead of the wait for the first one, instead of after the references
+    const bool all_up_front = n_iter == NSETS;  // block-uniform
+    if (all_up_front) load_batch(NSETS - 1, rp[NSETS - 1], rq[NSETS - 1]);
     if (n_iter == 1) mask_last(rp[0], rq[0]);  // block-uniform
     {   // references from the first batch
         float mp = slot_max<BF16>(rp[0][0]), mq = -INFINITY;
@@ -382,7 +429,7 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
     }
     // the last 1..NSETS batches
     const int rem = n_iter - it;
-    if (rem == NSETS) load_batch(it + NSETS - 1, rp[NSETS - 1], rq[NSETS - 1]);
+    if (rem == NSETS && !all_up_front) load_batch(it + NSETS - 1, rp[NSETS - 1], rq[NSETS - 1]);
 #pragma unroll
     for (int s = 0; s < NSETS; ++s) {
         if (s < rem) {
@@ -396,16 +443,10 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
         sp += (double)accp[j];
         sq += (double)accq[j];
     }
-    if constexpr (ONE_TERM) {  // exp2(z c + K) = exp2((z - ref) c) * exp2(K + ref c): undo the residue
-        sp *= exp2_f64(-((double)Kp + (double)refp * (double)p.c_f));
-        if constexpr (TWO) sq *= exp2_f64(-((double)Kq + (double)refq * (double)p.c_f));
-    }
-    block_combine(refp, sp, sh, parity, 0, p, Mp, Sp);
+    // (ONE_TERM: exp2(z c + K) = exp2((z - ref) c) * exp2(K + ref c); the combine undoes the residue)
+    block_combine_fast<TWO, ONE_TERM>(refp, sp, refq, sq, sh, parity, p, Mp, Sp, Mq, Sq);
     bool ok = Sp > 0.0 && Sp < 1.0e300;
-    if constexpr (TWO) {
-        block_combine(refq, sq, sh, parity, 1, p, Mq, Sq);
-        ok = ok && Sq > 0.0 && Sq < 1.0e300;
-    }
+    if constexpr (TWO) ok = ok && Sq > 0.0 && Sq < 1.0e300;
     return ok;
 }
 
