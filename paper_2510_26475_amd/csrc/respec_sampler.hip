@@ -26,6 +26,8 @@
 // references are reconciled in fp64 when threads (and parts) are combined.
 #include "respec_sampler_rows.hpp"
 
+#include <type_traits>
+
 namespace respec {
 namespace {
 
@@ -151,7 +153,7 @@ __device__ inline void row_stats_any(const void *rowp, const void *rowq, int nsl
         Sp = Sq = 0.0;
         ok = FULL;
     } else if constexpr (FULL) {
-        ok = row_stats_fast<BF16, TWO, ONE_TERM, true>(rowp, rowq, nslots, Vrow, sh, parity, p, Mp, Sp, Mq, Sq);
+        ok = row_stats_fast<BF16, TWO, ONE_TERM>(rowp, rowq, nslots, Vrow, sh, parity, p, Mp, Sp, Mq, Sq);
     }
     if constexpr (FULL) {
         const double mine[8] = {(double)Mp, Sp, (double)Mq, Sq, ok ? 1.0 : 0.0, 0.0, 0.0, 0.0};
@@ -211,11 +213,11 @@ __device__ inline int row_stats_two_items(const void *pa, const void *qa, const 
     A.Mp = A.Mq = Bn.Mp = Bn.Mq = kRefInit;
     A.Sp = A.Sq = Bn.Sp = Bn.Sq = 0.0;
     if (nslots > 0) {  // (a part without slots has nothing to read and no mass)
-        ok_a = row_stats_fast<BF16, true, ONE_TERM, true>(pa, qa, nslots, Vrow, sh, 0, p, A.Mp, A.Sp, A.Mq, A.Sq);
+        ok_a = row_stats_fast<BF16, true, ONE_TERM>(pa, qa, nslots, Vrow, sh, 0, p, A.Mp, A.Sp, A.Mq, A.Sq);
         if (b_pair)  // block-uniform
-            ok_b = row_stats_fast<BF16, true, ONE_TERM, true>(pb, qb, nslots, Vrow, sh, 1, p, Bn.Mp, Bn.Sp, Bn.Mq, Bn.Sq);
+            ok_b = row_stats_fast<BF16, true, ONE_TERM>(pb, qb, nslots, Vrow, sh, 1, p, Bn.Mp, Bn.Sp, Bn.Mq, Bn.Sq);
         else
-            ok_b = row_stats_fast<BF16, false, ONE_TERM, true>(pb, pb, nslots, Vrow, sh, 1, p, Bn.Mp, Bn.Sp, Bn.Mq, Bn.Sq);
+            ok_b = row_stats_fast<BF16, false, ONE_TERM>(pb, pb, nslots, Vrow, sh, 1, p, Bn.Mp, Bn.Sp, Bn.Mq, Bn.Sq);
     }
     // two binary32 references travel as the halves of one 8-byte word (moved, never computed with)
     auto pack = [](float lo, float hi) {
@@ -284,10 +286,13 @@ __device__ inline void slot_weights(const u32x4 &vp, const u32x4 &vq, float Mp, 
 // The same weights in fp32, for calls whose exponent constant rounds well (RowMath::one_term):
 // p(x) = exp2(z c_f + K) (1 + e) with K + log2(1 + e) = -M c_f - log2(S) split so that the
 // rounding of K is put back to first order; the weights of a slot are summed in fp32 in a
-// fixed pairwise order, and everything above a slot is carried in fp64.  A weight is within a
-// few 1e-7 (relative) of its fp64 value, far inside the boundary band of 1e-6; the scan is
-// bound by instruction issue, and this form needs about half of the instructions.
-// Returns the slot's total (fp32, pairwise); w[] are its elements' weights.
+// fixed pairwise order, and everything above a slot is carried in fp64.  A draw only compares
+// running sums with u times their total, so the weights may carry a common factor: they are
+// formed as w / (1 + ep), that is pe - qe (1 + eq - ep) for Eq. 2 and plain pe for a row of p,
+// which takes one correction per pair of elements instead of two.  A weight is within a few
+// 1e-7 (relative) of its fp64 value (times the common factor), far inside the boundary band of
+// 1e-6; the scan is bound by instruction issue, and this form needs about half of the
+// instructions.  Returns the slot's total (fp32, pairwise); w[] are its elements' weights.
 template <bool BF16, bool RESID>
 __device__ inline float slot_weights_f32(const u32x4 &vp, const u32x4 &vq, const FastNorm &f, const RowMath &p,
                                          float (&w)[Elem<BF16>::EPV]) {
@@ -298,12 +303,11 @@ __device__ inline float slot_weights_f32(const u32x4 &vp, const u32x4 &vq, const
 #pragma unroll
     for (int j = 0; j < EPV; ++j) {
         const float pe = hw_exp2(fmaf(zp[j], p.c_f, f.Kp));
-        const float P = fmaf(pe, f.ep, pe);
         if constexpr (RESID) {
             const float qe = hw_exp2(fmaf(zq[j], p.c_f, f.Kq));
-            w[j] = fmaxf(P - fmaf(qe, f.eq, qe), 0.f);
+            w[j] = fmaxf(fmaf(-qe, f.e_rel, pe - qe), 0.f);
         } else {
-            w[j] = P;
+            w[j] = pe;
         }
     }
     if constexpr (EPV == 8)
@@ -374,10 +378,12 @@ __device__ inline void draw_region_totals(const RowPart &part, const DrawNorm &n
         // a ring of register sets: all but one are in flight while one is summed
         constexpr int NSETS = FULL ? kSetsDraw : 2;  // (the guarded loads of the general form need the registers)
         u32x4 rp[NSETS][kUnroll], rq[NSETS][kUnroll];
-        auto sum_batch = [&](int s0, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll]) __attribute__((always_inline)) {
+        // (whole: every slot of the batch lies inside the region, which holds for all batches but
+        // a region's last; the selects that a ragged batch needs are a tenth of the loop)
+        auto sum_batch = [&](int s0, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll], auto whole) __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < kUnroll; ++c) {
-                const bool in = s0 + c * 64 + lane < end;
+                const bool in = decltype(whole)::value || s0 + c * 64 + lane < end;
                 const u32x4 a = in ? xp[c] : neg_inf_slot<BF16>();
                 const u32x4 b = RESID ? (in ? xq[c] : neg_inf_slot<BF16>()) : a;
                 if constexpr (FAST) {
@@ -406,14 +412,14 @@ __device__ inline void draw_region_totals(const RowPart &part, const DrawNorm &n
             for (int s = 0; s < NSETS; ++s) {
                 constexpr int kAhead = NSETS - 1;
                 load_batch(beg + (ib + s + kAhead) * kStep, rp[(s + kAhead) % NSETS], rq[(s + kAhead) % NSETS]);
-                sum_batch(beg + (ib + s) * kStep, rp[s], rq[s]);
+                sum_batch(beg + (ib + s) * kStep, rp[s], rq[s], std::true_type{});
             }
         }
         const int rem = n_b - ib;  // 1..NSETS
         if (rem == NSETS) load_batch(beg + (ib + NSETS - 1) * kStep, rp[NSETS - 1], rq[NSETS - 1]);
 #pragma unroll
         for (int s = 0; s < NSETS; ++s)
-            if (s < rem) sum_batch(beg + (ib + s) * kStep, rp[s], rq[s]);
+            if (s < rem) sum_batch(beg + (ib + s) * kStep, rp[s], rq[s], std::false_type{});
     }
     const double region_total = wave_sum(lane_sum);
     if (lane == 0) sh.wave_total[wave] = region_total;
@@ -1135,8 +1141,9 @@ respec_status_t sample_common(const void *target_logits, const void *draft_logit
     p.split = split;
     p.boxes = static_cast<char *>(workspace);
     // Two chain items per stage read a row pair that the chain may not need.  That pays while
-    // the stage is bound by what one compute unit can stream, not by HBM: few sequences.
-    p.two_items = split > 1 && kn.get(&Knobs::sampler_two_items, (long)B * 8 <= cus ? 1 : 0) != 0;
+    // the extra bytes are cheaper than the exchange they save: up to a quarter as many sequences
+    // as compute units (measured: B = 8..64 gain 3-6 us per call, B = 128 loses 3).
+    p.two_items = split > 1 && kn.get(&Knobs::sampler_two_items, (long)B * 4 <= cus ? 1 : 0) != 0;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int epv = logits_dt == RESPEC_BF16 ? 8 : 4;

@@ -337,10 +337,7 @@ __device__ inline float slot_max(const u32x4 &v) {
 // exp2 keeps full relative precision for any offset, only a logit more than ~88/c above the
 // reference would overflow.  Returns false (every thread alike) when a sum came out
 // non-finite or empty, and the caller then repeats the row with the guarded pass below.
-// DEEP: a ring of three register sets.  For the short parts of a shared sequence (two or three
-// batches per thread) the whole part is then in flight before the first sum, one memory latency
-// instead of one per batch; on whole rows the third set measured slower (see kSetsTwoRows).
-template <bool BF16, bool TWO, bool ONE_TERM, bool DEEP = false>
+template <bool BF16, bool TWO, bool ONE_TERM>
 __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int nslots, int Vrow,
                                       SharedState &sh, int parity, const RowMath &p, float &Mp,
                                       double &Sp, float &Mq, double &Sq) {
@@ -387,14 +384,10 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
     // the compiler's wait for the batch in front of it a wait for everything in flight (it must
     // assume the branch was not taken), and then no load overlaps any sum.  Batches past the
     // row's end read its last slot again and are never summed.
-    constexpr int NSETS = DEEP ? 3 : (TWO ? kSetsTwoRows : kSetsOneRow);
+    constexpr int NSETS = TWO ? kSetsTwoRows : kSetsOneRow;
     u32x4 rp[NSETS][kUnroll], rq[NSETS][kUnroll];
 #pragma unroll
     for (int s = 0; s + 1 < NSETS; ++s) load_batch(s, rp[s], rq[s]);
-    // a row of exactly NSETS batches never enters the loop below: its last batch is requested
-    // here, ahead of the wait for the first one, instead of after the references
-    const bool all_up_front = n_iter == NSETS;  // block-uniform
-    if (all_up_front) load_batch(NSETS - 1, rp[NSETS - 1], rq[NSETS - 1]);
     if (n_iter == 1) mask_last(rp[0], rq[0]);  // block-uniform
     {   // references from the first batch
         float mp = slot_max<BF16>(rp[0][0]), mq = -INFINITY;
@@ -429,7 +422,7 @@ __device__ inline bool row_stats_fast(const void *rowp, const void *rowq, int ns
     }
     // the last 1..NSETS batches
     const int rem = n_iter - it;
-    if (rem == NSETS && !all_up_front) load_batch(it + NSETS - 1, rp[NSETS - 1], rq[NSETS - 1]);
+    if (rem == NSETS) load_batch(it + NSETS - 1, rp[NSETS - 1], rq[NSETS - 1]);
 #pragma unroll
     for (int s = 0; s < NSETS; ++s) {
         if (s < rem) {
@@ -485,6 +478,7 @@ __device__ inline void row_stats(const void *rowp, const void *rowq, int nslots,
 // is split so that the rounding of K is put back to first order through e.
 struct FastNorm {
     float Kp, ep, Kq, eq;
+    float e_rel;  // eq - ep: the q row's correction relative to the p row's
 };
 
 __device__ inline FastNorm make_fast_norm(float Mp, double Sp, float Mq, double Sq, const RowMath &p) {
@@ -495,6 +489,7 @@ __device__ inline FastNorm make_fast_norm(float Mp, double Sp, float Mq, double 
     f.Kq = (float)kq;
     f.ep = (float)((kp - (double)f.Kp) * 0.69314718055994530942);
     f.eq = (float)((kq - (double)f.Kq) * 0.69314718055994530942);
+    f.e_rel = (float)(((kq - (double)f.Kq) - (kp - (double)f.Kp)) * 0.69314718055994530942);
     return f;
 }
 

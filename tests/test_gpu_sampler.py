@@ -9,7 +9,7 @@ import pytest
 import torch
 from scipy import stats
 
-from helpers import compare_sampler, flag_bound, gpu_sample, oracle_sample, sampler_split
+from helpers import compare_sampler, env_setting, flag_bound, gpu_sample, oracle_sample, sampler_split
 from paper_2510_26475_amd import binding, synth
 
 pytestmark = pytest.mark.gpu
@@ -135,6 +135,60 @@ def test_sequences_shared_by_several_work_groups(oracle, split):
             gpu = gpu_sample(batch)
             tally = compare_sampler(gpu, ref)
             assert tally["flagged"] <= 3, tally
+
+
+@pytest.mark.parametrize("two_items", [0, 1])
+@pytest.mark.parametrize("split", [2, 4, 8])
+def test_shared_sequences_one_or_two_chain_items_per_stage(oracle, split, two_items):
+    # a shared sequence may take the normalisers of two consecutive items of its chain (two
+    # positions, or the last position and the bonus token's row) in one exchange; both ways must
+    # give the oracle's tokens, for every chain length and for chains that end at every position
+    wl = _wl("two_items", 151936, "bf16", sigma=0.5)
+    ks = [4] * 12 + [3, 0, 1, 2, 3, 4, 2, 1]
+    batch = _batch(wl, ks, seed=37)
+    ref = oracle_sample(oracle, batch)
+    n_acc = ref[1].tolist()
+    assert len(set(n_acc)) >= 3 and 4 in n_acc     # rejections at several positions and full chains
+    with sampler_split(split), env_setting("RESPEC_SAMPLER_TWO_ITEMS", two_items):
+        for _ in range(2):
+            tally = compare_sampler(gpu_sample(batch), ref)
+            assert tally["flagged"] <= 4, tally
+
+
+@pytest.mark.parametrize("two_items", [0, 1])
+def test_shared_sequences_never_use_rows_past_the_first_rejection(oracle, two_items):
+    # with two items per stage the row pair after a rejected position is read ahead of the test
+    # that makes it unnecessary; whatever it holds (here NaN) must not reach the outputs
+    wl = _wl("poison_shared", 151936, "bf16", sigma=1.5)
+    ks = [4] * 12
+    batch = _batch(wl, ks, seed=9)
+    ref = oracle_sample(oracle, batch)
+    qi = batch.q_indptr.tolist()
+    for b, k in enumerate(ks):
+        n = int(ref[1][b])
+        batch.target_logits[qi[b] + n + 1: qi[b + 1]] = float("nan")
+        d0 = qi[b] - b
+        batch.draft_logits[d0 + n + 1: d0 + k] = float("nan")
+        batch.u_accept[d0 + n + 1: d0 + k] = float("nan")
+    with sampler_split(4), env_setting("RESPEC_SAMPLER_TWO_ITEMS", two_items):
+        compare_sampler(gpu_sample(batch), ref)
+    assert len(set(ref[1].tolist())) >= 3
+
+
+def test_shared_sequences_with_outliers_repeat_the_item_with_the_guarded_pass(oracle):
+    # an overflowing fast pass in one part of one item of a two-item stage: that item alone is
+    # repeated by all parts with the guarded pass, the other item's numbers stand
+    wl = _wl("outlier_shared", 151936, "bf16", sigma=0.5)
+    batch = _batch(wl, [4] * 6, seed=22)
+    qi = batch.q_indptr.tolist()
+    batch.target_logits[qi[0] + 1, 100000] = 400.0     # second item of sequence 0's first stage
+    batch.draft_logits[qi[1] - 1 + 0, 77] = 300.0       # first item of sequence 1's first stage
+    batch.target_logits[qi[2] + 4, 5] = 350.0           # the bonus row of sequence 2
+    batch.target_logits[qi[3] + 2, :60000] = float("-inf")
+    ref = oracle_sample(oracle, batch)
+    for split in (2, 8):
+        with sampler_split(split), env_setting("RESPEC_SAMPLER_TWO_ITEMS", 1):
+            compare_sampler(gpu_sample(batch), ref)
 
 
 @pytest.mark.parametrize("V", [1000, 70, 4099])
