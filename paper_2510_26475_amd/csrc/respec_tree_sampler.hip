@@ -18,6 +18,8 @@
 // acceptance test needs only the candidate's own two logits.
 #include "respec_sampler_rows.hpp"
 
+#include <type_traits>
+
 namespace respec {
 namespace {
 
@@ -171,10 +173,11 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
     if (beg < end) {  // wave-uniform
         // two register sets take turns: one is summed while the other's loads are in flight
         u32x4 vp[kUnroll], vq[kUnroll], np[kUnroll], nq[kUnroll];
-        auto sum_batch = [&](int s0, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll]) __attribute__((always_inline)) {
+        // (whole: every slot of the batch lies inside the region, true for all but a region's last)
+        auto sum_batch = [&](int s0, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll], auto whole) __attribute__((always_inline)) {
 #pragma unroll
             for (int c = 0; c < kUnroll; ++c) {
-                const bool in = s0 + c * 64 + lane < end;  // slots past the region count as -inf
+                const bool in = decltype(whole)::value || s0 + c * 64 + lane < end;  // slots past the region count as -inf
                 const u32x4 a = in ? xp[c] : neg_inf_slot<BF16>(), b = in ? xq[c] : neg_inf_slot<BF16>();
                 if constexpr (FAST) {
                     float w[EPV];
@@ -194,16 +197,16 @@ __device__ inline double tree_region_totals(const void *rowp, const void *rowq, 
         int s0 = beg;
         for (; s0 + 2 * kStep < end; s0 += 2 * kStep) {
             load_batch(s0 + kStep, np, nq);
-            sum_batch(s0, vp, vq);
+            sum_batch(s0, vp, vq, std::true_type{});
             load_batch(s0 + 2 * kStep, vp, vq);
-            sum_batch(s0 + kStep, np, nq);
+            sum_batch(s0 + kStep, np, nq, std::true_type{});
         }
         if (s0 + kStep < end) {
             load_batch(s0 + kStep, np, nq);
-            sum_batch(s0, vp, vq);
-            sum_batch(s0 + kStep, np, nq);
+            sum_batch(s0, vp, vq, std::true_type{});
+            sum_batch(s0 + kStep, np, nq, std::false_type{});
         } else {
-            sum_batch(s0, vp, vq);
+            sum_batch(s0, vp, vq, std::false_type{});
         }
     }
     const double region_total = wave_sum(lane_sum);
