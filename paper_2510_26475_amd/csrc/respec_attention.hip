@@ -1176,7 +1176,9 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(AttnParams p) {
 // ------------------------------------------------------------------------------------------
 template <int D, typename OutT>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
-    constexpr int kTpc = D / 4;             // threads per column (float4 each)
+    // (eight values of d per thread: half as many work-groups as with four, so that the launch
+    // fits the device in one round; the kernel is a chain of two memory latencies, not bandwidth)
+    constexpr int kTpc = D / 8;             // threads per column
     constexpr int kCols = 256 / kTpc;       // columns per block
     const int kvh = blockIdx.x % p.Hkv;  // blockIdx.x = sequence * Hkv + KV head
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0 && *p.error_flag != 0) {
@@ -1196,7 +1198,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     if (!dense) sp = make_split(p, p.tile_prefix[p.B]);
     const int sub = kvh / (p.Hkv / p.HI);
     const int n = blockIdx.y * kCols + threadIdx.x / kTpc;
-    const int d4 = (threadIdx.x % kTpc) * 4;
+    const int d8 = (threadIdx.x % kTpc) * 8;
     const int M = p.G * si.R;
     if (n >= M) return;
     const int i = n / p.G, gh = n % p.G;
@@ -1204,7 +1206,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     // ones; when there are fewer tiles than parts some own no tile and wrote nothing.  They are
     // folded in that order, four at a time so that their loads are in flight together.
     float mt = -INFINITY, lt = 0.f;
-    floatx4 o = {0.f, 0.f, 0.f, 0.f};
+    floatx4 o = {0.f, 0.f, 0.f, 0.f}, o2 = {0.f, 0.f, 0.f, 0.f};
     for (int r = r_first; r <= r_last;) {
         int64_t prow[4];
         int cnt = 0;
@@ -1219,12 +1221,12 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
             ++cnt;
         }
         floatx4 stats[4];
-        u32x2 q[4];
+        u32x4 q[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (j < cnt) {
                 stats[j] = *reinterpret_cast<const floatx4 *>(p.ws_ml + prow[j] * 4);
-                q[j] = *reinterpret_cast<const u32x2 *>(p.ws_o + prow[j] * D + d4);
+                q[j] = *reinterpret_cast<const u32x4 *>(p.ws_o + prow[j] * D + d8);
             }
         }
 #pragma unroll
@@ -1236,24 +1238,31 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
                 const float unit = stats[j][2] * (1.f / 32767.f) * wgt;
                 const floatx4 x = {(float)(int16_t)(q[j][0] & 0xffffu), (float)(int16_t)(q[j][0] >> 16),
                                    (float)(int16_t)(q[j][1] & 0xffffu), (float)(int16_t)(q[j][1] >> 16)};
+                const floatx4 x2 = {(float)(int16_t)(q[j][2] & 0xffffu), (float)(int16_t)(q[j][2] >> 16),
+                                    (float)(int16_t)(q[j][3] & 0xffffu), (float)(int16_t)(q[j][3] >> 16)};
                 lt = lt * keep + stats[j][1] * wgt;
                 o = o * keep + x * unit;
+                o2 = o2 * keep + x2 * unit;
                 mt = mnew;
             }
         }
     }
     const float inv = lt > 0.f ? 1.f / lt : 0.f;
     const int64_t orow = (int64_t)(si.q0 + i) * p.Hq + kvh * p.G + gh;
-    OutT *dst = static_cast<OutT *>(p.out) + orow * D + d4;
+    OutT *dst = static_cast<OutT *>(p.out) + orow * D + d8;
     if constexpr (sizeof(OutT) == 2) {
         const bf16x2 a = __builtin_convertvector(floatx2{o[0] * inv, o[1] * inv}, bf16x2);
         const bf16x2 c2 = __builtin_convertvector(floatx2{o[2] * inv, o[3] * inv}, bf16x2);
-        *reinterpret_cast<u32x2 *>(dst) =
-            u32x2{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, c2)};
+        const bf16x2 a2 = __builtin_convertvector(floatx2{o2[0] * inv, o2[1] * inv}, bf16x2);
+        const bf16x2 c4 = __builtin_convertvector(floatx2{o2[2] * inv, o2[3] * inv}, bf16x2);
+        *reinterpret_cast<u32x4 *>(dst) =
+            u32x4{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, c2),
+                  __builtin_bit_cast(uint32_t, a2), __builtin_bit_cast(uint32_t, c4)};
     } else {
         *reinterpret_cast<floatx4 *>(dst) = o * inv;
+        *reinterpret_cast<floatx4 *>(dst + 4) = o2 * inv;
     }
-    if (p.lse && d4 == 0)
+    if (p.lse && d8 == 0)
         p.lse[orow] = lt > 0.f ? (mt + log2f(lt)) * 0.6931471805599453f : -INFINITY;
 }
 
@@ -1613,7 +1622,7 @@ respec_status_t verify_attention_any(const void *q, const void *k_cache, const v
         g_mark_after_main = nullptr;
     }
     {
-        const int cols_per_block = 256 / (D / 4);
+        const int cols_per_block = 256 / (D / 8);
         const dim3 cgrid((unsigned)(B * Hkv), (unsigned)((M + cols_per_block - 1) / cols_per_block));
         if (D == 128)
             hipLaunchKernelGGL((attn_combine_kernel<128, uint16_t>), cgrid, dim3(256), 0, stream, p);
