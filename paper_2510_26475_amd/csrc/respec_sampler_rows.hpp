@@ -15,9 +15,10 @@ constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / 64;
 constexpr int kUnroll = 4;
 // Register sets of the streaming loops (one is summed while the others' loads are in flight).
-// Two is the measured optimum: a compute unit does not take more requests than one batch of a
-// 512-thread work-group at a time, so a third set only makes waves block at the issue of their
-// loads (headline workload: 103 us with two sets, 109 us with three, 135 us with four).
+// Two is the measured optimum: a work-group's pass is bound by the issue of its arithmetic (a
+// sequence alone on the device is as fast on rows flushed from the caches as on rows in L2), so
+// one batch in flight covers the latency and further sets only cost registers (headline
+// workload: 103 us with two sets, 109 us with three, 135 us with four).
 constexpr int kSetsTwoRows = 2;  // fast normaliser pass over a row pair
 constexpr int kSetsOneRow = 2;   // ... over one row
 constexpr int kSetsDraw = 2;     // the final draw's pass over the row pair
