@@ -176,8 +176,10 @@ __device__ inline float sum_across_rows(float x) {
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-// The split.  The KV heads form HI sub-lists of Hkv/HI heads; a sub-list is the flat tile list
-// (head, sequence, tile) of its heads, `sub_total` tiles long, cut evenly into W/HI parts.
+// The split.  The KV heads form HI sub-lists of Hkv/HI heads (sub-list s: the heads s, s + HI,
+// ...: the heads that the waves of one work-group read at a time are neighbours in a cache row);
+// a sub-list is the flat tile list (head, sequence, tile) of its heads, `sub_total` tiles long,
+// cut evenly into W/HI parts.
 // Wave u takes part u / HI of sub-list u % HI.  Part r owns flat tiles
 // [range_begin(r), range_begin(r+1)) of its sub-list.
 struct Split {
@@ -233,7 +235,7 @@ __device__ inline WaveStart make_wave_start(const AttnParams &p, const Split &sp
         const int64_t a0 = range_begin(sp, r), a1 = range_begin(sp, r + 1);
         st.n = (int32_t)(a1 - a0);
         const int64_t head = a0 < T ? 0 : div_nonneg(a0, T);  // (one head per sub-list: always 0)
-        st.h = sub * sp.hps + (int32_t)head;
+        st.h = (int32_t)head * p.HI + sub;
         const int32_t rem = (int32_t)(a0 - head * T);
         int lo = 0, hi = p.B - 1;          // last b with prefix[b] <= rem
         while (lo < hi) {
@@ -261,7 +263,7 @@ __device__ inline void write_cut(const AttnParams &p, const Split &sp, int idx, 
     const int tiles = prefix(b + 1) - prefix(b);
     int r_first = 0, r_last = 0;
     if (tiles > 0) {
-        const int64_t first_tile = (int64_t)(kvh % sp.hps) * sp.T + prefix(b);
+        const int64_t first_tile = (int64_t)(kvh / p.HI) * sp.T + prefix(b);
         r_first = part_of_tile(sp, first_tile);
         r_last = part_of_tile(sp, first_tile + tiles - 1);
     }
@@ -433,7 +435,7 @@ __device__ inline void cursor_find_next(const AttnParams &p, Cursor &c) {
     for (;;) {
         if (++c.nb >= p.B) {
             c.nb = 0;
-            ++c.nh;
+            c.nh += p.HI;  // the next head of this wave's sub-list
         }
         if (c.nh >= p.Hkv) return;
         c.nsi = seq_info(p, c.nb);
@@ -1196,7 +1198,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnParams p) {
     si.R = cut.w;
     Split sp{};
     if (!dense) sp = make_split(p, p.tile_prefix[p.B]);
-    const int sub = kvh / (p.Hkv / p.HI);
+    const int sub = kvh % p.HI;
     const int n = blockIdx.y * kCols + threadIdx.x / kTpc;
     const int d8 = (threadIdx.x % kTpc) * 8;
     const int M = p.G * si.R;
