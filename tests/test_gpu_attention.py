@@ -213,6 +213,17 @@ def test_custom_scale_and_no_lse(oracle):
     _check(out, None, ref, None, "bf16")
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_a_scale_of_zero_weighs_every_visible_key_alike(oracle, dtype):
+    # every score is zero then, hidden keys still count for nothing
+    wl = _wl("zero_scale", 8, 2, 128 if dtype == "bf16" else 64, dtype)
+    batch = synth.make_batch(wl, device="cuda", kv_lens=[300, 40, 5], k_per_seq=[3, 1, 4], seed=12,
+                             with_logits=False)
+    out, lse = gpu_attention(batch, sm_scale=0.0)
+    ref, ref_lse = oracle_attention(oracle, batch, sm_scale=0.0)
+    _check(out, lse, ref, ref_lse, dtype)
+
+
 def test_qwen3b_workload_full_batch(oracle):
     wl = synth.WORKLOADS["qwen3b_b64_k4"]
     batch = synth.make_batch(wl, device="cuda", with_logits=False)
