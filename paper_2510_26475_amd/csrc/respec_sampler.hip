@@ -862,6 +862,24 @@ __device__ inline void greedy_sequence(const SamplerParams &p, int b, int row0, 
     }
 }
 
+// The largest logit among the first kThreads slots of a (16-byte aligned, whole-slot) row; every
+// thread returns the same value (-inf when none of them is finite).  Ends with a barrier.
+template <bool BF16>
+__device__ inline float block_max_of_row_start(const void *row, int nslots, SharedState &sh) {
+    const int lane = opaque_thread_index() & 63, wave = threadIdx.x >> 6;
+    float m = -INFINITY;
+    if ((int)threadIdx.x < nslots) m = slot_max<BF16>(load_slot<BF16, true>(row, threadIdx.x, 0, true));
+    m = wave_max(m);
+    __syncthreads();  // (earlier readers of arg_val are done)
+    if (lane == 0) sh.arg_val[wave] = m;
+    __syncthreads();
+    float r = sh.arg_val[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) r = fmaxf(r, sh.arg_val[w]);
+    __syncthreads();
+    return r;
+}
+
 template <bool BF16, bool ONE_TERM, bool FULL, bool SHARED>
 __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParams p) {
     __shared__ SharedState sh;
@@ -936,6 +954,7 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
     constexpr bool kTwoItems = SHARED && FULL;
     DrawNorm ahead{};
     int ahead_of = -1;
+    float last_Mp = -INFINITY;  // reference of the target row of the position tested last
     const char *scan_row = tbase;  // row, reference and sum of the final inverse-CDF walk over p
     float scan_M = 0.f;
     double scan_S = 1.0;
@@ -955,8 +974,8 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
             zqx = reinterpret_cast<const float *>(rowq)[x];
         }
         const double u = (double)p.u_accept[drow0 + i];
-        float Mp, Mq;
-        double Sp, Sq;
+        float Mp = 0.f, Mq = 0.f;
+        double Sp = 0.0, Sq = 0.0;
         bool have = false;
         if constexpr (kTwoItems) {
             if (ahead_of == i) {  // this position's normalisers came with the previous stage (block-uniform)
@@ -982,6 +1001,7 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         if (!have)
             row_stats_any<BF16, true, ONE_TERM, FULL, SHARED>(rowp + (size_t)lo * 16, rowq + (size_t)lo * 16, nslots, Vrow, sh,
                                                       i & 1, mb, p, Mp, Sp, Mq, Sq);
+        last_Mp = Mp;
         // Eq. 1 in fp64: rho = p(x)/q(x) = exp(((zp-Mp) - (zq-Mq))/T) * Sq/Sp
         double rho;
         if (zqx == -INFINITY)
@@ -1011,7 +1031,40 @@ __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParam
         break;
     }
     bool scan_target = false;
-    if (!rejected) {  // every draft accepted (or none offered): bonus token from target row k
+    bool drawn = false;
+    if constexpr (FULL && kFastScan) {
+        // The bonus token's draw needs no normaliser: it compares running sums of weights with u
+        // times their total, so exp((z - M0)/T) serves for any reference M0 that keeps the
+        // weights in range: one pass over the row instead of two.  With one work-group per
+        // sequence M0 is the largest logit among the row's first 512 slots; the parts of a shared
+        // sequence need the same M0 and take the reference of the last draft's target row, which
+        // they all hold (a sequence without drafts, or whose bonus row came with the last stage,
+        // goes the ordinary way).  A total that is not a positive finite number (an outlier far
+        // above M0, a row start without any finite logit) leaves the draw to the two passes below;
+        // every part sees the same total and decides alike.
+        if (!rejected && (!SHARED || (k > 0 && ahead_of != k))) {
+            scan_row = tbase + (size_t)(row0 + k) * p.ld_t * esz;
+            float M0;
+            if constexpr (SHARED) M0 = last_Mp;
+            else M0 = block_max_of_row_start<BF16>(scan_row, nslots, sh);
+            if (M0 > -INFINITY && M0 < INFINITY) {  // block-uniform
+                double Z;
+                int edge = 0;
+                const int tok = inverse_cdf_pass<BF16, false, FULL, SHARED, kFastScan>(scan_row + (size_t)lo * 16, scan_row + (size_t)lo * 16, nslots, Vrow, tok_off,
+                                                                               M0, 1.0, M0, 1.0, u_fin, sh, mb, p, edge, Z, mine, tab);
+                if (Z > 0.0 && Z < 1.0e300) {
+                    final_token = tok;
+                    flag_cdf = edge;
+                    drawn = true;
+                } else {
+                    mine = false;
+                }
+            }
+        }
+    }
+    if (drawn) {
+        // (nothing left to do)
+    } else if (!rejected) {  // every draft accepted (or none offered): bonus token from target row k
         scan_row = tbase + (size_t)(row0 + k) * p.ld_t * esz;
         float Mq;
         double Sq;

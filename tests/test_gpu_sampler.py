@@ -122,6 +122,32 @@ def test_huge_outlier_logit_takes_the_guarded_pass(oracle):
     gpu, ref, _ = _parity(oracle, batch)
 
 
+def test_bonus_rows_drawn_in_one_pass_and_their_fallbacks(oracle):
+    # the bonus token (and plain sampling, k = 0) is drawn in one pass against a reference taken
+    # from the row's first 512 slots; a logit far above it overflows that pass and a row start
+    # without finite logits gives no reference: both fall back to normaliser pass plus draw
+    wl = _wl("bonus", 151936, "bf16", sigma=1.0)
+    ks = [0] * 10 + [2, 3]
+    batch = _batch(wl, ks, seed=41)
+    qi = batch.q_indptr.tolist()
+    batch.target_logits[qi[0], 100000] = 400.0          # overflows the one-pass weights
+    batch.target_logits[qi[1], :5000] = float("-inf")   # no reference in the first 512 slots
+    batch.target_logits[qi[2], 140001] = 60.0           # far above the reference, still in range
+    batch.target_logits[qi[3], 17] = 90.0               # the reference itself is the outlier
+    batch.target_logits[qi[4], 4096:] = float("-inf")   # all the mass inside the first 512 slots
+    for b in (10, 11):                                   # every draft accepted: the bonus row is used
+        k = ks[b]
+        batch.draft_logits[qi[b] - b: qi[b] - b + k] = batch.target_logits[qi[b]: qi[b] + k]
+    batch.u_accept.fill_(0.25)
+    ref = oracle_sample(oracle, batch)
+    for workspace in (None, "shared"):   # one work-group per sequence (the one-pass form), and shared
+        gpu = gpu_sample(batch, workspace=workspace)
+        tally = compare_sampler(gpu, ref)
+        assert tally["flagged"] <= 2, tally
+        assert gpu[1].tolist() == ks
+        assert gpu[0][0, 0] == 100000 and gpu[0][3, 0] == 17
+
+
 @pytest.mark.parametrize("split", [1, 2, 4, 8])
 def test_sequences_shared_by_several_work_groups(oracle, split):
     # the vocabulary of a sequence is cut into `split` parts that exchange partial sums; the
