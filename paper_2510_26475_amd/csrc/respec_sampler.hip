@@ -862,24 +862,6 @@ __device__ inline void greedy_sequence(const SamplerParams &p, int b, int row0, 
     }
 }
 
-// The largest logit among the first kThreads slots of a (16-byte aligned, whole-slot) row; every
-// thread returns the same value (-inf when none of them is finite).  Ends with a barrier.
-template <bool BF16>
-__device__ inline float block_max_of_row_start(const void *row, int nslots, SharedState &sh) {
-    const int lane = opaque_thread_index() & 63, wave = threadIdx.x >> 6;
-    float m = -INFINITY;
-    if ((int)threadIdx.x < nslots) m = slot_max<BF16>(load_slot<BF16, true>(row, threadIdx.x, 0, true));
-    m = wave_max(m);
-    __syncthreads();  // (earlier readers of arg_val are done)
-    if (lane == 0) sh.arg_val[wave] = m;
-    __syncthreads();
-    float r = sh.arg_val[0];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) r = fmaxf(r, sh.arg_val[w]);
-    __syncthreads();
-    return r;
-}
-
 template <bool BF16, bool ONE_TERM, bool FULL, bool SHARED>
 __global__ __launch_bounds__(kThreads) void rejection_sample_kernel(SamplerParams p) {
     __shared__ SharedState sh;

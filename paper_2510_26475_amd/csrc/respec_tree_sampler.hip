@@ -430,6 +430,22 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
         int c = cur + 1;
         while (c < R && sh_parent[c] != cur) ++c;
         if (c >= R || n >= p.max_depth) {  // a leaf (or the output row is full): draw from the target
+            const Depth d0{0, 1.0, 1.0, sh_inv_z};
+            if constexpr (FULL && ONE_TERM) {
+                // One pass instead of two: the draw compares running sums with u times their
+                // total, so any reference that keeps the weights in range will do; a total that
+                // is not a positive finite number sends the draw the ordinary way below.
+                const float M0 = block_max_of_row_start<BF16>(rowp, nslots, sh);
+                if (M0 > -INFINITY && M0 < INFINITY) {  // block-uniform
+                    const double Z = tree_region_totals<BF16, FULL, ONE_TERM>(rowp, rowp, nslots, p.V, M0, 1.0, M0, 1.0, d0, sh, p);
+                    if (Z > 0.0 && Z < 1.0e300) {
+                        int edge = 0;
+                        final_token = tree_draw<BF16, FULL, ONE_TERM>(rowp, rowp, nslots, p.V, M0, 1.0, M0, 1.0, d0, (double)p.u_final[b], sh, p, edge);
+                        flag_cdf |= edge;
+                        break;
+                    }
+                }
+            }
             float M, Mq;
             double S, Sq;
             if constexpr (FULL) {
@@ -440,7 +456,6 @@ __global__ __launch_bounds__(kThreads) void tree_rejection_sample_kernel(TreePar
             } else {
                 row_stats<BF16, false>(rowp, rowp, nslots, p.V, sh, parity, p, M, S, Mq, Sq);
             }
-            const Depth d0{0, 1.0, 1.0, sh_inv_z};
             const double Z = tree_region_totals<BF16, FULL, ONE_TERM>(rowp, rowp, nslots, p.V, M, S, M, S, d0, sh, p);
             if (Z > 0.0) {
                 int edge = 0;
