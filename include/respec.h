@@ -306,7 +306,10 @@ size_t respec_rejection_sample_workspace_bytes(int32_t B, int32_t total_q, int32
  * token out_tokens[b,n] is drawn from max(0,p-q)/Z (Eq. 2) and the sequence stops; if all
  * k_b are accepted (or k_b == 0) out_tokens[b,k_b] is drawn from softmax(target row k_b / T).
  * That one draw is an inverse-CDF walk in ascending token id: the first x whose running
- * sum exceeds u_final[b]*Z.  Rows after the first rejection are not read.
+ * sum exceeds u_final[b]*Z.  Rows after the first rejection are never used; with a workspace
+ * (sequences shared by several work-groups) the row pair right behind a rejected position may
+ * have been read ahead of the test, so those rows have to be readable memory of the logits
+ * buffers, which they are by the layout above, but may hold anything.
  *
  *   target_logits [total_q, V], row stride ld_t elements (>= V)    logits_dt
  *   draft_logits  [total_q-B, V], row stride ld_d elements (>= V)  logits_dt; may be NULL

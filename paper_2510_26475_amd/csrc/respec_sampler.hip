@@ -3,7 +3,8 @@
 // row and the drafter row are streamed once (16-byte loads, fp32 exp2, sums carried in
 // fp64), the acceptance test is taken in fp64, and at the first rejection a second pass
 // over that one row pair draws from max(0, p-q) by an ordered fp64 prefix scan.  Rows after
-// the first rejection are never touched.
+// the first rejection are never used (a shared sequence may have read the pair right behind
+// the rejected position ahead of the test, see row_stats_two_items).
 //
 // Parallelisation.  The chain of positions of one sequence is sequential and its length
 // differs from sequence to sequence, so one work-group per sequence leaves most of the
