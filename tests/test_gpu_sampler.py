@@ -352,6 +352,23 @@ def test_qwen7b_headline_workload_full_batch(oracle):
     print("qwen7b sampler tally", tally, "emitted/seq", emitted)
 
 
+@pytest.mark.parametrize("B", [64, 16])
+def test_qwen3b_small_batches_in_the_library_s_own_choice_of_sharing(oracle, B):
+    """B = 64 (the baseline's small workload) and B = 16, k = 4, V = 151936 bf16 with the mailbox
+    workspace and no knob set: the library shares a sequence among four or eight work-groups and
+    takes two chain items per exchange; three calls in a row on one workspace."""
+    import dataclasses
+    wl = dataclasses.replace(synth.WORKLOADS["qwen3b_b64_k4"], B=B)
+    batch = synth.make_batch(wl, device="cuda", with_attention=False)
+    ref = oracle_sample(oracle, batch)
+    from helpers import sampler_workspace
+    ws = sampler_workspace(B, wl.V, binding.RESPEC_BF16, "cuda")
+    for _ in range(3):
+        tally = compare_sampler(gpu_sample(batch, workspace=ws), ref)
+        assert tally["flagged"] <= flag_bound(B, wl.V), tally
+    assert len(set(ref[1].tolist())) >= 4      # chains of every length, full ones among them
+
+
 def test_bad_arguments_are_rejected_before_any_launch():
     wl = _wl("err", 1024, "f32")
     batch = _batch(wl, [2, 2], seed=1)
