@@ -181,6 +181,20 @@ def test_shared_sequences_one_or_two_chain_items_per_stage(oracle, split, two_it
             assert tally["flagged"] <= 4, tally
 
 
+@pytest.mark.parametrize("dtype,T", [("f32", 0.7), ("bf16", 0.6), ("f32", 1.0)])
+def test_two_chain_items_per_stage_in_the_other_kernel_forms(oracle, dtype, T):
+    # f32 logits and temperatures whose exponent constant takes the two-term form: the other
+    # instantiations of the shared kernel
+    wl = _wl("two_items_forms", 50000, dtype, sigma=0.5, T=T)
+    ks = [4] * 6 + [3, 0, 1, 2]
+    batch = _batch(wl, ks, seed=43)
+    ref = oracle_sample(oracle, batch)
+    for two_items in (0, 1):
+        with sampler_split(4), env_setting("RESPEC_SAMPLER_TWO_ITEMS", two_items):
+            tally = compare_sampler(gpu_sample(batch), ref)
+            assert tally["flagged"] <= 3, tally
+
+
 @pytest.mark.parametrize("two_items", [0, 1])
 def test_shared_sequences_never_use_rows_past_the_first_rejection(oracle, two_items):
     # with two items per stage the row pair after a rejected position is read ahead of the test
