@@ -14,6 +14,8 @@
 // summed per thread in fp32 over one batch of slots (at most 32 terms) and in fp64 from there on.
 #include "respec_sampler_rows.hpp"
 
+#include <type_traits>
+
 namespace respec {
 namespace {
 
@@ -88,6 +90,14 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
         parity ^= 1;
         // log2 of the normalisers; p = exp2((z - Mp) c - lsp), q alike
         const float lsp = (float)log2(Sp), lsq = (float)log2(Sq);
+        // One-term form (the exponent constant rounds well, as log2(e) does): the log2 of a
+        // probability is one multiply-add, z c_f + K with K = -M c_f - log2(S) rounded to
+        // binary32; what the rounding of K leaves out (dKa, dKb, a few 1e-7) shifts every term
+        // of the row's KL alike and is put back once per row.
+        const double ka = -(double)Mp * (double)p.c_f - log2(Sp), kb = -(double)Mq * (double)p.c_f - log2(Sq);
+        const float Ka = (float)ka, Kb = (float)kb;
+        const double kl_shift = (ka - (double)Ka) - (kb - (double)Kb);
+        const bool one_term = p.one_term != 0;  // block-uniform
         auto load_batch = [&](int it, u32x4 (&vp)[kUnroll], u32x4 (&vq)[kUnroll]) __attribute__((always_inline)) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -99,19 +109,27 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
             }
         };
         double kl = 0.0;
-        auto work_batch = [&](int it, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll]) __attribute__((always_inline)) {
+        // `one`: the one-term form of the log2-probabilities; `whole`: every slot of the batch lies
+        // inside the row (all batches but the row's last, which the pass takes first)
+        auto work_batch = [&](int it, const u32x4 (&xp)[kUnroll], const u32x4 (&xq)[kUnroll], auto one, auto whole) __attribute__((always_inline)) {
             float klb = 0.f;
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const int s = it * kBatch + u * kThreads + (int)threadIdx.x;
-                if (s < nslots) {
+                if (decltype(whole)::value || s < nslots) {
                     float zp[EPV], zq[EPV], gr[EPV];
                     unpack<BF16>(xp[u], zp);
                     unpack<BF16>(xq[u], zq);
 #pragma unroll
                     for (int j = 0; j < EPV; ++j) {
-                        const float a = exp2_arg(zp[j], Mp, p.c_hi, p.c_lo) - lsp;
-                        const float b = exp2_arg(zq[j], Mq, p.c_hi, p.c_lo) - lsq;
+                        float a, b;
+                        if constexpr (decltype(one)::value) {
+                            a = fmaf(zp[j], p.c_f, Ka);
+                            b = fmaf(zq[j], p.c_f, Kb);
+                        } else {
+                            a = exp2_arg(zp[j], Mp, p.c_hi, p.c_lo) - lsp;
+                            b = exp2_arg(zq[j], Mq, p.c_hi, p.c_lo) - lsq;
+                        }
                         const float pe = hw_exp2(a), qe = hw_exp2(b);
                         if (pe > 0.f) klb += pe * (a - b);
                         gr[j] = w * (qe - pe);
@@ -122,25 +140,36 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
             }
             kl += (double)klb;
         };
-        // two register sets take turns: one batch is worked on while the next one's loads are in flight
-        u32x4 vp[kUnroll], vq[kUnroll], wp[kUnroll], wq[kUnroll];
-        // (the loads of the steady state are unconditional: behind a condition the wait for the
-        // batch in front of a load becomes a wait for everything in flight)
-        load_batch(n_iter - 1, vp, vq);
-        int it = n_iter - 1;  // vp holds batch `it`
-        for (; it >= 2; it -= 2) {
-            load_batch(it - 1, wp, wq);
-            work_batch(it, vp, vq);
-            load_batch(it - 2, vp, vq);
-            work_batch(it - 1, wp, wq);
-        }
-        if (it == 1) {
-            load_batch(0, wp, wq);
-            work_batch(1, vp, vq);
-            work_batch(0, wp, wq);
-        } else {
-            work_batch(0, vp, vq);
-        }
+        // two register sets take turns: one batch is worked on while the next one's loads are in
+        // flight.  (The loads of the steady state are unconditional: behind a condition the wait
+        // for the batch in front of a load becomes a wait for everything in flight.)
+        auto pass2 = [&](auto one) __attribute__((always_inline)) {
+            constexpr std::true_type whole{};
+            u32x4 vp[kUnroll], vq[kUnroll], wp[kUnroll], wq[kUnroll];
+            load_batch(n_iter - 1, vp, vq);
+            if (n_iter == 1) {
+                work_batch(0, vp, vq, one, std::false_type{});
+                return;
+            }
+            load_batch(n_iter - 2, wp, wq);
+            work_batch(n_iter - 1, vp, vq, one, std::false_type{});  // the row's last, ragged batch
+            int it = n_iter - 2;  // wp holds batch `it`
+            for (; it >= 2; it -= 2) {
+                load_batch(it - 1, vp, vq);
+                work_batch(it, wp, wq, one, whole);
+                load_batch(it - 2, wp, wq);
+                work_batch(it - 1, vp, vq, one, whole);
+            }
+            if (it == 1) {
+                load_batch(0, vp, vq);
+                work_batch(1, wp, wq, one, whole);
+                work_batch(0, vp, vq, one, whole);
+            } else {
+                work_batch(0, wp, wq, one, whole);
+            }
+        };
+        if (one_term) pass2(std::true_type{});
+        else pass2(std::false_type{});
         // KL(p || q) of the row in nats, summed in a fixed order
         const double kw = wave_sum(kl);
         if (lane == 0) sh.loss_wave[wave] = kw;
@@ -148,6 +177,7 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
         if (threadIdx.x == 0) {
             double t = 0.0;
             for (int x = 0; x < kWaves; ++x) t += sh.loss_wave[x];
+            if (one_term) t += kl_shift;  // sum_x p(x) = 1
             p.row_kl[r] = t * 0.69314718055994530942;
         }
         // (the next row's normaliser pass has a barrier before anything writes loss_wave again)
