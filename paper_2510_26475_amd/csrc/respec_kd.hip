@@ -131,7 +131,11 @@ __global__ __launch_bounds__(kThreads) void kd_stream_kernel(KdParams p) {
                             b = exp2_arg(zq[j], Mq, p.c_hi, p.c_lo) - lsq;
                         }
                         const float pe = hw_exp2(a), qe = hw_exp2(b);
-                        if (pe > 0.f) klb += pe * (a - b);
+                        // (a token without target mass adds nothing, whatever a - b is then, -inf
+                        // minus -inf included: the legacy multiply takes 0 times anything as 0)
+                        float term;
+                        asm("v_mul_legacy_f32 %0, %1, %2" : "=v"(term) : "v"(pe), "v"(a - b));
+                        klb += term;
                         gr[j] = w * (qe - pe);
                     }
                     store_grad<BF16>(g + (size_t)s * 16, gr);
